@@ -1,0 +1,174 @@
+"""CPU oracle for the mixed-batch LoRA linear layer -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes wrapper around ``collm_oracle.c`` (plain fp64 loops).  Only the tests, the
+smoke check and the benchmark's CPU-baseline leg may import this package; the GPU library
+and its Python binding never do, and this package imports nothing from them.
+
+The operation is the LoRA-instrumented linear layer of the paper's section 4.2
+(frozen W_pre plus Delta W = B_g A_g) evaluated on one batch that mixes inference and
+training segments sharing one weight copy (section 2.1, "model sharing").  Row-vector
+convention: ``x [T, d_in]``, ``W [d_in, d_out]``, ``A[a] [d_in, r_a]``, ``B[a] [r_a, d_out]``.
+
+Pins (tests/test_oracle_pins.py): a hand-worked one-token example, numpy's matmul for the
+base term and for the merged weight X (W + s A B), segment independence, permutation
+invariance, closed-form gradients, and central finite differences.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "collm_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+_f64p = ctypes.POINTER(ctypes.c_double)
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_u8p = ctypes.POINTER(ctypes.c_uint8)
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (OpenMP over independent tokens / output entries)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-o", tmp, _SRC]
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.oracle_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _ptr_table(arrs):
+    tab = (ctypes.c_void_p * max(1, len(arrs)))()
+    for k, a in enumerate(arrs):
+        tab[k] = None if a is None else a.ctypes.data
+    return tab
+
+
+def token_map(seg_start, seg_adapter, seg_is_train):
+    """Per-token (segment, adapter, is_train) arrays from the segment description."""
+    seg_start = np.ascontiguousarray(seg_start, dtype=np.int32)
+    seg_adapter = np.ascontiguousarray(seg_adapter, dtype=np.int32)
+    seg_is_train = np.ascontiguousarray(seg_is_train, dtype=np.uint8)
+    S = len(seg_adapter)
+    T = int(seg_start[S]) if S > 0 else 0
+    tok_seg = np.full(T, -7, dtype=np.int32)
+    tok_adapter = np.full(T, -7, dtype=np.int32)
+    tok_train = np.full(T, 7, dtype=np.uint8)
+    _load().oracle_token_map(
+        ctypes.c_int32(S),
+        seg_start.ctypes.data_as(_i32p),
+        seg_adapter.ctypes.data_as(_i32p),
+        seg_is_train.ctypes.data_as(_u8p),
+        tok_seg.ctypes.data_as(_i32p),
+        tok_adapter.ctypes.data_as(_i32p),
+        tok_train.ctypes.data_as(_u8p),
+    )
+    return tok_seg, tok_adapter, tok_train
+
+
+def base_matmul(x, W):
+    x, W = _f64(x), _f64(W)
+    T, d_in = x.shape
+    d_out = W.shape[1]
+    assert W.shape[0] == d_in
+    y = np.empty((T, d_out), dtype=np.float64)
+    _load().oracle_base_matmul(
+        ctypes.c_int32(T), ctypes.c_int32(d_in), ctypes.c_int32(d_out),
+        x.ctypes.data_as(_f64p), W.ctypes.data_as(_f64p), y.ctypes.data_as(_f64p),
+    )
+    return y
+
+
+def lora_linear_fwd(x, W, A, B, tok_adapter, scale):
+    """Returns (y [T, d_out], h [T, r_max]) in fp64; h = x A_a, unscaled."""
+    x, W = _f64(x), _f64(W)
+    A = [_f64(a) for a in A]
+    B = [_f64(b) for b in B]
+    T, d_in = x.shape
+    d_out = W.shape[1]
+    assert W.shape[0] == d_in
+    rank = np.array([a.shape[1] for a in A], dtype=np.int32)
+    for a, b, r in zip(A, B, rank):
+        assert a.shape == (d_in, r) and b.shape == (r, d_out)
+    tok_adapter = np.ascontiguousarray(tok_adapter, dtype=np.int32)
+    assert tok_adapter.shape == (T,)
+    assert tok_adapter.size == 0 or (tok_adapter.min() >= -1 and tok_adapter.max() < len(A))
+    rmax = int(rank.max()) if len(rank) else 1
+    y = np.empty((T, d_out), dtype=np.float64)
+    h = np.empty((T, rmax), dtype=np.float64)
+    _load().oracle_lora_linear_fwd(
+        ctypes.c_int32(T), ctypes.c_int32(d_in), ctypes.c_int32(d_out),
+        x.ctypes.data_as(_f64p), W.ctypes.data_as(_f64p),
+        _ptr_table(A), _ptr_table(B),
+        rank.ctypes.data_as(_i32p), tok_adapter.ctypes.data_as(_i32p),
+        ctypes.c_double(scale), y.ctypes.data_as(_f64p), h.ctypes.data_as(_f64p),
+        ctypes.c_int32(rmax),
+    )
+    return y, h
+
+
+def lora_linear_bwd(x, W, A, B, tok_adapter, tok_is_train, scale, dy, want_dx=True,
+                    want_dab=True):
+    """Returns (dx or None, dA list, dB list).
+
+    dx rows of inference tokens are NaN (never written); dA[a]/dB[a] is None for an adapter
+    without a training token.
+    """
+    x = _f64(x)
+    A = [_f64(a) for a in A]
+    B = [_f64(b) for b in B]
+    dy = _f64(dy)
+    T, d_in = x.shape
+    d_out = dy.shape[1]
+    rank = np.array([a.shape[1] for a in A], dtype=np.int32)
+    tok_adapter = np.ascontiguousarray(tok_adapter, dtype=np.int32)
+    tok_is_train = np.ascontiguousarray(tok_is_train, dtype=np.uint8)
+    assert tok_adapter.shape == (T,) and tok_is_train.shape == (T,) and dy.shape[0] == T
+    trained = sorted(set(int(a) for a in tok_adapter[tok_is_train != 0]))
+    assert all(0 <= a < len(A) for a in trained), "training tokens need an adapter"
+    dx = None
+    Wp = None
+    if want_dx:
+        W = _f64(W)
+        assert W.shape == (d_in, d_out)
+        Wp = W.ctypes.data_as(_f64p)
+        dx = np.full((T, d_in), np.nan, dtype=np.float64)
+    dA = [None] * len(A)
+    dB = [None] * len(A)
+    if want_dab:
+        for a in trained:
+            dA[a] = np.full((d_in, rank[a]), np.nan, dtype=np.float64)
+            dB[a] = np.full((rank[a], d_out), np.nan, dtype=np.float64)
+    _load().oracle_lora_linear_bwd(
+        ctypes.c_int32(T), ctypes.c_int32(d_in), ctypes.c_int32(d_out), ctypes.c_int32(len(A)),
+        x.ctypes.data_as(_f64p), Wp, _ptr_table(A), _ptr_table(B),
+        rank.ctypes.data_as(_i32p), tok_adapter.ctypes.data_as(_i32p),
+        tok_is_train.ctypes.data_as(_u8p), ctypes.c_double(scale),
+        dy.ctypes.data_as(_f64p),
+        None if dx is None else dx.ctypes.data_as(_f64p),
+        _ptr_table(dA) if want_dab else None,
+        _ptr_table(dB) if want_dab else None,
+    )
+    return dx, dA, dB

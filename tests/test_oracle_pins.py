@@ -1,0 +1,269 @@
+"""Pins for the CPU oracle: what the problem itself fixes, independent of the oracle's code.
+
+ * a hand-worked one-token example (tests/golden/hand_example.json);
+ * B = 0 reproduces X W exactly, and X W agrees with numpy's matmul;
+ * the unmerged result equals X (W + s A_a B_a) with merged weights (numpy matmul);
+ * a mixed batch equals its segments run one at a time; segment order does not matter;
+ * closed-form gradients through merged weights; gradients of inference-only adapters
+   and inference rows are absent;
+ * central finite differences of L = sum_{t in train} <dY[t], Y[t]> to 1e-6 relative.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2604_16400_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rel(a, b):
+    return float(np.max(np.abs(np.asarray(a) - np.asarray(b))) / max(np.max(np.abs(b)), 1e-300))
+
+
+def _small(seed=3, d_in=24, d_out=20, ranks=(3, 5, 2, 4), lens=(4, 0, 3, 6, 1, 5),
+           adapters=(0, 2, -1, 1, 3, 1), train=(0, 0, 0, 1, 0, 1), scale=0.7):
+    w = wl.make_adhoc("small", "f32", d_in, d_out, ranks, lens, adapters, train, scale=scale,
+                      seed=seed, std_x=1.0, std_w=0.5, std_a=0.4, std_b=0.3)
+    t = wl.make_tensors(w)
+    f = lambda a: np.asarray(a, dtype=np.float64)
+    return w, f(t.x), f(t.W), [f(a) for a in t.A], [f(b) for b in t.B], f(t.dy)
+
+
+# ---------------------------------------------------------------- bookkeeping ------------
+def test_token_map_definition_and_properties():
+    rng = np.random.default_rng(0)
+    for _ in range(300):
+        S = int(rng.integers(0, 12))
+        lens = rng.integers(0, 6, size=S)
+        seg_start = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        ad = rng.integers(-1, 5, size=S).astype(np.int32)
+        tr = rng.integers(0, 2, size=S).astype(np.uint8)
+        ts, ta, tt = oracle.token_map(seg_start, ad, tr)
+        # numpy's repeat is the library statement of "every token inherits its segment's tag"
+        assert np.array_equal(ts, np.repeat(np.arange(S, dtype=np.int32), lens))
+        assert np.array_equal(ta, np.repeat(ad, lens))
+        assert np.array_equal(tt, np.repeat(tr, lens))
+        assert len(ts) == lens.sum()
+        assert np.all(np.diff(ts) >= 0)
+        assert np.array_equal(np.bincount(ts, minlength=S)[:S], lens) if S else True
+
+
+def test_token_map_config1_literal():
+    w = wl.make_config(1)
+    ts, ta, tt = oracle.token_map(w.seg_start, w.seg_adapter, w.seg_is_train)
+    assert list(ts) == [0] * 20 + [1] * 12 + [2] * 32
+    assert list(ta) == [0] * 20 + [3] * 12 + [1] * 32
+    assert list(tt) == [0] * 32 + [1] * 32
+
+
+# ---------------------------------------------------------------- hand example -----------
+def test_hand_worked_example():
+    g = json.load(open(os.path.join(GOLDEN, "hand_example.json")))
+    x, W, A, B = (np.array(g[k], dtype=np.float64) for k in ("x", "W", "A", "B"))
+    y, h = oracle.lora_linear_fwd(x, W, [A], [B], [0], g["scale"])
+    assert np.array_equal(h, np.array(g["h"]))
+    assert np.array_equal(y, np.array(g["y"]))
+    for case in g["backward"]:
+        dy = np.array(case["dy"], dtype=np.float64)
+        dx, dA, dB = oracle.lora_linear_bwd(x, W, [A], [B], [0], [1], g["scale"], dy)
+        assert np.array_equal(dx, np.array(case["dx"]))
+        assert np.array_equal(dA[0], np.array(case["dA"]))
+        assert np.array_equal(dB[0], np.array(case["dB"]))
+
+
+# ---------------------------------------------------------------- forward ----------------
+def test_base_term_matches_numpy_matmul():
+    w, x, W, A, B, dy = _small(d_in=37, d_out=29)
+    y0 = oracle.base_matmul(x, W)
+    assert _rel(y0, x @ W) < 1e-13
+    # a non-symmetric probe: unit vectors pick out single rows of W, exactly
+    e = np.eye(37)[[0, 5, 36]]
+    assert np.array_equal(oracle.base_matmul(e, W), W[[0, 5, 36]])
+
+
+def test_zero_B_reproduces_base_exactly():
+    w, x, W, A, B, dy = _small()
+    _, ta, _ = oracle.token_map(w.seg_start, w.seg_adapter, w.seg_is_train)
+    y, h = oracle.lora_linear_fwd(x, W, A, [np.zeros_like(b) for b in B], ta, w.scale)
+    assert np.array_equal(y, oracle.base_matmul(x, W))
+    # base-only tokens never get a low-rank term even with non-zero B
+    y2, h2 = oracle.lora_linear_fwd(x, W, A, B, ta, w.scale)
+    base = oracle.base_matmul(x, W)
+    assert np.array_equal(y2[ta < 0], base[ta < 0])
+    assert np.all(h2[ta < 0] == 0.0)
+
+
+@pytest.mark.parametrize("scale", [2.0, 0.3])
+def test_merged_weight_identity(scale):
+    w, x, W, A, B, dy = _small(scale=scale)
+    _, ta, _ = oracle.token_map(w.seg_start, w.seg_adapter, w.seg_is_train)
+    y, h = oracle.lora_linear_fwd(x, W, A, B, ta, scale)
+    for t in range(w.n_tokens):
+        a = ta[t]
+        Wm = W if a < 0 else W + scale * (A[a] @ B[a])
+        assert _rel(y[t], x[t] @ Wm) < 1e-12
+        if a >= 0:
+            assert _rel(h[t, : w.ranks[a]], x[t] @ A[a]) < 1e-12
+            assert np.all(h[t, w.ranks[a]:] == 0.0)
+
+
+def test_config1_merged_weight_identity():
+    w = wl.make_config(1)
+    t = wl.make_tensors(w)
+    f = lambda a: np.asarray(a, dtype=np.float64)
+    _, ta, _ = oracle.token_map(w.seg_start, w.seg_adapter, w.seg_is_train)
+    y, _ = oracle.lora_linear_fwd(t.x, t.W, t.A, t.B, ta, w.scale)
+    for k in range(w.n_segments):
+        lo, hi, a = w.seg_start[k], w.seg_start[k + 1], w.seg_adapter[k]
+        Wm = f(t.W) + w.scale * (f(t.A[a]) @ f(t.B[a]))
+        assert _rel(y[lo:hi], f(t.x[lo:hi]) @ Wm) < 1e-12
+
+
+def test_segments_run_alone_are_bit_equal():
+    w, x, W, A, B, dy = _small()
+    _, ta, tt = oracle.token_map(w.seg_start, w.seg_adapter, w.seg_is_train)
+    y, h = oracle.lora_linear_fwd(x, W, A, B, ta, w.scale)
+    dx, dA, dB = oracle.lora_linear_bwd(x, W, A, B, ta, tt, w.scale, dy)
+    for k in range(w.n_segments):
+        lo, hi = w.seg_start[k], w.seg_start[k + 1]
+        if hi == lo:
+            continue
+        a = np.full(hi - lo, w.seg_adapter[k], dtype=np.int32)
+        yk, hk = oracle.lora_linear_fwd(x[lo:hi], W, A, B, a, w.scale)
+        assert np.array_equal(yk, y[lo:hi]) and np.array_equal(hk, h[lo:hi])
+        if w.seg_is_train[k]:
+            tr = np.ones(hi - lo, dtype=np.uint8)
+            dxk, _, _ = oracle.lora_linear_bwd(x[lo:hi], W, A, B, a, tr, w.scale, dy[lo:hi])
+            assert np.array_equal(dxk, dx[lo:hi])
+    # adapter 1 owns two training segments: its gradient is the sum of the per-segment ones
+    parts_A, parts_B = [], []
+    for k in range(w.n_segments):
+        if w.seg_is_train[k] and w.seg_adapter[k] == 1:
+            lo, hi = w.seg_start[k], w.seg_start[k + 1]
+            a = np.full(hi - lo, 1, dtype=np.int32)
+            tr = np.ones(hi - lo, dtype=np.uint8)
+            _, dAk, dBk = oracle.lora_linear_bwd(x[lo:hi], W, A, B, a, tr, w.scale, dy[lo:hi])
+            parts_A.append(dAk[1])
+            parts_B.append(dBk[1])
+    assert len(parts_A) == 2
+    assert _rel(dA[1], parts_A[0] + parts_A[1]) < 1e-13
+    assert _rel(dB[1], parts_B[0] + parts_B[1]) < 1e-13
+
+
+def test_segment_order_invariance():
+    w, x, W, A, B, dy = _small()
+    _, ta, tt = oracle.token_map(w.seg_start, w.seg_adapter, w.seg_is_train)
+    y, _ = oracle.lora_linear_fwd(x, W, A, B, ta, w.scale)
+    dx, dA, dB = oracle.lora_linear_bwd(x, W, A, B, ta, tt, w.scale, dy)
+    ws, tok_perm = wl.shuffled_segments(w, seed=11)
+    _, ta2, tt2 = oracle.token_map(ws.seg_start, ws.seg_adapter, ws.seg_is_train)
+    assert np.array_equal(ta2, ta[tok_perm])
+    y2, _ = oracle.lora_linear_fwd(x[tok_perm], W, A, B, ta2, w.scale)
+    dx2, dA2, dB2 = oracle.lora_linear_bwd(x[tok_perm], W, A, B, ta2, tt2, w.scale, dy[tok_perm])
+    assert np.array_equal(y2, y[tok_perm])
+    assert np.array_equal(dx2[tt2 != 0], dx[tok_perm][tt2 != 0])
+    for a in range(w.n_adapters):
+        assert (dA[a] is None) == (dA2[a] is None)
+        if dA[a] is not None:
+            assert _rel(dA2[a], dA[a]) < 1e-12 and _rel(dB2[a], dB[a]) < 1e-12
+
+
+# ---------------------------------------------------------------- backward ---------------
+@pytest.mark.parametrize("scale", [2.0, 0.3])
+def test_backward_closed_forms(scale):
+    w, x, W, A, B, dy = _small(scale=scale)
+    _, ta, tt = oracle.token_map(w.seg_start, w.seg_adapter, w.seg_is_train)
+    dx, dA, dB = oracle.lora_linear_bwd(x, W, A, B, ta, tt, scale, dy)
+    trained = sorted(set(ta[tt != 0]))
+    assert trained == [1]
+    for a in range(w.n_adapters):
+        if a not in trained:
+            assert dA[a] is None and dB[a] is None
+            continue
+        m = (tt != 0) & (ta == a)
+        assert _rel(dB[a], scale * (x[m] @ A[a]).T @ dy[m]) < 1e-12
+        assert _rel(dA[a], scale * x[m].T @ (dy[m] @ B[a].T)) < 1e-12
+        assert _rel(dx[m], dy[m] @ (W + scale * A[a] @ B[a]).T) < 1e-12
+    assert np.all(np.isnan(dx[tt == 0]))  # inference rows are never written
+
+
+def _loss(x, W, A, B, ta, tt, scale, dy):
+    rows = np.flatnonzero(tt)
+    y, _ = oracle.lora_linear_fwd(x[rows], W, A, B, ta[rows], scale)
+    return float(np.sum(y * dy[rows]))
+
+
+def _fd_check(x, W, A, B, ta, tt, scale, dy, entries, rng):
+    dx, dA, dB = oracle.lora_linear_bwd(x, W, A, B, ta, tt, scale, dy)
+    worst = 0.0
+    for kind, a, idx in entries:
+        arr = {"A": A, "B": B}[kind][a] if kind != "x" else x
+        ana_arr = ({"A": dA, "B": dB}[kind][a] if kind != "x" else dx)
+        old = arr[idx]
+        step = 1e-3 * max(1.0, abs(old))
+        arr[idx] = old + step
+        lp = _loss(x, W, A, B, ta, tt, scale, dy)
+        arr[idx] = old - step
+        lm = _loss(x, W, A, B, ta, tt, scale, dy)
+        arr[idx] = old
+        num = (lp - lm) / (2 * step)
+        if ana_arr is None or (kind == "x" and not tt[idx[0]]):
+            assert num == 0.0  # not a training parameter: the loss does not depend on it
+            continue
+        ana = ana_arr[idx]
+        scale_ref = max(np.max(np.abs(ana_arr[np.isfinite(ana_arr)])), 1e-300)
+        worst = max(worst, abs(num - ana) / scale_ref)
+    return worst
+
+
+def test_finite_differences_small_every_entry():
+    w, x, W, A, B, dy = _small(d_in=10, d_out=9, ranks=(2, 3, 1, 2))
+    _, ta, tt = oracle.token_map(w.seg_start, w.seg_adapter, w.seg_is_train)
+    entries = []
+    for a in range(w.n_adapters):
+        entries += [("A", a, idx) for idx in np.ndindex(A[a].shape)]
+        entries += [("B", a, idx) for idx in np.ndindex(B[a].shape)]
+    entries += [("x", None, idx) for idx in np.ndindex(x.shape)]
+    worst = _fd_check(x, W, A, B, ta, tt, w.scale, dy, entries, None)
+    assert worst < 1e-6, worst
+
+
+def test_finite_differences_config1():
+    w = wl.make_config(1)
+    t = wl.make_tensors(w)
+    f = lambda a: np.array(a, dtype=np.float64)
+    x, W, A, B, dy = f(t.x), f(t.W), [f(a) for a in t.A], [f(b) for b in t.B], f(t.dy)
+    _, ta, tt = oracle.token_map(w.seg_start, w.seg_adapter, w.seg_is_train)
+    rng = np.random.default_rng(5)
+    entries = []
+    for a in range(4):
+        ia = rng.choice(A[a].size, size=200 if a == 1 else 10, replace=False)
+        entries += [("A", a, np.unravel_index(i, A[a].shape)) for i in ia]
+        ib = rng.choice(B[a].size, size=200 if a == 1 else 10, replace=False)
+        entries += [("B", a, np.unravel_index(i, B[a].shape)) for i in ib]
+    ix = rng.choice(x.size, size=300, replace=False)
+    entries += [("x", None, np.unravel_index(i, x.shape)) for i in ix]
+    worst = _fd_check(x, W, A, B, ta, tt, w.scale, dy, entries, rng)
+    assert worst < 1e-6, worst
+
+
+def test_untrained_adapters_and_inference_rows_are_untouched():
+    w = wl.make_config(1)
+    t = wl.make_tensors(w)
+    _, ta, tt = oracle.token_map(w.seg_start, w.seg_adapter, w.seg_is_train)
+    dx, dA, dB = oracle.lora_linear_bwd(t.x, t.W, t.A, t.B, ta, tt, w.scale, t.dy)
+    assert [a is None for a in dA] == [True, False, True, True]
+    assert np.all(np.isnan(dx[:32])) and np.all(np.isfinite(dx[32:]))
+    # dy of inference rows is never read: poisoning it changes nothing
+    dy2 = np.array(t.dy, dtype=np.float64)
+    dy2[:32] = np.nan
+    dx2, dA2, dB2 = oracle.lora_linear_bwd(t.x, t.W, t.A, t.B, ta, tt, w.scale, dy2)
+    assert np.array_equal(dx2[32:], dx[32:]) and np.array_equal(dA2[1], dA[1])
+    assert np.array_equal(dB2[1], dB[1])
+    # skipping the W-sized contraction leaves the adapter gradients unchanged
+    _, dA3, dB3 = oracle.lora_linear_bwd(t.x, None, t.A, t.B, ta, tt, w.scale, t.dy, want_dx=False)
+    assert np.array_equal(dA3[1], dA[1]) and np.array_equal(dB3[1], dB[1])
