@@ -1,0 +1,183 @@
+/*
+ * collm_lora.h -- C ABI of the mixed-batch LoRA linear layer for AMD MI355X (gfx950).
+ *
+ * The layer is the LoRA-instrumented linear layer of the paper's section 4.2 (a frozen
+ * base weight W_pre plus a trainable low-rank update Delta W = B_g A_g; only the adapters
+ * train), evaluated the way the paper's model sharing runs it (section 2.1, "CoLLM's model
+ * sharing"; section 7, "Concurrent Inference and Fine-tuning via Model Sharing"): inference
+ * requests and fine-tuning sequences use ONE copy of the base weight and of the adapters at
+ * the same time.  Here the two kinds of work arrive as one batch of tokens cut into
+ * segments; a segment names its adapter and says whether it trains.  The inference batch b
+ * and the training batch B of the paper's coordinator (section 5) are the inference-token
+ * and training-token counts of that batch.
+ *
+ * Row-vector convention, all matrices row-major and dense:
+ *     x  [T, d_in]        batch of tokens
+ *     W  [d_in, d_out]    base weight (= W_pre^T), frozen
+ *     A[a] [d_in, r_a]    down-projection of adapter a (= A_g^T)
+ *     B[a] [r_a, d_out]   up-projection of adapter a   (= B_g^T)
+ * For token t of a segment with adapter a:
+ *     h[t,:] = x[t,:] A[a]                       y[t,:] = x[t,:] W + scale * h[t,:] B[a]
+ * and for a token of a training segment, given dy = dL/dy:
+ *     dh[t,:] = scale * dy[t,:] B[a]^T           dx[t,:] = dy[t,:] W^T + dh[t,:] A[a]^T
+ *     dA[a] += x[t,:]^T dh[t,:]                  dB[a] += scale * h[t,:]^T dy[t,:]
+ * There is no gradient for W.
+ *
+ * Element types: COLLM_BF16 (x, W, A, B, y, dy, dx are bfloat16; every product is
+ * accumulated in fp32 and y / dx are rounded to bfloat16 once, on the final store) or
+ * COLLM_F32 (all fp32, plain fp32 fused multiply-add).  h_save, dA and dB are always fp32.
+ *
+ * Conventions common to all entry points
+ *   - "dev" pointers are device memory on the context's GPU, 16-byte aligned; "HOST"
+ *     pointers are ordinary host memory.  The caller owns every buffer; the library owns
+ *     only the context and its workspace and keeps no caller pointer after a call returns.
+ *   - The compute calls are asynchronous: they enqueue work on `stream` (a hipStream_t, NULL
+ *     = the default stream) and return.  Host arrays are copied before the call returns and
+ *     may be reused at once.  One context serves one stream at a time; calls on the same
+ *     context must not overlap on different streams, and a context is not thread-safe.
+ *   - Every call returns a status: COLLM_OK (0) or a negative error.  All validation is done
+ *     on the host before anything is launched; on an error no output buffer is touched.
+ *   - d_in and d_out must be multiples of 8 (bf16) or 4 (fp32).  Ranks may be any value in
+ *     1..max_rank.  Empty segments and an empty batch are legal.
+ */
+#ifndef COLLM_LORA_H
+#define COLLM_LORA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct collm_ctx collm_ctx; /* opaque: pinned staging, device plan and workspace */
+
+typedef enum { COLLM_F32 = 0, COLLM_BF16 = 1 } collm_dtype;
+
+enum {
+    COLLM_OK = 0,
+    COLLM_E_NULL = -1,     /* a required pointer is NULL                                    */
+    COLLM_E_SHAPE = -2,    /* non-positive or unsupported size, or beyond the context maxima */
+    COLLM_E_SEGMENTS = -3, /* seg_start[0] != 0, decreasing, or seg_start[S] != n_tokens     */
+    COLLM_E_ADAPTER = -4,  /* adapter index outside [-1, N), training segment without an     */
+                           /* adapter, NULL table of a used adapter, NULL dA/dB of a trained */
+    COLLM_E_RANK = -5,     /* rank outside 1..max_rank                                       */
+    COLLM_E_DTYPE = -6,    /* unknown element type                                           */
+    COLLM_E_ALIGN = -7,    /* a device pointer is not 16-byte aligned                        */
+    COLLM_E_HIP = -8,      /* a HIP call failed; see collm_last_error()                      */
+    COLLM_E_NOMEM = -9     /* host or device allocation failed                               */
+};
+
+typedef struct {
+    int32_t d_in, d_out;
+    int32_t n_tokens;   /* T */
+    int32_t n_segments; /* S */
+    int32_t n_adapters; /* N */
+    int32_t dtype;      /* collm_dtype */
+    float scale;        /* multiplies the low-rank term */
+} collm_shape;
+
+/* Create a context on GPU `device` able to serve calls with n_tokens <= max_tokens,
+ * n_segments <= max_segments, n_adapters <= max_adapters, every rank <= max_rank
+ * (max_rank <= 256) and d_in, d_out <= max_d.  Allocates pinned staging and the device
+ * workspace once; the compute calls allocate nothing.  *out is NULL on failure. */
+int collm_ctx_create(collm_ctx **out, int device, int32_t max_tokens, int32_t max_segments,
+                     int32_t max_adapters, int32_t max_rank, int32_t max_d);
+/* Waits for the device to finish the context's work, then frees everything it owns. */
+int collm_ctx_destroy(collm_ctx *ctx);
+/* Bytes of device workspace the context holds. */
+int64_t collm_ctx_workspace_bytes(const collm_ctx *ctx);
+
+const char *collm_status_string(int status);
+/* Text of the last HIP failure seen by this thread ("" if none). */
+const char *collm_last_error(void);
+
+/*
+ * Forward (the definition above; paper section 4.2 for the parameterisation, section 2.1
+ * for inference and training tokens sharing W and the adapters).
+ *
+ * Steps, all in the library's kernels: the host turns the segment table into a device plan
+ * (token -> segment/adapter map, rows grouped by adapter, tile tables); a segmented shrink
+ * computes h = x A[a] in fp32; one GEMM computes x W and adds scale * h B[a] as extra
+ * K-steps before the single rounding of y.
+ *
+ *   x            dev  [T, d_in]
+ *   W            dev  [d_in, d_out]
+ *   A, B         HOST arrays [N] of dev pointers, A[i]: [d_in, rank[i]], B[i]: [rank[i], d_out];
+ *                an entry may be NULL if no segment uses adapter i
+ *   rank         HOST [N]
+ *   seg_start    HOST [S+1], seg_start[0] = 0, non-decreasing, seg_start[S] = T
+ *   seg_adapter  HOST [S], 0..N-1, or -1 = base weight only (inference segments only)
+ *   seg_is_train HOST [S], 0 or 1
+ *   y            dev  [T, d_out]; every row is written
+ *   h_save       dev  fp32 [T, max_rank] (row stride = the context's max_rank) or NULL.
+ *                Rows of training tokens receive h (unscaled), zero-filled from rank[a] up
+ *                to max_rank; rows of inference tokens are not touched.
+ */
+int collm_lora_linear_fwd(collm_ctx *ctx, const collm_shape *shape, const void *x, const void *W,
+                          const void *const *A, const void *const *B, const int32_t *rank,
+                          const int32_t *seg_start, const int32_t *seg_adapter,
+                          const uint8_t *seg_is_train, void *y, float *h_save, void *stream);
+
+/*
+ * Backward for the training segments (only adapters train: paper section 4.2).
+ *
+ *   x, W, A, B, rank, seg_*   as in the forward call (same batch)
+ *   dy           dev  [T, d_out]; only rows of training tokens are read
+ *   h_save       dev  fp32 [T, max_rank] as written by the forward call, or NULL to recompute
+ *   dx           dev  [T, d_in] or NULL; only rows of training tokens are written
+ *   dA, dB       HOST arrays [N] of dev fp32 pointers, dA[i]: [d_in, rank[i]],
+ *                dB[i]: [rank[i], d_out].  Only adapters that own a training segment are
+ *                written (their entries must be non-NULL); all others are ignored.
+ *                Both arrays may be NULL to skip the adapter gradients.
+ *   accumulate   0: overwrite dA/dB of the trained adapters; 1: add to what they hold
+ *                (gradient accumulation over micro-batches, paper section 2.2 footnote)
+ *
+ * Gradients of one adapter are summed over its training tokens in ascending token order in
+ * fixed-size partial sums that are then added in order: no floating-point atomics, so two
+ * runs give the same bits.
+ */
+int collm_lora_linear_bwd(collm_ctx *ctx, const collm_shape *shape, const void *x, const void *W,
+                          const void *const *A, const void *const *B, const int32_t *rank,
+                          const int32_t *seg_start, const int32_t *seg_adapter,
+                          const uint8_t *seg_is_train, const void *dy, const float *h_save,
+                          void *dx, float *const *dA, float *const *dB, int accumulate,
+                          void *stream);
+
+/*
+ * Integer bookkeeping on the host (no GPU needed): per-token segment index, adapter index
+ * and training flag.  All pointers HOST; outputs have n_tokens entries.  Uses only
+ * n_tokens, n_segments and n_adapters of `shape`.
+ */
+int collm_token_map(const collm_shape *shape, const int32_t *seg_start,
+                    const int32_t *seg_adapter, const uint8_t *seg_is_train,
+                    int32_t *tok_segment, int32_t *tok_adapter, uint8_t *tok_is_train);
+
+/*
+ * Debug: read back the plan the DEVICE holds from the context's last compute call and undo
+ * its row grouping, giving the token map the kernels actually used.  Synchronises the
+ * context's last stream.  Outputs HOST, n_tokens entries of the last call.
+ */
+int collm_debug_device_token_map(collm_ctx *ctx, int32_t *tok_segment, int32_t *tok_adapter,
+                                 uint8_t *tok_is_train);
+
+/*
+ * Debug/tuning: force the tile shape of the forward GEMM and of the dX GEMM
+ * (0: 256x256, 1: 256x128, 2: 128x128 rows x columns of the output; -1: let the library
+ * choose from the problem size).  Affects only speed, never results beyond rounding order.
+ */
+int collm_debug_set_tiles(collm_ctx *ctx, int fwd_tile, int bwd_tile);
+
+/*
+ * Debug/profiling: average duration in milliseconds, measured with HIP events on the
+ * call's own stream, of each kernel launched by the context's last compute call.
+ * collm_profile_enable(ctx, 1) makes every later call record events around each launch;
+ * collm_profile_read synchronises, fills names[i] (static strings) and ms[i] for up to
+ * `cap` kernels and returns how many there were (or a negative status).
+ */
+int collm_profile_enable(collm_ctx *ctx, int enable);
+int collm_profile_read(collm_ctx *ctx, const char **names, float *ms, int cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COLLM_LORA_H */

@@ -1,0 +1,230 @@
+"""Python face of libcollm_lora.so: argument marshalling only.
+
+Every step of the layer (plan, shrink, GEMM with fused expand, gradients) runs inside the
+C-ABI library; this module turns torch tensors into pointers, sizes and a stream handle.
+PyTorch is used for device memory and streams and for nothing else.  There is no fallback:
+if the library cannot be loaded, or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcollm_lora.so")
+
+COLLM_F32 = 0
+COLLM_BF16 = 1
+
+TILE_AUTO, TILE_256x256, TILE_256x128, TILE_128x128 = -1, 0, 1, 2
+
+
+class CollmError(RuntimeError):
+    def __init__(self, status: int, where: str, detail: str = ""):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({detail})")
+
+
+class collm_shape(ctypes.Structure):
+    _fields_ = [
+        ("d_in", ctypes.c_int32), ("d_out", ctypes.c_int32), ("n_tokens", ctypes.c_int32),
+        ("n_segments", ctypes.c_int32), ("n_adapters", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("scale", ctypes.c_float),
+    ]
+
+
+_lib = None
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_u8p = ctypes.POINTER(ctypes.c_uint8)
+_vpp = ctypes.POINTER(ctypes.c_void_p)
+
+
+def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
+    """Loads libcollm_lora.so (building it first only if it does not exist)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        if not build_if_missing:
+            raise FileNotFoundError(LIB_PATH)
+        from . import build as _build
+
+        _build.build()
+    try:
+        # the HIP runtime PyTorch has loaded must be the one this library binds to
+        import torch  # noqa: F401
+    except Exception:  # pragma: no cover - torch is only needed for device memory
+        pass
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, sp = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(collm_shape)
+    lib.collm_ctx_create.argtypes = [_vpp, ctypes.c_int, i32, i32, i32, i32, i32]
+    lib.collm_ctx_create.restype = ctypes.c_int
+    lib.collm_ctx_destroy.argtypes = [vp]
+    lib.collm_ctx_destroy.restype = ctypes.c_int
+    lib.collm_ctx_workspace_bytes.argtypes = [vp]
+    lib.collm_ctx_workspace_bytes.restype = ctypes.c_int64
+    lib.collm_status_string.argtypes = [ctypes.c_int]
+    lib.collm_status_string.restype = ctypes.c_char_p
+    lib.collm_last_error.argtypes = []
+    lib.collm_last_error.restype = ctypes.c_char_p
+    lib.collm_lora_linear_fwd.argtypes = [vp, sp, vp, vp, _vpp, _vpp, _i32p, _i32p, _i32p, _u8p, vp, vp, vp]
+    lib.collm_lora_linear_fwd.restype = ctypes.c_int
+    lib.collm_lora_linear_bwd.argtypes = [vp, sp, vp, vp, _vpp, _vpp, _i32p, _i32p, _i32p, _u8p, vp, vp, vp,
+                                          _vpp, _vpp, ctypes.c_int, vp]
+    lib.collm_lora_linear_bwd.restype = ctypes.c_int
+    lib.collm_token_map.argtypes = [sp, _i32p, _i32p, _u8p, _i32p, _i32p, _u8p]
+    lib.collm_token_map.restype = ctypes.c_int
+    lib.collm_debug_device_token_map.argtypes = [vp, _i32p, _i32p, _u8p]
+    lib.collm_debug_device_token_map.restype = ctypes.c_int
+    lib.collm_debug_set_tiles.argtypes = [vp, ctypes.c_int, ctypes.c_int]
+    lib.collm_debug_set_tiles.restype = ctypes.c_int
+    lib.collm_profile_enable.argtypes = [vp, ctypes.c_int]
+    lib.collm_profile_enable.restype = ctypes.c_int
+    lib.collm_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float),
+                                       ctypes.c_int]
+    lib.collm_profile_read.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        lib = load_library()
+        detail = lib.collm_status_string(status).decode()
+        if status == -8:
+            detail += ": " + lib.collm_last_error().decode()
+        raise CollmError(status, where, detail)
+
+
+def _seg_arrays(seg_start, seg_adapter, seg_is_train):
+    ss = np.ascontiguousarray(seg_start, dtype=np.int32)
+    sa = np.ascontiguousarray(seg_adapter, dtype=np.int32)
+    st = np.ascontiguousarray(seg_is_train, dtype=np.uint8)
+    if len(ss) != len(sa) + 1 or len(st) != len(sa):
+        raise ValueError("seg_start needs S+1 entries, seg_adapter and seg_is_train S")
+    return ss, sa, st
+
+
+def collm_token_map(seg_start, seg_adapter, seg_is_train, n_tokens: Optional[int] = None,
+                    n_adapters: int = 1 << 30):
+    """Host-only integer bookkeeping: per-token (segment, adapter, is_train)."""
+    lib = load_library()
+    ss, sa, st = _seg_arrays(seg_start, seg_adapter, seg_is_train)
+    T = int(ss[-1]) if n_tokens is None else int(n_tokens)
+    sh = collm_shape(8, 8, T, len(sa), n_adapters, COLLM_BF16, 1.0)
+    ts = np.full(max(T, 0), -9, np.int32)
+    ta = np.full(max(T, 0), -9, np.int32)
+    tt = np.full(max(T, 0), 9, np.uint8)
+    _check(lib.collm_token_map(ctypes.byref(sh), ss.ctypes.data_as(_i32p), sa.ctypes.data_as(_i32p),
+                               st.ctypes.data_as(_u8p), ts.ctypes.data_as(_i32p), ta.ctypes.data_as(_i32p),
+                               tt.ctypes.data_as(_u8p)), "collm_token_map")
+    return ts, ta, tt
+
+
+def _ptr_table(tensors: Optional[Sequence], n: int):
+    tab = (ctypes.c_void_p * max(n, 1))()
+    if tensors is not None:
+        for i, t in enumerate(tensors):
+            tab[i] = None if t is None else t.data_ptr()
+    return tab
+
+
+class Context:
+    """Owns one collm_ctx (pinned staging + device workspace) on one GPU."""
+
+    def __init__(self, max_tokens: int, max_segments: int, max_adapters: int, max_rank: int, max_d: int,
+                 device: int = 0):
+        self._lib = load_library()
+        self._h = ctypes.c_void_p()
+        self.max_rank = int(max_rank)
+        _check(self._lib.collm_ctx_create(ctypes.byref(self._h), device, max_tokens, max_segments,
+                                          max_adapters, max_rank, max_d), "collm_ctx_create")
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            self._lib.collm_ctx_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def workspace_bytes(self) -> int:
+        return int(self._lib.collm_ctx_workspace_bytes(self._h))
+
+    def set_tiles(self, fwd_tile: int = TILE_AUTO, bwd_tile: int = TILE_AUTO):
+        _check(self._lib.collm_debug_set_tiles(self._h, fwd_tile, bwd_tile), "collm_debug_set_tiles")
+
+    def profile_enable(self, on: bool):
+        _check(self._lib.collm_profile_enable(self._h, 1 if on else 0), "collm_profile_enable")
+
+    def profile_read(self):
+        names = (ctypes.c_char_p * 16)()
+        ms = (ctypes.c_float * 16)()
+        n = self._lib.collm_profile_read(self._h, names, ms, 16)
+        if n < 0:
+            _check(n, "collm_profile_read")
+        return [(names[i].decode(), float(ms[i])) for i in range(n)]
+
+    def device_token_map(self, n_tokens: int):
+        ts = np.full(n_tokens, -9, np.int32)
+        ta = np.full(n_tokens, -9, np.int32)
+        tt = np.full(n_tokens, 9, np.uint8)
+        _check(self._lib.collm_debug_device_token_map(self._h, ts.ctypes.data_as(_i32p),
+                                                      ta.ctypes.data_as(_i32p), tt.ctypes.data_as(_u8p)),
+               "collm_debug_device_token_map")
+        return ts, ta, tt
+
+    # ------------------------------------------------------------------------------------
+    def _shape(self, x, d_out, n_seg, n_adapters, scale):
+        import torch
+
+        if x.dtype == torch.bfloat16:
+            dt = COLLM_BF16
+        elif x.dtype == torch.float32:
+            dt = COLLM_F32
+        else:
+            raise TypeError("x must be bfloat16 or float32")
+        return collm_shape(int(x.shape[1]), int(d_out), int(x.shape[0]), n_seg, n_adapters, dt, float(scale))
+
+    @staticmethod
+    def _stream(stream):
+        import torch
+
+        s = torch.cuda.current_stream() if stream is None else stream
+        return ctypes.c_void_p(s.cuda_stream)
+
+    def collm_lora_linear_fwd(self, x, W, A: List, B: List, rank, seg_start, seg_adapter, seg_is_train,
+                              scale: float, y, h_save=None, stream=None):
+        """y <- x W + scale (x A_a) B_a per segment; h_save (optional) <- x A_a on training rows."""
+        ss, sa, st = _seg_arrays(seg_start, seg_adapter, seg_is_train)
+        rk = np.ascontiguousarray(rank, dtype=np.int32)
+        sh = self._shape(x, W.shape[1], len(sa), len(rk), scale)
+        At, Bt = _ptr_table(A, len(rk)), _ptr_table(B, len(rk))
+        _check(self._lib.collm_lora_linear_fwd(
+            self._h, ctypes.byref(sh), x.data_ptr(), W.data_ptr(), At, Bt, rk.ctypes.data_as(_i32p),
+            ss.ctypes.data_as(_i32p), sa.ctypes.data_as(_i32p), st.ctypes.data_as(_u8p), y.data_ptr(),
+            None if h_save is None else h_save.data_ptr(), self._stream(stream)), "collm_lora_linear_fwd")
+        return y
+
+    def collm_lora_linear_bwd(self, x, W, A: List, B: List, rank, seg_start, seg_adapter, seg_is_train,
+                              scale: float, dy, h_save=None, dx=None, dA: Optional[List] = None,
+                              dB: Optional[List] = None, accumulate: bool = False, stream=None):
+        """Training rows: dx <- dy W^T + dh A_a^T; dA_a, dB_a (fp32) summed over the adapter's tokens."""
+        ss, sa, st = _seg_arrays(seg_start, seg_adapter, seg_is_train)
+        rk = np.ascontiguousarray(rank, dtype=np.int32)
+        sh = self._shape(x, W.shape[1], len(sa), len(rk), scale)
+        At, Bt = _ptr_table(A, len(rk)), _ptr_table(B, len(rk))
+        dAt = _ptr_table(dA, len(rk)) if dA is not None else None
+        dBt = _ptr_table(dB, len(rk)) if dB is not None else None
+        _check(self._lib.collm_lora_linear_bwd(
+            self._h, ctypes.byref(sh), x.data_ptr(), W.data_ptr(), At, Bt, rk.ctypes.data_as(_i32p),
+            ss.ctypes.data_as(_i32p), sa.ctypes.data_as(_i32p), st.ctypes.data_as(_u8p), dy.data_ptr(),
+            None if h_save is None else h_save.data_ptr(), None if dx is None else dx.data_ptr(),
+            dAt, dBt, 1 if accumulate else 0, self._stream(stream)), "collm_lora_linear_bwd")

@@ -1,0 +1,667 @@
+// C ABI of the mixed-batch LoRA linear layer: context, validation, plan upload, launches.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "collm_lora.h"
+#include "kernels.h"
+#include "planner.h"
+
+using namespace collm;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int hip_fail(hipError_t e, const char *what)
+{
+    char buf[256];
+    std::snprintf(buf, sizeof buf, "%s: %s", what, hipGetErrorString(e));
+    g_last_error = buf;
+    return COLLM_E_HIP;
+}
+
+#define HIP_TRY(expr)                                     \
+    do {                                                  \
+        hipError_t e_ = (expr);                           \
+        if (e_ != hipSuccess) return hip_fail(e_, #expr); \
+    } while (0)
+
+constexpr int kSlots = 4;              // pinned staging ring
+constexpr size_t kPartialBytes = 64u << 20;  // each of the two partial-sum buffers
+constexpr int kMaxProfile = 16;
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace
+
+struct collm_ctx {
+    int device = 0;
+    int max_tokens = 0, max_segments = 0, max_adapters = 0, max_rank = 0, max_d = 0;
+    int rows_cap = 0;   // padded row capacity
+    int rpad_cap = 0;   // max_rank rounded up to 16
+
+    size_t plan_cap = 0;  // int32 units
+    int32_t *h_stage[kSlots] = {};
+    hipEvent_t stage_ev[kSlots] = {};
+    bool stage_busy[kSlots] = {};
+    int slot = 0;
+    int32_t *d_plan = nullptr;
+
+    void *d_hs = nullptr;     // scaled low-rank activations, forward row order  [rows][rpad]
+    void *d_dhs = nullptr;    // dh in the element type, training row order      [rows][rpad]
+    float *d_h32 = nullptr;   // recomputed h, training row order                [rows][rpad]
+    float *d_dh32 = nullptr;  // dh in fp32, training row order                  [rows][rpad]
+    float *d_part_skinny = nullptr;
+    float *d_part_grad = nullptr;
+    int *d_counters = nullptr;
+    int n_counters_skinny = 0, n_counters_grad = 0;
+    int64_t workspace_bytes = 0;
+
+    std::vector<int32_t> plan;
+    PlanLayout L;
+    bool plan_valid = false;
+    // what the cached plan was built from
+    collm_shape key_shape{};
+    int key_bm_all = 0, key_bm_train = 0;
+    std::vector<int32_t> key_seg_start, key_seg_adapter, key_rank;
+    std::vector<uint8_t> key_seg_train;
+    std::vector<uint64_t> key_A, key_B;
+
+    int tile_fwd = -1, tile_bwd = -1;  // forced GEMM tile shapes (-1 = choose)
+    hipStream_t last_stream = nullptr;
+
+    bool profile = false;
+    int n_prof = 0;
+    const char *prof_name[kMaxProfile] = {};
+    hipEvent_t prof_ev[kMaxProfile][2] = {};
+    bool prof_ev_made = false;
+};
+
+namespace {
+
+int pick_tile(int rows, int cols)
+{
+    // Take the largest tile that still gives the 256 CUs about one tile each.
+    const int rp = round_up(std::max(rows, 1), kRowPad);
+    const long t256 = (long)(rp / 256) * ((cols + 255) / 256);
+    if (t256 >= 200) return kTile256x256;
+    const long t256x128 = (long)(rp / 256) * ((cols + 127) / 128);
+    if (t256x128 >= 200) return kTile256x128;
+    return kTile128x128;
+}
+
+struct Prof {
+    collm_ctx *c;
+    hipStream_t st;
+    int idx = -1;
+    Prof(collm_ctx *c_, hipStream_t st_, const char *name) : c(c_), st(st_)
+    {
+        if (c->profile && c->n_prof < kMaxProfile) {
+            idx = c->n_prof++;
+            c->prof_name[idx] = name;
+            (void)hipEventRecord(c->prof_ev[idx][0], st);
+        }
+    }
+    ~Prof()
+    {
+        if (idx >= 0) (void)hipEventRecord(c->prof_ev[idx][1], st);
+    }
+};
+
+int check_common(collm_ctx *ctx, const collm_shape *s, const void *x, const void *W,
+                 const void *const *A, const void *const *B, const int32_t *rank,
+                 const int32_t *seg_start, const int32_t *seg_adapter, const uint8_t *seg_is_train)
+{
+    if (!ctx || !s) return COLLM_E_NULL;
+    if (s->dtype != COLLM_F32 && s->dtype != COLLM_BF16) return COLLM_E_DTYPE;
+    const int q = s->dtype == COLLM_BF16 ? 8 : 4;
+    if (s->d_in <= 0 || s->d_out <= 0 || s->d_in % q || s->d_out % q) return COLLM_E_SHAPE;
+    if (s->d_in > ctx->max_d || s->d_out > ctx->max_d) return COLLM_E_SHAPE;
+    if (s->n_tokens < 0 || s->n_tokens > ctx->max_tokens) return COLLM_E_SHAPE;
+    if (s->n_segments < 0 || s->n_segments > ctx->max_segments) return COLLM_E_SHAPE;
+    if (s->n_adapters < 0 || s->n_adapters > ctx->max_adapters) return COLLM_E_SHAPE;
+    if (!seg_start) return COLLM_E_NULL;
+    if (s->n_adapters > 0 && (!rank || !A || !B)) return COLLM_E_NULL;
+    int rc = validate_batch(s, rank, seg_start, seg_adapter, seg_is_train, ctx->max_rank);
+    if (rc != COLLM_OK) return rc;
+    if (s->n_tokens > 0 && (!x || !W)) return COLLM_E_NULL;
+    if (!aligned16(x) || !aligned16(W)) return COLLM_E_ALIGN;
+    for (int k = 0; k < s->n_segments; ++k) {
+        const int a = seg_adapter[k];
+        if (a < 0 || seg_start[k + 1] == seg_start[k]) continue;
+        if (!A[a] || !B[a]) return COLLM_E_ADAPTER;
+        if (!aligned16(A[a]) || !aligned16(B[a])) return COLLM_E_ALIGN;
+    }
+    return COLLM_OK;
+}
+
+bool same_key(collm_ctx *c, const collm_shape *s, const void *const *A, const void *const *B,
+              const int32_t *rank, const int32_t *seg_start, const int32_t *seg_adapter,
+              const uint8_t *seg_is_train, int bm_all, int bm_train)
+{
+    if (!c->plan_valid) return false;
+    const collm_shape &k = c->key_shape;
+    if (k.d_in != s->d_in || k.d_out != s->d_out || k.n_tokens != s->n_tokens ||
+        k.n_segments != s->n_segments || k.n_adapters != s->n_adapters || k.dtype != s->dtype)
+        return false;
+    if (bm_all != c->key_bm_all || bm_train != c->key_bm_train) return false;
+    const int S = s->n_segments, N = s->n_adapters;
+    if (std::memcmp(c->key_seg_start.data(), seg_start, sizeof(int32_t) * (S + 1))) return false;
+    if (S && std::memcmp(c->key_seg_adapter.data(), seg_adapter, sizeof(int32_t) * S)) return false;
+    if (S && std::memcmp(c->key_seg_train.data(), seg_is_train, S)) return false;
+    if (N && std::memcmp(c->key_rank.data(), rank, sizeof(int32_t) * N)) return false;
+    for (int a = 0; a < N; ++a)
+        if (c->key_A[a] != (uint64_t)(uintptr_t)A[a] || c->key_B[a] != (uint64_t)(uintptr_t)B[a]) return false;
+    return true;
+}
+
+// Copy ints [lo, hi) of the host plan to the device plan through a pinned staging slot.
+int upload(collm_ctx *c, size_t lo, size_t hi, hipStream_t st)
+{
+    if (hi <= lo) return COLLM_OK;
+    const int sl = c->slot;
+    c->slot = (c->slot + 1) % kSlots;
+    if (c->stage_busy[sl]) HIP_TRY(hipEventSynchronize(c->stage_ev[sl]));
+    std::memcpy(c->h_stage[sl] + lo, c->plan.data() + lo, (hi - lo) * sizeof(int32_t));
+    HIP_TRY(hipMemcpyAsync(c->d_plan + lo, c->h_stage[sl] + lo, (hi - lo) * sizeof(int32_t),
+                           hipMemcpyHostToDevice, st));
+    HIP_TRY(hipEventRecord(c->stage_ev[sl], st));
+    c->stage_busy[sl] = true;
+    return COLLM_OK;
+}
+
+// Build (or reuse) the plan of this batch and put it on the device.
+int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const void *const *B,
+                 const int32_t *rank, const int32_t *seg_start, const int32_t *seg_adapter,
+                 const uint8_t *seg_is_train, float *const *dA, float *const *dB, bool allow_reuse,
+                 hipStream_t st)
+{
+    const bool f32 = s->dtype == COLLM_F32;
+    int n_train = 0;
+    for (int k = 0; k < s->n_segments; ++k)
+        if (seg_is_train[k]) n_train += seg_start[k + 1] - seg_start[k];
+    const int tile_fwd = c->tile_fwd >= 0 ? c->tile_fwd : pick_tile(s->n_tokens, s->d_out);
+    const int tile_bwd = c->tile_bwd >= 0 ? c->tile_bwd : pick_tile(n_train, s->d_in);
+    const int bm_all = f32 ? 64 : gemm_tile_rows(tile_fwd);
+    const int bm_train = f32 ? 64 : gemm_tile_rows(tile_bwd);
+
+    const bool reuse = allow_reuse && same_key(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train,
+                                               bm_all, bm_train);
+    if (!reuse) {
+        PlanRequest rq;
+        rq.shape = s;
+        rq.rank = rank;
+        rq.seg_start = seg_start;
+        rq.seg_adapter = seg_adapter;
+        rq.seg_is_train = seg_is_train;
+        rq.A = A;
+        rq.B = B;
+        rq.dA = dA;
+        rq.dB = dB;
+        rq.bm_all = bm_all;
+        rq.bm_train = bm_train;
+        rq.grad_n_tiles = std::max(1, (std::min(s->d_in, s->d_out) + 127) / 128);
+        // partial sums of the gradient launches must fit their buffer
+        rq.grad_max_ksplit = 64;
+        c->plan_valid = false;
+        int rc = build_plan(rq, c->plan, c->L);
+        if (rc != COLLM_OK) return rc;
+        const size_t need = (size_t)c->L.grad_part_rows * std::max(s->d_in, s->d_out) * sizeof(float);
+        if (need > kPartialBytes) {  // fall back to fewer, longer slices
+            rq.grad_max_ksplit = 1;
+            rc = build_plan(rq, c->plan, c->L);
+            if (rc != COLLM_OK) return rc;
+        }
+        if ((size_t)c->L.total_ints > c->plan_cap) return COLLM_E_SHAPE;
+        rc = upload(c, 0, c->L.total_ints, st);
+        if (rc != COLLM_OK) return rc;
+        // remember what this plan was built from
+        const int S = s->n_segments, N = s->n_adapters;
+        c->key_shape = *s;
+        c->key_bm_all = bm_all;
+        c->key_bm_train = bm_train;
+        c->key_seg_start.assign(seg_start, seg_start + S + 1);
+        c->key_seg_adapter.assign(seg_adapter, seg_adapter + S);
+        c->key_seg_train.assign(seg_is_train, seg_is_train + S);
+        c->key_rank.assign(rank, rank + N);
+        c->key_A.resize(N);
+        c->key_B.resize(N);
+        for (int a = 0; a < N; ++a) {
+            c->key_A[a] = (uint64_t)(uintptr_t)A[a];
+            c->key_B[a] = (uint64_t)(uintptr_t)B[a];
+        }
+        c->plan_valid = true;
+    } else if (dA || dB) {
+        // same batch as the forward call: only the gradient pointer tables are new
+        const int N = s->n_adapters;
+        for (int a = 0; a < N; ++a) {
+            const uint64_t va = dA ? (uint64_t)(uintptr_t)dA[a] : 0, vb = dB ? (uint64_t)(uintptr_t)dB[a] : 0;
+            std::memcpy(c->plan.data() + c->L.off_dA_ptr + 2 * a, &va, 8);
+            std::memcpy(c->plan.data() + c->L.off_dB_ptr + 2 * a, &vb, 8);
+        }
+        int rc = upload(c, c->L.off_dA_ptr, (size_t)c->L.off_dB_ptr + 2 * (size_t)std::max(N, 1), st);
+        if (rc != COLLM_OK) return rc;
+    }
+    c->last_stream = st;
+    return COLLM_OK;
+}
+
+int skinny_ksplit(int n_items, int K, int rows_pad, int rpad, int &k_slice)
+{
+    int want = n_items > 0 ? (768 + n_items - 1) / n_items : 1;
+    const size_t per_split = (size_t)rows_pad * rpad * sizeof(float);
+    want = std::min<int>(want, (int)std::max<size_t>(1, kPartialBytes / per_split));
+    want = std::max(1, std::min(want, 32));
+    k_slice = round_up((K + want - 1) / want, 64);
+    // never less than 256 of K per block: below that the table load dominates
+    k_slice = std::max(k_slice, std::min(round_up(K, 64), 256));
+    return (K + k_slice - 1) / k_slice;
+}
+
+// One skinny pass over a row order.
+int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, const void *in, int K,
+               int32_t off_tab, bool t_kmajor, float *f32_out, int64_t f32_ld, int f32_cols,
+               int f32_by_token, float f32_mult, void *bf_out, float bf_mult, const char *name,
+               hipStream_t st)
+{
+    if (R.n_items == 0) return COLLM_OK;
+    SkinnyArgs a{};
+    a.in = in;
+    a.ld_in = K;
+    a.K = K;
+    a.tab = reinterpret_cast<const uint64_t *>(c->d_plan + off_tab);
+    a.items = reinterpret_cast<const SkinnyItem *>(c->d_plan + R.off_items);
+    a.row_tok = c->d_plan + R.off_row_tok;
+    a.tok_train = c->d_plan + c->L.off_tok_train;
+    a.partial = c->d_part_skinny;
+    a.rows_pad = R.n_rows_pad;
+    a.rpad_ld = c->L.rpad;
+    a.counters = c->d_counters;
+    a.f32_out = f32_out;
+    a.f32_ld = f32_ld;
+    a.f32_cols = f32_cols;
+    a.f32_by_token = f32_by_token;
+    a.f32_mult = f32_mult;
+    a.bf_out = bf_out;
+    a.bf_ld = c->L.rpad;
+    a.bf_mult = bf_mult;
+    Prof prof(c, st, name);
+    if (s->dtype == COLLM_F32) {
+        a.k_slice = K;
+        HIP_TRY(launch_skinny_f32(a, R.n_items, t_kmajor, st));
+    } else {
+        int k_slice = K;
+        const int ksplit = skinny_ksplit(R.n_items, K, R.n_rows_pad, c->L.rpad, k_slice);
+        a.k_slice = k_slice;
+        HIP_TRY(launch_skinny(a, R.n_items, ksplit, c->L.rpad, t_kmajor, st));
+    }
+    return COLLM_OK;
+}
+
+}  // namespace
+
+// -----------------------------------------------------------------------------------------
+extern "C" {
+
+const char *collm_status_string(int status)
+{
+    switch (status) {
+    case COLLM_OK: return "ok";
+    case COLLM_E_NULL: return "a required pointer is NULL";
+    case COLLM_E_SHAPE: return "unsupported size, or beyond what the context was created for";
+    case COLLM_E_SEGMENTS: return "bad segment table";
+    case COLLM_E_ADAPTER: return "bad adapter index or missing adapter table";
+    case COLLM_E_RANK: return "rank out of range";
+    case COLLM_E_DTYPE: return "unknown element type";
+    case COLLM_E_ALIGN: return "device pointer not 16-byte aligned";
+    case COLLM_E_HIP: return "HIP call failed";
+    case COLLM_E_NOMEM: return "allocation failed";
+    default: return "unknown status";
+    }
+}
+
+const char *collm_last_error(void) { return g_last_error.c_str(); }
+
+int collm_token_map(const collm_shape *shape, const int32_t *seg_start, const int32_t *seg_adapter,
+                    const uint8_t *seg_is_train, int32_t *tok_segment, int32_t *tok_adapter,
+                    uint8_t *tok_is_train)
+{
+    if (!shape || !seg_start) return COLLM_E_NULL;
+    int rc = validate_batch(shape, nullptr, seg_start, seg_adapter, seg_is_train, kMaxRank);
+    if (rc != COLLM_OK) return rc;
+    if (shape->n_tokens > 0 && (!tok_segment || !tok_adapter || !tok_is_train)) return COLLM_E_NULL;
+    token_map(shape, seg_start, seg_adapter, seg_is_train, tok_segment, tok_adapter, tok_is_train);
+    return COLLM_OK;
+}
+
+int collm_ctx_create(collm_ctx **out, int device, int32_t max_tokens, int32_t max_segments,
+                     int32_t max_adapters, int32_t max_rank, int32_t max_d)
+{
+    if (!out) return COLLM_E_NULL;
+    *out = nullptr;
+    if (max_tokens < 1 || max_segments < 1 || max_adapters < 0 || max_d < 1) return COLLM_E_SHAPE;
+    if (max_rank < 1 || max_rank > kMaxRank) return COLLM_E_RANK;
+    HIP_TRY(hipSetDevice(device));
+    collm_ctx *c = new (std::nothrow) collm_ctx();
+    if (!c) return COLLM_E_NOMEM;
+    c->device = device;
+    c->max_tokens = max_tokens;
+    c->max_segments = max_segments;
+    c->max_adapters = max_adapters;
+    c->max_rank = max_rank;
+    c->max_d = max_d;
+    c->rows_cap = round_up(max_tokens, kRowPad);
+    c->rpad_cap = round_up(max_rank, kKStep);
+    c->plan_cap = plan_ints_upper_bound(max_tokens, max_segments, max_adapters, max_rank);
+
+    auto fail = [&](int rc) {
+        collm_ctx_destroy(c);
+        return rc;
+    };
+    int64_t ws = 0;
+    auto dev_alloc = [&](void **p, size_t bytes) -> hipError_t {
+        ws += (int64_t)bytes;
+        return hipMalloc(p, bytes);
+    };
+    for (int i = 0; i < kSlots; ++i) {
+        if (hipHostMalloc((void **)&c->h_stage[i], c->plan_cap * sizeof(int32_t), hipHostMallocDefault) != hipSuccess)
+            return fail(COLLM_E_NOMEM);
+        if (hipEventCreateWithFlags(&c->stage_ev[i], hipEventDisableTiming) != hipSuccess) return fail(COLLM_E_HIP);
+    }
+    const size_t act = (size_t)c->rows_cap * c->rpad_cap;
+    c->n_counters_skinny = c->rows_cap / kSkinnyRows + max_adapters + 8;
+    c->n_counters_grad = (max_adapters + 1) * ((max_d + 127) / 128 + 1);
+    const size_t n_counters = (size_t)c->n_counters_skinny + 2 * (size_t)c->n_counters_grad;
+    if (dev_alloc((void **)&c->d_plan, c->plan_cap * sizeof(int32_t)) != hipSuccess ||
+        dev_alloc(&c->d_hs, act * 4) != hipSuccess || dev_alloc(&c->d_dhs, act * 4) != hipSuccess ||
+        dev_alloc((void **)&c->d_h32, act * 4) != hipSuccess ||
+        dev_alloc((void **)&c->d_dh32, act * 4) != hipSuccess ||
+        dev_alloc((void **)&c->d_part_skinny, kPartialBytes) != hipSuccess ||
+        dev_alloc((void **)&c->d_part_grad, kPartialBytes) != hipSuccess ||
+        dev_alloc((void **)&c->d_counters, n_counters * sizeof(int)) != hipSuccess)
+        return fail(COLLM_E_NOMEM);
+    if (hipMemset(c->d_counters, 0, n_counters * sizeof(int)) != hipSuccess) return fail(COLLM_E_HIP);
+    if (hipDeviceSynchronize() != hipSuccess) return fail(COLLM_E_HIP);
+    c->workspace_bytes = ws;
+    *out = c;
+    return COLLM_OK;
+}
+
+int collm_ctx_destroy(collm_ctx *c)
+{
+    if (!c) return COLLM_OK;
+    (void)hipSetDevice(c->device);
+    (void)hipDeviceSynchronize();
+    for (int i = 0; i < kSlots; ++i) {
+        if (c->h_stage[i]) (void)hipHostFree(c->h_stage[i]);
+        if (c->stage_ev[i]) (void)hipEventDestroy(c->stage_ev[i]);
+    }
+    if (c->prof_ev_made)
+        for (int i = 0; i < kMaxProfile; ++i) {
+            (void)hipEventDestroy(c->prof_ev[i][0]);
+            (void)hipEventDestroy(c->prof_ev[i][1]);
+        }
+    void *bufs[] = {c->d_plan, c->d_hs, c->d_dhs, c->d_h32, c->d_dh32, c->d_part_skinny, c->d_part_grad, c->d_counters};
+    for (void *b : bufs)
+        if (b) (void)hipFree(b);
+    delete c;
+    return COLLM_OK;
+}
+
+int64_t collm_ctx_workspace_bytes(const collm_ctx *c) { return c ? c->workspace_bytes : 0; }
+
+int collm_debug_set_tiles(collm_ctx *c, int fwd_tile, int bwd_tile)
+{
+    if (!c) return COLLM_E_NULL;
+    if (fwd_tile < -1 || fwd_tile > kTile128x128 || bwd_tile < -1 || bwd_tile > kTile128x128) return COLLM_E_SHAPE;
+    c->tile_fwd = fwd_tile;
+    c->tile_bwd = bwd_tile;
+    return COLLM_OK;
+}
+
+int collm_profile_enable(collm_ctx *c, int enable)
+{
+    if (!c) return COLLM_E_NULL;
+    if (enable && !c->prof_ev_made) {
+        for (int i = 0; i < kMaxProfile; ++i) {
+            HIP_TRY(hipEventCreate(&c->prof_ev[i][0]));
+            HIP_TRY(hipEventCreate(&c->prof_ev[i][1]));
+        }
+        c->prof_ev_made = true;
+    }
+    c->profile = enable != 0;
+    c->n_prof = 0;
+    return COLLM_OK;
+}
+
+int collm_profile_read(collm_ctx *c, const char **names, float *ms, int cap)
+{
+    if (!c || !names || !ms) return COLLM_E_NULL;
+    const int n = std::min(c->n_prof, cap);
+    for (int i = 0; i < n; ++i) {
+        HIP_TRY(hipEventSynchronize(c->prof_ev[i][1]));
+        names[i] = c->prof_name[i];
+        HIP_TRY(hipEventElapsedTime(&ms[i], c->prof_ev[i][0], c->prof_ev[i][1]));
+    }
+    return n;
+}
+
+int collm_lora_linear_fwd(collm_ctx *c, const collm_shape *s, const void *x, const void *W,
+                          const void *const *A, const void *const *B, const int32_t *rank,
+                          const int32_t *seg_start, const int32_t *seg_adapter,
+                          const uint8_t *seg_is_train, void *y, float *h_save, void *stream)
+{
+    int rc = check_common(c, s, x, W, A, B, rank, seg_start, seg_adapter, seg_is_train);
+    if (rc != COLLM_OK) return rc;
+    if (s->n_tokens > 0 && !y) return COLLM_E_NULL;
+    if (!aligned16(y) || !aligned16(h_save)) return COLLM_E_ALIGN;
+    if (s->n_tokens == 0) return COLLM_OK;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipSetDevice(c->device));
+    c->n_prof = 0;
+    rc = prepare_plan(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, nullptr, nullptr, false, st);
+    if (rc != COLLM_OK) return rc;
+    const PlanLayout &L = c->L;
+    const bool f32 = s->dtype == COLLM_F32;
+
+    // shrink: h = x A_a (fp32), kept as s*h in the element type for the GEMM's extra K-steps
+    rc = run_skinny(c, s, L.all, x, s->d_in, L.off_A_ptr, false, h_save, c->max_rank, c->max_rank, 1, 1.0f,
+                    c->d_hs, s->scale, "shrink", st);
+    if (rc != COLLM_OK) return rc;
+
+    GemmArgs g{};
+    g.a = x;
+    g.lda = s->d_in;
+    g.b = W;
+    g.ldb = s->d_out;
+    g.out = y;
+    g.ldo = s->d_out;
+    g.N = s->d_out;
+    g.K = s->d_in;
+    g.tiles_m = L.all.n_tiles_m;
+    g.row_tok = c->d_plan + L.all.off_row_tok;
+    g.ext_off = c->d_plan + L.all.off_ext_off;
+    g.ext = reinterpret_cast<const ExtStep *>(c->d_plan + L.all.off_ext);
+    g.hs = c->d_hs;
+    g.hs_ld = L.rpad;
+    g.ext_tab = reinterpret_cast<const uint64_t *>(c->d_plan + L.off_B_ptr);
+    g.ext_ld = s->d_out;
+    g.rank = c->d_plan + L.off_rank;
+    {
+        Prof prof(c, st, "gemm_fwd");
+        if (f32) {
+            HIP_TRY(launch_gemm_f32(g, false, st));
+        } else {
+            const int tile = c->tile_fwd >= 0 ? c->tile_fwd : pick_tile(s->n_tokens, s->d_out);
+            g.tiles_n = (s->d_out + gemm_tile_cols(tile) - 1) / gemm_tile_cols(tile);
+            HIP_TRY(launch_gemm(g, tile, false, st));
+        }
+    }
+    return COLLM_OK;
+}
+
+int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, const void *W,
+                          const void *const *A, const void *const *B, const int32_t *rank,
+                          const int32_t *seg_start, const int32_t *seg_adapter,
+                          const uint8_t *seg_is_train, const void *dy, const float *h_save, void *dx,
+                          float *const *dA, float *const *dB, int accumulate, void *stream)
+{
+    int rc = check_common(c, s, x, W, A, B, rank, seg_start, seg_adapter, seg_is_train);
+    if (rc != COLLM_OK) return rc;
+    if ((dA == nullptr) != (dB == nullptr)) return COLLM_E_NULL;
+    int n_train = 0;
+    for (int k = 0; k < s->n_segments; ++k) {
+        if (!seg_is_train[k] || seg_start[k + 1] == seg_start[k]) continue;
+        n_train += seg_start[k + 1] - seg_start[k];
+        const int a = seg_adapter[k];
+        if (dA) {
+            if (!dA[a] || !dB[a]) return COLLM_E_ADAPTER;
+            if (!aligned16(dA[a]) || !aligned16(dB[a])) return COLLM_E_ALIGN;
+        }
+    }
+    if (n_train > 0 && !dy) return COLLM_E_NULL;
+    if (!aligned16(dy) || !aligned16(dx) || !aligned16(h_save)) return COLLM_E_ALIGN;
+    if (n_train == 0) return COLLM_OK;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(hipSetDevice(c->device));
+    c->n_prof = 0;
+    rc = prepare_plan(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, dA, dB, true, st);
+    if (rc != COLLM_OK) return rc;
+    const PlanLayout &L = c->L;
+    const bool f32 = s->dtype == COLLM_F32;
+
+    // h of the training rows, if the forward call did not keep it
+    if (!h_save && dA) {
+        rc = run_skinny(c, s, L.train, x, s->d_in, L.off_A_ptr, false, c->d_h32, L.rpad, L.rpad, 0, 1.0f,
+                        nullptr, 0.f, "shrink_recompute", st);
+        if (rc != COLLM_OK) return rc;
+    }
+    // dh = s dy B_a^T: fp32 for dA, element type for the dX GEMM's extra K-steps
+    rc = run_skinny(c, s, L.train, dy, s->d_out, L.off_B_ptr, true, c->d_dh32, L.rpad, L.rpad, 0, s->scale,
+                    c->d_dhs, s->scale, "dh", st);
+    if (rc != COLLM_OK) return rc;
+
+    if (dA) {
+        GradArgs ga{};
+        ga.row_tok = c->d_plan + L.train.off_row_tok;
+        ga.items = reinterpret_cast<const GradItem *>(c->d_plan + L.off_grad);
+        ga.slices = c->d_plan + L.off_slices;
+        ga.partial = c->d_part_grad;
+        ga.accumulate = accumulate ? 1 : 0;
+        // dB_a = s h^T dy
+        ga.big = dy;
+        ga.ld_big = s->d_out;
+        ga.N = s->d_out;
+        if (h_save) {
+            ga.small_ = h_save;
+            ga.ld_small = c->max_rank;
+            ga.small_by_token = 1;
+        } else {
+            ga.small_ = c->d_h32;
+            ga.ld_small = L.rpad;
+            ga.small_by_token = 0;
+        }
+        ga.small_mult = s->scale;
+        ga.counters = c->d_counters + c->n_counters_skinny;
+        ga.out_tab = reinterpret_cast<const uint64_t *>(c->d_plan + L.off_dB_ptr);
+        ga.out_transposed = 0;
+        {
+            Prof prof(c, st, "grad_dB");
+            if (f32) HIP_TRY(launch_grad_f32(ga, L.n_grad, st));
+            else HIP_TRY(launch_grad(ga, (s->d_out + 127) / 128, L.n_slices, L.rpad, st));
+        }
+        // dA_a = x^T dh
+        ga.big = x;
+        ga.ld_big = s->d_in;
+        ga.N = s->d_in;
+        ga.small_ = c->d_dh32;
+        ga.ld_small = L.rpad;
+        ga.small_by_token = 0;
+        ga.small_mult = 1.0f;
+        ga.counters = c->d_counters + c->n_counters_skinny + c->n_counters_grad;
+        ga.out_tab = reinterpret_cast<const uint64_t *>(c->d_plan + L.off_dA_ptr);
+        ga.out_transposed = 1;
+        {
+            Prof prof(c, st, "grad_dA");
+            if (f32) HIP_TRY(launch_grad_f32(ga, L.n_grad, st));
+            else HIP_TRY(launch_grad(ga, (s->d_in + 127) / 128, L.n_slices, L.rpad, st));
+        }
+    }
+
+    if (dx) {
+        GemmArgs g{};
+        g.a = dy;
+        g.lda = s->d_out;
+        g.b = W;
+        g.ldb = s->d_out;
+        g.out = dx;
+        g.ldo = s->d_in;
+        g.N = s->d_in;
+        g.K = s->d_out;
+        g.tiles_m = L.train.n_tiles_m;
+        g.row_tok = c->d_plan + L.train.off_row_tok;
+        g.ext_off = c->d_plan + L.train.off_ext_off;
+        g.ext = reinterpret_cast<const ExtStep *>(c->d_plan + L.train.off_ext);
+        g.hs = c->d_dhs;
+        g.hs_ld = L.rpad;
+        g.ext_tab = reinterpret_cast<const uint64_t *>(c->d_plan + L.off_A_ptr);
+        g.ext_ld = 0;
+        g.rank = c->d_plan + L.off_rank;
+        Prof prof(c, st, "gemm_dx");
+        if (f32) {
+            HIP_TRY(launch_gemm_f32(g, true, st));
+        } else {
+            const int tile = c->tile_bwd >= 0 ? c->tile_bwd : pick_tile(n_train, s->d_in);
+            g.tiles_n = (s->d_in + gemm_tile_cols(tile) - 1) / gemm_tile_cols(tile);
+            HIP_TRY(launch_gemm(g, tile, true, st));
+        }
+    }
+    return COLLM_OK;
+}
+
+int collm_debug_device_token_map(collm_ctx *c, int32_t *tok_segment, int32_t *tok_adapter,
+                                 uint8_t *tok_is_train)
+{
+    if (!c) return COLLM_E_NULL;
+    if (!c->plan_valid) return COLLM_E_SHAPE;
+    const PlanLayout &L = c->L;
+    if (L.n_tokens > 0 && (!tok_segment || !tok_adapter || !tok_is_train)) return COLLM_E_NULL;
+    HIP_TRY(hipSetDevice(c->device));
+    HIP_TRY(hipStreamSynchronize(c->last_stream));
+    std::vector<int32_t> dev((size_t)L.total_ints);
+    HIP_TRY(hipMemcpy(dev.data(), c->d_plan, dev.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+    // Undo the adapter grouping: row r of the forward row order is token row_tok[r] and was
+    // given adapter row_adapter[r]; segment and training flag come from the per-token arrays
+    // the kernels read.
+    for (int t = 0; t < L.n_tokens; ++t) tok_adapter[t] = -2;
+    for (int r = 0; r < L.all.n_rows_pad; ++r) {
+        const int tok = dev[L.all.off_row_tok + r];
+        if (tok < 0) continue;
+        if (tok >= L.n_tokens) return COLLM_E_SHAPE;
+        tok_adapter[tok] = dev[L.all.off_row_adapter + r];
+    }
+    for (int t = 0; t < L.n_tokens; ++t) {
+        tok_segment[t] = dev[L.off_tok_segment + t];
+        tok_is_train[t] = (uint8_t)dev[L.off_tok_train + t];
+        // the per-token adapter array must agree with the row order
+        if (dev[L.off_tok_adapter + t] != tok_adapter[t]) tok_adapter[t] = -3;
+    }
+    // training rows must be exactly the training tokens
+    std::vector<uint8_t> seen((size_t)std::max(L.n_tokens, 1), 0);
+    for (int r = 0; r < L.train.n_rows_pad; ++r) {
+        const int tok = dev[L.train.off_row_tok + r];
+        if (tok >= 0 && tok < L.n_tokens) seen[tok] = 1;
+    }
+    for (int t = 0; t < L.n_tokens; ++t)
+        if (seen[t] != tok_is_train[t]) tok_is_train[t] = 0xEE;
+    return COLLM_OK;
+}
+
+}  // extern "C"

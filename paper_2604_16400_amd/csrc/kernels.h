@@ -1,0 +1,85 @@
+// Kernel argument blocks and launchers (device side of the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "plan.h"
+
+namespace collm {
+
+enum { kTile256x256 = 0, kTile256x128 = 1, kTile128x128 = 2 };
+
+// out[tok(m)][n] = sum_k a[tok(m)][k] * b(k, n)  +  sum over the row tile's extension steps
+struct GemmArgs {
+    const void *a;      // rows gathered through row_tok, K contiguous
+    int64_t lda;
+    const void *b;      // [K][N] (row length ldb) or, K-major, [N][K]
+    int64_t ldb;
+    void *out;          // rows scattered through row_tok
+    int64_t ldo;
+    int N, K;
+    int tiles_m, tiles_n;
+    const int32_t *row_tok;   // [tiles_m * BM]
+    const int32_t *ext_off;   // [tiles_m + 1]
+    const ExtStep *ext;
+    const void *hs;           // low-rank activations of the rows, [rows][hs_ld], row order
+    int hs_ld;
+    const uint64_t *ext_tab;  // adapter -> device pointer of the extension's table
+    int64_t ext_ld;           // row length of a [rank][N] table (forward)
+    const int32_t *rank;
+};
+
+// out[m][q] = sum_k in[tok(m)][k] * tab_a(k, q), one SkinnyItem per blockIdx.x
+struct SkinnyArgs {
+    const void *in;
+    int64_t ld_in;
+    int K;
+    int k_slice;              // K range of one blockIdx.y (multiple of 64)
+    const uint64_t *tab;      // adapter -> table; [K][rank] or, K-major, [rank][K]
+    const SkinnyItem *items;
+    const int32_t *row_tok;
+    const int32_t *tok_train;
+    float *partial;           // [ksplit][rows_pad][rpad_ld]
+    int rows_pad, rpad_ld;
+    int *counters;            // one per item, zero between launches
+    float *f32_out;           // optional fp32 result
+    int64_t f32_ld;
+    int f32_cols;             // columns written per row (zero beyond the rank)
+    int f32_by_token;         // 1: row = token index, training tokens only; 0: row order
+    float f32_mult;
+    void *bf_out;             // optional scaled copy in the element type, row order
+    int bf_ld;
+    float bf_mult;
+};
+
+// out_a(q, n) = sum_t small[t][q] * big[tok(t)][n] over one adapter's training rows
+struct GradArgs {
+    const void *big;          // [T][N] gathered through row_tok
+    int64_t ld_big;
+    int N;
+    const float *small_;      // fp32 [.][ld_small]; row = token (small_by_token) or row order
+    int64_t ld_small;
+    int small_by_token;
+    float small_mult;
+    const int32_t *row_tok;   // training row order
+    const GradItem *items;
+    const int32_t *slices;    // {item, slice} pairs, one per blockIdx.y
+    float *partial;           // [grad_part_rows][N]
+    int *counters;            // [n_grad][gridDim.x], zero between launches
+    const uint64_t *out_tab;  // adapter -> fp32 output
+    int out_transposed;       // 0: out[q][n] (row length N); 1: out[n][q] (row length rank)
+    int accumulate;
+};
+
+hipError_t launch_gemm(const GemmArgs &a, int tile_cfg, bool b_kmajor, hipStream_t st);
+int gemm_tile_rows(int tile_cfg);
+int gemm_tile_cols(int tile_cfg);
+hipError_t launch_skinny(const SkinnyArgs &a, int n_items, int ksplit, int rpad, bool t_kmajor, hipStream_t st);
+hipError_t launch_grad(const GradArgs &a, int n_tiles, int n_slices, int rpad, hipStream_t st);
+
+// fp32 element type: same argument blocks, plain fp32 FMA kernels
+hipError_t launch_gemm_f32(const GemmArgs &a, bool b_kmajor, hipStream_t st);
+hipError_t launch_skinny_f32(const SkinnyArgs &a, int n_items, bool t_kmajor, hipStream_t st);
+hipError_t launch_grad_f32(const GradArgs &a, int n_grad, hipStream_t st);
+
+}  // namespace collm

@@ -1,0 +1,261 @@
+// Host-side planner: segment table -> device plan (see plan.h).  Integer work only.
+#include "planner.h"
+
+#include <algorithm>
+#include <cstring>
+
+namespace collm {
+
+int validate_batch(const collm_shape *s, const int32_t *rank, const int32_t *seg_start,
+                   const int32_t *seg_adapter, const uint8_t *seg_is_train, int max_rank)
+{
+    if (!s || !seg_start) return COLLM_E_NULL;
+    if (s->n_tokens < 0 || s->n_segments < 0 || s->n_adapters < 0) return COLLM_E_SHAPE;
+    if (s->n_segments > 0 && (!seg_adapter || !seg_is_train)) return COLLM_E_NULL;
+    if (s->n_adapters > 0 && rank) {
+        for (int a = 0; a < s->n_adapters; ++a)
+            if (rank[a] < 1 || rank[a] > max_rank) return COLLM_E_RANK;
+    }
+    if (seg_start[0] != 0) return COLLM_E_SEGMENTS;
+    for (int k = 0; k < s->n_segments; ++k)
+        if (seg_start[k + 1] < seg_start[k]) return COLLM_E_SEGMENTS;
+    if (seg_start[s->n_segments] != s->n_tokens) return COLLM_E_SEGMENTS;
+    for (int k = 0; k < s->n_segments; ++k) {
+        const int a = seg_adapter[k];
+        if (a < -1 || a >= s->n_adapters) return COLLM_E_ADAPTER;
+        if (seg_is_train[k] > 1) return COLLM_E_SEGMENTS;
+        if (seg_is_train[k] && a < 0) return COLLM_E_ADAPTER;
+    }
+    return COLLM_OK;
+}
+
+void token_map(const collm_shape *s, const int32_t *seg_start, const int32_t *seg_adapter,
+               const uint8_t *seg_is_train, int32_t *tok_segment, int32_t *tok_adapter,
+               uint8_t *tok_is_train)
+{
+    for (int k = 0; k < s->n_segments; ++k) {
+        const int lo = seg_start[k], hi = seg_start[k + 1];
+        std::fill(tok_segment + lo, tok_segment + hi, k);
+        std::fill(tok_adapter + lo, tok_adapter + hi, seg_adapter[k]);
+        std::fill(tok_is_train + lo, tok_is_train + hi, seg_is_train[k]);
+    }
+}
+
+static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+namespace {
+
+struct Builder {
+    std::vector<int32_t> &blk;
+    explicit Builder(std::vector<int32_t> &b) : blk(b) {}
+    int32_t alloc(size_t n_ints, int align_ints = 4)
+    {
+        size_t off = (blk.size() + align_ints - 1) / align_ints * align_ints;
+        blk.resize(off + n_ints, 0);
+        return (int32_t)off;
+    }
+};
+
+// Rows (token indices, already filtered) sorted by adapter, stable; items; extension tables.
+void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &tokens,
+                     const int32_t *tok_adapter, const int32_t *rank, int n_adapters, int bm)
+{
+    const int n = (int)tokens.size();
+    L.n_rows = n;
+    L.n_rows_pad = round_up(std::max(n, 1), kRowPad);
+    L.off_row_tok = b.alloc(L.n_rows_pad);
+    L.off_row_adapter = b.alloc(L.n_rows_pad);
+
+    // counting sort by key = adapter + 1 (base-only rows first), stable in token order
+    std::vector<int32_t> start(n_adapters + 2, 0);
+    for (int i = 0; i < n; ++i) start[tok_adapter[tokens[i]] + 2]++;
+    for (int k = 1; k < n_adapters + 2; ++k) start[k] += start[k - 1];
+    {
+        int32_t *row_tok = b.blk.data() + L.off_row_tok;
+        int32_t *row_ad = b.blk.data() + L.off_row_adapter;
+        std::vector<int32_t> cur(start.begin(), start.end() - 1);
+        for (int i = 0; i < n; ++i) {
+            const int a = tok_adapter[tokens[i]];
+            const int pos = cur[a + 1]++;
+            row_tok[pos] = tokens[i];
+            row_ad[pos] = a;
+        }
+        for (int i = n; i < L.n_rows_pad; ++i) {
+            row_tok[i] = -1;
+            row_ad[i] = -1;
+        }
+    }
+
+    // skinny items: runs of one adapter, cut into pieces of at most kSkinnyRows rows
+    std::vector<SkinnyItem> items;
+    for (int a = 0; a < n_adapters; ++a) {
+        const int lo = start[a + 1], hi = start[a + 2];
+        for (int r = lo; r < hi; r += kSkinnyRows)
+            items.push_back({a, r, std::min(kSkinnyRows, hi - r), rank[a]});
+    }
+    L.n_items = (int)items.size();
+    L.off_items = b.alloc(items.size() * 4 + 4);
+    if (!items.empty())
+        std::memcpy(b.blk.data() + L.off_items, items.data(), items.size() * sizeof(SkinnyItem));
+
+    // low-rank extension steps of every GEMM row tile
+    L.bm = bm;
+    L.n_tiles_m = L.n_rows_pad / bm;
+    std::vector<int32_t> ext_off(L.n_tiles_m + 1, 0);
+    std::vector<ExtStep> ext;
+    L.max_ext_per_tile = 0;
+    for (int t = 0; t < L.n_tiles_m; ++t) {
+        ext_off[t] = (int)ext.size();
+        const int r0 = t * bm, r1 = std::min(n, r0 + bm);
+        int r = r0;
+        while (r < r1) {
+            const int a = b.blk[L.off_row_adapter + r];
+            int e = r + 1;
+            while (e < r1 && b.blk[L.off_row_adapter + e] == a) ++e;
+            if (a >= 0) {
+                for (int k = 0; k < rank[a]; k += kKStep) ext.push_back({a, k, r - r0, e - r0});
+            }
+            r = e;
+        }
+        L.max_ext_per_tile = std::max(L.max_ext_per_tile, (int)ext.size() - ext_off[t]);
+    }
+    ext_off[L.n_tiles_m] = (int)ext.size();
+    L.off_ext_off = b.alloc(ext_off.size());
+    std::memcpy(b.blk.data() + L.off_ext_off, ext_off.data(), ext_off.size() * 4);
+    L.n_ext = (int)ext.size();
+    L.off_ext = b.alloc(ext.size() * 4 + 4);
+    if (!ext.empty()) std::memcpy(b.blk.data() + L.off_ext, ext.data(), ext.size() * sizeof(ExtStep));
+}
+
+}  // namespace
+
+int build_plan(const PlanRequest &rq, std::vector<int32_t> &blk, PlanLayout &L)
+{
+    const collm_shape *s = rq.shape;
+    const int T = s->n_tokens, N = s->n_adapters;
+    blk.clear();
+    blk.reserve((size_t)T * 8 + 4096);
+    Builder b(blk);
+    L = PlanLayout();
+    L.n_tokens = T;
+    L.n_segments = s->n_segments;
+    L.n_adapters = N;
+    int rmax = 1;
+    for (int a = 0; a < N; ++a) rmax = std::max(rmax, rq.rank[a]);
+    L.rpad = round_up(rmax, kKStep);
+
+    L.off_tok_segment = b.alloc(std::max(T, 1));
+    L.off_tok_adapter = b.alloc(std::max(T, 1));
+    L.off_tok_train = b.alloc(std::max(T, 1));
+    {
+        std::vector<uint8_t> tr((size_t)std::max(T, 1));
+        token_map(s, rq.seg_start, rq.seg_adapter, rq.seg_is_train, blk.data() + L.off_tok_segment,
+                  blk.data() + L.off_tok_adapter, tr.data());
+        for (int t = 0; t < T; ++t) blk[L.off_tok_train + t] = tr[t];
+    }
+    L.off_rank = b.alloc(std::max(N, 1));
+    for (int a = 0; a < N; ++a) blk[L.off_rank + a] = rq.rank[a];
+    L.off_A_ptr = b.alloc((size_t)std::max(N, 1) * 2);
+    L.off_B_ptr = b.alloc((size_t)std::max(N, 1) * 2);
+    L.off_dA_ptr = b.alloc((size_t)std::max(N, 1) * 2);
+    L.off_dB_ptr = b.alloc((size_t)std::max(N, 1) * 2);
+    auto put_ptrs = [&](int32_t off, const void *const *p) {
+        if (!p) return;
+        for (int a = 0; a < N; ++a) {
+            const uint64_t v = (uint64_t)(uintptr_t)p[a];
+            std::memcpy(blk.data() + off + 2 * a, &v, 8);
+        }
+    };
+    put_ptrs(L.off_A_ptr, rq.A);
+    put_ptrs(L.off_B_ptr, rq.B);
+    put_ptrs(L.off_dA_ptr, (const void *const *)rq.dA);
+    put_ptrs(L.off_dB_ptr, (const void *const *)rq.dB);
+
+    std::vector<int32_t> all((size_t)T), train;
+    for (int t = 0; t < T; ++t) all[t] = t;
+    train.reserve(T);
+    for (int t = 0; t < T; ++t)
+        if (blk[L.off_tok_train + t]) train.push_back(t);
+
+    // the vector may reallocate inside build_row_order: always index through blk.data()
+    {
+        std::vector<int32_t> tok_adapter(blk.begin() + L.off_tok_adapter,
+                                         blk.begin() + L.off_tok_adapter + T);
+        build_row_order(b, L.all, all, tok_adapter.data(), rq.rank, N, rq.bm_all);
+        build_row_order(b, L.train, train, tok_adapter.data(), rq.rank, N, rq.bm_train);
+    }
+
+    // gradient items: one per trained adapter, rows contiguous in the training row order
+    std::vector<GradItem> grad;
+    {
+        const int32_t *row_ad = blk.data() + L.train.off_row_adapter;
+        int r = 0;
+        while (r < L.train.n_rows) {
+            const int a = row_ad[r];
+            int e = r + 1;
+            while (e < L.train.n_rows && row_ad[e] == a) ++e;
+            GradItem g{};
+            g.adapter = a;
+            g.row_lo = r;
+            g.row_hi = e;
+            g.rank = rq.rank[a];
+            grad.push_back(g);
+            r = e;
+        }
+    }
+    // Cut the sum over tokens into slices so that one launch has enough blocks to fill the
+    // GPU; slices are multiples of 64 rows and every item gets at least one.
+    {
+        const int n_items = std::max<int>(1, (int)grad.size());
+        int want = (rq.grad_target_blocks + rq.grad_n_tiles * n_items - 1) /
+                   std::max(1, rq.grad_n_tiles * n_items);
+        want = std::max(1, std::min(want, rq.grad_max_ksplit));
+        int part_row = 0, slice0 = 0;
+        for (auto &g : grad) {
+            const int rows = g.row_hi - g.row_lo;
+            int slice_rows = round_up((rows + want - 1) / want, 64);
+            g.slice_rows = slice_rows;
+            g.ksplit = (rows + slice_rows - 1) / slice_rows;
+            g.part_row = part_row;
+            g.slice0 = slice0;
+            part_row += g.ksplit * round_up(g.rank, kKStep);
+            slice0 += g.ksplit;
+        }
+        L.grad_part_rows = part_row;
+        L.n_slices = slice0;
+    }
+    L.n_grad = (int)grad.size();
+    L.off_grad = b.alloc(grad.size() * 8 + 8);
+    if (!grad.empty()) std::memcpy(blk.data() + L.off_grad, grad.data(), grad.size() * sizeof(GradItem));
+    L.off_slices = b.alloc((size_t)L.n_slices * 2 + 2);
+    for (int i = 0; i < L.n_grad; ++i)
+        for (int k = 0; k < grad[i].ksplit; ++k) {
+            blk[L.off_slices + 2 * (grad[i].slice0 + k)] = i;
+            blk[L.off_slices + 2 * (grad[i].slice0 + k) + 1] = k;
+        }
+    b.alloc(0, 64);
+    L.total_ints = (int32_t)blk.size();
+    return COLLM_OK;
+}
+
+size_t plan_ints_upper_bound(int max_tokens, int max_segments, int max_adapters, int max_rank)
+{
+    (void)max_segments;
+    const size_t Tp = (size_t)round_up(std::max(max_tokens, 1), kRowPad);
+    const size_t N = (size_t)std::max(max_adapters, 1);
+    const size_t steps = (size_t)round_up(max_rank, kKStep) / kKStep;
+    size_t n = 0;
+    n += 3 * Tp;                         // token map
+    n += 9 * N + 64;                     // rank + four pointer tables
+    for (int k = 0; k < 2; ++k) {
+        n += 2 * Tp;                     // row_tok, row_adapter
+        n += 4 * (Tp / kSkinnyRows + N) + 8;          // skinny items
+        n += Tp / 64 + 8;                // ext_off (smallest tile 64 rows)
+        n += 4 * steps * (Tp / 64 + N) + 8;           // ext steps: (tiles + adapter runs) x steps
+    }
+    n += 8 * N + 8;                      // grad items
+    n += 2 * (Tp / 64 + N) + 8;          // slices
+    return n + 1024;
+}
+
+}  // namespace collm

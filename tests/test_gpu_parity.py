@@ -1,0 +1,299 @@
+"""GPU parity: the C-ABI library against the fp64 CPU oracle on the same seeded inputs.
+
+Tolerances (max|got - ref| / max|ref| per output tensor): 1e-2 for bf16 inputs with fp32
+accumulation, 1e-5 for fp32.  Index work (token -> segment / adapter) is compared bit for bit.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2604_16400_amd import binding
+from paper_2604_16400_amd import workloads as wl
+
+from gpu_util import TOL, DeviceLayer, check_full, make_ctx, maxrel, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_full(w, tol=None, h_save=True, **kw):
+    t = wl.make_tensors(w)
+    ctx = make_ctx(w, **kw)
+    layer = DeviceLayer(w, t, ctx)
+    layer.fwd(h_save=h_save)
+    layer.bwd(h_save=h_save)
+    errs = check_full(layer, TOL[w.dtype] if tol is None else tol, check_h=h_save)
+    # the plan the device holds encodes exactly the oracle's token map
+    ts, ta, tt = ctx.device_token_map(w.n_tokens)
+    rs, ra, rt = oracle.token_map(w.seg_start, w.seg_adapter, w.seg_is_train)
+    assert np.array_equal(ts, rs) and np.array_equal(ta, ra) and np.array_equal(tt, rt)
+    ctx.close()
+    return errs
+
+
+# ------------------------------------------------------------------ the five configurations
+def test_config1_fp32_every_element():
+    errs = _run_full(wl.make_config(1))
+    print("config 1 errors", errs)
+
+
+def test_config2_bf16_every_element():
+    errs = _run_full(wl.make_config(2))
+    print("config 2 errors", errs)
+    # one bf16 rounding of the output is ~2^-9 of the row scale; anything near 1e-2 is a bug
+    assert errs["y"] < 6e-3 and errs["dx"] < 6e-3
+
+
+def _sampled_projection(cfg, proj_index, n_rows=192, n_cols=768):
+    """Full-size run in the launch configuration the benchmark times.  The two W-sized
+    contractions are checked on sampled rows x sampled columns (the oracle computes each of
+    those outputs from its definition); h, dA and dB are checked on every element."""
+    import torch
+
+    w = wl.make_config(cfg)
+    p = w.projections[proj_index]
+    t = wl.make_tensors(w, proj_index)
+    ctx = make_ctx(w)
+    layer = DeviceLayer(w, t, ctx, proj_index)
+    layer.fwd()
+    layer.bwd()
+    torch.cuda.synchronize()
+    tol = TOL[w.dtype]
+    ta, tt = layer.tok_adapter, layer.tok_train
+    rng = np.random.default_rng(cfg * 100 + proj_index)
+    rows_all = wl.sample_rows(w, seed=proj_index)
+    tr_rows = rows_all[tt[rows_all] != 0]
+    inf_rows = rows_all[tt[rows_all] == 0]
+    pick = lambda r, n: r if len(r) <= n else np.sort(rng.choice(r, size=n, replace=False))
+    rows = np.concatenate([pick(inf_rows, n_rows // 2), pick(tr_rows, n_rows // 2)])
+
+    def cols_of(d):
+        blocks = [np.arange(0, 64), np.arange(d - 64, d)]
+        starts = rng.integers(0, d // 8 - 8, size=(n_cols - 128) // 64) * 8
+        blocks += [np.arange(s, s + 64) for s in starts]
+        return np.unique(np.concatenate(blocks))
+
+    # forward: y[rows, cols]
+    cj = cols_of(p.d_out)
+    y_ref, _ = oracle.lora_linear_fwd(t.x[rows], t.W[:, cj], t.A, [b[:, cj] for b in t.B], ta[rows], w.scale)
+    y = to_host(layer.y)
+    assert np.all(np.isfinite(y))
+    e_y = maxrel(y[np.ix_(rows, cj)], y_ref)
+    # backward: dx[train rows, cols] needs all of dy's columns but only rows ci of W and A
+    trs = rows[tt[rows] != 0]
+    ci = cols_of(p.d_in)
+    dx_ref, _, _ = oracle.lora_linear_bwd(t.x[np.ix_(trs, ci)], t.W[ci], [a[ci] for a in t.A], t.B, ta[trs],
+                                          np.ones(len(trs), np.uint8), w.scale, t.dy[trs], want_dab=False)
+    dx = to_host(layer.dx)
+    assert np.all(np.isnan(dx[tt == 0])) and np.all(np.isfinite(dx[tt != 0]))
+    e_dx = maxrel(dx[np.ix_(trs, ci)], dx_ref)
+    # low-rank terms in full
+    _, dA_ref, dB_ref = oracle.lora_linear_bwd(t.x, None, t.A, t.B, ta, tt, w.scale, t.dy, want_dx=False)
+    errs = {"y": e_y, "dx": e_dx}
+    for a in range(w.n_adapters):
+        dA, dB = to_host(layer.dA[a]), to_host(layer.dB[a])
+        if dA_ref[a] is None:
+            assert np.all(np.isnan(dA)) and np.all(np.isnan(dB))
+        else:
+            errs[f"dA{a}"] = maxrel(dA, dA_ref[a])
+            errs[f"dB{a}"] = maxrel(dB, dB_ref[a])
+    hs = to_host(layer.h_save)
+    tr = tt != 0
+    assert np.all(np.isnan(hs[~tr]))
+    h_ref = np.zeros((int(tr.sum()), hs.shape[1]))
+    for k, tok in enumerate(np.flatnonzero(tr)):
+        a = ta[tok]
+        h_ref[k, : w.ranks[a]] = np.asarray(t.x[tok], dtype=np.float64) @ np.asarray(t.A[a], dtype=np.float64)
+    errs["h"] = maxrel(hs[tr], h_ref)
+    ts, ta_d, tt_d = ctx.device_token_map(w.n_tokens)
+    rs, ra, rt = oracle.token_map(w.seg_start, w.seg_adapter, w.seg_is_train)
+    assert np.array_equal(ts, rs) and np.array_equal(ta_d, ra) and np.array_equal(tt_d, rt)
+    ctx.close()
+    print(f"config {cfg} {p.name}: rows {len(rows)} cols {len(cj)}/{len(ci)} errors", errs)
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, bad
+    return errs
+
+
+@pytest.mark.parametrize("proj", [0, 1, 2])
+def test_config3_sampled(proj):
+    _sampled_projection(3, proj)
+
+
+@pytest.mark.parametrize("proj", [0, 1])
+def test_config4_sampled(proj):
+    _sampled_projection(4, proj)
+
+
+@pytest.mark.parametrize("proj", [0, 1, 2])
+def test_config5_sampled(proj):
+    _sampled_projection(5, proj)
+
+
+# ------------------------------------------------------------------ edge cases
+def _adhoc(dtype, d_in, d_out, ranks, lens, adapters, train, scale=2.0, seed=7):
+    return wl.make_adhoc("adhoc", dtype, d_in, d_out, ranks, lens, adapters, train, scale=scale, seed=seed)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_ragged_shapes_odd_ranks_empty_segments(dtype):
+    # sizes that are no multiple of any tile, ranks that are no multiple of 8, empty segments,
+    # base-only segments, two training segments on one adapter, an adapter used by both kinds
+    q = 8 if dtype == "bf16" else 4
+    w = _adhoc(dtype, 25 * q, 41 * q, [3, 5, 17, 8, 1, 24], [5, 0, 37, 1, 130, 0, 70, 2, 64, 301],
+               [0, 1, -1, 2, 2, 3, 5, -1, 4, 2], [0, 0, 0, 0, 1, 0, 1, 0, 0, 1], scale=0.3)
+    _run_full(w)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_shuffled_segment_order(dtype):
+    w = _adhoc(dtype, 256, 192, [16, 8, 32], [40, 1, 1, 1, 90, 33, 1, 260], [0, 1, 2, 0, 1, 2, 1, 0],
+               [0, 0, 0, 0, 1, 0, 0, 1])
+    ws, _ = wl.shuffled_segments(w, seed=3)
+    _run_full(ws)
+
+
+def test_all_inference_batch_and_all_training_batch():
+    w = _adhoc("bf16", 128, 256, [16, 16], [10, 20, 30], [0, 1, -1], [0, 0, 0])
+    t = wl.make_tensors(w)
+    ctx = make_ctx(w)
+    layer = DeviceLayer(w, t, ctx)
+    layer.fwd()
+    layer.bwd()  # nothing trains: a no-op that must leave every output untouched
+    check_full(layer, TOL["bf16"])
+    ctx.close()
+    w = _adhoc("bf16", 128, 256, [16, 16], [100, 200], [1, 0], [1, 1])
+    _run_full(w)
+
+
+def test_single_token_and_empty_batch():
+    _run_full(_adhoc("bf16", 64, 64, [8], [1], [0], [1]))
+    _run_full(_adhoc("f32", 64, 64, [8], [1], [0], [0]))
+    w = _adhoc("bf16", 64, 64, [8], [0, 0], [0, -1], [0, 0])
+    t = wl.make_tensors(w)
+    ctx = make_ctx(w)
+    layer = DeviceLayer(w, t, ctx)
+    layer.fwd()
+    layer.bwd()
+    ctx.close()
+
+
+def test_many_adapters_in_one_tile_and_large_rank():
+    # 300 one-token decode segments over 40 adapters (many adapters per GEMM row tile), ranks
+    # up to the largest supported (256), plus training segments
+    rng = np.random.default_rng(1)
+    ranks = rng.choice([8, 16, 64, 256], size=40)
+    lens = [1] * 300 + [150, 90]
+    ads = list(rng.integers(0, 40, size=300)) + [3, 17]
+    w = _adhoc("bf16", 512, 384, ranks, lens, ads, [0] * 300 + [1, 1])
+    _run_full(w)
+
+
+@pytest.mark.parametrize("tile", [binding.TILE_256x256, binding.TILE_256x128, binding.TILE_128x128])
+def test_every_gemm_tile_shape(tile):
+    w = _adhoc("bf16", 448, 584, [16, 32, 8], [1] * 50 + [300, 77, 200], list(np.arange(50) % 3) + [0, 1, 2],
+               [0] * 50 + [1, 0, 1])
+    t = wl.make_tensors(w)
+    ctx = make_ctx(w)
+    ctx.set_tiles(tile, tile)
+    layer = DeviceLayer(w, t, ctx)
+    layer.fwd()
+    layer.bwd()
+    check_full(layer, TOL["bf16"])
+    ctx.close()
+
+
+# ------------------------------------------------------------------ contracts
+def test_recompute_h_and_accumulate_and_run_to_run():
+    import torch
+
+    w = wl.make_config(2)
+    t = wl.make_tensors(w)
+    ctx = make_ctx(w)
+    layer = DeviceLayer(w, t, ctx)
+    layer.fwd()
+    layer.bwd()
+    torch.cuda.synchronize()
+    y1, dx1 = layer.y.clone(), layer.dx.clone()
+    dA1 = [a.clone() for a in layer.dA]
+    dB1 = [b.clone() for b in layer.dB]
+    # run to run: same bits (no floating-point atomics anywhere)
+    layer.fwd()
+    layer.bwd()
+    torch.cuda.synchronize()
+    eq = lambda a, b: torch.equal(a.view(torch.int16 if a.dtype == torch.bfloat16 else torch.int32),
+                                  b.view(torch.int16 if b.dtype == torch.bfloat16 else torch.int32))
+    assert eq(layer.y, y1) and eq(layer.dx, dx1)
+    tr_ad = int(w.seg_adapter[-1])
+    assert eq(layer.dA[tr_ad], dA1[tr_ad]) and eq(layer.dB[tr_ad], dB1[tr_ad])
+    # h recomputed inside the backward call gives the same gradients as the saved one
+    layer.bwd(h_save=False)
+    torch.cuda.synchronize()
+    assert eq(layer.dA[tr_ad], dA1[tr_ad]) and eq(layer.dB[tr_ad], dB1[tr_ad]) and eq(layer.dx, dx1)
+    # accumulate adds to what the buffers hold
+    layer.bwd(accumulate=True)
+    torch.cuda.synchronize()
+    assert torch.allclose(layer.dA[tr_ad], 2 * dA1[tr_ad], rtol=1e-6, atol=0)
+    assert torch.allclose(layer.dB[tr_ad], 2 * dB1[tr_ad], rtol=1e-6, atol=0)
+    ctx.close()
+
+
+def test_backward_without_dx_or_without_adapter_gradients():
+    import torch
+
+    w = _adhoc("bf16", 256, 128, [16, 8], [30, 100, 60], [0, 1, 0], [0, 1, 1])
+    t = wl.make_tensors(w)
+    ctx = make_ctx(w)
+    full = DeviceLayer(w, t, ctx)
+    full.fwd()
+    full.bwd()
+    a = DeviceLayer(w, t, ctx)
+    a.fwd()
+    a.bwd(dx=False)
+    b = DeviceLayer(w, t, ctx)
+    b.fwd()
+    b.bwd(dab=False)
+    torch.cuda.synchronize()
+    assert torch.isnan(a.dx).all()
+    assert all(torch.equal(p, q) for p, q in zip(a.dA, full.dA))
+    assert all(torch.isnan(p).all() for p in b.dA + b.dB)
+    tr = torch.from_numpy(full.tok_train != 0).cuda()
+    assert torch.equal(b.dx[tr].view(torch.int16), full.dx[tr].view(torch.int16))
+    ctx.close()
+
+
+def test_error_statuses_touch_nothing():
+    import torch
+
+    w = _adhoc("bf16", 64, 64, [8, 8], [10, 20], [0, 1], [0, 1])
+    t = wl.make_tensors(w)
+    ctx = make_ctx(w)
+    layer = DeviceLayer(w, t, ctx)
+
+    def expect(status, fn):
+        with pytest.raises(binding.CollmError) as e:
+            fn()
+        assert e.value.status == status, e.value
+
+    c = ctx.collm_lora_linear_fwd
+    args = lambda **k: dict(dict(x=layer.x, W=layer.W, A=layer.A, B=layer.B, rank=w.ranks, seg_start=w.seg_start,
+                                 seg_adapter=w.seg_adapter, seg_is_train=w.seg_is_train, scale=2.0, y=layer.y), **k)
+    expect(-3, lambda: c(**args(seg_start=[0, 10, 29])))
+    expect(-3, lambda: c(**args(seg_start=[1, 10, 30])))
+    expect(-4, lambda: c(**args(seg_adapter=[0, 2])))
+    expect(-4, lambda: c(**args(seg_adapter=[0, -1])))          # training segment without adapter
+    expect(-4, lambda: c(**args(A=[layer.A[0], None])))        # used adapter without table
+    expect(-5, lambda: c(**args(rank=[8, 9])))                 # beyond the context's max_rank
+    expect(-5, lambda: c(**args(rank=[8, 0])))
+    odd = layer.x.view(-1)[4:][: 29 * 64].view(29, 64)  # 8 bytes off a 16-byte boundary
+    expect(-7, lambda: c(**args(x=odd, seg_start=[0, 10, 29])))
+    big = torch.zeros((31, 64), dtype=torch.bfloat16, device="cuda")
+    expect(-2, lambda: c(**args(x=big, seg_start=[0, 10, 31])))  # more tokens than the context holds
+    expect(-2, lambda: c(**args(x=layer.x[:, :60].contiguous())))  # d_in not a multiple of 8
+    torch.cuda.synchronize()
+    assert torch.isnan(layer.y).all()
+    # backward: trained adapter without gradient buffers
+    expect(-4, lambda: ctx.collm_lora_linear_bwd(layer.x, layer.W, layer.A, layer.B, w.ranks, w.seg_start,
+                                                 w.seg_adapter, w.seg_is_train, 2.0, layer.dy, None, layer.dx,
+                                                 [layer.dA[0], None], [layer.dB[0], None]))
+    assert torch.isnan(layer.dx).all()
+    ctx.close()

@@ -1,0 +1,81 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what the header declares, and its
+host-only integer bookkeeping equals the oracle's bit for bit."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2604_16400_amd import binding
+from paper_2604_16400_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load_library()
+    hdr = open(os.path.join(ROOT, "include", "collm_lora.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = re.findall(r"\b(collm_[a-z_0-9]+)\s*\(", hdr)
+    assert len(set(names)) >= 11
+    for n in set(names):
+        assert hasattr(lib, n), n
+    assert lib.collm_status_string(0) == b"ok"
+    assert lib.collm_status_string(-3) != lib.collm_status_string(-4)
+
+
+def test_token_map_matches_oracle_bit_for_bit_fuzz():
+    rng = np.random.default_rng(20260416)
+    for it in range(10000):
+        S = int(rng.integers(0, 40))
+        kind = it % 4
+        if kind == 0:
+            lens = rng.integers(0, 4, size=S)
+        elif kind == 1:
+            lens = rng.integers(1, 300, size=S)
+        elif kind == 2:
+            lens = (rng.random(S) < 0.3) * rng.integers(0, 2000, size=S)
+        else:
+            lens = np.ones(S, dtype=np.int64)
+        seg_start = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        tr = rng.integers(0, 2, size=S).astype(np.uint8)
+        ad = rng.integers(-1, 7, size=S).astype(np.int32)
+        ad[(tr != 0) & (ad < 0)] = 0
+        got = binding.collm_token_map(seg_start, ad, tr, n_adapters=7)
+        ref = oracle.token_map(seg_start, ad, tr)
+        for g, r in zip(got, ref):
+            assert g.dtype == r.dtype and np.array_equal(g, r)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_token_map_configs(cfg):
+    w = wl.make_config(cfg)
+    got = binding.collm_token_map(w.seg_start, w.seg_adapter, w.seg_is_train, n_adapters=w.n_adapters)
+    ref = oracle.token_map(w.seg_start, w.seg_adapter, w.seg_is_train)
+    for g, r in zip(got, ref):
+        assert np.array_equal(g, r)
+    assert int(np.count_nonzero(got[2])) == w.n_train_tokens
+
+
+def test_token_map_rejects_bad_tables():
+    f = binding.collm_token_map
+    with pytest.raises(binding.CollmError) as e:
+        f([1, 3], [0], [0])  # does not start at 0
+    assert e.value.status == -3
+    with pytest.raises(binding.CollmError) as e:
+        f([0, 3, 2], [0, 0], [0, 0])  # decreasing
+    assert e.value.status == -3
+    with pytest.raises(binding.CollmError) as e:
+        f([0, 3], [0], [0], n_tokens=4)  # does not end at T
+    assert e.value.status == -3
+    with pytest.raises(binding.CollmError) as e:
+        f([0, 3], [5], [0], n_adapters=5)  # adapter out of range
+    assert e.value.status == -4
+    with pytest.raises(binding.CollmError) as e:
+        f([0, 3], [-1], [1], n_adapters=5)  # training segment without adapter
+    assert e.value.status == -4
+    with pytest.raises(binding.CollmError) as e:
+        f([0, 3], [-2], [0], n_adapters=5)
+    assert e.value.status == -4
