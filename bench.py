@@ -1,0 +1,264 @@
+#!/usr/bin/env python3
+"""Benchmark of the mixed-batch LoRA linear layer on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch: plan, shrink, GEMM with
+fused expand (forward), then dh, dB, dA and the dX GEMM (backward for the training segments).
+The headline workload is configuration 2 (Llama-7B-shaped q_proj 4096->4096, bf16, 2048 tokens:
+256 decode tokens over 16 rank-16 adapters + one 1792-token training segment); the other
+bf16 configurations are reported per projection in `all_configs`.
+
+Prints ONE JSON line.  `value` is effective TFLOP/s: algorithmic flops of forward + backward
+(base GEMMs plus the low-rank terms) divided by wall time, inputs resident in HBM.
+`roofline` is for the dominant kernel (the forward GEMM with the fused expand): flops of one
+launch over its average duration, measured with HIP events recorded on the launch stream in a
+second, profiled pass over the same steps.  `cpu_baseline` times the fp64 CPU oracle on the
+same workload in the same run; it is a reported baseline, not a target.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
+
+
+def _dev_tensors(w, proj_index, torch, exact=False):
+    """Inputs on the GPU.  exact=True uploads the workload module's numpy tensors (identical to
+    what the oracle reads); otherwise the same distributions are drawn on the device."""
+    from paper_2604_16400_amd import workloads as wl
+
+    p = w.projections[proj_index]
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    if exact:
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from gpu_util import to_dev
+
+        t = wl.make_tensors(w, proj_index)
+        return (to_dev(t.x, w.dtype), to_dev(t.W, w.dtype), [to_dev(a, w.dtype) for a in t.A],
+                [to_dev(b, w.dtype) for b in t.B], to_dev(t.dy, w.dtype), t)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(w.seed * 16 + proj_index)
+    rn = lambda shape, std: (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * std).to(dt)
+    std_a = w.std_a if w.std_a is not None else p.d_in ** -0.5
+    x = rn((w.n_tokens, p.d_in), w.std_x)
+    W = rn((p.d_in, p.d_out), w.std_w)
+    A = [rn((p.d_in, int(r)), std_a) for r in w.ranks]
+    B = [rn((int(r), p.d_out), w.std_b) for r in w.ranks]
+    dy = rn((w.n_tokens, p.d_out), w.std_dy)
+    return x, W, A, B, dy, None
+
+
+def _algorithmic_bytes(w, p):
+    """HBM bytes the low-rank passes must move (element size 2)."""
+    import numpy as np
+
+    e = 2
+    lens = np.diff(w.seg_start)
+    used = sorted(set(int(a) for a, n in zip(w.seg_adapter, lens) if a >= 0 and n > 0))
+    rows_ad = int(lens[w.seg_adapter >= 0].sum())
+    r_tok = sum(int(n) * int(w.ranks[a]) for a, n in zip(w.seg_adapter, lens) if a >= 0)
+    shrink = rows_ad * p.d_in * e + sum(p.d_in * int(w.ranks[a]) * e for a in used) + 4 * r_tok
+    trained = sorted(set(int(a) for a, tr, n in zip(w.seg_adapter, w.seg_is_train, lens) if tr and n > 0))
+    t_tr = w.n_train_tokens
+    r_tr = sum(int(n) * int(w.ranks[a]) for a, tr, n in zip(w.seg_adapter, w.seg_is_train, lens) if tr)
+    dh = t_tr * p.d_out * e + sum(p.d_out * int(w.ranks[a]) * e for a in trained) + 4 * r_tr
+    gdB = t_tr * p.d_out * e + 4 * r_tr + sum(4 * p.d_out * int(w.ranks[a]) for a in trained)
+    gdA = t_tr * p.d_in * e + 4 * r_tr + sum(4 * p.d_in * int(w.ranks[a]) for a in trained)
+    return {"shrink": shrink, "dh": dh, "grad_dB": gdB, "grad_dA": gdA}
+
+
+class Runner:
+    def __init__(self, w, proj_index, torch, exact=False):
+        from paper_2604_16400_amd import binding
+
+        self.w, self.p, self.torch = w, w.projections[proj_index], torch
+        d = max(self.p.d_in, self.p.d_out)
+        self.max_rank = int(w.ranks.max())
+        self.ctx = binding.Context(w.n_tokens, w.n_segments, w.n_adapters, self.max_rank, d)
+        self.x, self.W, self.A, self.B, self.dy, self.host = _dev_tensors(w, proj_index, torch, exact)
+        dt = self.x.dtype
+        T = w.n_tokens
+        self.y = torch.empty((T, self.p.d_out), dtype=dt, device="cuda")
+        self.dx = torch.empty((T, self.p.d_in), dtype=dt, device="cuda")
+        self.h_save = torch.empty((T, self.max_rank), dtype=torch.float32, device="cuda")
+        self.dA = [torch.empty((self.p.d_in, int(r)), dtype=torch.float32, device="cuda") for r in w.ranks]
+        self.dB = [torch.empty((int(r), self.p.d_out), dtype=torch.float32, device="cuda") for r in w.ranks]
+
+    def step(self):
+        w, c = self.w, self.ctx
+        c.collm_lora_linear_fwd(self.x, self.W, self.A, self.B, w.ranks, w.seg_start, w.seg_adapter,
+                                w.seg_is_train, w.scale, self.y, self.h_save)
+        c.collm_lora_linear_bwd(self.x, self.W, self.A, self.B, w.ranks, w.seg_start, w.seg_adapter,
+                                w.seg_is_train, w.scale, self.dy, self.h_save, self.dx, self.dA, self.dB, False)
+
+    def timed(self, steps, warmup):
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    def kernel_times(self, steps):
+        """Average duration (ms) of every kernel of a step: HIP events recorded on the launch
+        stream around each launch, read after each half step."""
+        w, c = self.w, self.ctx
+        c.profile_enable(True)
+        acc = {}
+        for _ in range(steps):
+            c.collm_lora_linear_fwd(self.x, self.W, self.A, self.B, w.ranks, w.seg_start, w.seg_adapter,
+                                    w.seg_is_train, w.scale, self.y, self.h_save)
+            for name, ms in c.profile_read():
+                acc.setdefault(name, []).append(ms)
+            c.collm_lora_linear_bwd(self.x, self.W, self.A, self.B, w.ranks, w.seg_start, w.seg_adapter,
+                                    w.seg_is_train, w.scale, self.dy, self.h_save, self.dx, self.dA, self.dB,
+                                    False)
+            for name, ms in c.profile_read():
+                acc.setdefault(name, []).append(ms)
+        c.profile_enable(False)
+        return {k: sum(v) / len(v) for k, v in acc.items()}
+
+    def report(self, steps, warmup, prof_steps):
+        w, p = self.w, self.p
+        sec = self.timed(steps, warmup)
+        f_fwd, f_bwd = w.flops(p)
+        kt = self.kernel_times(prof_steps)
+        by = _algorithmic_bytes(w, p)
+        gemm_fwd_flops = 2.0 * w.n_tokens * p.d_in * p.d_out
+        gemm_dx_flops = 2.0 * w.n_train_tokens * p.d_in * p.d_out
+        out = {
+            "workload": f"{w.name}/{p.name}", "d_in": p.d_in, "d_out": p.d_out, "tokens": w.n_tokens,
+            "train_tokens": w.n_train_tokens, "segments": w.n_segments,
+            "ms_per_step": sec * 1e3, "tflops": (f_fwd + f_bwd) / sec / 1e12, "tokens_per_s": w.n_tokens / sec,
+            "kernel_ms": {k: round(v, 5) for k, v in kt.items()},
+        }
+        if "gemm_fwd" in kt:
+            out["gemm_fwd_tflops"] = gemm_fwd_flops / (kt["gemm_fwd"] * 1e-3) / 1e12
+            out["gemm_fwd_frac_mfma_peak"] = out["gemm_fwd_tflops"] / PEAK_BF16_TFLOPS
+        if "gemm_dx" in kt:
+            out["gemm_dx_tflops"] = gemm_dx_flops / (kt["gemm_dx"] * 1e-3) / 1e12
+            out["gemm_dx_frac_mfma_peak"] = out["gemm_dx_tflops"] / PEAK_BF16_TFLOPS
+        for k in ("shrink", "dh", "grad_dB", "grad_dA"):
+            if k in kt:
+                gbs = by[k] / (kt[k] * 1e-3) / 1e9
+                out[f"{k}_GBs"] = gbs
+                out[f"{k}_frac_hbm_peak"] = gbs / PEAK_HBM_GBS
+        return out, sec, kt
+
+    def close(self):
+        self.ctx.close()
+
+
+def _cpu_baseline(w, t):
+    """The oracle as it stands, timed on the host cores on the same workload."""
+    import numpy as np
+
+    import oracle
+
+    _, ta, tt = oracle.token_map(w.seg_start, w.seg_adapter, w.seg_is_train)
+    p = w.projections[0]
+    t0 = time.perf_counter()
+    oracle.lora_linear_fwd(t.x, t.W, t.A, t.B, ta, w.scale)
+    oracle.lora_linear_bwd(t.x, t.W, t.A, t.B, ta, tt, w.scale, np.asarray(t.dy, dtype=np.float64))
+    sec = time.perf_counter() - t0
+    f_fwd, f_bwd = w.flops(p)
+    return {"value": (f_fwd + f_bwd) / sec / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": sec,
+            "sample": f"{w.name} in full: {w.n_tokens} tokens, forward + backward, fp64 (includes fp32->fp64 widening)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--configs", type=str, default="2,3,4,5", help="configurations to report (2 is always run)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU; run it with --gpus 1 (no collectives or sharding exist)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2604_16400_amd import binding
+    from paper_2604_16400_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    binding.load_library()
+    props = torch.cuda.get_device_properties(0)
+
+    w2 = wl.make_config(2)
+    r = Runner(w2, 0, torch, exact=True)
+    head, sec, kt = r.report(args.steps, args.warmup, max(10, min(args.steps, 50)))
+    host_tensors = r.host
+    r.close()
+    del r
+    torch.cuda.empty_cache()
+
+    p = w2.projections[0]
+    gemm_flops = 2.0 * w2.n_tokens * p.d_in * p.d_out
+    lens_r = sum(int(n) * int(w2.ranks[a]) for a, n in zip(w2.seg_adapter, (w2.seg_start[1:] - w2.seg_start[:-1])) if a >= 0)
+    gemm_flops += 2.0 * lens_r * p.d_out  # fused expand K-steps
+    achieved = gemm_flops / (kt["gemm_fwd"] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "gemm_lora_kernel (forward: x W + fused expand)",
+                "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                "avg_launch_ms": kt["gemm_fwd"], "flops_per_launch": gemm_flops}
+
+    all_cfg = [head]
+    for c in [int(s) for s in args.configs.split(",") if s.strip()]:
+        if c in (1, 2):
+            continue
+        w = wl.make_config(c)
+        for pi in range(len(w.projections)):
+            rr = Runner(w, pi, torch)
+            steps = max(5, min(args.steps, 30))
+            o, _, _ = rr.report(steps, 3, min(steps, 10))
+            all_cfg.append(o)
+            rr.close()
+            del rr
+            torch.cuda.empty_cache()
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = _cpu_baseline(w2, host_tensors)
+
+    f_fwd, f_bwd = w2.flops(p)
+    line = {
+        "metric": "mixed-batch LoRA layer TFLOP/s (fwd+bwd)", "value": (f_fwd + f_bwd) / sec / 1e12,
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config 2: Llama-7B q_proj 4096->4096 bf16, 2048 tokens (256 decode over 16 "
+                               "rank-16 adapters + 1792-token training segment), fwd + bwd",
+                   "tokens": w2.n_tokens, "train_tokens": w2.n_train_tokens, "segments": w2.n_segments,
+                   "seed": w2.seed},
+        "tokens_per_s": w2.n_tokens / sec,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "frac_mfma_peak_whole_step": (f_fwd + f_bwd) / sec / 1e12 / PEAK_BF16_TFLOPS,
+        "all_configs": all_cfg,
+        "device": {"name": props.name, "cus": props.multi_processor_count,
+                   "peak_bf16_tflops_used": PEAK_BF16_TFLOPS, "peak_hbm_gbs_used": PEAK_HBM_GBS},
+        "paper_context": "paper reports system-level gains only (up to 1.5x goodput, 2.2x quality-weighted "
+                         "goodput, +40% GPU utilisation on 32x NVIDIA H20); it has no per-layer number",
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
