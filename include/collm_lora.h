@@ -37,8 +37,9 @@
  *     context must not overlap on different streams, and a context is not thread-safe.
  *   - Every call returns a status: COLLM_OK (0) or a negative error.  All validation is done
  *     on the host before anything is launched; on an error no output buffer is touched.
- *   - d_in and d_out must be multiples of 8 (bf16) or 4 (fp32).  Ranks may be any value in
- *     1..max_rank.  Empty segments and an empty batch are legal.
+ *   - d_in and d_out must be multiples of 8 (bf16) or 4 (fp32); x, dy and W must each stay
+ *     below 2 GiB (COLLM_E_SHAPE otherwise).  Ranks may be any value in 1..max_rank.  Empty
+ *     segments and an empty batch are legal.
  */
 #ifndef COLLM_LORA_H
 #define COLLM_LORA_H
@@ -162,7 +163,8 @@ int collm_debug_device_token_map(collm_ctx *ctx, int32_t *tok_segment, int32_t *
 
 /*
  * Debug/tuning: force the tile shape of the forward GEMM and of the dX GEMM
- * (0: 256x256, 1: 256x128, 2: 128x128 rows x columns of the output; -1: let the library
+ * (0: 256x256, 1: 256x128, 2: 128x128 rows x columns of the output, 3: 256x256 run by eight
+ * waves instead of four; -1: let the library
  * choose from the problem size).  Affects only speed, never results beyond rounding order.
  */
 int collm_debug_set_tiles(collm_ctx *ctx, int fwd_tile, int bwd_tile);

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libcollm_lora.so")
 COLLM_F32 = 0
 COLLM_BF16 = 1
 
-TILE_AUTO, TILE_256x256, TILE_256x128, TILE_128x128 = -1, 0, 1, 2
+TILE_AUTO, TILE_256x256, TILE_256x128, TILE_128x128, TILE_256x256_W8 = -1, 0, 1, 2, 3
 
 
 class CollmError(RuntimeError):

@@ -125,6 +125,12 @@ int check_common(collm_ctx *ctx, const collm_shape *s, const void *x, const void
     if (s->d_in <= 0 || s->d_out <= 0 || s->d_in % q || s->d_out % q) return COLLM_E_SHAPE;
     if (s->d_in > ctx->max_d || s->d_out > ctx->max_d) return COLLM_E_SHAPE;
     if (s->n_tokens < 0 || s->n_tokens > ctx->max_tokens) return COLLM_E_SHAPE;
+    {
+        // the kernels address each operand tensor with 32-bit byte offsets below 2 GiB
+        const int64_t lim = (int64_t)1 << 31, e = s->dtype == COLLM_BF16 ? 2 : 4;
+        const int64_t dmax = std::max(s->d_in, s->d_out), dmin = std::min(s->d_in, s->d_out);
+        if (((int64_t)s->n_tokens + 1) * dmax * e >= lim || (dmax + 128) * dmin * e >= lim) return COLLM_E_SHAPE;
+    }
     if (s->n_segments < 0 || s->n_segments > ctx->max_segments) return COLLM_E_SHAPE;
     if (s->n_adapters < 0 || s->n_adapters > ctx->max_adapters) return COLLM_E_SHAPE;
     if (!seg_start) return COLLM_E_NULL;
@@ -420,7 +426,7 @@ int64_t collm_ctx_workspace_bytes(const collm_ctx *c) { return c ? c->workspace_
 int collm_debug_set_tiles(collm_ctx *c, int fwd_tile, int bwd_tile)
 {
     if (!c) return COLLM_E_NULL;
-    if (fwd_tile < -1 || fwd_tile > kTile128x128 || bwd_tile < -1 || bwd_tile > kTile128x128) return COLLM_E_SHAPE;
+    if (fwd_tile < -1 || fwd_tile >= kNumTiles || bwd_tile < -1 || bwd_tile >= kNumTiles) return COLLM_E_SHAPE;
     c->tile_fwd = fwd_tile;
     c->tile_bwd = bwd_tile;
     return COLLM_OK;
@@ -485,6 +491,8 @@ int collm_lora_linear_fwd(collm_ctx *c, const collm_shape *s, const void *x, con
     g.ldo = s->d_out;
     g.N = s->d_out;
     g.K = s->d_in;
+    g.a_bytes = (uint32_t)((int64_t)s->n_tokens * s->d_in * 2);
+    g.b_bytes = (uint32_t)((int64_t)s->d_in * s->d_out * 2);
     g.tiles_m = L.all.n_tiles_m;
     g.row_tok = c->d_plan + L.all.off_row_tok;
     g.ext_off = c->d_plan + L.all.off_ext_off;
@@ -605,6 +613,8 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
         g.ldo = s->d_in;
         g.N = s->d_in;
         g.K = s->d_out;
+        g.a_bytes = (uint32_t)((int64_t)s->n_tokens * s->d_out * 2);
+        g.b_bytes = (uint32_t)((int64_t)s->d_in * s->d_out * 2);
         g.tiles_m = L.train.n_tiles_m;
         g.row_tok = c->d_plan + L.train.off_row_tok;
         g.ext_off = c->d_plan + L.train.off_ext_off;

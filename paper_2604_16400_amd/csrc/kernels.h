@@ -7,7 +7,7 @@
 
 namespace collm {
 
-enum { kTile256x256 = 0, kTile256x128 = 1, kTile128x128 = 2 };
+enum { kTile256x256 = 0, kTile256x128 = 1, kTile128x128 = 2, kTile256x256w8 = 3, kNumTiles = 4 };
 
 // out[tok(m)][n] = sum_k a[tok(m)][k] * b(k, n)  +  sum over the row tile's extension steps
 struct GemmArgs {
@@ -18,6 +18,7 @@ struct GemmArgs {
     void *out;          // rows scattered through row_tok
     int64_t ldo;
     int N, K;
+    uint32_t a_bytes, b_bytes;  // sizes of the two operand tensors (each below 2 GiB)
     int tiles_m, tiles_n;
     const int32_t *row_tok;   // [tiles_m * BM]
     const int32_t *ext_off;   // [tiles_m + 1]

@@ -172,7 +172,43 @@ __device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, i
 
 // =========================================================================================
 // gemm_lora
+//
+// Block tile BM x BN, K step 64, WGM x WGN waves of (BM/WGM) x (BN/WGN) each.  Software
+// pipeline, two LDS stages:
+//   * the registers `areg`/`breg` always hold a tile in flight: the part of tile kc+1 that is
+//     written to LDS during MFMA step s of tile kc is re-loaded at once with tile kc+2, so a
+//     global load has a whole K step (64 MFMAs per wave) to arrive;
+//   * operand fragments of MFMA step s+1 are read from LDS while step s multiplies.
+// Global loads are buffer loads: rows that do not exist (padding rows, columns beyond N,
+// K tail) get an offset beyond the buffer and read as zero, so the loop has no branches.
 // =========================================================================================
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr uint32_t kOob = 0x80000000u;  // beyond any buffer (tensors are limited to 2 GiB)
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ uint4 buf16(__amdgpu_buffer_rsrc_t r, uint32_t off)
+{
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// 4 rows x 8 columns of 16-bit values (4 x uint4) -> for each column the 4 row values (uint2)
+__device__ __forceinline__ void transpose4x8(const uint4 (&in)[4], uint2 (&out)[8])
+{
+    const uint32_t *v = reinterpret_cast<const uint32_t *>(in);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const uint32_t r0 = v[0 * 4 + p], r1 = v[1 * 4 + p], r2 = v[2 * 4 + p], r3 = v[3 * 4 + p];
+        out[2 * p].x = (r0 & 0xffffu) | (r1 << 16);
+        out[2 * p].y = (r2 & 0xffffu) | (r3 << 16);
+        out[2 * p + 1].x = (r0 >> 16) | (r1 & 0xffff0000u);
+        out[2 * p + 1].y = (r2 >> 16) | (r3 & 0xffff0000u);
+    }
+}
+
 template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR>
 __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 {
@@ -180,6 +216,12 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int MI = WM / 32, NI = WN / 32;
     constexpr int STAGE = (BM + BN) * 128;
+    constexpr int ACH = BM * 8 / NT;   // 16-byte chunks of the row tile per thread
+    constexpr int BCH = BN * 8 / NT;   // K-major second operand: chunks per thread
+    constexpr int BHU = 2 * BN / NT;   // N-major second operand: (4 k x 8 n) blocks per thread
+    constexpr int NG = BN / 8;
+    static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0 && (2 * BN) % NT == 0 && NT % NG == 0, "tile/thread mismatch");
+    static_assert(ACH % 4 == 0 || ACH == 2, "row chunks are moved in four (or two) parts per K step");
     extern __shared__ __align__(16) uint8_t smem[];
 
     const int tid = threadIdx.x;
@@ -189,38 +231,95 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int K = p.K, N = p.N;
-
-    const uint16_t *__restrict__ Arows = reinterpret_cast<const uint16_t *>(p.a);
-    const uint16_t *__restrict__ Bmat = reinterpret_cast<const uint16_t *>(p.b);
     const int32_t *__restrict__ row_tok = p.row_tok;
 
-    auto a_row_ptr = [&](int r) -> const uint16_t * {
-        const int tok = row_tok[m0 + r];
-        return tok >= 0 ? Arows + (int64_t)tok * p.lda : nullptr;
+    const __amdgpu_buffer_rsrc_t ra = make_rsrc(p.a, p.a_bytes);
+    const __amdgpu_buffer_rsrc_t rb = make_rsrc(p.b, p.b_bytes);
+
+    // ---- per-thread source offsets (bytes) and LDS destinations ---------------------------
+    const int c8 = tid & 7;        // chunk column of this thread in K-major tiles
+    const int r8 = tid >> 3;       // first row of this thread in K-major tiles
+    uint32_t aoff[ACH];
+#pragma unroll
+    for (int i = 0; i < ACH; ++i) {
+        const int tok = row_tok[m0 + r8 + i * (NT / 8)];
+        aoff[i] = tok >= 0 ? (uint32_t)tok * (uint32_t)p.lda * 2u + c8 * 16u : kOob;
+    }
+    constexpr int NB = B_KMAJOR ? BCH : BHU;
+    uint32_t boff[NB];
+    uint32_t bstep = 0;  // N-major: advance of one K step, zero for columns beyond N
+    if constexpr (B_KMAJOR) {
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int n = n0 + r8 + i * (NT / 8);
+            boff[i] = n < N ? (uint32_t)n * (uint32_t)p.ldb * 2u + c8 * 16u : kOob;
+        }
+    } else {
+        const int ng = tid % NG;
+        const bool on = n0 + ng * 8 < N;
+        bstep = on ? 64u * (uint32_t)p.ldb * 2u : 0u;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int kq = (tid + i * NT) / NG;  // 4-row group 0..15 of the K step
+            boff[i] = on ? ((uint32_t)(kq * 4) * (uint32_t)p.ldb + n0 + ng * 8) * 2u : kOob;
+        }
+    }
+    const uint32_t ldb2 = (uint32_t)p.ldb * 2u;
+
+    uint4 areg[ACH];
+    uint4 breg[B_KMAJOR ? BCH : BHU * 4];
+
+    // loads part `part` of `parts` of the tile that starts at K index k0
+    auto load_a = [&](int k0, int part, int parts) {
+        const bool kin = k0 + c8 * 8 < K;
+#pragma unroll
+        for (int i = 0; i < ACH; ++i)
+            if (i * parts / ACH == part) areg[i] = buf16(ra, kin ? aoff[i] + (uint32_t)k0 * 2u : kOob);
     };
-
-    KMajorMover<BM, NT> amov;
-    KMajorMover<BN, NT> bmov_k;
-    NMajorMover<BN, NT> bmov_n;
-
-    auto load_tiles = [&](int k0) {
-        amov.load(tid, k0, K, a_row_ptr);
+    auto store_a = [&](int stage, int part, int parts) {
+        uint8_t *ta = smem + stage * STAGE;
+#pragma unroll
+        for (int i = 0; i < ACH; ++i)
+            if (i * parts / ACH == part)
+                *reinterpret_cast<uint4 *>(ta + tile_off(r8 + i * (NT / 8), c8)) = areg[i];
+    };
+    auto load_b = [&](int k0, int kc, int part, int parts) {
         if constexpr (B_KMAJOR) {
-            bmov_k.load(tid, k0, K, [&](int r) -> const uint16_t * {
-                return (n0 + r < N) ? Bmat + (int64_t)(n0 + r) * p.ldb : nullptr;
-            });
+            const bool kin = k0 + c8 * 8 < K;
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
+                if (i * parts / NB == part) breg[i] = buf16(rb, kin ? boff[i] + (uint32_t)k0 * 2u : kOob);
         } else {
-            bmov_n.load(tid, N - n0, [&](int k) -> const uint16_t * {
-                return (k0 + k < K) ? Bmat + (int64_t)(k0 + k) * p.ldb + n0 : nullptr;
-            });
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
+                if (i * parts / NB == part) {
+                    const uint32_t o = boff[i] + (uint32_t)kc * bstep;  // rows beyond K are beyond the buffer
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) breg[i * 4 + j] = buf16(rb, o + j * ldb2);
+                }
         }
     };
-    auto store_tiles = [&](int stage) {
-        uint8_t *ta = smem + stage * STAGE;
-        uint8_t *tb = ta + BM * 128;
-        amov.store(tid, ta);
-        if constexpr (B_KMAJOR) bmov_k.store(tid, tb);
-        else bmov_n.store(tid, tb);
+    auto store_b = [&](int stage, int part, int parts) {
+        uint8_t *tb = smem + stage * STAGE + BM * 128;
+        if constexpr (B_KMAJOR) {
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
+                if (i * parts / NB == part)
+                    *reinterpret_cast<uint4 *>(tb + tile_off(r8 + i * (NT / 8), c8)) = breg[i];
+        } else {
+            const int ng = tid % NG;
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
+                if (i * parts / NB == part) {
+                    const int kq = (tid + i * NT) / NG;
+                    uint4 in[4] = {breg[i * 4], breg[i * 4 + 1], breg[i * 4 + 2], breg[i * 4 + 3]};
+                    uint2 t[8];
+                    transpose4x8(in, t);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        *reinterpret_cast<uint2 *>(tb + tile_off(ng * 8 + j, kq >> 1) + (kq & 1) * 8) = t[j];
+                }
+        }
     };
 
     // acc[ni][mi] holds the transposed 32x32 block: lane = row m, registers = columns n
@@ -232,39 +331,53 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[ni][mi][j] = 0.f;
 
-    auto mma_steps = [&](int stage, int nsteps) {
+    const int rl = lane & 31, kh = lane >> 5;
+    bf16x8 af[2][MI], bf[2][NI];
+    auto read_frags = [&](int stage, int ks, int buf) {
         const uint8_t *ta = smem + stage * STAGE;
         const uint8_t *tb = ta + BM * 128;
-        const int rl = lane & 31, kh = lane >> 5;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            if (ks < nsteps) {
-                bf16x8 af[MI], bf[NI];
+        for (int mi = 0; mi < MI; ++mi) af[buf][mi] = lds_frag(ta, wm * WM + mi * 32 + rl, ks * 2 + kh);
 #pragma unroll
-                for (int mi = 0; mi < MI; ++mi) af[mi] = lds_frag(ta, wm * WM + mi * 32 + rl, ks * 2 + kh);
+        for (int ni = 0; ni < NI; ++ni) bf[buf][ni] = lds_frag(tb, wn * WN + ni * 32 + rl, ks * 2 + kh);
+    };
+    auto mma = [&](int buf) {
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni) bf[ni] = lds_frag(tb, wn * WN + ni * 32 + rl, ks * 2 + kh);
+        for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                    for (int mi = 0; mi < MI; ++mi)
-                        acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[ni], af[mi], acc[ni][mi], 0, 0, 0);
-            }
-        }
+            for (int mi = 0; mi < MI; ++mi)
+                acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[buf][ni], af[buf][mi], acc[ni][mi], 0, 0, 0);
     };
 
-    // ---- main K loop: register prefetch of the next tile pair, two LDS stages -------------
+    // ---- main K loop ----------------------------------------------------------------------
     const int nk = (K + 63) >> 6;
     if (nk > 0) {
-        load_tiles(0);
-        store_tiles(0);
+        load_a(0, 0, 1);
+        load_b(0, 0, 0, 1);
+        store_a(0, 0, 1);
+        store_b(0, 0, 1);
+        load_a(64, 0, 1);      // tile 1 stays in flight in the registers
+        load_b(64, 1, 0, 1);
         __syncthreads();
+        read_frags(0, 0, 0);
         for (int kc = 0; kc < nk; ++kc) {
-            const bool more = kc + 1 < nk;
-            if (more) load_tiles((kc + 1) << 6);
-            mma_steps(kc & 1, 4);
-            if (more) store_tiles((kc + 1) & 1);
+            const int cur = kc & 1, nxt = cur ^ 1;
+            const int k2 = (kc + 2) << 6;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                if (s < 3) read_frags(cur, s + 1, (s + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+                mma(s & 1);
+                __builtin_amdgcn_sched_barrier(0);
+                // move one quarter of tile kc+1 from registers to LDS, refill with tile kc+2
+                store_a(nxt, s, 4);
+                store_b(nxt, s, 4);
+                load_a(k2, s, 4);
+                load_b(k2, kc + 2, s, 4);
+                __builtin_amdgcn_sched_barrier(0);
+            }
             __syncthreads();
+            if (kc + 1 < nk) read_frags(nxt, 0, 0);
         }
     }
 
@@ -292,61 +405,71 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                 }
             }
             // rows: chunk c of row r belongs to step c / 2, rank indices koff + 8 (c % 2) ..
-            {
-                constexpr int CH = (BM * 8 + NT - 1) / NT;
 #pragma unroll
-                for (int i = 0; i < CH; ++i) {
-                    const int idx = tid + i * NT;
-                    const int r = idx >> 3, c = idx & 7;
-                    if (BM * 8 % NT == 0 || idx < BM * 8) {
-                        const int j = c >> 1;
-                        uint4 v = make_uint4(0, 0, 0, 0);
-                        if (j < nsteps && r >= st[j].row_lo && r < st[j].row_hi)
-                            v = ldg16(Hs + (int64_t)(m0 + r) * p.hs_ld + st[j].koff + (c & 1) * 8);
-                        *reinterpret_cast<uint4 *>(ta + tile_off(r, c)) = v;
-                    }
-                }
+            for (int i = 0; i < ACH; ++i) {
+                const int r = r8 + i * (NT / 8), c = c8;
+                const int j = c >> 1;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (j < nsteps && r >= st[j].row_lo && r < st[j].row_hi)
+                    v = ldg16(Hs + (int64_t)(m0 + r) * p.hs_ld + st[j].koff + (c & 1) * 8);
+                *reinterpret_cast<uint4 *>(ta + tile_off(r, c)) = v;
             }
             if constexpr (B_KMAJOR) {
                 // table rows are output columns: A_a[n][q], row length rank
-                constexpr int CH = (BN * 8 + NT - 1) / NT;
 #pragma unroll
-                for (int i = 0; i < CH; ++i) {
-                    const int idx = tid + i * NT;
-                    const int r = idx >> 3, c = idx & 7;
-                    if (BN * 8 % NT == 0 || idx < BN * 8) {
-                        const int j = c >> 1;
-                        uint4 v = make_uint4(0, 0, 0, 0);
-                        if (j < nsteps && n0 + r < N) {
-                            const int q0 = st[j].koff + (c & 1) * 8;
-                            const uint16_t *src = tab[j] + (int64_t)(n0 + r) * rk[j] + q0;
-                            if ((rk[j] & 7) == 0) {
-                                if (q0 < rk[j]) v = ldg16(src);
-                            } else {
-                                uint16_t e[8];
+                for (int i = 0; i < BCH; ++i) {
+                    const int r = r8 + i * (NT / 8), c = c8;
+                    const int j = c >> 1;
+                    uint4 v = make_uint4(0, 0, 0, 0);
+                    if (j < nsteps && n0 + r < N) {
+                        const int q0 = st[j].koff + (c & 1) * 8;
+                        const uint16_t *src = tab[j] + (int64_t)(n0 + r) * rk[j] + q0;
+                        if ((rk[j] & 7) == 0) {
+                            if (q0 < rk[j]) v = ldg16(src);
+                        } else {
+                            uint16_t e[8];
 #pragma unroll
-                                for (int q = 0; q < 8; ++q) e[q] = (q0 + q < rk[j]) ? src[q] : (uint16_t)0;
-                                v.x = e[0] | ((uint32_t)e[1] << 16);
-                                v.y = e[2] | ((uint32_t)e[3] << 16);
-                                v.z = e[4] | ((uint32_t)e[5] << 16);
-                                v.w = e[6] | ((uint32_t)e[7] << 16);
-                            }
+                            for (int q = 0; q < 8; ++q) e[q] = (q0 + q < rk[j]) ? src[q] : (uint16_t)0;
+                            v.x = e[0] | ((uint32_t)e[1] << 16);
+                            v.y = e[2] | ((uint32_t)e[3] << 16);
+                            v.z = e[4] | ((uint32_t)e[5] << 16);
+                            v.w = e[6] | ((uint32_t)e[7] << 16);
                         }
-                        *reinterpret_cast<uint4 *>(tb + tile_off(r, c)) = v;
                     }
+                    *reinterpret_cast<uint4 *>(tb + tile_off(r, c)) = v;
                 }
             } else {
-                // table rows are rank indices: B_a[q][n], row length ldb_ext
-                bmov_n.load(tid, N - n0, [&](int k) -> const uint16_t * {
-                    const int j = k >> 4;
-                    if (j >= nsteps) return nullptr;
-                    const int q = st[j].koff + (k & 15);
-                    return q < rk[j] ? tab[j] + (int64_t)q * p.ext_ld + n0 : nullptr;
-                });
-                bmov_n.store(tid, tb);
+                // table rows are rank indices: B_a[q][n], row length ext_ld
+                const int ng = tid % NG;
+#pragma unroll
+                for (int i = 0; i < BHU; ++i) {
+                    const int kq = (tid + i * NT) / NG;
+                    const int j = kq >> 2;  // step of this 4-row group
+                    uint4 in[4];
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) {
+                        uint4 v = make_uint4(0, 0, 0, 0);
+                        if (j < nsteps && n0 + ng * 8 < N) {
+                            const int q = st[j].koff + (kq & 3) * 4 + jj;
+                            if (q < rk[j]) v = ldg16(tab[j] + (int64_t)q * p.ext_ld + n0 + ng * 8);
+                        }
+                        in[jj] = v;
+                    }
+                    uint2 t[8];
+                    transpose4x8(in, t);
+#pragma unroll
+                    for (int jj = 0; jj < 8; ++jj)
+                        *reinterpret_cast<uint2 *>(tb + tile_off(ng * 8 + jj, kq >> 1) + (kq & 1) * 8) = t[jj];
+                }
             }
             __syncthreads();
-            mma_steps(0, nsteps);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                if (ks < nsteps) {
+                    read_frags(0, ks, 0);
+                    mma(0);
+                }
+            }
             __syncthreads();
         }
     }
@@ -354,7 +477,6 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     // ---- epilogue: one rounding to bf16, rows scattered back to their tokens --------------
     {
         uint16_t *__restrict__ Out = reinterpret_cast<uint16_t *>(p.out);
-        const int rl = lane & 31, kh = lane >> 5;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
             const int tok = row_tok[m0 + wm * WM + mi * 32 + rl];
@@ -757,13 +879,15 @@ hipError_t launch_gemm(const GemmArgs &a, int tile_cfg, bool b_kmajor, hipStream
         return b_kmajor ? launch_gemm_t<256, 128, 2, 2, true>(a, st) : launch_gemm_t<256, 128, 2, 2, false>(a, st);
     case kTile128x128:
         return b_kmajor ? launch_gemm_t<128, 128, 2, 2, true>(a, st) : launch_gemm_t<128, 128, 2, 2, false>(a, st);
+    case kTile256x256w8:
+        return b_kmajor ? launch_gemm_t<256, 256, 2, 4, true>(a, st) : launch_gemm_t<256, 256, 2, 4, false>(a, st);
     default:
         return hipErrorInvalidValue;
     }
 }
 
 int gemm_tile_rows(int tile_cfg) { return tile_cfg == kTile128x128 ? 128 : 256; }
-int gemm_tile_cols(int tile_cfg) { return tile_cfg == kTile256x256 ? 256 : 128; }
+int gemm_tile_cols(int tile_cfg) { return (tile_cfg == kTile256x256 || tile_cfg == kTile256x256w8) ? 256 : 128; }
 
 template <int RP, bool KM>
 static hipError_t launch_skinny_t(const SkinnyArgs &a, int n_items, int ksplit, hipStream_t st)

@@ -188,7 +188,8 @@ def test_many_adapters_in_one_tile_and_large_rank():
     _run_full(w)
 
 
-@pytest.mark.parametrize("tile", [binding.TILE_256x256, binding.TILE_256x128, binding.TILE_128x128])
+@pytest.mark.parametrize("tile", [binding.TILE_256x256, binding.TILE_256x128, binding.TILE_128x128,
+                                  binding.TILE_256x256_W8])
 def test_every_gemm_tile_shape(tile):
     w = _adhoc("bf16", 448, 584, [16, 32, 8], [1] * 50 + [300, 77, 200], list(np.arange(50) % 3) + [0, 1, 2],
                [0] * 50 + [1, 0, 1])
