@@ -48,6 +48,18 @@ __device__ __forceinline__ bf16x8 lds_frag(const uint8_t *tile, int row, int c)
     return *reinterpret_cast<const bf16x8 *>(tile + tile_off(row, c));
 }
 
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+// ds_read_b64_tr_b16: within each group of 16 lanes, lane s supplies the address of 4
+// consecutive 16-bit values (row s / 4, columns 4 (s % 4) ..) of a 4 x 16 block and lane i
+// receives column i of that block (checked on the device)
+__device__ __forceinline__ bf16x4 lds_tr(const uint8_t *p)
+{
+    typedef short short4v __attribute__((ext_vector_type(4)));
+    const short4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (short4v __attribute__((address_space(3))) *)(p));
+    return __builtin_bit_cast(bf16x4, v);
+}
+
 __device__ __forceinline__ uint4 ldg16(const void *p) { return *reinterpret_cast<const uint4 *>(p); }
 
 // 8x8 transpose of 16-bit values held as 8 rows of 4 dwords: out[n] holds the 8 values of
@@ -215,12 +227,16 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     constexpr int NT = WGM * WGN * 64;
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int MI = WM / 32, NI = WN / 32;
-    constexpr int STAGE = (BM + BN) * 128;
+    // second operand in LDS: K-major -> BN rows of 64 K values (swizzled chunks); N-major ->
+    // 64 rows (K) of BN values as they lie in memory, row pitch padded by 64 bytes so that the
+    // four rows a transposing read touches fall into different banks
+    constexpr int BPITCH = BN * 2 + 64;
+    constexpr int BTILE = B_KMAJOR ? BN * 128 : 64 * BPITCH;
+    constexpr int STAGE = BM * 128 + BTILE;
     constexpr int ACH = BM * 8 / NT;   // 16-byte chunks of the row tile per thread
-    constexpr int BCH = BN * 8 / NT;   // K-major second operand: chunks per thread
-    constexpr int BHU = 2 * BN / NT;   // N-major second operand: (4 k x 8 n) blocks per thread
-    constexpr int NG = BN / 8;
-    static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0 && (2 * BN) % NT == 0 && NT % NG == 0, "tile/thread mismatch");
+    constexpr int BCH = BN * 8 / NT;   // chunks of the second operand's tile per thread
+    constexpr int NG = BN / 8;         // chunks per N-major row
+    static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0 && NT % NG == 0, "tile/thread mismatch");
     static_assert(ACH % 4 == 0 || ACH == 2, "row chunks are moved in four (or two) parts per K step");
     extern __shared__ __align__(16) uint8_t smem[];
 
@@ -245,9 +261,10 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         const int tok = row_tok[m0 + r8 + i * (NT / 8)];
         aoff[i] = tok >= 0 ? (uint32_t)tok * (uint32_t)p.lda * 2u + c8 * 16u : kOob;
     }
-    constexpr int NB = B_KMAJOR ? BCH : BHU;
+    constexpr int NB = BCH;
     uint32_t boff[NB];
     uint32_t bstep = 0;  // N-major: advance of one K step, zero for columns beyond N
+    const int bng = tid % NG, bk0 = tid / NG;  // N-major: chunk column and first K row of this thread
     if constexpr (B_KMAJOR) {
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
@@ -255,19 +272,15 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
             boff[i] = n < N ? (uint32_t)n * (uint32_t)p.ldb * 2u + c8 * 16u : kOob;
         }
     } else {
-        const int ng = tid % NG;
-        const bool on = n0 + ng * 8 < N;
+        const bool on = n0 + bng * 8 < N;
         bstep = on ? 64u * (uint32_t)p.ldb * 2u : 0u;
 #pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            const int kq = (tid + i * NT) / NG;  // 4-row group 0..15 of the K step
-            boff[i] = on ? ((uint32_t)(kq * 4) * (uint32_t)p.ldb + n0 + ng * 8) * 2u : kOob;
-        }
+        for (int i = 0; i < NB; ++i)
+            boff[i] = on ? ((uint32_t)(bk0 + i * (NT / NG)) * (uint32_t)p.ldb + n0 + bng * 8) * 2u : kOob;
     }
-    const uint32_t ldb2 = (uint32_t)p.ldb * 2u;
 
     uint4 areg[ACH];
-    uint4 breg[B_KMAJOR ? BCH : BHU * 4];
+    uint4 breg[BCH];
 
     // loads part `part` of `parts` of the tile that starts at K index k0
     auto load_a = [&](int k0, int part, int parts) {
@@ -291,35 +304,20 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                 if (i * parts / NB == part) breg[i] = buf16(rb, kin ? boff[i] + (uint32_t)k0 * 2u : kOob);
         } else {
 #pragma unroll
-            for (int i = 0; i < NB; ++i)
-                if (i * parts / NB == part) {
-                    const uint32_t o = boff[i] + (uint32_t)kc * bstep;  // rows beyond K are beyond the buffer
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) breg[i * 4 + j] = buf16(rb, o + j * ldb2);
-                }
+            for (int i = 0; i < NB; ++i)  // rows beyond K lie beyond the buffer and read as zero
+                if (i * parts / NB == part) breg[i] = buf16(rb, boff[i] + (uint32_t)kc * bstep);
         }
     };
     auto store_b = [&](int stage, int part, int parts) {
         uint8_t *tb = smem + stage * STAGE + BM * 128;
-        if constexpr (B_KMAJOR) {
 #pragma unroll
-            for (int i = 0; i < NB; ++i)
-                if (i * parts / NB == part)
+        for (int i = 0; i < NB; ++i)
+            if (i * parts / NB == part) {
+                if constexpr (B_KMAJOR)
                     *reinterpret_cast<uint4 *>(tb + tile_off(r8 + i * (NT / 8), c8)) = breg[i];
-        } else {
-            const int ng = tid % NG;
-#pragma unroll
-            for (int i = 0; i < NB; ++i)
-                if (i * parts / NB == part) {
-                    const int kq = (tid + i * NT) / NG;
-                    uint4 in[4] = {breg[i * 4], breg[i * 4 + 1], breg[i * 4 + 2], breg[i * 4 + 3]};
-                    uint2 t[8];
-                    transpose4x8(in, t);
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        *reinterpret_cast<uint2 *>(tb + tile_off(ng * 8 + j, kq >> 1) + (kq & 1) * 8) = t[j];
-                }
-        }
+                else
+                    *reinterpret_cast<uint4 *>(tb + (bk0 + i * (NT / NG)) * BPITCH + bng * 16) = breg[i];
+            }
     };
 
     // acc[ni][mi] holds the transposed 32x32 block: lane = row m, registers = columns n
@@ -338,8 +336,22 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         const uint8_t *tb = ta + BM * 128;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) af[buf][mi] = lds_frag(ta, wm * WM + mi * 32 + rl, ks * 2 + kh);
+        if constexpr (B_KMAJOR) {
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) bf[buf][ni] = lds_frag(tb, wn * WN + ni * 32 + rl, ks * 2 + kh);
+            for (int ni = 0; ni < NI; ++ni) bf[buf][ni] = lds_frag(tb, wn * WN + ni * 32 + rl, ks * 2 + kh);
+        } else {
+            // transposing reads: 16 lanes fetch a 4 (K) x 16 (N) block, lane i of them reads 4
+            // values of row i / 4 and receives the 4 K values of column i
+            const int g = lane >> 4, i16 = lane & 15;
+            const uint8_t *src = tb + (ks * 16 + (g >> 1) * 8 + (i16 >> 2)) * BPITCH +
+                                 (wn * WN + (g & 1) * 16 + (i16 & 3) * 4) * 2;
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+                const bf16x4 lo = lds_tr(src + ni * 64);
+                const bf16x4 hi = lds_tr(src + ni * 64 + 4 * BPITCH);
+                bf[buf][ni] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+        }
     };
     auto mma = [&](int buf) {
 #pragma unroll
@@ -439,27 +451,18 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                     *reinterpret_cast<uint4 *>(tb + tile_off(r, c)) = v;
                 }
             } else {
-                // table rows are rank indices: B_a[q][n], row length ext_ld
-                const int ng = tid % NG;
+                // table rows are rank indices: B_a[q][n], row length ext_ld; tile row 16 j + i
+                // is rank index koff_j + i
 #pragma unroll
-                for (int i = 0; i < BHU; ++i) {
-                    const int kq = (tid + i * NT) / NG;
-                    const int j = kq >> 2;  // step of this 4-row group
-                    uint4 in[4];
-#pragma unroll
-                    for (int jj = 0; jj < 4; ++jj) {
-                        uint4 v = make_uint4(0, 0, 0, 0);
-                        if (j < nsteps && n0 + ng * 8 < N) {
-                            const int q = st[j].koff + (kq & 3) * 4 + jj;
-                            if (q < rk[j]) v = ldg16(tab[j] + (int64_t)q * p.ext_ld + n0 + ng * 8);
-                        }
-                        in[jj] = v;
+                for (int i = 0; i < NB; ++i) {
+                    const int k = bk0 + i * (NT / NG);
+                    const int j = k >> 4;
+                    uint4 v = make_uint4(0, 0, 0, 0);
+                    if (j < nsteps && n0 + bng * 8 < N) {
+                        const int q = st[j].koff + (k & 15);
+                        if (q < rk[j]) v = ldg16(tab[j] + (int64_t)q * p.ext_ld + n0 + bng * 8);
                     }
-                    uint2 t[8];
-                    transpose4x8(in, t);
-#pragma unroll
-                    for (int jj = 0; jj < 8; ++jj)
-                        *reinterpret_cast<uint2 *>(tb + tile_off(ng * 8 + jj, kq >> 1) + (kq & 1) * 8) = t[jj];
+                    *reinterpret_cast<uint4 *>(tb + k * BPITCH + bng * 16) = v;
                 }
             }
             __syncthreads();
@@ -855,7 +858,7 @@ template <int BM, int BN, int WGM, int WGN, bool KM>
 static hipError_t launch_gemm_t(const GemmArgs &a, hipStream_t st)
 {
     constexpr int NT = WGM * WGN * 64;
-    constexpr int smem = 2 * (BM + BN) * 128;
+    constexpr int smem = 2 * (BM * 128 + (KM ? BN * 128 : 64 * (BN * 2 + 64)));
     auto kern = gemm_lora_kernel<BM, BN, WGM, WGN, KM>;
     static bool attr_done = false;
     if (!attr_done) {
