@@ -33,7 +33,6 @@ int hip_fail(hipError_t e, const char *what)
     } while (0)
 
 constexpr int kSlots = 4;              // pinned staging ring
-constexpr size_t kPartialBytes = 64u << 20;  // each of the two partial-sum buffers
 constexpr int kMaxProfile = 16;
 
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
@@ -58,10 +57,6 @@ struct collm_ctx {
     void *d_dhs = nullptr;    // dh in the element type, training row order      [rows][rpad]
     float *d_h32 = nullptr;   // recomputed h, training row order                [rows][rpad]
     float *d_dh32 = nullptr;  // dh in fp32, training row order                  [rows][rpad]
-    float *d_part_skinny = nullptr;
-    float *d_part_grad = nullptr;
-    int *d_counters = nullptr;
-    int n_counters_skinny = 0, n_counters_grad = 0;
     int64_t workspace_bytes = 0;
 
     std::vector<int32_t> plan;
@@ -213,18 +208,9 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
         rq.dB = dB;
         rq.bm_all = bm_all;
         rq.bm_train = bm_train;
-        rq.grad_n_tiles = std::max(1, (std::min(s->d_in, s->d_out) + 127) / 128);
-        // partial sums of the gradient launches must fit their buffer
-        rq.grad_max_ksplit = 64;
         c->plan_valid = false;
         int rc = build_plan(rq, c->plan, c->L);
         if (rc != COLLM_OK) return rc;
-        const size_t need = (size_t)c->L.grad_part_rows * std::max(s->d_in, s->d_out) * sizeof(float);
-        if (need > kPartialBytes) {  // fall back to fewer, longer slices
-            rq.grad_max_ksplit = 1;
-            rc = build_plan(rq, c->plan, c->L);
-            if (rc != COLLM_OK) return rc;
-        }
         if ((size_t)c->L.total_ints > c->plan_cap) return COLLM_E_SHAPE;
         rc = upload(c, 0, c->L.total_ints, st);
         if (rc != COLLM_OK) return rc;
@@ -259,18 +245,6 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
     return COLLM_OK;
 }
 
-int skinny_ksplit(int n_items, int K, int rows_pad, int rpad, int &k_slice)
-{
-    int want = n_items > 0 ? (768 + n_items - 1) / n_items : 1;
-    const size_t per_split = (size_t)rows_pad * rpad * sizeof(float);
-    want = std::min<int>(want, (int)std::max<size_t>(1, kPartialBytes / per_split));
-    want = std::max(1, std::min(want, 32));
-    k_slice = round_up((K + want - 1) / want, 64);
-    // never less than 256 of K per block: below that the table load dominates
-    k_slice = std::max(k_slice, std::min(round_up(K, 64), 256));
-    return (K + k_slice - 1) / k_slice;
-}
-
 // One skinny pass over a row order.
 int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, const void *in, int K,
                int32_t off_tab, bool t_kmajor, float *f32_out, int64_t f32_ld, int f32_cols,
@@ -281,15 +255,12 @@ int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, cons
     SkinnyArgs a{};
     a.in = in;
     a.ld_in = K;
+    a.in_bytes = (uint32_t)((int64_t)s->n_tokens * K * (s->dtype == COLLM_BF16 ? 2 : 4));
     a.K = K;
     a.tab = reinterpret_cast<const uint64_t *>(c->d_plan + off_tab);
     a.items = reinterpret_cast<const SkinnyItem *>(c->d_plan + R.off_items);
     a.row_tok = c->d_plan + R.off_row_tok;
     a.tok_train = c->d_plan + c->L.off_tok_train;
-    a.partial = c->d_part_skinny;
-    a.rows_pad = R.n_rows_pad;
-    a.rpad_ld = c->L.rpad;
-    a.counters = c->d_counters;
     a.f32_out = f32_out;
     a.f32_ld = f32_ld;
     a.f32_cols = f32_cols;
@@ -300,13 +271,9 @@ int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, cons
     a.bf_mult = bf_mult;
     Prof prof(c, st, name);
     if (s->dtype == COLLM_F32) {
-        a.k_slice = K;
         HIP_TRY(launch_skinny_f32(a, R.n_items, t_kmajor, st));
     } else {
-        int k_slice = K;
-        const int ksplit = skinny_ksplit(R.n_items, K, R.n_rows_pad, c->L.rpad, k_slice);
-        a.k_slice = k_slice;
-        HIP_TRY(launch_skinny(a, R.n_items, ksplit, c->L.rpad, t_kmajor, st));
+        HIP_TRY(launch_skinny(a, R.n_items, c->L.rpad, t_kmajor, st));
     }
     return COLLM_OK;
 }
@@ -382,18 +349,11 @@ int collm_ctx_create(collm_ctx **out, int device, int32_t max_tokens, int32_t ma
         if (hipEventCreateWithFlags(&c->stage_ev[i], hipEventDisableTiming) != hipSuccess) return fail(COLLM_E_HIP);
     }
     const size_t act = (size_t)c->rows_cap * c->rpad_cap;
-    c->n_counters_skinny = c->rows_cap / kSkinnyRows + max_adapters + 8;
-    c->n_counters_grad = (max_adapters + 1) * ((max_d + 127) / 128 + 1);
-    const size_t n_counters = (size_t)c->n_counters_skinny + 2 * (size_t)c->n_counters_grad;
     if (dev_alloc((void **)&c->d_plan, c->plan_cap * sizeof(int32_t)) != hipSuccess ||
         dev_alloc(&c->d_hs, act * 4) != hipSuccess || dev_alloc(&c->d_dhs, act * 4) != hipSuccess ||
         dev_alloc((void **)&c->d_h32, act * 4) != hipSuccess ||
-        dev_alloc((void **)&c->d_dh32, act * 4) != hipSuccess ||
-        dev_alloc((void **)&c->d_part_skinny, kPartialBytes) != hipSuccess ||
-        dev_alloc((void **)&c->d_part_grad, kPartialBytes) != hipSuccess ||
-        dev_alloc((void **)&c->d_counters, n_counters * sizeof(int)) != hipSuccess)
+        dev_alloc((void **)&c->d_dh32, act * 4) != hipSuccess)
         return fail(COLLM_E_NOMEM);
-    if (hipMemset(c->d_counters, 0, n_counters * sizeof(int)) != hipSuccess) return fail(COLLM_E_HIP);
     if (hipDeviceSynchronize() != hipSuccess) return fail(COLLM_E_HIP);
     c->workspace_bytes = ws;
     *out = c;
@@ -414,7 +374,7 @@ int collm_ctx_destroy(collm_ctx *c)
             (void)hipEventDestroy(c->prof_ev[i][0]);
             (void)hipEventDestroy(c->prof_ev[i][1]);
         }
-    void *bufs[] = {c->d_plan, c->d_hs, c->d_dhs, c->d_h32, c->d_dh32, c->d_part_skinny, c->d_part_grad, c->d_counters};
+    void *bufs[] = {c->d_plan, c->d_hs, c->d_dhs, c->d_h32, c->d_dh32};
     for (void *b : bufs)
         if (b) (void)hipFree(b);
     delete c;
@@ -560,12 +520,12 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
         GradArgs ga{};
         ga.row_tok = c->d_plan + L.train.off_row_tok;
         ga.items = reinterpret_cast<const GradItem *>(c->d_plan + L.off_grad);
-        ga.slices = c->d_plan + L.off_slices;
-        ga.partial = c->d_part_grad;
         ga.accumulate = accumulate ? 1 : 0;
         // dB_a = s h^T dy
+        const int64_t esz = f32 ? 4 : 2;
         ga.big = dy;
         ga.ld_big = s->d_out;
+        ga.big_bytes = (uint32_t)((int64_t)s->n_tokens * s->d_out * esz);
         ga.N = s->d_out;
         if (h_save) {
             ga.small_ = h_save;
@@ -577,29 +537,28 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
             ga.small_by_token = 0;
         }
         ga.small_mult = s->scale;
-        ga.counters = c->d_counters + c->n_counters_skinny;
         ga.out_tab = reinterpret_cast<const uint64_t *>(c->d_plan + L.off_dB_ptr);
         ga.out_transposed = 0;
         {
             Prof prof(c, st, "grad_dB");
             if (f32) HIP_TRY(launch_grad_f32(ga, L.n_grad, st));
-            else HIP_TRY(launch_grad(ga, (s->d_out + 127) / 128, L.n_slices, L.rpad, st));
+            else HIP_TRY(launch_grad(ga, L.n_grad, L.rpad, st));
         }
         // dA_a = x^T dh
         ga.big = x;
         ga.ld_big = s->d_in;
+        ga.big_bytes = (uint32_t)((int64_t)s->n_tokens * s->d_in * esz);
         ga.N = s->d_in;
         ga.small_ = c->d_dh32;
         ga.ld_small = L.rpad;
         ga.small_by_token = 0;
         ga.small_mult = 1.0f;
-        ga.counters = c->d_counters + c->n_counters_skinny + c->n_counters_grad;
         ga.out_tab = reinterpret_cast<const uint64_t *>(c->d_plan + L.off_dA_ptr);
         ga.out_transposed = 1;
         {
             Prof prof(c, st, "grad_dA");
             if (f32) HIP_TRY(launch_grad_f32(ga, L.n_grad, st));
-            else HIP_TRY(launch_grad(ga, (s->d_in + 127) / 128, L.n_slices, L.rpad, st));
+            else HIP_TRY(launch_grad(ga, L.n_grad, L.rpad, st));
         }
     }
 

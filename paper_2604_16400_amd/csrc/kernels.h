@@ -34,15 +34,12 @@ struct GemmArgs {
 struct SkinnyArgs {
     const void *in;
     int64_t ld_in;
+    uint32_t in_bytes;        // size of the streamed tensor (below 2 GiB)
     int K;
-    int k_slice;              // K range of one blockIdx.y (multiple of 64)
     const uint64_t *tab;      // adapter -> table; [K][rank] or, K-major, [rank][K]
     const SkinnyItem *items;
     const int32_t *row_tok;
     const int32_t *tok_train;
-    float *partial;           // [ksplit][rows_pad][rpad_ld]
-    int rows_pad, rpad_ld;
-    int *counters;            // one per item, zero between launches
     float *f32_out;           // optional fp32 result
     int64_t f32_ld;
     int f32_cols;             // columns written per row (zero beyond the rank)
@@ -57,16 +54,14 @@ struct SkinnyArgs {
 struct GradArgs {
     const void *big;          // [T][N] gathered through row_tok
     int64_t ld_big;
+    uint32_t big_bytes;       // size of `big` (below 2 GiB)
     int N;
     const float *small_;      // fp32 [.][ld_small]; row = token (small_by_token) or row order
     int64_t ld_small;
     int small_by_token;
     float small_mult;
     const int32_t *row_tok;   // training row order
-    const GradItem *items;
-    const int32_t *slices;    // {item, slice} pairs, one per blockIdx.y
-    float *partial;           // [grad_part_rows][N]
-    int *counters;            // [n_grad][gridDim.x], zero between launches
+    const GradItem *items;    // one per trained adapter
     const uint64_t *out_tab;  // adapter -> fp32 output
     int out_transposed;       // 0: out[q][n] (row length N); 1: out[n][q] (row length rank)
     int accumulate;
@@ -75,8 +70,8 @@ struct GradArgs {
 hipError_t launch_gemm(const GemmArgs &a, int tile_cfg, bool b_kmajor, hipStream_t st);
 int gemm_tile_rows(int tile_cfg);
 int gemm_tile_cols(int tile_cfg);
-hipError_t launch_skinny(const SkinnyArgs &a, int n_items, int ksplit, int rpad, bool t_kmajor, hipStream_t st);
-hipError_t launch_grad(const GradArgs &a, int n_tiles, int n_slices, int rpad, hipStream_t st);
+hipError_t launch_skinny(const SkinnyArgs &a, int n_items, int rpad, bool t_kmajor, hipStream_t st);
+hipError_t launch_grad(const GradArgs &a, int n_grad, int rpad, hipStream_t st);
 
 // fp32 element type: same argument blocks, plain fp32 FMA kernels
 hipError_t launch_gemm_f32(const GemmArgs &a, bool b_kmajor, hipStream_t st);

@@ -503,352 +503,385 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 }
 
 // =========================================================================================
-// skinny: out[m][q] = sum_k in[tok(m)][k] * table_a[k][q]     (rank-wide output)
-// One block = one item (<= 64 rows of one adapter) x one K slice.  Four waves own 16 rows
-// each (16x16x32 MFMA); the adapter table tile is staged in LDS for all of them.
+// skinny: out[m][q] = sum_k in[tok(m)][k] * table_a(k, q)     (rank-wide output, HBM-bound)
+//
+// One block = one item (<= 16 rows of one adapter).  Its KW waves split K; every wave runs
+// 16x16x32 MFMAs on its own K range and the partial sums meet in LDS in wave order (fixed
+// order, no atomics).  The streamed operand (rows of x or dy) goes from global memory
+// straight into MFMA operand registers: lane l holds 8 consecutive K values of row l % 16.
+// The adapter table is either K-major ([rank][K], read the same way) or N-major ([K][rank]):
+// then each wave copies its chunk as it lies in memory into a private LDS area and builds the
+// operand with transposing reads.  Nothing in the K loop needs a block barrier.
 // =========================================================================================
+template <int RP>
+struct SkinnyCfg {
+    static constexpr int CHK = RP <= 16 ? 128 : (RP <= 64 ? 64 : 32);  // K values per chunk
+    static constexpr int STEPS = CHK / 32;
+    static constexpr int KW = RP <= 32 ? 8 : 4;                       // waves per block
+    static constexpr int NB = RP / 16;                                // 16-wide rank blocks
+    static constexpr int PITCH = RP * 2 + 16;                         // LDS row pitch of an N-major chunk
+    static constexpr int STAGE_BYTES = CHK * PITCH;                   // per wave
+    static constexpr int RED_LD = RP + 4;                             // floats
+    static constexpr int RED_BYTES = KW * 16 * RED_LD * 4;
+};
+
 template <int RP, bool T_KMAJOR>
-__global__ void __launch_bounds__(256) skinny_kernel(SkinnyArgs p)
+__global__ void __launch_bounds__(SkinnyCfg<RP>::KW * 64) skinny_kernel(SkinnyArgs p)
 {
-    constexpr int NT = 256, BM = kSkinnyRows;
-    constexpr int NI = RP / 16;
-    constexpr int STAGE = (BM + RP) * 128;
+    using C = SkinnyCfg<RP>;
+    constexpr int KW = C::KW, STEPS = C::STEPS, CHK = C::CHK, NB = C::NB;
     extern __shared__ __align__(16) uint8_t smem[];
-    __shared__ int s_last;
+    float *red = reinterpret_cast<float *>(smem);
+    uint8_t *stage = smem + C::RED_BYTES + (threadIdx.x >> 6) * C::STAGE_BYTES;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const SkinnyItem it = p.items[blockIdx.x];
-    const int ks = blockIdx.y;
-    const int K = p.K;
-    const int k_lo = ks * p.k_slice;
-    const int k_hi = (k_lo + p.k_slice) < K ? (k_lo + p.k_slice) : K;
-    const int rank = it.rank;
+    const int K = p.K, rank = it.rank;
     const int rp = (rank + 15) & ~15;
+    const int l16 = lane & 15, kg = lane >> 4;
 
-    const uint16_t *__restrict__ In = reinterpret_cast<const uint16_t *>(p.in);
-    const uint16_t *__restrict__ tab = reinterpret_cast<const uint16_t *>(p.tab[it.adapter]);
-    const int32_t *__restrict__ row_tok = p.row_tok;
+    // K range of this wave (multiple of 32 long, except at the end of K)
+    const int per = (((K + KW - 1) / KW) + 31) & ~31;
+    const int k_lo = wave * per;
+    const int k_hi = (k_lo + per) < K ? (k_lo + per) : K;
 
-    KMajorMover<BM, NT> amov;
-    KMajorMover<RP, NT> bmov_k;
-    NMajorMover<RP, NT> bmov_n;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.in, p.in_bytes);
+    const __amdgpu_buffer_rsrc_t rt = make_rsrc(reinterpret_cast<const void *>(p.tab[it.adapter]),
+                                                (uint32_t)rank * (uint32_t)K * 2u);
+    uint32_t xoff = kOob;
+    if (l16 < it.n_rows) {
+        const int tok = p.row_tok[it.row_lo + l16];
+        if (tok >= 0) xoff = (uint32_t)tok * (uint32_t)p.ld_in * 2u + kg * 16u;
+    }
 
-    auto a_row_ptr = [&](int r) -> const uint16_t * {
-        if (r >= it.n_rows) return nullptr;
-        const int tok = row_tok[it.row_lo + r];
-        return tok >= 0 ? In + (int64_t)tok * p.ld_in : nullptr;
+    uint4 xreg[2][STEPS];
+    auto load_x = [&](int k0, int buf) {
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            const int k = k0 + s * 32;
+            xreg[buf][s] = buf16(rx, (k + kg * 8 < k_hi) ? xoff + (uint32_t)k * 2u : kOob);
+        }
     };
-    auto load_tiles = [&](int k0) {
-        amov.load(tid, k0, k_hi, a_row_ptr);
-        if constexpr (T_KMAJOR) {  // table [rank][K]
-            bmov_k.load(tid, k0, k_hi, [&](int r) -> const uint16_t * {
-                return r < rank ? tab + (int64_t)r * K : nullptr;
-            });
-        } else {  // table [K][rank]; rows of `rank` elements are only 16-byte loadable if rank % 8 == 0
-            if ((rank & 7) == 0) {
-                bmov_n.load(tid, rank, [&](int k) -> const uint16_t * {
-                    return (k0 + k < k_hi) ? tab + (int64_t)(k0 + k) * rank : nullptr;
-                });
+
+    // K-major table: operand registers straight from memory
+    uint4 treg[T_KMAJOR ? 2 : 1][T_KMAJOR ? STEPS * NB : 1];
+    auto load_t_kmajor = [&](int k0, int buf) {
+        if constexpr (T_KMAJOR) {
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                const int k = k0 + s * 32 + kg * 8;
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const int q = nb * 16 + l16;
+                    treg[buf][s * NB + nb] =
+                        buf16(rt, (q < rank && k < k_hi) ? ((uint32_t)q * (uint32_t)K + (uint32_t)k) * 2u : kOob);
+                }
+            }
+        }
+    };
+    // N-major table: the chunk [CHK][rank] is contiguous; copy it to LDS rows of PITCH bytes
+    constexpr int NCP = T_KMAJOR ? 1 : (CHK * RP * 2 / 16 + 63) / 64;  // 16-byte pieces per lane
+    uint4 creg[NCP];
+    const bool fast_copy = (rank & 7) == 0;
+    const int cpr = rank >> 3;  // 16-byte pieces per table row
+    auto load_t_nmajor = [&](int k0) {
+        if constexpr (!T_KMAJOR) {
+            if (fast_copy) {
+#pragma unroll
+                for (int i = 0; i < NCP; ++i) {
+                    const int c = lane + i * 64;
+                    const bool in = c < CHK * cpr;
+                    // rows beyond K lie beyond the table and read as zero
+                    creg[i] = buf16(rt, in ? ((uint32_t)k0 * (uint32_t)rank) * 2u + (uint32_t)c * 16u : kOob);
+                }
+            }
+        }
+    };
+    auto store_t_nmajor = [&](int k0) {
+        if constexpr (!T_KMAJOR) {
+            if (fast_copy) {
+#pragma unroll
+                for (int i = 0; i < NCP; ++i) {
+                    const int c = lane + i * 64;
+                    if (c < CHK * cpr) {
+                        const int r = c / cpr, cc = c - r * cpr;
+                        *reinterpret_cast<uint4 *>(stage + r * C::PITCH + cc * 16) = creg[i];
+                    }
+                }
             } else {
-#pragma unroll
-                for (int u = 0; u < bmov_n.UN; ++u) {
-                    const int idx = tid + u * NT;
-                    const int ng = idx % bmov_n.NG, kg = idx / bmov_n.NG;
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        uint16_t e[8];
-                        const int k = k0 + kg * 8 + j;
-#pragma unroll
-                        for (int q = 0; q < 8; ++q) {
-                            const int col = ng * 8 + q;
-                            e[q] = ((RP % NT == 0 || idx < RP) && k < k_hi && col < rank)
-                                       ? tab[(int64_t)k * rank + col]
-                                       : (uint16_t)0;
-                        }
-                        bmov_n.reg[u][j] = make_uint4(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16),
-                                                      e[4] | ((uint32_t)e[5] << 16), e[6] | ((uint32_t)e[7] << 16));
-                    }
+                // ranks that are no multiple of 8: element by element
+                const uint16_t *tab = reinterpret_cast<const uint16_t *>(p.tab[it.adapter]);
+                for (int e = lane; e < CHK * rank; e += 64) {
+                    const int r = e / rank, q = e - r * rank;
+                    const int k = k0 + r;
+                    reinterpret_cast<uint16_t *>(stage + r * C::PITCH)[q] = k < K ? tab[(int64_t)k * rank + q] : (uint16_t)0;
                 }
             }
         }
     };
-    auto store_tiles = [&](int stage) {
-        uint8_t *ta = smem + stage * STAGE;
-        uint8_t *tb = ta + BM * 128;
-        amov.store(tid, ta);
-        if constexpr (T_KMAJOR) bmov_k.store(tid, tb);
-        else bmov_n.store(tid, tb);
-    };
 
-    floatx4 acc[NI];
+    floatx4 acc[NB];
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) acc[ni] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int nb = 0; nb < NB; ++nb) acc[nb] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    const int nk = (k_hi - k_lo + 63) >> 6;
-    if (nk > 0) {
-        load_tiles(k_lo);
-        store_tiles(0);
-        __syncthreads();
-        for (int kc = 0; kc < nk; ++kc) {
-            const bool more = kc + 1 < nk;
-            if (more) load_tiles(k_lo + ((kc + 1) << 6));
-            {
-                const uint8_t *ta = smem + (kc & 1) * STAGE;
-                const uint8_t *tb = ta + BM * 128;
-                const int rl = lane & 15, kq = lane >> 4;
+    if (k_lo < k_hi) {
+        load_x(k_lo, 0);
+        load_t_kmajor(k_lo, 0);
+        load_t_nmajor(k_lo);
+        int buf = 0;
+        for (int k0 = k_lo; k0 < k_hi; k0 += CHK, buf ^= 1) {
+            store_t_nmajor(k0);
+            // next chunk in flight while this one multiplies
+            load_x(k0 + CHK, buf ^ 1);
+            load_t_kmajor(k0 + CHK, buf ^ 1);
+            load_t_nmajor(k0 + CHK);
 #pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    const bf16x8 af = lds_frag(ta, wave * 16 + rl, s * 4 + kq);
+            for (int s = 0; s < STEPS; ++s) {
+                const bf16x8 xf = __builtin_bit_cast(bf16x8, xreg[buf][s]);
 #pragma unroll
-                    for (int ni = 0; ni < NI; ++ni) {
-                        if (ni * 16 < rp) {
-                            const bf16x8 bf = lds_frag(tb, ni * 16 + rl, s * 4 + kq);
-                            acc[ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bf, af, acc[ni], 0, 0, 0);
+                for (int nb = 0; nb < NB; ++nb) {
+                    if (nb * 16 < rp) {
+                        bf16x8 tf;
+                        if constexpr (T_KMAJOR) {
+                            tf = __builtin_bit_cast(bf16x8, treg[buf][s * NB + nb]);
+                        } else {
+                            const uint8_t *src = stage + (s * 32 + kg * 8 + (l16 >> 2)) * C::PITCH +
+                                                 (nb * 16 + (l16 & 3) * 4) * 2;
+                            const bf16x4 lo = lds_tr(src), hi = lds_tr(src + 4 * C::PITCH);
+                            tf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                         }
+                        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tf, xf, acc[nb], 0, 0, 0);
                     }
                 }
             }
-            if (more) store_tiles((kc + 1) & 1);
-            __syncthreads();
         }
     }
 
-    // lane holds row m = wave*16 + lane%16, columns q = ni*16 + 4*(lane/16) + 0..3
-    const int m = wave * 16 + (lane & 15);
-    const int qb = 4 * (lane >> 4);
-    const int n_split = gridDim.y;
-    if (n_split > 1) {
-        float *part = p.partial + ((int64_t)ks * p.rows_pad + it.row_lo) * p.rpad_ld;
-        if (m < it.n_rows) {
+    // lane holds row m = lane % 16, columns q = nb*16 + 4*(lane/16) + 0..3
+    {
+        float *mine = red + (wave * 16 + l16) * C::RED_LD;
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-                if (ni * 16 < rp)
-                    *reinterpret_cast<floatx4 *>(part + (int64_t)m * p.rpad_ld + ni * 16 + qb) = acc[ni];
-        }
-        __threadfence();
-        __syncthreads();
-        if (tid == 0) {
-            const int old = atomicAdd(p.counters + blockIdx.x, 1);
-            s_last = (old == n_split - 1);
-            if (s_last) p.counters[blockIdx.x] = 0;  // ready for the next launch
-        }
-        __syncthreads();
-        if (!s_last) return;
-        __threadfence();
-        if (m < it.n_rows) {
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
-                if (ni * 16 < rp) {
-                    floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};
-                    for (int s = 0; s < n_split; ++s) {
-                        const float *ps = p.partial + ((int64_t)s * p.rows_pad + it.row_lo + m) * p.rpad_ld + ni * 16 + qb;
-                        sum += *reinterpret_cast<const floatx4 *>(ps);
-                    }
-                    acc[ni] = sum;
-                }
-            }
-        }
+        for (int nb = 0; nb < NB; ++nb)
+            *reinterpret_cast<floatx4 *>(mine + nb * 16 + kg * 4) = acc[nb];
     }
-    if (m >= it.n_rows) return;
+    __syncthreads();
 
-    // finalize: fp32 copy (token-indexed h_save or row-indexed workspace) and scaled bf16 copy
-    const int row = it.row_lo + m;
-    const int tok = row_tok[row];
-    float *f32_row = nullptr;
-    if (p.f32_out) {
-        if (p.f32_by_token) {
-            if (p.tok_train[tok]) f32_row = p.f32_out + (int64_t)tok * p.f32_ld;
-        } else {
-            f32_row = p.f32_out + (int64_t)row * p.f32_ld;
-        }
-    }
-    uint16_t *bf_row = p.bf_out ? reinterpret_cast<uint16_t *>(p.bf_out) + (int64_t)row * p.bf_ld : nullptr;
+    // sum over the waves in wave order, then write the fp32 copy (token-indexed h_save or
+    // row-indexed workspace) and the scaled copy in the element type
+    for (int idx = tid; idx < 16 * (RP / 4); idx += KW * 64) {
+        const int m = idx & 15, q = (idx >> 4) * 4;
+        if (m >= it.n_rows || q >= rp) continue;
+        floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) {
-        if (ni * 16 < rp) {
-            const int q = ni * 16 + qb;
-            float v[4];
+        for (int w = 0; w < KW; ++w) sum += *reinterpret_cast<const floatx4 *>(red + (w * 16 + m) * C::RED_LD + q);
+        float v[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = (q + e < rank) ? acc[ni][e] : 0.f;
-            if (f32_row) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (q + e < p.f32_cols) f32_row[q + e] = v[e] * p.f32_mult;
-            }
-            if (bf_row) {
-                uint2 o;
-                o.x = pack_bf16(v[0] * p.bf_mult, v[1] * p.bf_mult);
-                o.y = pack_bf16(v[2] * p.bf_mult, v[3] * p.bf_mult);
-                *reinterpret_cast<uint2 *>(bf_row + q) = o;
+        for (int e = 0; e < 4; ++e) v[e] = (q + e < rank) ? sum[e] : 0.f;
+        const int row = it.row_lo + m;
+        const int tok = p.row_tok[row];
+        float *f32_row = nullptr;
+        if (p.f32_out) {
+            if (p.f32_by_token) {
+                if (p.tok_train[tok]) f32_row = p.f32_out + (int64_t)tok * p.f32_ld;
+            } else {
+                f32_row = p.f32_out + (int64_t)row * p.f32_ld;
             }
         }
-    }
-    // zero fill of the fp32 row beyond the padded rank (h_save is max_rank wide)
-    if (f32_row) {
-        for (int q = rp + qb; q < p.f32_cols; q += 16)
+        if (f32_row) {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                if (q + e < p.f32_cols) f32_row[q + e] = 0.f;
+                if (q + e < p.f32_cols) f32_row[q + e] = v[e] * p.f32_mult;
+            // zero fill beyond the padded rank (h_save rows are max_rank wide)
+            if (q + 4 == rp)
+                for (int z = rp; z < p.f32_cols; ++z) f32_row[z] = 0.f;
+        }
+        if (p.bf_out) {
+            uint16_t *bf_row = reinterpret_cast<uint16_t *>(p.bf_out) + (int64_t)row * p.bf_ld;
+            uint2 o;
+            o.x = pack_bf16(v[0] * p.bf_mult, v[1] * p.bf_mult);
+            o.y = pack_bf16(v[2] * p.bf_mult, v[3] * p.bf_mult);
+            *reinterpret_cast<uint2 *>(bf_row + q) = o;
+        }
     }
 }
 
 // =========================================================================================
-// grad: out_a[q][n] = mult * sum_t small[t][q] * big[tok(t)][n]   over the adapter's rows t
-// (dB_a: small = h, big = dy;  dA_a^T: small = dh, big = x).  One block = one slice of one
-// adapter's training rows x 128 output columns; 4 waves own 32 columns each.
+// grad: out_a(q, n) = sum_t small[t][q] * big[tok(t)][n]   over the adapter's training rows t
+// (dB_a: small = s h, big = dy;  dA_a^T: small = dh, big = x).
+//
+// One block = one trained adapter x 64 output columns (x one 128-wide slice of the rank).
+// Its KW waves split the adapter's rows; each wave copies 32 rows of `big` (64 columns, as
+// they lie in memory) and of `small` (converted to bf16) into a private LDS area and builds
+// both 16x16x32 MFMA operands with transposing reads, since the contraction index (the
+// token) is the slow index of both.  The partial sums of the waves meet in LDS in wave
+// order: fixed order, no atomics, one writer per output element.
 // =========================================================================================
 template <int RP>
-__global__ void __launch_bounds__(256) grad_kernel(GradArgs p)
+struct GradCfg {
+    static constexpr int KW = RP <= 32 ? 8 : 4;
+    static constexpr int CHT = 32;                 // rows per chunk = one MFMA K step
+    static constexpr int MB = RP / 16;
+    static constexpr int BPITCH = 64 * 2 + 32;     // bytes
+    static constexpr int SPITCH = RP * 2 + 16;
+    static constexpr int STAGE_BYTES = CHT * (BPITCH + SPITCH);  // per wave
+    static constexpr int RED_LD = 65;              // floats
+    static constexpr int RED_BYTES = KW * RP * RED_LD * 4;
+    static constexpr int SMEM = (KW * STAGE_BYTES > RED_BYTES) ? KW * STAGE_BYTES : RED_BYTES;
+    static constexpr int SV = CHT * RP / 4 / 64;   // float4 pieces of `small` per lane
+    static constexpr int SROW = 64 * 4 / RP;       // rows advanced per piece index
+};
+
+template <int RP>
+__global__ void __launch_bounds__(GradCfg<RP>::KW * 64) grad_kernel(GradArgs p)
 {
-    constexpr int NT = 256, BN = 128;
-    constexpr int MI = RP / 32;
-    constexpr int STAGE = (RP + BN) * 128;
+    using C = GradCfg<RP>;
+    constexpr int KW = C::KW, MB = C::MB, SV = C::SV;
     extern __shared__ __align__(16) uint8_t smem[];
-    __shared__ int s_last;
-
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n0 = blockIdx.x * BN;
-    const int gi = p.slices[2 * blockIdx.y], sl = p.slices[2 * blockIdx.y + 1];
-    const GradItem it = p.items[gi];
-    const int rank = it.rank;
-    const int rp16 = (rank + 15) & ~15;
-    const int t_lo = it.row_lo + sl * it.slice_rows;
-    const int t_hi = (t_lo + it.slice_rows) < it.row_hi ? (t_lo + it.slice_rows) : it.row_hi;
-    const int N = p.N;
+    uint8_t *stage_b = smem + wave * C::STAGE_BYTES;
+    uint8_t *stage_s = stage_b + C::CHT * C::BPITCH;
+    float *red = reinterpret_cast<float *>(smem);
 
-    const uint16_t *__restrict__ Big = reinterpret_cast<const uint16_t *>(p.big);
+    const int n0 = blockIdx.x * 64;
+    const GradItem it = p.items[blockIdx.y];
+    const int q0 = blockIdx.z * RP;
+    const int rank = it.rank;
+    const int N = p.N;
+    const int l16 = lane & 15, kg = lane >> 4;
+
+    const int n_rows = it.row_hi - it.row_lo;
+    const int per = (((n_rows + KW - 1) / KW) + 31) & ~31;
+    const int t_lo = it.row_lo + wave * per;
+    const int t_hi = (t_lo + per) < it.row_hi ? (t_lo + per) : it.row_hi;
+
+    const __amdgpu_buffer_rsrc_t rbig = make_rsrc(p.big, p.big_bytes);
     const int32_t *__restrict__ row_tok = p.row_tok;
     const float *__restrict__ Small = p.small_;
 
-    NMajorMover<BN, NT> bmov;
-    constexpr int SU = RP * 8 / NT;  // (q, chunk) units of the small operand per thread
-    uint4 sreg[SU];
+    // big: lane copies chunk column c = lane % 8 of rows lane / 8 + 8 i
+    const int bc = lane & 7, br = lane >> 3;
+    const uint32_t bcol = (n0 + bc * 8 < N) ? (uint32_t)(n0 + bc * 8) * 2u : kOob;
+    // small: lane converts the float4 piece (row sr + SROW i, columns 4 sq ..)
+    const int sq = lane % (RP / 4), sr = lane / (RP / 4);
+    const bool small_vec = (p.ld_small & 3) == 0;
 
-    auto load_tiles = [&](int t0) {
-        bmov.load(tid, N - n0, [&](int k) -> const uint16_t * {
-            const int t = t0 + k;
-            if (t >= t_hi) return nullptr;
-            return Big + (int64_t)row_tok[t] * p.ld_big + n0;
-        });
+    int tokb[4], toks[SV];  // token of each row this lane touches in the next chunk (-1: none)
+    auto load_toks = [&](int t0) {
 #pragma unroll
-        for (int u = 0; u < SU; ++u) {
-            const int idx = tid + u * NT;
-            const int q = idx % RP, c = idx / RP;
-            float v[8];
+        for (int i = 0; i < 4; ++i) {
+            const int t = t0 + br + i * 8;
+            tokb[i] = t < t_hi ? row_tok[t] : -1;
+        }
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int t = t0 + c * 8 + j;
-                float x = 0.f;
-                if (t < t_hi && q < rank) {
-                    const int64_t r = p.small_by_token ? (int64_t)row_tok[t] : (int64_t)t;
-                    x = Small[r * p.ld_small + q] * p.small_mult;
-                }
-                v[j] = x;
-            }
-            sreg[u] = make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]),
-                                 pack_bf16(v[6], v[7]));
+        for (int i = 0; i < SV; ++i) {
+            const int t = t0 + sr + i * C::SROW;
+            toks[i] = t < t_hi ? (p.small_by_token ? row_tok[t] : t) : -1;
         }
     };
-    auto store_tiles = [&](int stage) {
-        uint8_t *ts = smem + stage * STAGE;
-        uint8_t *tb = ts + RP * 128;
+    uint4 breg[4];
+    floatx4 sreg[SV];
+    auto load_data = [&]() {
 #pragma unroll
-        for (int u = 0; u < SU; ++u) {
-            const int idx = tid + u * NT;
-            const int q = idx % RP, c = idx / RP;
-            *reinterpret_cast<uint4 *>(ts + tile_off(q, c)) = sreg[u];
+        for (int i = 0; i < 4; ++i)
+            breg[i] = buf16(rbig, (tokb[i] >= 0 && bcol != kOob) ? (uint32_t)tokb[i] * (uint32_t)p.ld_big * 2u + bcol : kOob);
+#pragma unroll
+        for (int i = 0; i < SV; ++i) {
+            floatx4 v = floatx4{0.f, 0.f, 0.f, 0.f};
+            const int q = q0 + sq * 4;
+            if (toks[i] >= 0 && q < rank) {
+                const float *src = Small + (int64_t)toks[i] * p.ld_small + q;
+                if (small_vec) {
+                    v = *reinterpret_cast<const floatx4 *>(src);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (q + e < rank) v[e] = src[e];
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (q + e >= rank) v[e] = 0.f;
+            }
+            sreg[i] = v;
         }
-        bmov.store(tid, tb);
+    };
+    auto store_data = [&]() {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4 *>(stage_b + (br + i * 8) * C::BPITCH + bc * 16) = breg[i];
+#pragma unroll
+        for (int i = 0; i < SV; ++i) {
+            uint2 o;
+            o.x = pack_bf16(sreg[i][0] * p.small_mult, sreg[i][1] * p.small_mult);
+            o.y = pack_bf16(sreg[i][2] * p.small_mult, sreg[i][3] * p.small_mult);
+            *reinterpret_cast<uint2 *>(stage_s + (sr + i * C::SROW) * C::SPITCH + sq * 8) = o;
+        }
     };
 
-    floatx16 acc[MI];
+    floatx4 acc[MB][4];
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) acc[mi][j] = 0.f;
+        for (int nb = 0; nb < 4; ++nb) acc[mb][nb] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    const int nk = (t_hi - t_lo + 63) >> 6;
-    if (nk > 0) {
-        load_tiles(t_lo);
-        store_tiles(0);
-        __syncthreads();
-        for (int kc = 0; kc < nk; ++kc) {
-            const bool more = kc + 1 < nk;
-            if (more) load_tiles(t_lo + ((kc + 1) << 6));
-            {
-                const uint8_t *ts = smem + (kc & 1) * STAGE;
-                const uint8_t *tb = ts + RP * 128;
-                const int rl = lane & 31, kh = lane >> 5;
+    if (t_lo < t_hi) {
+        load_toks(t_lo);
+        load_data();
+        load_toks(t_lo + C::CHT);
+        for (int t0 = t_lo; t0 < t_hi; t0 += C::CHT) {
+            store_data();
+            load_data();                      // rows of the next chunk (tokens fetched one chunk ahead)
+            load_toks(t0 + 2 * C::CHT);
+            const int rrow = kg * 8 + (l16 >> 2), rcol = (l16 & 3) * 4;
+            bf16x8 bf[4];
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    const bf16x8 bf = lds_frag(tb, wave * 32 + rl, s * 2 + kh);
+            for (int nb = 0; nb < 4; ++nb) {
+                const uint8_t *src = stage_b + rrow * C::BPITCH + (nb * 16 + rcol) * 2;
+                const bf16x4 lo = lds_tr(src), hi = lds_tr(src + 4 * C::BPITCH);
+                bf[nb] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
 #pragma unroll
-                    for (int mi = 0; mi < MI; ++mi) {
-                        if (mi * 32 < rp16) {
-                            const bf16x8 sf = lds_frag(ts, mi * 32 + rl, s * 2 + kh);
-                            acc[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf, bf, acc[mi], 0, 0, 0);
-                        }
-                    }
+            for (int mb = 0; mb < MB; ++mb) {
+                if (q0 + mb * 16 < rank) {
+                    const uint8_t *src = stage_s + rrow * C::SPITCH + (mb * 16 + rcol) * 2;
+                    const bf16x4 lo = lds_tr(src), hi = lds_tr(src + 4 * C::SPITCH);
+                    const bf16x8 sf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+                    for (int nb = 0; nb < 4; ++nb)
+                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf, bf[nb], acc[mb][nb], 0, 0, 0);
                 }
             }
-            if (more) store_tiles((kc + 1) & 1);
-            __syncthreads();
         }
     }
 
-    // lane holds column n, register j of block mi holds row q = mi*32 + 8*(j/4) + 4*(lane/32) + j%4
-    const int n = n0 + wave * 32 + (lane & 31);
-    const int kh = lane >> 5;
-    if (it.ksplit > 1) {
-        float *part = p.partial + ((int64_t)it.part_row + (int64_t)sl * rp16) * N;
-        if (n < N) {
+    __syncthreads();  // every wave is done with its staging area: the sums may reuse it
+    // lane holds column n = nb*16 + lane%16, rows q = mb*16 + 4*(lane/16) + j
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int q = mi * 32 + 8 * (j >> 2) + 4 * kh + (j & 3);
-                    if (q < rp16) part[(int64_t)q * N + n] = acc[mi][j];
-                }
-        }
-        __threadfence();
-        __syncthreads();
-        int *counter = p.counters + gi * gridDim.x + blockIdx.x;
-        if (tid == 0) {
-            const int old = atomicAdd(counter, 1);
-            s_last = (old == it.ksplit - 1);
-            if (s_last) *counter = 0;
-        }
-        __syncthreads();
-        if (!s_last) return;
-        __threadfence();
-        if (n < N) {
+        for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int q = mi * 32 + 8 * (j >> 2) + 4 * kh + (j & 3);
-                    float sum = 0.f;
-                    if (q < rp16) {
-                        const float *ps = p.partial + ((int64_t)it.part_row + q) * N + n;
-                        for (int s = 0; s < it.ksplit; ++s) sum += ps[(int64_t)s * rp16 * N];
-                    }
-                    acc[mi][j] = sum;
-                }
-        }
-    }
-    if (n >= N) return;
+            for (int j = 0; j < 4; ++j)
+                red[(wave * RP + mb * 16 + kg * 4 + j) * C::RED_LD + nb * 16 + l16] = acc[mb][nb][j];
+    __syncthreads();
+
     float *out = reinterpret_cast<float *>(p.out_tab[it.adapter]);
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const int q = mi * 32 + 8 * (j >> 2) + 4 * kh + (j & 3);
-            if (q < rank) {
-                float *dst = p.out_transposed ? out + (int64_t)n * rank + q : out + (int64_t)q * N + n;
-                const float v = acc[mi][j];
-                *dst = p.accumulate ? (*dst + v) : v;
-            }
+    const int qn = (rank - q0) < RP ? (rank - q0) : RP;  // rank indices of this slice
+    if (qn <= 0) return;
+    for (int idx = tid; idx < 64 * qn; idx += KW * 64) {
+        int q, n;
+        if (p.out_transposed) {
+            n = idx / qn;
+            q = idx - n * qn;
+        } else {
+            q = idx >> 6;
+            n = idx & 63;
         }
+        if (n0 + n >= N) continue;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < KW; ++w) sum += red[(w * RP + q) * C::RED_LD + n];
+        float *dst = p.out_transposed ? out + (int64_t)(n0 + n) * rank + q0 + q : out + (int64_t)(q0 + q) * N + n0 + n;
+        *dst = p.accumulate ? (*dst + sum) : sum;
+    }
 }
 
 // =========================================================================================
@@ -893,9 +926,10 @@ int gemm_tile_rows(int tile_cfg) { return tile_cfg == kTile128x128 ? 128 : 256; 
 int gemm_tile_cols(int tile_cfg) { return (tile_cfg == kTile256x256 || tile_cfg == kTile256x256w8) ? 256 : 128; }
 
 template <int RP, bool KM>
-static hipError_t launch_skinny_t(const SkinnyArgs &a, int n_items, int ksplit, hipStream_t st)
+static hipError_t launch_skinny_t(const SkinnyArgs &a, int n_items, hipStream_t st)
 {
-    constexpr int smem = 2 * (kSkinnyRows + RP) * 128;
+    using C = SkinnyCfg<RP>;
+    constexpr int smem = C::RED_BYTES + (KM ? 0 : C::KW * C::STAGE_BYTES);
     auto kern = skinny_kernel<RP, KM>;
     static bool attr_done = false;
     if (!attr_done) {
@@ -904,16 +938,16 @@ static hipError_t launch_skinny_t(const SkinnyArgs &a, int n_items, int ksplit, 
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(n_items, ksplit), dim3(256), smem, st, a);
+    hipLaunchKernelGGL(kern, dim3(n_items), dim3(C::KW * 64), smem, st, a);
     return hipGetLastError();
 }
 
-hipError_t launch_skinny(const SkinnyArgs &a, int n_items, int ksplit, int rpad, bool t_kmajor, hipStream_t st)
+hipError_t launch_skinny(const SkinnyArgs &a, int n_items, int rpad, bool t_kmajor, hipStream_t st)
 {
     if (n_items <= 0) return hipSuccess;
-#define COLLM_SK(RP)                                                                         \
-    return t_kmajor ? launch_skinny_t<RP, true>(a, n_items, ksplit, st)                      \
-                    : launch_skinny_t<RP, false>(a, n_items, ksplit, st)
+#define COLLM_SK(RP) \
+    return t_kmajor ? launch_skinny_t<RP, true>(a, n_items, st) : launch_skinny_t<RP, false>(a, n_items, st)
+    if (rpad <= 16) { COLLM_SK(16); }
     if (rpad <= 32) { COLLM_SK(32); }
     if (rpad <= 64) { COLLM_SK(64); }
     if (rpad <= 128) { COLLM_SK(128); }
@@ -922,28 +956,29 @@ hipError_t launch_skinny(const SkinnyArgs &a, int n_items, int ksplit, int rpad,
 }
 
 template <int RP>
-static hipError_t launch_grad_t(const GradArgs &a, int n_tiles, int n_slices, hipStream_t st)
+static hipError_t launch_grad_t(const GradArgs &a, int n_grad, int rpad, hipStream_t st)
 {
-    constexpr int smem = 2 * (RP + 128) * 128;
+    using C = GradCfg<RP>;
     auto kern = grad_kernel<RP>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(n_tiles, n_slices), dim3(256), smem, st, a);
+    const dim3 grid((a.N + 63) / 64, n_grad, (rpad + RP - 1) / RP);
+    hipLaunchKernelGGL(kern, grid, dim3(C::KW * 64), C::SMEM, st, a);
     return hipGetLastError();
 }
 
-hipError_t launch_grad(const GradArgs &a, int n_tiles, int n_slices, int rpad, hipStream_t st)
+hipError_t launch_grad(const GradArgs &a, int n_grad, int rpad, hipStream_t st)
 {
-    if (n_tiles <= 0 || n_slices <= 0) return hipSuccess;
-    if (rpad <= 32) return launch_grad_t<32>(a, n_tiles, n_slices, st);
-    if (rpad <= 64) return launch_grad_t<64>(a, n_tiles, n_slices, st);
-    if (rpad <= 128) return launch_grad_t<128>(a, n_tiles, n_slices, st);
-    return launch_grad_t<256>(a, n_tiles, n_slices, st);
+    if (n_grad <= 0 || a.N <= 0) return hipSuccess;
+    if (rpad <= 16) return launch_grad_t<16>(a, n_grad, rpad, st);
+    if (rpad <= 32) return launch_grad_t<32>(a, n_grad, rpad, st);
+    if (rpad <= 64) return launch_grad_t<64>(a, n_grad, rpad, st);
+    return launch_grad_t<128>(a, n_grad, rpad, st);  // larger ranks: 128-wide slices on grid.z
 }
 
 }  // namespace collm

@@ -16,7 +16,7 @@ namespace collm {
 
 constexpr int kRowPad = 256;   // row orders are padded to a multiple of the largest GEMM tile
 constexpr int kMaxRank = 256;  // largest adapter rank the kernels accept
-constexpr int kSkinnyRows = 64;  // rows of one skinny work item
+constexpr int kSkinnyRows = 16;  // rows of one skinny work item (one MFMA tile)
 constexpr int kKStep = 16;       // K extent of one low-rank extension step (one MFMA K)
 
 // Run of rows of one adapter inside a row order (never crosses an adapter boundary).
@@ -39,10 +39,6 @@ struct ExtStep {
 struct GradItem {
     int32_t adapter;
     int32_t row_lo, row_hi;  // rows of the training row order
-    int32_t ksplit;          // number of token slices the sum over rows is cut into
-    int32_t slice_rows;      // rows per slice (multiple of 64)
-    int32_t part_row;        // first row of this item's partial sums (units of output rows)
-    int32_t slice0;          // index of this item's first slice in the slice table
     int32_t rank;
 };
 
@@ -72,8 +68,6 @@ struct PlanLayout {
     RowOrderLayout all;           // every token (forward)
     RowOrderLayout train;         // training tokens (backward)
     int32_t n_grad = 0, off_grad = 0;        // GradItem[n_grad]
-    int32_t n_slices = 0, off_slices = 0;    // int2 {grad item, slice index} [n_slices]
-    int32_t grad_part_rows = 0;              // total rows of partial sums (x d gives floats)
     int32_t total_ints = 0;
 };
 

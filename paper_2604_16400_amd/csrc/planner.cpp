@@ -203,36 +203,9 @@ int build_plan(const PlanRequest &rq, std::vector<int32_t> &blk, PlanLayout &L)
             r = e;
         }
     }
-    // Cut the sum over tokens into slices so that one launch has enough blocks to fill the
-    // GPU; slices are multiples of 64 rows and every item gets at least one.
-    {
-        const int n_items = std::max<int>(1, (int)grad.size());
-        int want = (rq.grad_target_blocks + rq.grad_n_tiles * n_items - 1) /
-                   std::max(1, rq.grad_n_tiles * n_items);
-        want = std::max(1, std::min(want, rq.grad_max_ksplit));
-        int part_row = 0, slice0 = 0;
-        for (auto &g : grad) {
-            const int rows = g.row_hi - g.row_lo;
-            int slice_rows = round_up((rows + want - 1) / want, 64);
-            g.slice_rows = slice_rows;
-            g.ksplit = (rows + slice_rows - 1) / slice_rows;
-            g.part_row = part_row;
-            g.slice0 = slice0;
-            part_row += g.ksplit * round_up(g.rank, kKStep);
-            slice0 += g.ksplit;
-        }
-        L.grad_part_rows = part_row;
-        L.n_slices = slice0;
-    }
     L.n_grad = (int)grad.size();
-    L.off_grad = b.alloc(grad.size() * 8 + 8);
+    L.off_grad = b.alloc(grad.size() * 4 + 4);
     if (!grad.empty()) std::memcpy(blk.data() + L.off_grad, grad.data(), grad.size() * sizeof(GradItem));
-    L.off_slices = b.alloc((size_t)L.n_slices * 2 + 2);
-    for (int i = 0; i < L.n_grad; ++i)
-        for (int k = 0; k < grad[i].ksplit; ++k) {
-            blk[L.off_slices + 2 * (grad[i].slice0 + k)] = i;
-            blk[L.off_slices + 2 * (grad[i].slice0 + k) + 1] = k;
-        }
     b.alloc(0, 64);
     L.total_ints = (int32_t)blk.size();
     return COLLM_OK;
@@ -253,8 +226,7 @@ size_t plan_ints_upper_bound(int max_tokens, int max_segments, int max_adapters,
         n += Tp / 64 + 8;                // ext_off (smallest tile 64 rows)
         n += 4 * steps * (Tp / 64 + N) + 8;           // ext steps: (tiles + adapter runs) x steps
     }
-    n += 8 * N + 8;                      // grad items
-    n += 2 * (Tp / 64 + N) + 8;          // slices
+    n += 4 * N + 8;                      // grad items
     return n + 1024;
 }
 

@@ -31,9 +31,6 @@ struct PlanRequest {
     float *const *dB = nullptr;
     int bm_all = 256;    // GEMM row tile of the forward GEMM
     int bm_train = 256;  // GEMM row tile of the dX GEMM
-    int grad_n_tiles = 1;          // column tiles of the narrower gradient launch
-    int grad_target_blocks = 384;  // blocks wanted per gradient launch
-    int grad_max_ksplit = 64;
 };
 
 // Builds the plan block for a batch that passed validate_batch.
