@@ -124,12 +124,25 @@ def collm_token_map(seg_start, seg_adapter, seg_is_train, n_tokens: Optional[int
     return ts, ta, tt
 
 
-def _ptr_table(tensors: Optional[Sequence], n: int):
-    tab = (ctypes.c_void_p * max(n, 1))()
-    if tensors is not None:
-        for i, t in enumerate(tensors):
-            tab[i] = None if t is None else t.data_ptr()
-    return tab
+class PointerTable:
+    """A HOST array of device pointers built once from a list of tensors (entries may be
+    None).  Passing the same PointerTable to many calls skips rebuilding the array; the
+    tensors are kept alive by the table."""
+
+    def __init__(self, tensors: Sequence):
+        self.tensors = list(tensors)
+        self.array = (ctypes.c_void_p * max(len(self.tensors), 1))()
+        for i, t in enumerate(self.tensors):
+            self.array[i] = None if t is None else t.data_ptr()
+
+    def __len__(self):
+        return len(self.tensors)
+
+
+def _ptr_table(tensors, n: int):
+    if isinstance(tensors, PointerTable):
+        return tensors.array
+    return PointerTable(tensors if tensors is not None else [None] * n).array
 
 
 class Context:

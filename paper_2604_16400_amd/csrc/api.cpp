@@ -6,6 +6,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "collm_lora.h"
@@ -32,7 +33,7 @@ int hip_fail(hipError_t e, const char *what)
         if (e_ != hipSuccess) return hip_fail(e_, #expr); \
     } while (0)
 
-constexpr int kSlots = 4;              // pinned staging ring
+constexpr int kSlots = 16;             // pinned staging ring: the host may run this many uploads ahead
 constexpr int kMaxProfile = 16;
 
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
@@ -47,9 +48,13 @@ struct collm_ctx {
     int rpad_cap = 0;   // max_rank rounded up to 16
 
     size_t plan_cap = 0;  // int32 units
-    int32_t *h_stage[kSlots] = {};
-    hipEvent_t stage_ev[kSlots] = {};
-    bool stage_busy[kSlots] = {};
+    int32_t *h_stage[kSlots] = {};      // pinned, device-visible
+    int32_t *h_stage_dev[kSlots] = {};  // the same memory as the GPU addresses it
+    uint32_t stage_seq[kSlots] = {};    // sequence number of the upload that last used the slot (0: none)
+    uint32_t seq = 0;                   // uploads issued so far
+    uint32_t *h_done = nullptr;         // pinned word: sequence number of the last finished upload
+    uint32_t *h_done_dev = nullptr;
+    int *d_copy_counter = nullptr;
     int slot = 0;
     int32_t *d_plan = nullptr;
 
@@ -83,13 +88,16 @@ namespace {
 
 int pick_tile(int rows, int cols)
 {
-    // Take the largest tile that still gives the 256 CUs about one tile each.
+    // Two shapes are worth choosing between: 256x256 run by eight waves (one block per CU,
+    // the most efficient inner loop) and 128x128 (two blocks per CU, about 0.8 of that
+    // efficiency, four times as many tiles).  Pick the one whose last, partly filled round
+    // of tiles over the 256 CUs costs less.
     const int rp = round_up(std::max(rows, 1), kRowPad);
     const long t256 = (long)(rp / 256) * ((cols + 255) / 256);
-    if (t256 >= 200) return kTile256x256;
-    const long t256x128 = (long)(rp / 256) * ((cols + 127) / 128);
-    if (t256x128 >= 200) return kTile256x128;
-    return kTile128x128;
+    const long t128 = (long)(rp / 128) * ((cols + 127) / 128);
+    const double cost256 = (double)((t256 + 255) / 256);
+    const double cost128 = (double)((t128 + 511) / 512) * 0.625;
+    return cost256 <= cost128 ? kTile256x256w8 : kTile128x128;
 }
 
 struct Prof {
@@ -169,12 +177,25 @@ int upload(collm_ctx *c, size_t lo, size_t hi, hipStream_t st)
     if (hi <= lo) return COLLM_OK;
     const int sl = c->slot;
     c->slot = (c->slot + 1) % kSlots;
-    if (c->stage_busy[sl]) HIP_TRY(hipEventSynchronize(c->stage_ev[sl]));
-    std::memcpy(c->h_stage[sl] + lo, c->plan.data() + lo, (hi - lo) * sizeof(int32_t));
-    HIP_TRY(hipMemcpyAsync(c->d_plan + lo, c->h_stage[sl] + lo, (hi - lo) * sizeof(int32_t),
-                           hipMemcpyHostToDevice, st));
-    HIP_TRY(hipEventRecord(c->stage_ev[sl], st));
-    c->stage_busy[sl] = true;
+    if (c->stage_seq[sl] != 0) {
+        // the slot is free once the upload that used it has been copied by the GPU
+        const volatile uint32_t *done = c->h_done;
+        int spins = 0;
+        while ((int32_t)(*done - c->stage_seq[sl]) < 0) {
+            if (++spins > 2000) {  // far behind: let the stream drain instead of spinning
+                HIP_TRY(hipStreamSynchronize(c->last_stream));
+                break;
+            }
+            std::this_thread::yield();
+        }
+    }
+    // rounded outwards to 16 bytes (the plan vector is padded to a multiple of 64 ints)
+    const size_t lo4 = lo & ~(size_t)3, hi4 = std::min((hi + 3) & ~(size_t)3, c->plan.size());
+    std::memcpy(c->h_stage[sl] + lo4, c->plan.data() + lo4, (hi4 - lo4) * sizeof(int32_t));
+    const uint32_t seq = ++c->seq == 0 ? ++c->seq : c->seq;
+    HIP_TRY(launch_plan_copy(c->h_stage_dev[sl], c->d_plan, lo4, hi4 - lo4, c->d_copy_counter, c->h_done_dev, seq, st));
+    c->stage_seq[sl] = seq;
+    c->last_stream = st;
     return COLLM_OK;
 }
 
@@ -344,16 +365,21 @@ int collm_ctx_create(collm_ctx **out, int device, int32_t max_tokens, int32_t ma
         return hipMalloc(p, bytes);
     };
     for (int i = 0; i < kSlots; ++i) {
-        if (hipHostMalloc((void **)&c->h_stage[i], c->plan_cap * sizeof(int32_t), hipHostMallocDefault) != hipSuccess)
+        if (hipHostMalloc((void **)&c->h_stage[i], c->plan_cap * sizeof(int32_t), hipHostMallocMapped) != hipSuccess)
             return fail(COLLM_E_NOMEM);
-        if (hipEventCreateWithFlags(&c->stage_ev[i], hipEventDisableTiming) != hipSuccess) return fail(COLLM_E_HIP);
+        if (hipHostGetDevicePointer((void **)&c->h_stage_dev[i], c->h_stage[i], 0) != hipSuccess) return fail(COLLM_E_HIP);
     }
+    if (hipHostMalloc((void **)&c->h_done, 64, hipHostMallocMapped) != hipSuccess) return fail(COLLM_E_NOMEM);
+    *c->h_done = 0;
+    if (hipHostGetDevicePointer((void **)&c->h_done_dev, c->h_done, 0) != hipSuccess) return fail(COLLM_E_HIP);
     const size_t act = (size_t)c->rows_cap * c->rpad_cap;
     if (dev_alloc((void **)&c->d_plan, c->plan_cap * sizeof(int32_t)) != hipSuccess ||
         dev_alloc(&c->d_hs, act * 4) != hipSuccess || dev_alloc(&c->d_dhs, act * 4) != hipSuccess ||
         dev_alloc((void **)&c->d_h32, act * 4) != hipSuccess ||
-        dev_alloc((void **)&c->d_dh32, act * 4) != hipSuccess)
+        dev_alloc((void **)&c->d_dh32, act * 4) != hipSuccess ||
+        dev_alloc((void **)&c->d_copy_counter, 64) != hipSuccess)
         return fail(COLLM_E_NOMEM);
+    if (hipMemset(c->d_copy_counter, 0, 64) != hipSuccess) return fail(COLLM_E_HIP);
     if (hipDeviceSynchronize() != hipSuccess) return fail(COLLM_E_HIP);
     c->workspace_bytes = ws;
     *out = c;
@@ -367,14 +393,14 @@ int collm_ctx_destroy(collm_ctx *c)
     (void)hipDeviceSynchronize();
     for (int i = 0; i < kSlots; ++i) {
         if (c->h_stage[i]) (void)hipHostFree(c->h_stage[i]);
-        if (c->stage_ev[i]) (void)hipEventDestroy(c->stage_ev[i]);
     }
+    if (c->h_done) (void)hipHostFree(c->h_done);
     if (c->prof_ev_made)
         for (int i = 0; i < kMaxProfile; ++i) {
             (void)hipEventDestroy(c->prof_ev[i][0]);
             (void)hipEventDestroy(c->prof_ev[i][1]);
         }
-    void *bufs[] = {c->d_plan, c->d_hs, c->d_dhs, c->d_h32, c->d_dh32};
+    void *bufs[] = {c->d_plan, c->d_hs, c->d_dhs, c->d_h32, c->d_dh32, c->d_copy_counter};
     for (void *b : bufs)
         if (b) (void)hipFree(b);
     delete c;

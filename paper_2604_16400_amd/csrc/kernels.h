@@ -73,6 +73,12 @@ int gemm_tile_cols(int tile_cfg);
 hipError_t launch_skinny(const SkinnyArgs &a, int n_items, int rpad, bool t_kmajor, hipStream_t st);
 hipError_t launch_grad(const GradArgs &a, int n_grad, int rpad, hipStream_t st);
 
+// copies ints [first_int, first_int + n_ints) (rounded outwards to 16 bytes) of a pinned host
+// block into the device plan, in stream order, then stores `seq` to the pinned word
+// `done_host_dev`; `counter` is a device int that is zero between uploads
+hipError_t launch_plan_copy(const int32_t *src_pinned, int32_t *dst, size_t first_int, size_t n_ints, int *counter,
+                            uint32_t *done_host_dev, uint32_t seq, hipStream_t st);
+
 // fp32 element type: same argument blocks, plain fp32 FMA kernels
 hipError_t launch_gemm_f32(const GemmArgs &a, bool b_kmajor, hipStream_t st);
 hipError_t launch_skinny_f32(const SkinnyArgs &a, int n_items, bool t_kmajor, hipStream_t st);

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace collm {
@@ -189,6 +191,39 @@ __global__ void __launch_bounds__(256) grad_f32_kernel(GradArgs p)
             }
         }
     }
+}
+
+// Plan upload: the host builds the plan in pinned, device-visible memory and this kernel
+// copies it into device memory in stream order (a kernel launch costs the host far less than
+// an asynchronous memcpy ordered against kernels on the same stream).  The block that
+// finishes last publishes the upload's sequence number in a pinned word, which is how the
+// host learns that the staging slot may be reused, without any event call.
+__global__ void __launch_bounds__(256) plan_copy_kernel(const int4 *__restrict__ src, int4 *__restrict__ dst, int n16,
+                                                        int *counter, volatile uint32_t *done_host, uint32_t seq)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += gridDim.x * blockDim.x) dst[i] = src[i];
+    __syncthreads();  // every load of this block has returned: its stores have been issued
+    if (threadIdx.x == 0) {
+        const int old = atomicAdd(counter, 1);
+        if (old == (int)gridDim.x - 1) {
+            *counter = 0;  // for the next upload (stream order)
+            *done_host = seq;
+            __threadfence_system();
+        }
+    }
+}
+
+hipError_t launch_plan_copy(const int32_t *src_pinned, int32_t *dst, size_t first_int, size_t n_ints, int *counter,
+                            uint32_t *done_host_dev, uint32_t seq, hipStream_t st)
+{
+    // both ends are rounded outwards to 16 bytes; the plan block is padded accordingly
+    const size_t lo = first_int & ~(size_t)3, hi = (first_int + n_ints + 3) & ~(size_t)3;
+    const int n16 = (int)((hi - lo) / 4);
+    const int blocks = std::max(1, std::min(256, (n16 + 255) / 256));
+    hipLaunchKernelGGL(plan_copy_kernel, dim3(blocks), dim3(256), 0, st,
+                       reinterpret_cast<const int4 *>(src_pinned + lo), reinterpret_cast<int4 *>(dst + lo), n16, counter,
+                       done_host_dev, seq);
+    return hipGetLastError();
 }
 
 hipError_t launch_gemm_f32(const GemmArgs &a, bool b_kmajor, hipStream_t st)
