@@ -221,22 +221,72 @@ __device__ __forceinline__ void transpose4x8(const uint4 (&in)[4], uint2 (&out)[
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR>
+// Explicit instruction interleave for one MFMA step: each MFMA is followed by its share of the
+// step's other work (LDS reads, then LDS writes, then global loads), so that a wave that owns
+// its SIMD alone keeps the matrix pipe fed while it moves data.
+template <int MASK> __device__ __forceinline__ void sched_group1() { __builtin_amdgcn_sched_group_barrier(MASK, 1, 0); }
+template <int J, int HI, int NR, int NW> struct SchedOthers {
+    static __device__ __forceinline__ void run()
+    {
+        if constexpr (J < HI) {
+            if constexpr (J < NR) sched_group1<0x100>();            // LDS read
+            else if constexpr (J < NR + NW) sched_group1<0x200>();  // LDS write
+            else sched_group1<0x020>();                             // global load
+            SchedOthers<J + 1, HI, NR, NW>::run();
+        }
+    }
+};
+template <int I, int NM, int NR, int NW, int NL> struct SchedStep {
+    static __device__ __forceinline__ void run()
+    {
+        if constexpr (I < NM) {
+            sched_group1<0x008>();  // MFMA
+            constexpr int others = NR + NW + NL;
+            SchedOthers<others * I / NM, others * (I + 1) / NM, NR, NW>::run();
+            SchedStep<I + 1, NM, NR, NW, NL>::run();
+        }
+    }
+};
+
+// Direct global -> LDS load of 16 bytes per lane (buffer_load_dwordx4 ... lds): the 64 lanes
+// of a wave fill 1 KiB of LDS starting at the wave-uniform address `lds_base`, lane l at
+// lds_base + 16 l; which 16 bytes a lane fetches is up to its own offset, so any permutation
+// inside that KiB is free.  Out-of-range offsets deliver zeros.  The load is tracked by vmcnt
+// only; the compiler does not know it writes LDS, so the code that issues it also waits
+// (s_waitcnt vmcnt(0)) before the barrier that publishes the data.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ i32x4 make_rsrc_words(const void *base, uint32_t bytes)
+{
+    const uint64_t b = reinterpret_cast<uint64_t>(base);
+    i32x4 r;
+    r.x = (int)(uint32_t)b;
+    r.y = (int)((uint32_t)(b >> 32) & 0xffffu);
+    r.z = (int)bytes;
+    r.w = 0x00020000;
+    return r;
+}
+__device__ __forceinline__ void dma16(i32x4 rsrc, uint32_t voff, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_base), "v"(voff), "s"(rsrc));
+}
+__device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR, bool PINGPONG>
 __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 {
     constexpr int NT = WGM * WGN * 64;
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int MI = WM / 32, NI = WN / 32;
     // second operand in LDS: K-major -> BN rows of 64 K values (swizzled chunks); N-major ->
-    // 64 rows (K) of BN values as they lie in memory, row pitch padded by 64 bytes so that the
-    // four rows a transposing read touches fall into different banks
-    constexpr int BPITCH = BN * 2 + 64;
+    // 64 rows (K) of BN values as they lie in memory, chunk c of row k stored at chunk position
+    // c ^ ((k & 3) << 2) so that the four rows a transposing read touches use different banks
+    constexpr int BPITCH = BN * 2;
     constexpr int BTILE = B_KMAJOR ? BN * 128 : 64 * BPITCH;
     constexpr int STAGE = BM * 128 + BTILE;
     constexpr int ACH = BM * 8 / NT;   // 16-byte chunks of the row tile per thread
     constexpr int BCH = BN * 8 / NT;   // chunks of the second operand's tile per thread
     constexpr int NG = BN / 8;         // chunks per N-major row
-    static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0 && NT % NG == 0, "tile/thread mismatch");
+    static_assert((BM * 8) % NT == 0 && (BN * 8) % NT == 0 && NT % NG == 0 && (NT / NG) % 4 == 0, "tile/thread mismatch");
     static_assert(ACH % 4 == 0 || ACH == 2, "row chunks are moved in four (or two) parts per K step");
     extern __shared__ __align__(16) uint8_t smem[];
 
@@ -252,72 +302,116 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     const __amdgpu_buffer_rsrc_t ra = make_rsrc(p.a, p.a_bytes);
     const __amdgpu_buffer_rsrc_t rb = make_rsrc(p.b, p.b_bytes);
 
-    // ---- per-thread source offsets (bytes) and LDS destinations ---------------------------
-    const int c8 = tid & 7;        // chunk column of this thread in K-major tiles
-    const int r8 = tid >> 3;       // first row of this thread in K-major tiles
+    // ---- per-thread source offsets (bytes) ------------------------------------------------
+    // A thread owns fixed LDS positions: in K-major tiles row r8 + i NT/8, chunk position c8;
+    // in the N-major tile row bk0 + i NT/NG, chunk position bng.  The 64 lanes of a wave own
+    // one contiguous KiB per i, which is what a direct-to-LDS load fills.  The swizzle decides
+    // which chunk of the source belongs at that position.
+    const int c8 = tid & 7, r8 = tid >> 3;
+    // rows r8 + i NT/8 differ in swizzle only through bit 2 of (row >> 3): NT/8 = 32 flips it
+    // for odd i, NT/8 = 64 never does
+    constexpr int SWZ_FLIP = (NT / 8 == 32) ? 4 : 0;
+    const int cl0 = c8 ^ swz(r8);  // source chunk of this thread for even i
     uint32_t aoff[ACH];
 #pragma unroll
     for (int i = 0; i < ACH; ++i) {
         const int tok = row_tok[m0 + r8 + i * (NT / 8)];
-        aoff[i] = tok >= 0 ? (uint32_t)tok * (uint32_t)p.lda * 2u + c8 * 16u : kOob;
+        const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
+        aoff[i] = tok >= 0 ? (uint32_t)tok * (uint32_t)p.lda * 2u + cl * 16u : kOob;
     }
     constexpr int NB = BCH;
     uint32_t boff[NB];
     uint32_t bstep = 0;  // N-major: advance of one K step, zero for columns beyond N
-    const int bng = tid % NG, bk0 = tid / NG;  // N-major: chunk column and first K row of this thread
+    const int bng = tid % NG, bk0 = tid / NG;
+    const int bcl = bng ^ ((bk0 & 3) << 2);  // N-major: source chunk of this thread (same for all i)
     if constexpr (B_KMAJOR) {
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             const int n = n0 + r8 + i * (NT / 8);
-            boff[i] = n < N ? (uint32_t)n * (uint32_t)p.ldb * 2u + c8 * 16u : kOob;
+            const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
+            boff[i] = n < N ? (uint32_t)n * (uint32_t)p.ldb * 2u + cl * 16u : kOob;
         }
     } else {
-        const bool on = n0 + bng * 8 < N;
+        const bool on = n0 + bcl * 8 < N;
         bstep = on ? 64u * (uint32_t)p.ldb * 2u : 0u;
 #pragma unroll
         for (int i = 0; i < NB; ++i)
-            boff[i] = on ? ((uint32_t)(bk0 + i * (NT / NG)) * (uint32_t)p.ldb + n0 + bng * 8) * 2u : kOob;
+            boff[i] = on ? ((uint32_t)(bk0 + i * (NT / NG)) * (uint32_t)p.ldb + n0 + bcl * 8) * 2u : kOob;
     }
+    // byte offset of the tile that starts at K index k0 = 64 kc, for chunk i; tiles that reach
+    // beyond K mask their tail (K-major) or run off the end of the buffer (N-major rows)
+    auto a_src = [&](int i, int k0, bool full) -> uint32_t {
+        const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
+        return (full || k0 + cl * 8 < K) ? aoff[i] + (uint32_t)k0 * 2u : kOob;
+    };
+    auto b_src = [&](int i, int k0, int kc, bool full) -> uint32_t {
+        if constexpr (B_KMAJOR) {
+            const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
+            return (full || k0 + cl * 8 < K) ? boff[i] + (uint32_t)k0 * 2u : kOob;
+        } else {
+            return boff[i] + (uint32_t)kc * bstep;
+        }
+    };
 
-    uint4 areg[ACH];
-    uint4 breg[BCH];
+    uint4 areg[PINGPONG ? ACH : 1];
+    uint4 breg[PINGPONG ? BCH : 1];
 
-    // loads part `part` of `parts` of the tile that starts at K index k0
+    // register path (ping-pong pipeline): loads part `part` of `parts` of tile kc
     auto load_a = [&](int k0, int part, int parts) {
-        const bool kin = k0 + c8 * 8 < K;
+        if constexpr (PINGPONG) {
 #pragma unroll
-        for (int i = 0; i < ACH; ++i)
-            if (i * parts / ACH == part) areg[i] = buf16(ra, kin ? aoff[i] + (uint32_t)k0 * 2u : kOob);
+            for (int i = 0; i < ACH; ++i)
+                if (i * parts / ACH == part) areg[i] = buf16(ra, a_src(i, k0, false));
+        }
     };
     auto store_a = [&](int stage, int part, int parts) {
-        uint8_t *ta = smem + stage * STAGE;
+        if constexpr (PINGPONG) {
+            uint8_t *ta = smem + stage * STAGE;
 #pragma unroll
-        for (int i = 0; i < ACH; ++i)
-            if (i * parts / ACH == part)
-                *reinterpret_cast<uint4 *>(ta + tile_off(r8 + i * (NT / 8), c8)) = areg[i];
+            for (int i = 0; i < ACH; ++i)
+                if (i * parts / ACH == part)
+                    *reinterpret_cast<uint4 *>(ta + (r8 + i * (NT / 8)) * 128 + c8 * 16) = areg[i];
+        }
     };
     auto load_b = [&](int k0, int kc, int part, int parts) {
-        if constexpr (B_KMAJOR) {
-            const bool kin = k0 + c8 * 8 < K;
+        if constexpr (PINGPONG) {
 #pragma unroll
             for (int i = 0; i < NB; ++i)
-                if (i * parts / NB == part) breg[i] = buf16(rb, kin ? boff[i] + (uint32_t)k0 * 2u : kOob);
-        } else {
-#pragma unroll
-            for (int i = 0; i < NB; ++i)  // rows beyond K lie beyond the buffer and read as zero
-                if (i * parts / NB == part) breg[i] = buf16(rb, boff[i] + (uint32_t)kc * bstep);
+                if (i * parts / NB == part) breg[i] = buf16(rb, b_src(i, k0, kc, false));
         }
     };
     auto store_b = [&](int stage, int part, int parts) {
-        uint8_t *tb = smem + stage * STAGE + BM * 128;
+        if constexpr (PINGPONG) {
+            uint8_t *tb = smem + stage * STAGE + BM * 128;
 #pragma unroll
-        for (int i = 0; i < NB; ++i)
-            if (i * parts / NB == part) {
-                if constexpr (B_KMAJOR)
-                    *reinterpret_cast<uint4 *>(tb + tile_off(r8 + i * (NT / 8), c8)) = breg[i];
-                else
-                    *reinterpret_cast<uint4 *>(tb + (bk0 + i * (NT / NG)) * BPITCH + bng * 16) = breg[i];
-            }
+            for (int i = 0; i < NB; ++i)
+                if (i * parts / NB == part) {
+                    if constexpr (B_KMAJOR)
+                        *reinterpret_cast<uint4 *>(tb + (r8 + i * (NT / 8)) * 128 + c8 * 16) = breg[i];
+                    else
+                        *reinterpret_cast<uint4 *>(tb + (bk0 + i * (NT / NG)) * BPITCH + bng * 16) = breg[i];
+                }
+        }
+    };
+    // direct-to-LDS path: the whole tile kc goes to `stage`; wave-uniform KiB (i NT/64 + wave)
+    const i32x4 ra_w = make_rsrc_words(p.a, p.a_bytes), rb_w = make_rsrc_words(p.b, p.b_bytes);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
+    auto dma_tile = [&](int stage, int kc) {
+        const int k0 = kc << 6;
+        const bool full = k0 + 64 <= K;
+        const uint32_t base_a = lds0 + stage * STAGE + wave * 1024;
+        const uint32_t base_b = base_a + BM * 128;
+        if (full) {
+#pragma unroll
+            for (int i = 0; i < ACH; ++i) dma16(ra_w, a_src(i, k0, true), __builtin_amdgcn_readfirstlane(base_a + i * (NT / 64) * 1024));
+#pragma unroll
+            for (int i = 0; i < NB; ++i) dma16(rb_w, b_src(i, k0, kc, true), __builtin_amdgcn_readfirstlane(base_b + i * (NT / 64) * 1024));
+        } else {
+#pragma unroll
+            for (int i = 0; i < ACH; ++i) dma16(ra_w, a_src(i, k0, false), __builtin_amdgcn_readfirstlane(base_a + i * (NT / 64) * 1024));
+#pragma unroll
+            for (int i = 0; i < NB; ++i) dma16(rb_w, b_src(i, k0, kc, false), __builtin_amdgcn_readfirstlane(base_b + i * (NT / 64) * 1024));
+        }
     };
 
     // acc[ni][mi] holds the transposed 32x32 block: lane = row m, registers = columns n
@@ -331,6 +425,17 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 
     const int rl = lane & 31, kh = lane >> 5;
     bf16x8 af[2][MI], bf[2][NI];
+    // N-major operand: byte offset of this lane's transposing read inside the tile for K step 0
+    uint32_t btr[NI];
+    {
+        const int g = lane >> 4, i16 = lane & 15;
+        const int krow = (g >> 1) * 8 + (i16 >> 2);  // (krow & 3) == i16 >> 2 also for rows + 4, + 16 ks
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            const int col = wn * WN + ni * 32 + (g & 1) * 16 + (i16 & 3) * 4;
+            btr[ni] = krow * BPITCH + ((((col >> 3) ^ ((i16 >> 2) << 2))) << 4) + (col & 7) * 2;
+        }
+    }
     auto read_frags = [&](int stage, int ks, int buf) {
         const uint8_t *ta = smem + stage * STAGE;
         const uint8_t *tb = ta + BM * 128;
@@ -342,13 +447,11 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         } else {
             // transposing reads: 16 lanes fetch a 4 (K) x 16 (N) block, lane i of them reads 4
             // values of row i / 4 and receives the 4 K values of column i
-            const int g = lane >> 4, i16 = lane & 15;
-            const uint8_t *src = tb + (ks * 16 + (g >> 1) * 8 + (i16 >> 2)) * BPITCH +
-                                 (wn * WN + (g & 1) * 16 + (i16 & 3) * 4) * 2;
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
-                const bf16x4 lo = lds_tr(src + ni * 64);
-                const bf16x4 hi = lds_tr(src + ni * 64 + 4 * BPITCH);
+                const uint8_t *src = tb + btr[ni] + ks * 16 * BPITCH;
+                const bf16x4 lo = lds_tr(src);
+                const bf16x4 hi = lds_tr(src + 4 * BPITCH);
                 bf[buf][ni] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             }
         }
@@ -361,36 +464,90 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                 acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[buf][ni], af[buf][mi], acc[ni][mi], 0, 0, 0);
     };
 
+    auto mma_half = [&](int buf, int half) {
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+                if ((ni * MI + mi) / (MI * NI / 2) == half)
+                    acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[buf][ni], af[buf][mi], acc[ni][mi], 0, 0, 0);
+    };
+
     // ---- main K loop ----------------------------------------------------------------------
     const int nk = (K + 63) >> 6;
     if (nk > 0) {
-        load_a(0, 0, 1);
-        load_b(0, 0, 0, 1);
-        store_a(0, 0, 1);
-        store_b(0, 0, 1);
-        load_a(64, 0, 1);      // tile 1 stays in flight in the registers
-        load_b(64, 1, 0, 1);
-        __syncthreads();
-        read_frags(0, 0, 0);
-        for (int kc = 0; kc < nk; ++kc) {
-            const int cur = kc & 1, nxt = cur ^ 1;
-            const int k2 = (kc + 2) << 6;
+        if constexpr (!PINGPONG) {
+            // One wave per SIMD.  Tiles travel global -> LDS without touching registers: the
+            // loads of tile kc+1 are issued as soon as every wave has left the stage they fill
+            // (the barrier inside step 3 of tile kc-1) and get a whole K step to land.  Every
+            // MFMA step also carries the LDS fragment reads of the next step.
+            constexpr int NR = MI + (B_KMAJOR ? NI : 2 * NI);
+            dma_tile(0, 0);
+            wait_dma();
+            __syncthreads();
+            if (nk > 1) dma_tile(1, 1);
+            read_frags(0, 0, 0);
+            for (int kc = 0; kc < nk; ++kc) {
+                const int cur = kc & 1, nxt = cur ^ 1;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                if (s < 3) read_frags(cur, s + 1, (s + 1) & 1);
+                for (int s = 0; s < 3; ++s) {
+                    read_frags(cur, s + 1, (s + 1) & 1);
+                    mma(s & 1);
+                    SchedStep<0, MI * NI, NR, 0, 0>::run();
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // last step: start its MFMAs, make sure tile kc+1 has landed, meet the other
+                // waves while the MFMAs run, send for tile kc+2 (into the stage everyone has
+                // just left) and fetch the first fragments of tile kc+1 behind the remaining MFMAs
+                mma_half(1, 0);
                 __builtin_amdgcn_sched_barrier(0);
-                mma(s & 1);
+                wait_dma();
+                __syncthreads();
+                if (kc + 2 < nk) dma_tile(cur, kc + 2);
                 __builtin_amdgcn_sched_barrier(0);
-                // move one quarter of tile kc+1 from registers to LDS, refill with tile kc+2
-                store_a(nxt, s, 4);
-                store_b(nxt, s, 4);
-                load_a(k2, s, 4);
-                load_b(k2, kc + 2, s, 4);
+                read_frags(nxt, 0, 0);
+                mma_half(1, 1);
+                SchedStep<0, MI * NI / 2, NR, 0, 0>::run();
                 __builtin_amdgcn_sched_barrier(0);
             }
+        } else {
+            // Two waves per SIMD in opposite phases: while one half of the waves multiplies out
+            // of registers, the other half reads its fragments of the next half K step and moves
+            // its share of the next tile; block barriers separate the phases, and the second
+            // half of the waves runs one phase behind the first.
+            load_a(0, 0, 1);
+            load_b(0, 0, 0, 1);
+            store_a(0, 0, 1);
+            store_b(0, 0, 1);
+            load_a(64, 0, 1);  // tile 1 stays in flight in the registers
+            load_b(64, 1, 0, 1);
             __syncthreads();
-            if (kc + 1 < nk) read_frags(nxt, 0, 0);
+            const bool late = wave >= (WGM * WGN / 2);
+            if (late) __syncthreads();
+            for (int kc = 0; kc < nk; ++kc) {
+                const int cur = kc & 1, nxt = cur ^ 1;
+                const int k2 = (kc + 2) << 6;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    read_frags(cur, 2 * h, 0);
+                    read_frags(cur, 2 * h + 1, 1);
+                    store_a(nxt, h, 2);
+                    store_b(nxt, h, 2);
+                    load_a(k2, h, 2);
+                    load_b(k2, kc + 2, h, 2);
+                    __builtin_amdgcn_sched_barrier(0);
+                    __syncthreads();
+                    __builtin_amdgcn_sched_barrier(0);
+                    mma(0);
+                    mma(1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    __syncthreads();
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            if (!late) __syncthreads();
         }
+        __syncthreads();
     }
 
     // ---- low-rank extension: K-steps [s h | dh] x [B_a | A_a^T] of the tile's adapters ----
@@ -458,11 +615,11 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                     const int k = bk0 + i * (NT / NG);
                     const int j = k >> 4;
                     uint4 v = make_uint4(0, 0, 0, 0);
-                    if (j < nsteps && n0 + bng * 8 < N) {
+                    if (j < nsteps && n0 + bcl * 8 < N) {
                         const int q = st[j].koff + (k & 15);
-                        if (q < rk[j]) v = ldg16(tab[j] + (int64_t)q * p.ext_ld + n0 + bng * 8);
+                        if (q < rk[j]) v = ldg16(tab[j] + (int64_t)q * p.ext_ld + n0 + bcl * 8);
                     }
-                    *reinterpret_cast<uint4 *>(tb + k * BPITCH + bng * 16) = v;
+                    *reinterpret_cast<uint4 *>(tb + k * BPITCH + bng * 16) = v;  // position bng holds chunk bcl
                 }
             }
             __syncthreads();
@@ -887,12 +1044,12 @@ __global__ void __launch_bounds__(GradCfg<RP>::KW * 64) grad_kernel(GradArgs p)
 // =========================================================================================
 // launchers
 // =========================================================================================
-template <int BM, int BN, int WGM, int WGN, bool KM>
+template <int BM, int BN, int WGM, int WGN, bool KM, bool PP>
 static hipError_t launch_gemm_t(const GemmArgs &a, hipStream_t st)
 {
     constexpr int NT = WGM * WGN * 64;
-    constexpr int smem = 2 * (BM * 128 + (KM ? BN * 128 : 64 * (BN * 2 + 64)));
-    auto kern = gemm_lora_kernel<BM, BN, WGM, WGN, KM>;
+    constexpr int smem = 2 * (BM + BN) * 128;
+    auto kern = gemm_lora_kernel<BM, BN, WGM, WGN, KM, PP>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -910,13 +1067,13 @@ hipError_t launch_gemm(const GemmArgs &a, int tile_cfg, bool b_kmajor, hipStream
 {
     switch (tile_cfg) {
     case kTile256x256:
-        return b_kmajor ? launch_gemm_t<256, 256, 2, 2, true>(a, st) : launch_gemm_t<256, 256, 2, 2, false>(a, st);
+        return b_kmajor ? launch_gemm_t<256, 256, 2, 2, true, false>(a, st) : launch_gemm_t<256, 256, 2, 2, false, false>(a, st);
     case kTile256x128:
-        return b_kmajor ? launch_gemm_t<256, 128, 2, 2, true>(a, st) : launch_gemm_t<256, 128, 2, 2, false>(a, st);
+        return b_kmajor ? launch_gemm_t<256, 128, 2, 2, true, false>(a, st) : launch_gemm_t<256, 128, 2, 2, false, false>(a, st);
     case kTile128x128:
-        return b_kmajor ? launch_gemm_t<128, 128, 2, 2, true>(a, st) : launch_gemm_t<128, 128, 2, 2, false>(a, st);
+        return b_kmajor ? launch_gemm_t<128, 128, 2, 2, true, false>(a, st) : launch_gemm_t<128, 128, 2, 2, false, false>(a, st);
     case kTile256x256w8:
-        return b_kmajor ? launch_gemm_t<256, 256, 2, 4, true>(a, st) : launch_gemm_t<256, 256, 2, 4, false>(a, st);
+        return b_kmajor ? launch_gemm_t<256, 256, 2, 4, true, true>(a, st) : launch_gemm_t<256, 256, 2, 4, false, true>(a, st);
     default:
         return hipErrorInvalidValue;
     }
