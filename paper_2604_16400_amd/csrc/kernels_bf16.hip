@@ -22,6 +22,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace collm {
@@ -269,7 +271,48 @@ __device__ __forceinline__ void dma16(i32x4 rsrc, uint32_t voff, uint32_t lds_ba
 {
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_base), "v"(voff), "s"(rsrc));
 }
+// the same with a wave-uniform byte offset added to every lane's address (not part of the range check)
+__device__ __forceinline__ void dma16s(i32x4 rsrc, uint32_t voff, uint32_t soff, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff));
+}
 __device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+template <int N> __device__ __forceinline__ void wait_dma_but() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+// every load and LDS read of this wave has completed, then meet the other waves
+__device__ __forceinline__ void drain_and_barrier() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Which direct load rides behind which MFMA.  A K tile of the direct-load pipeline has three phases
+// in which loads may be issued: the MFMAs of step 3 that follow the barrier (phase 0), step 0 (phase 1)
+// and step 1 (phase 2).  Measured on the 256 x 256 tile: bunching loads (one per MFMA) stalls the wave
+// on the CU's load path, issuing them late leaves the last ones too little time to land; 3/8 of the
+// loads in phase 0, 1/2 in phase 1 and the rest at the start of phase 2, evenly spaced inside a phase,
+// was the best split.  slot[phase][m] is the load issued behind MFMA m, or -1.
+template <int NM, int PRE, int ND>
+struct DmaSlots {
+    int slot[3][NM];
+    int n[3];
+    constexpr DmaSlots() : slot{}, n{ND * 3 / 8, ND / 2, ND - ND * 3 / 8 - ND / 2}
+    {
+        int d = 0;
+        for (int ph = 0; ph < 3; ++ph) {
+            const int lo = ph == 0 ? PRE : 0, width = NM - lo;
+            // more loads than slots cannot happen for the tile shapes in use (checked by the caller)
+            for (int m = 0; m < NM; ++m) slot[ph][m] = -1;
+            for (int i = 0; i < n[ph]; ++i) {
+                int m = lo + (ph == 2 ? i : i * width / n[ph]);  // phase 2: as early as possible
+                while (m < NM && slot[ph][m] >= 0) ++m;
+                if (m < NM) slot[ph][m] = d++;
+            }
+        }
+    }
+    constexpr int placed() const
+    {
+        int c = 0;
+        for (int ph = 0; ph < 3; ++ph)
+            for (int m = 0; m < NM; ++m) c += slot[ph][m] >= 0;
+        return c;
+    }
+};
 
 template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR, bool PINGPONG>
 __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
@@ -282,7 +325,13 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     // c ^ ((k & 3) << 2) so that the four rows a transposing read touches use different banks
     constexpr int BPITCH = BN * 2;
     constexpr int BTILE = B_KMAJOR ? BN * 128 : 64 * BPITCH;
-    constexpr int STAGE = BM * 128 + BTILE;
+    constexpr int ATILE = BM * 128;
+    constexpr int STAGE = ATILE + BTILE;
+    // LDS map.  Ping-pong pipeline: [A0 B0 A1 B1].  Direct-load pipeline: [A0 A1 B0 B1], so that the
+    // fragment reads of both stages lie within the immediate-offset range of one per-lane base.
+    constexpr int A_ST1 = PINGPONG ? STAGE : ATILE;
+    constexpr int B_ST0 = PINGPONG ? ATILE : 2 * ATILE;
+    constexpr int B_ST1 = PINGPONG ? STAGE + ATILE : 2 * ATILE + BTILE;
     constexpr int ACH = BM * 8 / NT;   // 16-byte chunks of the row tile per thread
     constexpr int BCH = BN * 8 / NT;   // chunks of the second operand's tile per thread
     constexpr int NG = BN / 8;         // chunks per N-major row
@@ -322,6 +371,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     constexpr int NB = BCH;
     uint32_t boff[NB];
     uint32_t bstep = 0;  // N-major: advance of one K step, zero for columns beyond N
+    const uint32_t bstep_u = 64u * (uint32_t)p.ldb * 2u;  // the same as a wave-uniform value
     const int bng = tid % NG, bk0 = tid / NG;
     const int bcl = bng ^ ((bk0 & 3) << 2);  // N-major: source chunk of this thread (same for all i)
     if constexpr (B_KMAJOR) {
@@ -366,7 +416,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     };
     auto store_a = [&](int stage, int part, int parts) {
         if constexpr (PINGPONG) {
-            uint8_t *ta = smem + stage * STAGE;
+            uint8_t *ta = smem + (stage ? A_ST1 : 0);
 #pragma unroll
             for (int i = 0; i < ACH; ++i)
                 if (i * parts / ACH == part)
@@ -382,7 +432,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     };
     auto store_b = [&](int stage, int part, int parts) {
         if constexpr (PINGPONG) {
-            uint8_t *tb = smem + stage * STAGE + BM * 128;
+            uint8_t *tb = smem + (stage ? B_ST1 : B_ST0);
 #pragma unroll
             for (int i = 0; i < NB; ++i)
                 if (i * parts / NB == part) {
@@ -393,24 +443,34 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                 }
         }
     };
-    // direct-to-LDS path: the whole tile kc goes to `stage`; wave-uniform KiB (i NT/64 + wave)
+    // direct-to-LDS path: chunk idx (row chunks first, then the second operand's) of the tile that starts
+    // at K index 64 kc goes to `stage`; the wave's 64 lanes fill the KiB (i NT/64 + wave) of the tile
     const i32x4 ra_w = make_rsrc_words(p.a, p.a_bytes), rb_w = make_rsrc_words(p.b, p.b_bytes);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
-    auto dma_tile = [&](int stage, int kc) {
+    const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds0 + wave * 1024);
+    constexpr int ND = ACH + BCH;
+    const int nk = (K + 63) >> 6;
+    const bool k_even = (K & 63) == 0;
+    // a tile beyond the last one gets a resource of size zero: every lane is out of range, nothing is
+    // fetched and the stage it would have gone to is never read
+    auto tile_rsrc = [&](i32x4 r, int kc) -> i32x4 {
+        r.z = kc < nk ? r.z : 0;
+        return r;
+    };
+    // even_c: K is a multiple of 64, so no lane of a tile below nk needs masking and the K offset of the
+    // tile can travel as the instruction's scalar offset
+    auto dma_chunk = [&](auto even_c, int idx, int stage, int kc, i32x4 ra_t, i32x4 rb_t) {
+        constexpr bool even = decltype(even_c)::value;
         const int k0 = kc << 6;
-        const bool full = k0 + 64 <= K;
-        const uint32_t base_a = lds0 + stage * STAGE + wave * 1024;
-        const uint32_t base_b = base_a + BM * 128;
-        if (full) {
-#pragma unroll
-            for (int i = 0; i < ACH; ++i) dma16(ra_w, a_src(i, k0, true), __builtin_amdgcn_readfirstlane(base_a + i * (NT / 64) * 1024));
-#pragma unroll
-            for (int i = 0; i < NB; ++i) dma16(rb_w, b_src(i, k0, kc, true), __builtin_amdgcn_readfirstlane(base_b + i * (NT / 64) * 1024));
+        if (idx < ACH) {
+            const uint32_t dst = lds_wave + (stage ? A_ST1 : 0) + idx * (NT / 64) * 1024;
+            if constexpr (even) dma16s(ra_t, aoff[idx], (uint32_t)k0 * 2u, dst);
+            else dma16(ra_t, a_src(idx, k0, false), dst);
         } else {
-#pragma unroll
-            for (int i = 0; i < ACH; ++i) dma16(ra_w, a_src(i, k0, false), __builtin_amdgcn_readfirstlane(base_a + i * (NT / 64) * 1024));
-#pragma unroll
-            for (int i = 0; i < NB; ++i) dma16(rb_w, b_src(i, k0, kc, false), __builtin_amdgcn_readfirstlane(base_b + i * (NT / 64) * 1024));
+            const int i = idx - ACH;
+            const uint32_t dst = lds_wave + (stage ? B_ST1 : B_ST0) + i * (NT / 64) * 1024;
+            if constexpr (even) dma16s(rb_t, boff[i], B_KMAJOR ? (uint32_t)k0 * 2u : (uint32_t)kc * bstep_u, dst);
+            else dma16(rb_t, b_src(i, k0, kc, false), dst);
         }
     };
 
@@ -437,8 +497,8 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         }
     }
     auto read_frags = [&](int stage, int ks, int buf) {
-        const uint8_t *ta = smem + stage * STAGE;
-        const uint8_t *tb = ta + BM * 128;
+        const uint8_t *ta = smem + (stage ? A_ST1 : 0);
+        const uint8_t *tb = smem + (stage ? B_ST1 : B_ST0);
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) af[buf][mi] = lds_frag(ta, wm * WM + mi * 32 + rl, ks * 2 + kh);
         if constexpr (B_KMAJOR) {
@@ -473,43 +533,108 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                     acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[buf][ni], af[buf][mi], acc[ni][mi], 0, 0, 0);
     };
 
+    // j-th fragment read of a K step (the order in which the MFMAs of the step need them):
+    // second operand block 0, the row blocks, then the remaining blocks of the second operand
+    auto read_one = [&](int stage, int ks, int buf, int j) {
+        const uint8_t *ta = smem + (stage ? A_ST1 : 0);
+        const uint8_t *tb = smem + (stage ? B_ST1 : B_ST0);
+        if (j >= 1 && j <= MI) {
+            af[buf][j - 1] = lds_frag(ta, wm * WM + (j - 1) * 32 + rl, ks * 2 + kh);
+        } else {
+            const int ni = j == 0 ? 0 : j - MI;
+            if constexpr (B_KMAJOR) {
+                bf[buf][ni] = lds_frag(tb, wn * WN + ni * 32 + rl, ks * 2 + kh);
+            } else {
+                const uint8_t *src = tb + btr[ni] + ks * 16 * BPITCH;
+                const bf16x4 lo = lds_tr(src);
+                const bf16x4 hi = lds_tr(src + 4 * BPITCH);
+                bf[buf][ni] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+        }
+    };
+    auto mma_one = [&](int buf, int m) {
+        const int ni = m / MI, mi = m % MI;
+        acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[buf][ni], af[buf][mi], acc[ni][mi], 0, 0, 0);
+    };
+
     // ---- main K loop ----------------------------------------------------------------------
-    const int nk = (K + 63) >> 6;
     if (nk > 0) {
         if constexpr (!PINGPONG) {
-            // One wave per SIMD.  Tiles travel global -> LDS without touching registers: the
-            // loads of tile kc+1 are issued as soon as every wave has left the stage they fill
-            // (the barrier inside step 3 of tile kc-1) and get a whole K step to land.  Every
-            // MFMA step also carries the LDS fragment reads of the next step.
-            constexpr int NR = MI + (B_KMAJOR ? NI : 2 * NI);
-            dma_tile(0, 0);
-            wait_dma();
-            __syncthreads();
-            if (nk > 1) dma_tile(1, 1);
-            read_frags(0, 0, 0);
-            for (int kc = 0; kc < nk; ++kc) {
-                const int cur = kc & 1, nxt = cur ^ 1;
+            // One wave per SIMD; tiles travel global -> LDS without touching registers.  A K tile is
+            // four MFMA steps.  Everything else a wave has to issue rides behind single MFMAs, one
+            // instruction at a time, so that the matrix pipe never waits for the issue of a load:
+            //   * the fragment reads of step s+1 follow the first MFMAs of step s;
+            //   * the ND direct loads of the next tile are spread over three steps (the last MFMAs of
+            //     step 3 of the tile before, then steps 0 and 1, see DmaSlots): issuing one takes a wave
+            //     about as long as half an MFMA, and the CU accepts 1 KiB only every 16-20 cycles;
+            //     steps 2 and 3 give the last of them time to land.
+            // One barrier per tile sits inside step 3, after its first MFMAs: before it every wave has
+            // received its own loads of tile kc+1 and all its fragments of tile kc, so after it the
+            // stage of tile kc may be overwritten (tile kc+2) and tile kc+1 may be read.
+            constexpr int NM = MI * NI;        // MFMAs per step
+            constexpr int NRD = MI + NI;       // fragment reads per step
+            constexpr int PRE = NM / 4;        // MFMAs of step 3 issued before the barrier
+            constexpr DmaSlots<NM, PRE, ND> SL{};
+            constexpr int D3 = SL.n[0];  // loads of a tile issued before its steps 0 and 1
+            static_assert(SL.placed() == ND, "not every direct load has a slot");
+            constexpr int RPS = (NRD + NM - 1) / NM;                  // reads per MFMA, steps 0..2
+            constexpr int RPS3 = (NRD + (NM - PRE) - 1) / (NM - PRE);  // reads per MFMA, tail of step 3
+
+            auto pipeline = [&](auto even_c) {
+            i32x4 ra_t = tile_rsrc(ra_w, 0), rb_t = tile_rsrc(rb_w, 0);
 #pragma unroll
-                for (int s = 0; s < 3; ++s) {
-                    read_frags(cur, s + 1, (s + 1) & 1);
-                    mma(s & 1);
-                    SchedStep<0, MI * NI, NR, 0, 0>::run();
+            for (int d = 0; d < ND; ++d) dma_chunk(even_c, d, 0, 0, ra_t, rb_t);
+            ra_t = tile_rsrc(ra_w, 1);
+            rb_t = tile_rsrc(rb_w, 1);
+#pragma unroll
+            for (int d = 0; d < D3; ++d) dma_chunk(even_c, d, 1, 1, ra_t, rb_t);
+            wait_dma_but<D3>();  // loads complete in order: tile 0 is in
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < NRD; ++j) read_one(0, 0, 0, j);
+
+            auto k_tile = [&](auto cur_c, int kc) {
+                constexpr int cur = decltype(cur_c)::value, nxt = cur ^ 1;
+                // steps 0..2: MFMAs of step s, fragment reads of step s+1, direct loads of tile kc+1
+#pragma unroll
+                for (int st = 0; st < 3; ++st) {
+#pragma unroll
+                    for (int m = 0; m < NM; ++m) {
+                        mma_one(st & 1, m);
+#pragma unroll
+                        for (int j = m * RPS; j < (m + 1) * RPS; ++j)
+                            if (j < NRD) read_one(cur, st + 1, (st + 1) & 1, j);
+                        if (st < 2 && SL.slot[st + 1][m] >= 0) dma_chunk(even_c, SL.slot[st + 1][m], nxt, kc + 1, ra_t, rb_t);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+                // step 3
+#pragma unroll
+                for (int m = 0; m < PRE; ++m) mma_one(1, m);
+                __builtin_amdgcn_sched_barrier(0);
+                drain_and_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+                ra_t = tile_rsrc(ra_w, kc + 2);
+                rb_t = tile_rsrc(rb_w, kc + 2);
+#pragma unroll
+                for (int m = PRE; m < NM; ++m) {
+                    mma_one(1, m);
+#pragma unroll
+                    for (int j = (m - PRE) * RPS3; j < (m - PRE + 1) * RPS3; ++j)
+                        if (j < NRD) read_one(nxt, 0, 0, j);
+                    if (SL.slot[0][m] >= 0) dma_chunk(even_c, SL.slot[0][m], cur, kc + 2, ra_t, rb_t);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                // last step: start its MFMAs, make sure tile kc+1 has landed, meet the other
-                // waves while the MFMAs run, send for tile kc+2 (into the stage everyone has
-                // just left) and fetch the first fragments of tile kc+1 behind the remaining MFMAs
-                mma_half(1, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                wait_dma();
-                __syncthreads();
-                if (kc + 2 < nk) dma_tile(cur, kc + 2);
-                __builtin_amdgcn_sched_barrier(0);
-                read_frags(nxt, 0, 0);
-                mma_half(1, 1);
-                SchedStep<0, MI * NI / 2, NR, 0, 0>::run();
-                __builtin_amdgcn_sched_barrier(0);
+            };
+            for (int kc = 0; kc < nk; kc += 2) {
+                k_tile(std::integral_constant<int, 0>{}, kc);
+                if (kc + 1 < nk) k_tile(std::integral_constant<int, 1>{}, kc + 1);
             }
+            wait_dma();  // loads of tiles beyond the last one fetch nothing but still signal completion
+            };
+            if (k_even) pipeline(std::true_type{});
+            else pipeline(std::false_type{});
         } else {
             // Two waves per SIMD in opposite phases: while one half of the waves multiplies out
             // of registers, the other half reads its fragments of the next half K step and moves
@@ -555,7 +680,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         const int e0 = p.ext_off[tile_m], e1 = p.ext_off[tile_m + 1];
         const uint16_t *__restrict__ Hs = reinterpret_cast<const uint16_t *>(p.hs);
         uint8_t *ta = smem;
-        uint8_t *tb = smem + BM * 128;
+        uint8_t *tb = smem + B_ST0;
         for (int eb = e0; eb < e1; eb += 4) {
             const int nsteps = (e1 - eb) < 4 ? (e1 - eb) : 4;
             ExtStep st[4];
