@@ -55,6 +55,7 @@ struct collm_ctx {
     uint32_t *h_done = nullptr;         // pinned word: sequence number of the last finished upload
     uint32_t *h_done_dev = nullptr;
     int *d_copy_counter = nullptr;
+    void *d_zeros = nullptr;  // 256 bytes of zeros for masked 16-byte loads
     int slot = 0;
     int32_t *d_plan = nullptr;
 
@@ -377,9 +378,10 @@ int collm_ctx_create(collm_ctx **out, int device, int32_t max_tokens, int32_t ma
         dev_alloc(&c->d_hs, act * 4) != hipSuccess || dev_alloc(&c->d_dhs, act * 4) != hipSuccess ||
         dev_alloc((void **)&c->d_h32, act * 4) != hipSuccess ||
         dev_alloc((void **)&c->d_dh32, act * 4) != hipSuccess ||
-        dev_alloc((void **)&c->d_copy_counter, 64) != hipSuccess)
+        dev_alloc((void **)&c->d_copy_counter, 64) != hipSuccess || dev_alloc(&c->d_zeros, 256) != hipSuccess)
         return fail(COLLM_E_NOMEM);
     if (hipMemset(c->d_copy_counter, 0, 64) != hipSuccess) return fail(COLLM_E_HIP);
+    if (hipMemset(c->d_zeros, 0, 256) != hipSuccess) return fail(COLLM_E_HIP);
     if (hipDeviceSynchronize() != hipSuccess) return fail(COLLM_E_HIP);
     c->workspace_bytes = ws;
     *out = c;
@@ -400,7 +402,7 @@ int collm_ctx_destroy(collm_ctx *c)
             (void)hipEventDestroy(c->prof_ev[i][0]);
             (void)hipEventDestroy(c->prof_ev[i][1]);
         }
-    void *bufs[] = {c->d_plan, c->d_hs, c->d_dhs, c->d_h32, c->d_dh32, c->d_copy_counter};
+    void *bufs[] = {c->d_plan, c->d_hs, c->d_dhs, c->d_h32, c->d_dh32, c->d_copy_counter, c->d_zeros};
     for (void *b : bufs)
         if (b) (void)hipFree(b);
     delete c;
@@ -485,9 +487,9 @@ int collm_lora_linear_fwd(collm_ctx *c, const collm_shape *s, const void *x, con
     g.ext = reinterpret_cast<const ExtStep *>(c->d_plan + L.all.off_ext);
     g.hs = c->d_hs;
     g.hs_ld = L.rpad;
-    g.ext_tab = reinterpret_cast<const uint64_t *>(c->d_plan + L.off_B_ptr);
+    g.hs_bytes = (uint32_t)((size_t)c->rows_cap * c->rpad_cap * 4);
     g.ext_ld = s->d_out;
-    g.rank = c->d_plan + L.off_rank;
+    g.zeros = c->d_zeros;
     {
         Prof prof(c, st, "gemm_fwd");
         if (f32) {
@@ -606,9 +608,9 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
         g.ext = reinterpret_cast<const ExtStep *>(c->d_plan + L.train.off_ext);
         g.hs = c->d_dhs;
         g.hs_ld = L.rpad;
-        g.ext_tab = reinterpret_cast<const uint64_t *>(c->d_plan + L.off_A_ptr);
+        g.hs_bytes = (uint32_t)((size_t)c->rows_cap * c->rpad_cap * 4);
         g.ext_ld = 0;
-        g.rank = c->d_plan + L.off_rank;
+        g.zeros = c->d_zeros;
         Prof prof(c, st, "gemm_dx");
         if (f32) {
             HIP_TRY(launch_gemm_f32(g, true, st));

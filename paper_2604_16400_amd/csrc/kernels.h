@@ -25,9 +25,9 @@ struct GemmArgs {
     const ExtStep *ext;
     const void *hs;           // low-rank activations of the rows, [rows][hs_ld], row order
     int hs_ld;
-    const uint64_t *ext_tab;  // adapter -> device pointer of the extension's table
+    uint32_t hs_bytes;        // size of hs
     int64_t ext_ld;           // row length of a [rank][N] table (forward)
-    const int32_t *rank;
+    const void *zeros;        // at least 16 bytes of zeros, 16-byte aligned (source of masked 16-byte loads)
 };
 
 // out[m][q] = sum_k in[tok(m)][k] * tab_a(k, q), one SkinnyItem per blockIdx.x

@@ -276,10 +276,22 @@ __device__ __forceinline__ void dma16s(i32x4 rsrc, uint32_t voff, uint32_t soff,
 {
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff));
 }
+// the same from a 64-bit address per lane (no range check)
+__device__ __forceinline__ void dma16g(uint64_t addr, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(addr));
+}
 __device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 template <int N> __device__ __forceinline__ void wait_dma_but() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 // every load and LDS read of this wave has completed, then meet the other waves
 __device__ __forceinline__ void drain_and_barrier() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Four consecutive extension steps of a row tile, unpacked into wave-uniform registers.
+struct ExtBatch {
+    uint32_t kr[kExtBatch];    // koff | rank << 16   (0: no step)
+    uint32_t rows[kExtBatch];  // row_lo | row_hi << 16
+    uint64_t tab[kExtBatch];
+};
 
 // Which direct load rides behind which MFMA.  A K tile of the direct-load pipeline has three phases
 // in which loads may be issued: the MFMAs of step 3 that follow the barrier (phase 0), step 0 (phase 1)
@@ -350,6 +362,33 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 
     const __amdgpu_buffer_rsrc_t ra = make_rsrc(p.a, p.a_bytes);
     const __amdgpu_buffer_rsrc_t rb = make_rsrc(p.b, p.b_bytes);
+
+    // extension steps of this row tile; the first batch is fetched now, long before it is needed
+    const int e0 = __builtin_amdgcn_readfirstlane(p.ext_off[tile_m]);
+    const int e1 = __builtin_amdgcn_readfirstlane(p.ext_off[tile_m + 1]);
+    // The records of a batch come through the scalar cache (their own counter, so waiting for them
+    // does not wait for the direct loads in flight).  Load and wait are one statement: registers
+    // that a load is still writing must never be visible to the compiler, which may move or spill
+    // them.  The step array is padded by a batch, and the index is clamped to the tile's last step,
+    // so the 64 bytes read always lie inside it.
+    typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+    auto fetch_batch = [&](int eb) {
+        const int last = e1 > 0 ? e1 - 1 : 0;
+        const int idx = eb < last ? eb : last;
+        const uint64_t addr = reinterpret_cast<uint64_t>(p.ext) + (uint64_t)idx * sizeof(ExtStep);
+        u32x16 raw;
+        asm volatile("s_load_dwordx16 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=&s"(raw) : "s"(addr));
+        ExtBatch bt;
+#pragma unroll
+        for (int j = 0; j < kExtBatch; ++j) {
+            const bool on = eb + j < e1;
+            bt.kr[j] = on ? raw[4 * j] : 0u;
+            bt.rows[j] = on ? raw[4 * j + 1] : 0u;
+            bt.tab[j] = ((uint64_t)raw[4 * j + 3] << 32) | raw[4 * j + 2];
+        }
+        return bt;
+    };
+    const ExtBatch first_b = fetch_batch(e0);
 
     // ---- per-thread source offsets (bytes) ------------------------------------------------
     // A thread owns fixed LDS positions: in K-major tiles row r8 + i NT/8, chunk position c8;
@@ -524,15 +563,6 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                 acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[buf][ni], af[buf][mi], acc[ni][mi], 0, 0, 0);
     };
 
-    auto mma_half = [&](int buf, int half) {
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-                if ((ni * MI + mi) / (MI * NI / 2) == half)
-                    acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[buf][ni], af[buf][mi], acc[ni][mi], 0, 0, 0);
-    };
-
     // j-th fragment read of a K step (the order in which the MFMAs of the step need them):
     // second operand block 0, the row blocks, then the remaining blocks of the second operand
     auto read_one = [&](int stage, int ks, int buf, int j) {
@@ -676,110 +706,150 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     }
 
     // ---- low-rank extension: K-steps [s h | dh] x [B_a | A_a^T] of the tile's adapters ----
-    {
-        const int e0 = p.ext_off[tile_m], e1 = p.ext_off[tile_m + 1];
-        const uint16_t *__restrict__ Hs = reinterpret_cast<const uint16_t *>(p.hs);
-        uint8_t *ta = smem;
-        uint8_t *tb = smem + B_ST0;
-        for (int eb = e0; eb < e1; eb += 4) {
-            const int nsteps = (e1 - eb) < 4 ? (e1 - eb) : 4;
-            ExtStep st[4];
-            const uint16_t *tab[4];
-            int rk[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (j < nsteps) {
-                    st[j] = p.ext[eb + j];
-                    tab[j] = reinterpret_cast<const uint16_t *>(p.ext_tab[st[j].adapter]);
-                    rk[j] = p.rank[st[j].adapter];
-                } else {
-                    st[j] = ExtStep{-1, 0, 0, 0};
-                    tab[j] = nullptr;
-                    rk[j] = 0;
-                }
-            }
-            // rows: chunk c of row r belongs to step c / 2, rank indices koff + 8 (c % 2) ..
+    // The steps are taken four at a time (one 64-wide K tile).  The operands of a batch travel
+    // global -> LDS like the tiles of the main loop, into the stage the batch before it does not
+    // use, while that batch multiplies; the step records of a batch are fetched one batch ahead
+    // of its loads, and those of the first batch before the main loop.  Rows of the tile outside a
+    // step's row range, rank indices beyond the adapter's rank and columns beyond N are filled
+    // with zeros (out-of-range buffer offsets, or the zero block).
+    if (e1 > e0) {
+        const i32x4 rh_w = make_rsrc_words(p.hs, p.hs_bytes);
+        const uint64_t zeros = reinterpret_cast<uint64_t>(p.zeros);
+        // per-lane choice among the four steps of a batch
+        auto pick = [](int j, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3) { return j == 0 ? v0 : (j == 1 ? v1 : (j == 2 ? v2 : v3)); };
+        auto issue_batch = [&](int stage, const ExtBatch &bt) {
+            // rows: position c8 of row r holds chunk cl; chunk cl belongs to step cl / 2, rank
+            // indices koff + 8 (cl % 2) ..
 #pragma unroll
             for (int i = 0; i < ACH; ++i) {
-                const int r = r8 + i * (NT / 8), c = c8;
-                const int j = c >> 1;
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (j < nsteps && r >= st[j].row_lo && r < st[j].row_hi)
-                    v = ldg16(Hs + (int64_t)(m0 + r) * p.hs_ld + st[j].koff + (c & 1) * 8);
-                *reinterpret_cast<uint4 *>(ta + tile_off(r, c)) = v;
+                const int r = r8 + i * (NT / 8);
+                const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
+                const int j = cl >> 1;
+                const uint32_t kr = pick(j, bt.kr[0], bt.kr[1], bt.kr[2], bt.kr[3]);
+                const uint32_t rows = pick(j, bt.rows[0], bt.rows[1], bt.rows[2], bt.rows[3]);
+                const bool in = r >= (int)(rows & 0xffffu) && r < (int)(rows >> 16);
+                const uint32_t off = in ? ((uint32_t)(m0 + r) * (uint32_t)p.hs_ld + (kr & 0xffffu) + (cl & 1) * 8u) * 2u : kOob;
+                dma16(rh_w, off, lds_wave + (stage ? A_ST1 : 0) + i * (NT / 64) * 1024);
             }
-            if constexpr (B_KMAJOR) {
-                // table rows are output columns: A_a[n][q], row length rank
+            if constexpr (!B_KMAJOR) {
+                // table rows are rank indices: B_a[q][n]; tile row 16 j + i is rank index koff_j + i.
+                // All lanes of a load belong to one step, whose table is the load's buffer: rank
+                // indices beyond the rank lie beyond it.
+                static_assert(16 % (NT / NG) == 0 || (NT / NG) % 16 == 0, "a direct load must not straddle two steps");
 #pragma unroll
                 for (int i = 0; i < BCH; ++i) {
-                    const int r = r8 + i * (NT / 8), c = c8;
-                    const int j = c >> 1;
-                    uint4 v = make_uint4(0, 0, 0, 0);
-                    if (j < nsteps && n0 + r < N) {
-                        const int q0 = st[j].koff + (c & 1) * 8;
-                        const uint16_t *src = tab[j] + (int64_t)(n0 + r) * rk[j] + q0;
-                        if ((rk[j] & 7) == 0) {
-                            if (q0 < rk[j]) v = ldg16(src);
-                        } else {
-                            uint16_t e[8];
-#pragma unroll
-                            for (int q = 0; q < 8; ++q) e[q] = (q0 + q < rk[j]) ? src[q] : (uint16_t)0;
-                            v.x = e[0] | ((uint32_t)e[1] << 16);
-                            v.y = e[2] | ((uint32_t)e[3] << 16);
-                            v.z = e[4] | ((uint32_t)e[5] << 16);
-                            v.w = e[6] | ((uint32_t)e[7] << 16);
-                        }
-                    }
-                    *reinterpret_cast<uint4 *>(tb + tile_off(r, c)) = v;
+                    const int j = (i * (NT / NG)) >> 4;
+                    const int k = bk0 + i * (NT / NG);
+                    const uint32_t rk = bt.kr[j] >> 16, koff = bt.kr[j] & 0xffffu;
+                    const i32x4 rt = make_rsrc_words(reinterpret_cast<const void *>(bt.tab[j]), rk * (uint32_t)p.ext_ld * 2u);
+                    const uint32_t off = (n0 + bcl * 8 < N) ? ((koff + (uint32_t)(k & 15)) * (uint32_t)p.ext_ld + (uint32_t)(n0 + bcl * 8)) * 2u : kOob;
+                    dma16(rt, off, lds_wave + (stage ? B_ST1 : B_ST0) + i * (NT / 64) * 1024);
                 }
             } else {
-                // table rows are rank indices: B_a[q][n], row length ext_ld; tile row 16 j + i
-                // is rank index koff_j + i
+                // table rows are output columns: A_a[n][q], row length rank.  The four steps of a
+                // batch may have four tables, so every lane forms its own 64-bit address.
+                const bool all8 = (((bt.kr[0] | bt.kr[1] | bt.kr[2] | bt.kr[3]) >> 16) & 7u) == 0;
+                if (all8) {
 #pragma unroll
-                for (int i = 0; i < NB; ++i) {
-                    const int k = bk0 + i * (NT / NG);
-                    const int j = k >> 4;
-                    uint4 v = make_uint4(0, 0, 0, 0);
-                    if (j < nsteps && n0 + bcl * 8 < N) {
-                        const int q = st[j].koff + (k & 15);
-                        if (q < rk[j]) v = ldg16(tab[j] + (int64_t)q * p.ext_ld + n0 + bcl * 8);
+                    for (int i = 0; i < BCH; ++i) {
+                        const int r = r8 + i * (NT / 8);
+                        const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
+                        const int j = cl >> 1;
+                        const uint32_t kr = pick(j, bt.kr[0], bt.kr[1], bt.kr[2], bt.kr[3]);
+                        const uint32_t tlo = pick(j, (uint32_t)bt.tab[0], (uint32_t)bt.tab[1], (uint32_t)bt.tab[2], (uint32_t)bt.tab[3]);
+                        const uint32_t thi = pick(j, (uint32_t)(bt.tab[0] >> 32), (uint32_t)(bt.tab[1] >> 32), (uint32_t)(bt.tab[2] >> 32), (uint32_t)(bt.tab[3] >> 32));
+                        const uint32_t rk = kr >> 16, q0 = (kr & 0xffffu) + (cl & 1) * 8u;
+                        const bool in = n0 + r < N && q0 < rk;
+                        const uint64_t addr = in ? (((uint64_t)thi << 32) | tlo) + ((uint64_t)(n0 + r) * rk + q0) * 2u : zeros;
+                        dma16g(addr, lds_wave + (stage ? B_ST1 : B_ST0) + i * (NT / 64) * 1024);
                     }
-                    *reinterpret_cast<uint4 *>(tb + k * BPITCH + bng * 16) = v;  // position bng holds chunk bcl
-                }
-            }
-            __syncthreads();
+                } else {
+                    // some rank is no multiple of 8: table rows are not 16-byte aligned; element by element
+                    uint8_t *tb = smem + (stage ? B_ST1 : B_ST0);
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                if (ks < nsteps) {
-                    read_frags(0, ks, 0);
-                    mma(0);
+                    for (int i = 0; i < BCH; ++i) {
+                        const int r = r8 + i * (NT / 8);
+                        const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
+                        const int j = cl >> 1;
+                        const uint32_t kr = pick(j, bt.kr[0], bt.kr[1], bt.kr[2], bt.kr[3]);
+                        const uint32_t tlo = pick(j, (uint32_t)bt.tab[0], (uint32_t)bt.tab[1], (uint32_t)bt.tab[2], (uint32_t)bt.tab[3]);
+                        const uint32_t thi = pick(j, (uint32_t)(bt.tab[0] >> 32), (uint32_t)(bt.tab[1] >> 32), (uint32_t)(bt.tab[2] >> 32), (uint32_t)(bt.tab[3] >> 32));
+                        const int rk = (int)(kr >> 16), q0 = (int)(kr & 0xffffu) + (cl & 1) * 8;
+                        uint16_t e[8];
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) e[q] = 0;
+                        if (n0 + r < N) {
+                            const uint16_t *src = reinterpret_cast<const uint16_t *>(((uint64_t)thi << 32) | tlo) + (int64_t)(n0 + r) * rk + q0;
+#pragma unroll
+                            for (int q = 0; q < 8; ++q)
+                                if (q0 + q < rk) e[q] = src[q];
+                        }
+                        uint4 v;
+                        v.x = e[0] | ((uint32_t)e[1] << 16);
+                        v.y = e[2] | ((uint32_t)e[3] << 16);
+                        v.z = e[4] | ((uint32_t)e[5] << 16);
+                        v.w = e[6] | ((uint32_t)e[7] << 16);
+                        *reinterpret_cast<uint4 *>(tb + (r8 + i * (NT / 8)) * 128 + c8 * 16) = v;
+                    }
                 }
             }
-            __syncthreads();
+        };
+
+        issue_batch(0, first_b);
+        ExtBatch nxt_b = fetch_batch(e0 + kExtBatch);
+        int stage = 0;
+        for (int eb = e0; eb < e1; eb += kExtBatch, stage ^= 1) {
+            drain_and_barrier();  // this batch has landed; the stage of the batch before it is free
+            const int nsteps = (e1 - eb) < kExtBatch ? (e1 - eb) : kExtBatch;
+            if (eb + kExtBatch < e1) issue_batch(stage ^ 1, nxt_b);
+            nxt_b = fetch_batch(eb + 2 * kExtBatch);  // a short wait, in the shadow of the loads just issued
+            read_frags(stage, 0, 0);
+#pragma unroll
+            for (int ks = 0; ks < kExtBatch; ++ks) {
+                if (ks < nsteps) {
+                    if (ks + 1 < nsteps) read_frags(stage, ks + 1, (ks + 1) & 1);
+                    mma(ks & 1);
+                }
+            }
         }
+        __syncthreads();
     }
 
     // ---- epilogue: one rounding to bf16, rows scattered back to their tokens --------------
+    // The accumulator layout gives a lane four consecutive columns of a row, and the 32 rows of a
+    // block go to 32 different tokens: storing from there would touch 32 lines per instruction
+    // with 8 bytes each.  Each wave instead writes its rounded tile to a private LDS area (row
+    // pitch EP: the row, then its token index) and reads it back row by row, 16 bytes per lane,
+    // so that a store instruction covers whole 128-byte lines of a few rows.
     {
-        uint16_t *__restrict__ Out = reinterpret_cast<uint16_t *>(p.out);
+        constexpr int EP = WN * 2 + 16;          // bytes per staged row
+        constexpr int LPR = WN / 8, RPI = 64 / LPR;  // lanes per row, rows per store instruction
+        uint8_t *ep = smem + wave * (WM * EP);
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
-            const int tok = row_tok[m0 + wm * WM + mi * 32 + rl];
-            if (tok < 0) continue;
-            uint16_t *orow = Out + (int64_t)tok * p.ldo;
+            uint8_t *erow = ep + (mi * 32 + rl) * EP;
+            if (kh == 0) *reinterpret_cast<int32_t *>(erow + WN * 2) = row_tok[m0 + wm * WM + mi * 32 + rl];
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const int n = n0 + wn * WN + ni * 32 + g * 8 + kh * 4;
-                    if (n < N) {
-                        uint2 v;
-                        v.x = pack_bf16(acc[ni][mi][g * 4 + 0], acc[ni][mi][g * 4 + 1]);
-                        v.y = pack_bf16(acc[ni][mi][g * 4 + 2], acc[ni][mi][g * 4 + 3]);
-                        *reinterpret_cast<uint2 *>(orow + n) = v;
-                    }
+                    uint2 v;
+                    v.x = pack_bf16(acc[ni][mi][g * 4 + 0], acc[ni][mi][g * 4 + 1]);
+                    v.y = pack_bf16(acc[ni][mi][g * 4 + 2], acc[ni][mi][g * 4 + 3]);
+                    *reinterpret_cast<uint2 *>(erow + (ni * 32 + g * 8 + kh * 4) * 2) = v;
                 }
             }
+        }
+        __builtin_amdgcn_wave_barrier();
+        uint16_t *__restrict__ Out = reinterpret_cast<uint16_t *>(p.out);
+        const int rr = lane / LPR, cc = lane % LPR;
+        const int n = n0 + wn * WN + cc * 8;
+#pragma unroll 4
+        for (int it = 0; it < WM / RPI; ++it) {
+            const uint8_t *erow = ep + (it * RPI + rr) * EP;
+            const uint4 v = *reinterpret_cast<const uint4 *>(erow + cc * 16);
+            const int tok = *reinterpret_cast<const int32_t *>(erow + WN * 2);
+            if (tok >= 0 && n < N) *reinterpret_cast<uint4 *>(Out + (int64_t)tok * p.ldo + n) = v;
         }
     }
 }
@@ -1173,7 +1243,9 @@ template <int BM, int BN, int WGM, int WGN, bool KM, bool PP>
 static hipError_t launch_gemm_t(const GemmArgs &a, hipStream_t st)
 {
     constexpr int NT = WGM * WGN * 64;
-    constexpr int smem = 2 * (BM + BN) * 128;
+    constexpr int stage_bytes = 2 * (BM + BN) * 128;
+    constexpr int epi_bytes = BM * BN * 2 + BM * WGN * 16;  // per wave (BM/WGM) rows of (BN/WGN) * 2 + 16 bytes
+    constexpr int smem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
     auto kern = gemm_lora_kernel<BM, BN, WGM, WGN, KM, PP>;
     static bool attr_done = false;
     if (!attr_done) {

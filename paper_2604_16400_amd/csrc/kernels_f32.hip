@@ -83,14 +83,15 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(GemmArgs p)
     const int e0 = p.ext_off[blockIdx.y], e1 = p.ext_off[blockIdx.y + 1];
     for (int e = e0; e < e1; ++e) {
         const ExtStep st = p.ext[e];
-        const int rk = p.rank[st.adapter];
-        const float *__restrict__ tab = reinterpret_cast<const float *>(p.ext_tab[st.adapter]);
-        const int q1 = (st.koff + kKStep) < rk ? (st.koff + kKStep) : rk;
+        const int koff = (int)(st.koff_rank & 0xffffu), rk = (int)(st.koff_rank >> 16);
+        const int row_lo = (int)(st.rows & 0xffffu), row_hi = (int)(st.rows >> 16);
+        const float *__restrict__ tab = reinterpret_cast<const float *>(st.tab);
+        const int q1 = (koff + kKStep) < rk ? (koff + kKStep) : rk;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int r = ty * 4 + i;
-            if (r < st.row_lo || r >= st.row_hi) continue;
-            for (int q = st.koff; q < q1; ++q) {
+            if (r < row_lo || r >= row_hi) continue;
+            for (int q = koff; q < q1; ++q) {
                 const float hv = Hs[(int64_t)(m0 + r) * p.hs_ld + q];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {

@@ -27,13 +27,15 @@ struct SkinnyItem {
     int32_t rank;    // rank of the adapter
 };
 
-// One 16-wide K-step of the low-rank extension inside a GEMM row tile.
+// One 16-wide K-step of the low-rank extension inside a GEMM row tile.  Self-contained (no
+// lookups through the adapter index) so that a kernel can fetch a step, and everything needed to
+// address its operands, with one 16-byte scalar load.
 struct ExtStep {
-    int32_t adapter;
-    int32_t koff;    // first rank index of the step (multiple of 16)
-    int32_t row_lo;  // rows [row_lo, row_hi) of the tile (tile-relative) use this adapter
-    int32_t row_hi;
+    uint32_t koff_rank;  // first rank index of the step (multiple of 16) | rank of the adapter << 16
+    uint32_t rows;       // row_lo | row_hi << 16: rows [row_lo, row_hi) of the tile use this adapter
+    uint64_t tab;        // device address of the adapter's table for this GEMM (B_a forward, A_a backward)
 };
+constexpr int kExtBatch = 4;  // steps a kernel fetches at a time; the step array is padded by as many
 
 // Training rows of one trained adapter inside the training row order.
 struct GradItem {

@@ -58,7 +58,8 @@ struct Builder {
 
 // Rows (token indices, already filtered) sorted by adapter, stable; items; extension tables.
 void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &tokens,
-                     const int32_t *tok_adapter, const int32_t *rank, int n_adapters, int bm)
+                     const int32_t *tok_adapter, const int32_t *rank, int n_adapters, int bm,
+                     const void *const *ext_tab)
 {
     const int n = (int)tokens.size();
     L.n_rows = n;
@@ -113,7 +114,9 @@ void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &
             int e = r + 1;
             while (e < r1 && b.blk[L.off_row_adapter + e] == a) ++e;
             if (a >= 0) {
-                for (int k = 0; k < rank[a]; k += kKStep) ext.push_back({a, k, r - r0, e - r0});
+                const uint64_t tab = ext_tab ? (uint64_t)(uintptr_t)ext_tab[a] : 0;
+                for (int k = 0; k < rank[a]; k += kKStep)
+                    ext.push_back({(uint32_t)k | ((uint32_t)rank[a] << 16), (uint32_t)(r - r0) | ((uint32_t)(e - r0) << 16), tab});
             }
             r = e;
         }
@@ -123,7 +126,7 @@ void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &
     L.off_ext_off = b.alloc(ext_off.size());
     std::memcpy(b.blk.data() + L.off_ext_off, ext_off.data(), ext_off.size() * 4);
     L.n_ext = (int)ext.size();
-    L.off_ext = b.alloc(ext.size() * 4 + 4);
+    L.off_ext = b.alloc((ext.size() + kExtBatch) * 4);  // padded: a kernel reads whole batches
     if (!ext.empty()) std::memcpy(b.blk.data() + L.off_ext, ext.data(), ext.size() * sizeof(ExtStep));
 }
 
@@ -181,8 +184,8 @@ int build_plan(const PlanRequest &rq, std::vector<int32_t> &blk, PlanLayout &L)
     {
         std::vector<int32_t> tok_adapter(blk.begin() + L.off_tok_adapter,
                                          blk.begin() + L.off_tok_adapter + T);
-        build_row_order(b, L.all, all, tok_adapter.data(), rq.rank, N, rq.bm_all);
-        build_row_order(b, L.train, train, tok_adapter.data(), rq.rank, N, rq.bm_train);
+        build_row_order(b, L.all, all, tok_adapter.data(), rq.rank, N, rq.bm_all, rq.B);
+        build_row_order(b, L.train, train, tok_adapter.data(), rq.rank, N, rq.bm_train, rq.A);
     }
 
     // gradient items: one per trained adapter, rows contiguous in the training row order
@@ -224,7 +227,7 @@ size_t plan_ints_upper_bound(int max_tokens, int max_segments, int max_adapters,
         n += 2 * Tp;                     // row_tok, row_adapter
         n += 4 * (Tp / kSkinnyRows + N) + 8;          // skinny items
         n += Tp / 64 + 8;                // ext_off (smallest tile 64 rows)
-        n += 4 * steps * (Tp / 64 + N) + 8;           // ext steps: (tiles + adapter runs) x steps
+        n += 4 * steps * (Tp / 64 + N) + 4 * kExtBatch + 8;  // ext steps: (tiles + adapter runs) x steps
     }
     n += 4 * N + 8;                      // grad items
     return n + 1024;
