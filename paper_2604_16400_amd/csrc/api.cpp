@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -56,6 +57,8 @@ struct collm_ctx {
     uint32_t *h_done_dev = nullptr;
     int *d_copy_counter = nullptr;
     void *d_zeros = nullptr;  // 256 bytes of zeros for masked 16-byte loads
+    float *d_part = nullptr;  // sums of the K slices of a skinny pass  [slices][rows][rpad]
+    size_t part_bytes = 0;
     int slot = 0;
     int32_t *d_plan = nullptr;
 
@@ -77,6 +80,9 @@ struct collm_ctx {
 
     int tile_fwd = -1, tile_bwd = -1;  // forced GEMM tile shapes (-1 = choose)
     hipStream_t last_stream = nullptr;
+    // the adapter gradients run beside dh and the dX GEMM on a second stream
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_dh = nullptr, ev_join = nullptr;
 
     bool profile = false;
     int n_prof = 0;
@@ -89,16 +95,19 @@ namespace {
 
 int pick_tile(int rows, int cols)
 {
-    // Two shapes are worth choosing between: 256x256 run by eight waves (one block per CU,
-    // the most efficient inner loop) and 128x128 (two blocks per CU, about 0.8 of that
-    // efficiency, four times as many tiles).  Pick the one whose last, partly filled round
-    // of tiles over the 256 CUs costs less.
+    // Two shapes are worth choosing between: 256x256 run by four waves (one block per CU, the most
+    // efficient inner loop) and 128x128 (two blocks per CU, about 0.85 of that efficiency, four
+    // times as many tiles).  The cost of a shape is the number of rounds its tiles take over the
+    // 256 CUs, in units of one round of 256x256 tiles, with two corrections read off measurements:
+    // a GPU that is not filled once clocks higher, and a last round of 128x128 tiles that leaves
+    // every CU at most one block runs faster than a full one.
     const int rp = round_up(std::max(rows, 1), kRowPad);
-    const long t256 = (long)(rp / 256) * ((cols + 255) / 256);
-    const long t128 = (long)(rp / 128) * ((cols + 127) / 128);
-    const double cost256 = (double)((t256 + 255) / 256);
-    const double cost128 = (double)((t128 + 511) / 512) * 0.625;
-    return cost256 <= cost128 ? kTile256x256w8 : kTile128x128;
+    const double x256 = (double)(rp / 256) * ((cols + 255) / 256) / 256.0;
+    const double x128 = (double)(rp / 128) * ((cols + 127) / 128) / 512.0;
+    const double cost256 = x256 <= 1.0 ? 0.5 + 0.5 * x256 : std::ceil(x256);
+    const double whole = std::floor(x128), part = x128 - whole;
+    const double cost128 = 0.6 * (whole + (part == 0.0 ? 0.0 : (part <= 0.5 ? 0.6 : 1.0)));
+    return cost256 <= cost128 ? kTile256x256 : kTile128x128;
 }
 
 struct Prof {
@@ -230,6 +239,11 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
         rq.dB = dB;
         rq.bm_all = bm_all;
         rq.bm_train = bm_train;
+        {
+            int rmax = 1;
+            for (int a = 0; a < s->n_adapters; ++a) rmax = std::max(rmax, rank[a]);
+            rq.max_row_tiles = f32 ? 1 : skinny_max_row_tiles(round_up(rmax, kKStep));
+        }
         c->plan_valid = false;
         int rc = build_plan(rq, c->plan, c->L);
         if (rc != COLLM_OK) return rc;
@@ -291,11 +305,27 @@ int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, cons
     a.bf_out = bf_out;
     a.bf_ld = c->L.rpad;
     a.bf_mult = bf_mult;
+    // The pass is bound by memory latency unless thousands of waves are in flight: cut K into slices
+    // until there are about 8 waves per CU (each keeps several chunks in flight), as long as a wave
+    // keeps at least 64 K values and the partial sums stay well below the bytes streamed (and inside
+    // the workspace).  The second kernel that adds the slices costs a few microseconds.
+    int n_split = 1;
+    if (s->dtype == COLLM_BF16) {
+        const int kw = skinny_waves(c->L.rpad);
+        const long per_split = (long)c->rows_cap * c->rpad_cap * 4;
+        long lim = std::min<long>(kSkinnyMaxSplit, (long)c->part_bytes / per_split);
+        lim = std::min<long>(lim, K / (4L * c->L.rpad));
+        lim = std::min<long>(lim, K / (64L * kw));
+        n_split = (int)std::max<long>(1, std::min<long>(lim, (2048 + (long)R.n_items * kw - 1) / ((long)R.n_items * kw)));
+    }
+    a.part = c->d_part;
+    a.part_rows = c->rows_cap;
+    a.part_ld = c->rpad_cap;
     Prof prof(c, st, name);
     if (s->dtype == COLLM_F32) {
         HIP_TRY(launch_skinny_f32(a, R.n_items, t_kmajor, st));
     } else {
-        HIP_TRY(launch_skinny(a, R.n_items, c->L.rpad, t_kmajor, st));
+        HIP_TRY(launch_skinny(a, R.n_items, c->L.rpad, R.item_rows / kSkinnyRows, n_split, t_kmajor, st));
     }
     return COLLM_OK;
 }
@@ -374,14 +404,22 @@ int collm_ctx_create(collm_ctx **out, int device, int32_t max_tokens, int32_t ma
     *c->h_done = 0;
     if (hipHostGetDevicePointer((void **)&c->h_done_dev, c->h_done, 0) != hipSuccess) return fail(COLLM_E_HIP);
     const size_t act = (size_t)c->rows_cap * c->rpad_cap;
+    // partial sums of the K slices: room for kSkinnyMaxSplit slices, but no more than 64 MiB (at least one)
+    c->part_bytes = std::max(act * 4, std::min(act * 4 * kSkinnyMaxSplit, (size_t)64 << 20));
     if (dev_alloc((void **)&c->d_plan, c->plan_cap * sizeof(int32_t)) != hipSuccess ||
         dev_alloc(&c->d_hs, act * 4) != hipSuccess || dev_alloc(&c->d_dhs, act * 4) != hipSuccess ||
         dev_alloc((void **)&c->d_h32, act * 4) != hipSuccess ||
         dev_alloc((void **)&c->d_dh32, act * 4) != hipSuccess ||
-        dev_alloc((void **)&c->d_copy_counter, 64) != hipSuccess || dev_alloc(&c->d_zeros, 256) != hipSuccess)
+        dev_alloc((void **)&c->d_copy_counter, 64) != hipSuccess || dev_alloc(&c->d_zeros, 256) != hipSuccess ||
+        dev_alloc((void **)&c->d_part, c->part_bytes) != hipSuccess)
         return fail(COLLM_E_NOMEM);
     if (hipMemset(c->d_copy_counter, 0, 64) != hipSuccess) return fail(COLLM_E_HIP);
     if (hipMemset(c->d_zeros, 0, 256) != hipSuccess) return fail(COLLM_E_HIP);
+    if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_dh, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess)
+        return fail(COLLM_E_HIP);
     if (hipDeviceSynchronize() != hipSuccess) return fail(COLLM_E_HIP);
     c->workspace_bytes = ws;
     *out = c;
@@ -397,12 +435,15 @@ int collm_ctx_destroy(collm_ctx *c)
         if (c->h_stage[i]) (void)hipHostFree(c->h_stage[i]);
     }
     if (c->h_done) (void)hipHostFree(c->h_done);
+    if (c->side) (void)hipStreamDestroy(c->side);
+    for (hipEvent_t e : {c->ev_fork, c->ev_dh, c->ev_join})
+        if (e) (void)hipEventDestroy(e);
     if (c->prof_ev_made)
         for (int i = 0; i < kMaxProfile; ++i) {
             (void)hipEventDestroy(c->prof_ev[i][0]);
             (void)hipEventDestroy(c->prof_ev[i][1]);
         }
-    void *bufs[] = {c->d_plan, c->d_hs, c->d_dhs, c->d_h32, c->d_dh32, c->d_copy_counter, c->d_zeros};
+    void *bufs[] = {c->d_plan, c->d_hs, c->d_dhs, c->d_h32, c->d_dh32, c->d_copy_counter, c->d_zeros, c->d_part};
     for (void *b : bufs)
         if (b) (void)hipFree(b);
     delete c;
@@ -539,18 +580,22 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
                         nullptr, 0.f, "shrink_recompute", st);
         if (rc != COLLM_OK) return rc;
     }
-    // dh = s dy B_a^T: fp32 for dA, element type for the dX GEMM's extra K-steps
-    rc = run_skinny(c, s, L.train, dy, s->d_out, L.off_B_ptr, true, c->d_dh32, L.rpad, L.rpad, 0, s->scale,
-                    c->d_dhs, s->scale, "dh", st);
-    if (rc != COLLM_OK) return rc;
-
+    // The adapter gradients depend on little (dB_a: h and dy; dA_a: dh and x) and are bound by memory
+    // latency, as is dh: they run on a second stream beside dh and the dX GEMM, which joins the
+    // caller's stream again before the call returns.  (Serial when kernels are being timed.)
+    const bool overlap = dA && !c->profile;
+    hipStream_t gs = overlap ? c->side : st;
+    GradArgs ga{};
+    const int64_t esz = f32 ? 4 : 2;
     if (dA) {
-        GradArgs ga{};
+        if (overlap) {
+            HIP_TRY(hipEventRecord(c->ev_fork, st));
+            HIP_TRY(hipStreamWaitEvent(c->side, c->ev_fork, 0));
+        }
         ga.row_tok = c->d_plan + L.train.off_row_tok;
         ga.items = reinterpret_cast<const GradItem *>(c->d_plan + L.off_grad);
         ga.accumulate = accumulate ? 1 : 0;
         // dB_a = s h^T dy
-        const int64_t esz = f32 ? 4 : 2;
         ga.big = dy;
         ga.ld_big = s->d_out;
         ga.big_bytes = (uint32_t)((int64_t)s->n_tokens * s->d_out * esz);
@@ -568,9 +613,21 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
         ga.out_tab = reinterpret_cast<const uint64_t *>(c->d_plan + L.off_dB_ptr);
         ga.out_transposed = 0;
         {
-            Prof prof(c, st, "grad_dB");
-            if (f32) HIP_TRY(launch_grad_f32(ga, L.n_grad, st));
-            else HIP_TRY(launch_grad(ga, L.n_grad, L.rpad, st));
+            Prof prof(c, gs, "grad_dB");
+            if (f32) HIP_TRY(launch_grad_f32(ga, L.n_grad, gs));
+            else HIP_TRY(launch_grad(ga, L.n_grad, L.rpad, gs));
+        }
+    }
+
+    // dh = s dy B_a^T: fp32 for dA, element type for the dX GEMM's extra K-steps
+    rc = run_skinny(c, s, L.train, dy, s->d_out, L.off_B_ptr, true, c->d_dh32, L.rpad, L.rpad, 0, s->scale,
+                    c->d_dhs, s->scale, "dh", st);
+    if (rc != COLLM_OK) return rc;
+
+    if (dA) {
+        if (overlap) {
+            HIP_TRY(hipEventRecord(c->ev_dh, st));
+            HIP_TRY(hipStreamWaitEvent(c->side, c->ev_dh, 0));
         }
         // dA_a = x^T dh
         ga.big = x;
@@ -584,10 +641,11 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
         ga.out_tab = reinterpret_cast<const uint64_t *>(c->d_plan + L.off_dA_ptr);
         ga.out_transposed = 1;
         {
-            Prof prof(c, st, "grad_dA");
-            if (f32) HIP_TRY(launch_grad_f32(ga, L.n_grad, st));
-            else HIP_TRY(launch_grad(ga, L.n_grad, L.rpad, st));
+            Prof prof(c, gs, "grad_dA");
+            if (f32) HIP_TRY(launch_grad_f32(ga, L.n_grad, gs));
+            else HIP_TRY(launch_grad(ga, L.n_grad, L.rpad, gs));
         }
+        if (overlap) HIP_TRY(hipEventRecord(c->ev_join, c->side));
     }
 
     if (dx) {
@@ -620,6 +678,7 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
             HIP_TRY(launch_gemm(g, tile, true, st));
         }
     }
+    if (overlap) HIP_TRY(hipStreamWaitEvent(st, c->ev_join, 0));
     return COLLM_OK;
 }
 

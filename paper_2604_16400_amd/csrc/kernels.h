@@ -48,6 +48,9 @@ struct SkinnyArgs {
     void *bf_out;             // optional scaled copy in the element type, row order
     int bf_ld;
     float bf_mult;
+    // K split over several blocks (bf16 kernels): sums of the slices, [slice][part_rows][part_ld]
+    float *part;
+    int part_rows, part_ld;
 };
 
 // out_a(q, n) = sum_t small[t][q] * big[tok(t)][n] over one adapter's training rows
@@ -70,7 +73,11 @@ struct GradArgs {
 hipError_t launch_gemm(const GemmArgs &a, int tile_cfg, bool b_kmajor, hipStream_t st);
 int gemm_tile_rows(int tile_cfg);
 int gemm_tile_cols(int tile_cfg);
-hipError_t launch_skinny(const SkinnyArgs &a, int n_items, int rpad, bool t_kmajor, hipStream_t st);
+// items hold up to 16 * row_tiles rows (row_tiles <= skinny_max_row_tiles(rpad)); n_split slices of K
+hipError_t launch_skinny(const SkinnyArgs &a, int n_items, int rpad, int row_tiles, int n_split, bool t_kmajor,
+                         hipStream_t st);
+int skinny_max_row_tiles(int rpad);
+int skinny_waves(int rpad);  // waves of a block, which split the block's K slice
 hipError_t launch_grad(const GradArgs &a, int n_grad, int rpad, hipStream_t st);
 
 // copies ints [first_int, first_int + n_ints) (rounded outwards to 16 bytes) of a pinned host

@@ -857,66 +857,118 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 // =========================================================================================
 // skinny: out[m][q] = sum_k in[tok(m)][k] * table_a(k, q)     (rank-wide output, HBM-bound)
 //
-// One block = one item (<= 16 rows of one adapter).  Its KW waves split K; every wave runs
-// 16x16x32 MFMAs on its own K range and the partial sums meet in LDS in wave order (fixed
-// order, no atomics).  The streamed operand (rows of x or dy) goes from global memory
-// straight into MFMA operand registers: lane l holds 8 consecutive K values of row l % 16.
-// The adapter table is either K-major ([rank][K], read the same way) or N-major ([K][rank]):
-// then each wave copies its chunk as it lies in memory into a private LDS area and builds the
-// operand with transposing reads.  Nothing in the K loop needs a block barrier.
+// One block = one item (RT = 1 or 2 tiles of 16 rows of one adapter) x one of gridDim.y slices of K.
+// Its KW waves split the slice; every wave runs 16x16x32 MFMAs on its own K range for all row
+// tiles of the item, so a table fragment is fetched once per item and used RT times.  The
+// streamed operand (rows of x or dy) goes from global memory straight into MFMA operand
+// registers: lane l holds 8 consecutive K values of row l % 16.  The adapter table is either
+// K-major ([rank][K], read the same way) or N-major ([K][rank]): then each wave copies its
+// chunk as it lies in memory into a private LDS area and builds the operand with transposing
+// reads.  Nothing in the K loop needs a block barrier.  The partial sums of the waves meet in
+// LDS in wave order.  With more than one K slice the block writes its sums to a workspace and
+// a second, small kernel adds the slices in slice order (fixed order, no float atomics, and no
+// fences inside a kernel: on this GPU a device-wide fence writes back and invalidates the L2).
 // =========================================================================================
+// Results of four rank indices q .. q + 3 of row m of an item: the fp32 copy (token-indexed h_save
+// or row-indexed workspace) and the scaled copy in the element type.
+__device__ __forceinline__ void skinny_store(const SkinnyArgs &p, const SkinnyItem &it, int m, int q, floatx4 sum)
+{
+    const int rank = it.rank, rp = (rank + 15) & ~15;
+    float v[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = (q + e < rank) ? sum[e] : 0.f;
+    const int row = it.row_lo + m;
+    const int tok = p.row_tok[row];
+    float *f32_row = nullptr;
+    if (p.f32_out) {
+        if (p.f32_by_token) {
+            if (p.tok_train[tok]) f32_row = p.f32_out + (int64_t)tok * p.f32_ld;
+        } else {
+            f32_row = p.f32_out + (int64_t)row * p.f32_ld;
+        }
+    }
+    if (f32_row) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (q + e < p.f32_cols) f32_row[q + e] = v[e] * p.f32_mult;
+        // zero fill beyond the padded rank (h_save rows are max_rank wide)
+        if (q + 4 == rp)
+            for (int z = rp; z < p.f32_cols; ++z) f32_row[z] = 0.f;
+    }
+    if (p.bf_out) {
+        uint16_t *bf_row = reinterpret_cast<uint16_t *>(p.bf_out) + (int64_t)row * p.bf_ld;
+        uint2 o;
+        o.x = pack_bf16(v[0] * p.bf_mult, v[1] * p.bf_mult);
+        o.y = pack_bf16(v[2] * p.bf_mult, v[3] * p.bf_mult);
+        *reinterpret_cast<uint2 *>(bf_row + q) = o;
+    }
+}
+
 template <int RP>
 struct SkinnyCfg {
-    static constexpr int CHK = RP <= 16 ? 128 : (RP <= 64 ? 64 : 32);  // K values per chunk
+    static constexpr int CHK = RP <= 64 ? 64 : 32;                    // K values per chunk
     static constexpr int STEPS = CHK / 32;
     static constexpr int KW = RP <= 32 ? 8 : 4;                       // waves per block
     static constexpr int NB = RP / 16;                                // 16-wide rank blocks
+    static constexpr int RTMAX = RP <= 128 ? 2 : 1;                   // row tiles per item
     static constexpr int PITCH = RP * 2 + 16;                         // LDS row pitch of an N-major chunk
     static constexpr int STAGE_BYTES = CHK * PITCH;                   // per wave
     static constexpr int RED_LD = RP + 4;                             // floats
-    static constexpr int RED_BYTES = KW * 16 * RED_LD * 4;
 };
 
-template <int RP, bool T_KMAJOR>
+template <int RP, bool T_KMAJOR, int RT>
 __global__ void __launch_bounds__(SkinnyCfg<RP>::KW * 64) skinny_kernel(SkinnyArgs p)
 {
     using C = SkinnyCfg<RP>;
     constexpr int KW = C::KW, STEPS = C::STEPS, CHK = C::CHK, NB = C::NB;
+    constexpr int ROWS = 16 * RT;
+    constexpr int RED_BYTES = KW * ROWS * C::RED_LD * 4;
     extern __shared__ __align__(16) uint8_t smem[];
     float *red = reinterpret_cast<float *>(smem);
-    uint8_t *stage = smem + C::RED_BYTES + (threadIdx.x >> 6) * C::STAGE_BYTES;
+    uint8_t *stage = smem + RED_BYTES + (threadIdx.x >> 6) * C::STAGE_BYTES;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const SkinnyItem it = p.items[blockIdx.x];
     const int K = p.K, rank = it.rank;
     const int rp = (rank + 15) & ~15;
     const int l16 = lane & 15, kg = lane >> 4;
+    const int n_rt = (it.n_rows + 15) >> 4;  // row tiles of this item
 
-    // K range of this wave (multiple of 32 long, except at the end of K)
-    const int per = (((K + KW - 1) / KW) + 31) & ~31;
-    const int k_lo = wave * per;
+    // K range of this wave: the slices of the blocks, cut again into the ranges of their waves
+    const int n_split = gridDim.y, split = blockIdx.y;
+    const int per = (((K + n_split * KW - 1) / (n_split * KW)) + 31) & ~31;
+    const int k_lo = (split * KW + wave) * per;
     const int k_hi = (k_lo + per) < K ? (k_lo + per) : K;
 
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.in, p.in_bytes);
     const __amdgpu_buffer_rsrc_t rt = make_rsrc(reinterpret_cast<const void *>(p.tab[it.adapter]),
                                                 (uint32_t)rank * (uint32_t)K * 2u);
-    uint32_t xoff = kOob;
-    if (l16 < it.n_rows) {
-        const int tok = p.row_tok[it.row_lo + l16];
-        if (tok >= 0) xoff = (uint32_t)tok * (uint32_t)p.ld_in * 2u + kg * 16u;
+    uint32_t xoff[RT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+        xoff[t] = kOob;
+        if (t * 16 + l16 < it.n_rows) {
+            const int tok = p.row_tok[it.row_lo + t * 16 + l16];
+            if (tok >= 0) xoff[t] = (uint32_t)tok * (uint32_t)p.ld_in * 2u + kg * 16u;
+        }
     }
 
-    uint4 xreg[2][STEPS];
+    // D chunks are in flight per wave (a ring of register sets): the pass is bound by memory latency.
+    // Four where the registers of a chunk are few enough to keep four waves per SIMD, else two.
+    constexpr int D = (RT * STEPS + STEPS * NB <= 8) ? 4 : 2;
+    uint4 xreg[D][RT][STEPS];
     auto load_x = [&](int k0, int buf) {
 #pragma unroll
-        for (int s = 0; s < STEPS; ++s) {
-            const int k = k0 + s * 32;
-            xreg[buf][s] = buf16(rx, (k + kg * 8 < k_hi) ? xoff + (uint32_t)k * 2u : kOob);
-        }
+        for (int t = 0; t < RT; ++t)
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                const int k = k0 + s * 32;
+                xreg[buf][t][s] = buf16(rx, (k + kg * 8 < k_hi) ? xoff[t] + (uint32_t)k * 2u : kOob);
+            }
     };
 
     // K-major table: operand registers straight from memory
-    uint4 treg[T_KMAJOR ? 2 : 1][T_KMAJOR ? STEPS * NB : 1];
+    uint4 treg[T_KMAJOR ? D : 1][T_KMAJOR ? STEPS * NB : 1];
     auto load_t_kmajor = [&](int k0, int buf) {
         if constexpr (T_KMAJOR) {
 #pragma unroll
@@ -933,33 +985,38 @@ __global__ void __launch_bounds__(SkinnyCfg<RP>::KW * 64) skinny_kernel(SkinnyAr
     };
     // N-major table: the chunk [CHK][rank] is contiguous; copy it to LDS rows of PITCH bytes
     constexpr int NCP = T_KMAJOR ? 1 : (CHK * RP * 2 / 16 + 63) / 64;  // 16-byte pieces per lane
-    uint4 creg[NCP];
+    uint4 creg[D][NCP];
     const bool fast_copy = (rank & 7) == 0;
     const int cpr = rank >> 3;  // 16-byte pieces per table row
-    auto load_t_nmajor = [&](int k0) {
+    // piece c of the chunk is piece c % cpr of row c / cpr; the division is done once
+    int crow[NCP], ccol[NCP];
+    if constexpr (!T_KMAJOR) {
+#pragma unroll
+        for (int i = 0; i < NCP; ++i) {
+            const int c = lane + i * 64;
+            crow[i] = fast_copy ? c / cpr : 0;
+            ccol[i] = fast_copy ? c - crow[i] * cpr : 0;
+        }
+    }
+    auto load_t_nmajor = [&](int k0, int buf) {
         if constexpr (!T_KMAJOR) {
             if (fast_copy) {
 #pragma unroll
                 for (int i = 0; i < NCP; ++i) {
                     const int c = lane + i * 64;
-                    const bool in = c < CHK * cpr;
                     // rows beyond K lie beyond the table and read as zero
-                    creg[i] = buf16(rt, in ? ((uint32_t)k0 * (uint32_t)rank) * 2u + (uint32_t)c * 16u : kOob);
+                    creg[buf][i] = buf16(rt, c < CHK * cpr ? ((uint32_t)k0 * (uint32_t)rank) * 2u + (uint32_t)c * 16u : kOob);
                 }
             }
         }
     };
-    auto store_t_nmajor = [&](int k0) {
+    auto store_t_nmajor = [&](int k0, int buf) {
         if constexpr (!T_KMAJOR) {
             if (fast_copy) {
 #pragma unroll
-                for (int i = 0; i < NCP; ++i) {
-                    const int c = lane + i * 64;
-                    if (c < CHK * cpr) {
-                        const int r = c / cpr, cc = c - r * cpr;
-                        *reinterpret_cast<uint4 *>(stage + r * C::PITCH + cc * 16) = creg[i];
-                    }
-                }
+                for (int i = 0; i < NCP; ++i)
+                    if (lane + i * 64 < CHK * cpr)
+                        *reinterpret_cast<uint4 *>(stage + crow[i] * C::PITCH + ccol[i] * 16) = creg[buf][i];
             } else {
                 // ranks that are no multiple of 8: element by element
                 const uint16_t *tab = reinterpret_cast<const uint16_t *>(p.tab[it.adapter]);
@@ -972,88 +1029,94 @@ __global__ void __launch_bounds__(SkinnyCfg<RP>::KW * 64) skinny_kernel(SkinnyAr
         }
     };
 
-    floatx4 acc[NB];
+    floatx4 acc[RT][NB];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) acc[nb] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < RT; ++t)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[t][nb] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     if (k_lo < k_hi) {
-        load_x(k_lo, 0);
-        load_t_kmajor(k_lo, 0);
-        load_t_nmajor(k_lo);
-        int buf = 0;
-        for (int k0 = k_lo; k0 < k_hi; k0 += CHK, buf ^= 1) {
-            store_t_nmajor(k0);
-            // next chunk in flight while this one multiplies
-            load_x(k0 + CHK, buf ^ 1);
-            load_t_kmajor(k0 + CHK, buf ^ 1);
-            load_t_nmajor(k0 + CHK);
 #pragma unroll
-            for (int s = 0; s < STEPS; ++s) {
-                const bf16x8 xf = __builtin_bit_cast(bf16x8, xreg[buf][s]);
+        for (int d = 0; d < D; ++d) {
+            load_x(k_lo + d * CHK, d);
+            load_t_kmajor(k_lo + d * CHK, d);
+            load_t_nmajor(k_lo + d * CHK, d);
+        }
+        for (int kb = k_lo; kb < k_hi; kb += D * CHK) {
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    if (nb * 16 < rp) {
-                        bf16x8 tf;
-                        if constexpr (T_KMAJOR) {
-                            tf = __builtin_bit_cast(bf16x8, treg[buf][s * NB + nb]);
-                        } else {
-                            const uint8_t *src = stage + (s * 32 + kg * 8 + (l16 >> 2)) * C::PITCH +
-                                                 (nb * 16 + (l16 & 3) * 4) * 2;
-                            const bf16x4 lo = lds_tr(src), hi = lds_tr(src + 4 * C::PITCH);
-                            tf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            for (int d = 0; d < D; ++d) {
+                const int k0 = kb + d * CHK;  // chunks beyond the wave's range were loaded as zeros
+                store_t_nmajor(k0, d);
+#pragma unroll
+                for (int s = 0; s < STEPS; ++s) {
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        if (nb * 16 < rp) {
+                            bf16x8 tf;
+                            if constexpr (T_KMAJOR) {
+                                tf = __builtin_bit_cast(bf16x8, treg[d][s * NB + nb]);
+                            } else {
+                                const uint8_t *src = stage + (s * 32 + kg * 8 + (l16 >> 2)) * C::PITCH +
+                                                     (nb * 16 + (l16 & 3) * 4) * 2;
+                                const bf16x4 lo = lds_tr(src), hi = lds_tr(src + 4 * C::PITCH);
+                                tf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                            }
+#pragma unroll
+                            for (int t = 0; t < RT; ++t)
+                                if (t < n_rt)
+                                    acc[t][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                        tf, __builtin_bit_cast(bf16x8, xreg[d][t][s]), acc[t][nb], 0, 0, 0);
                         }
-                        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tf, xf, acc[nb], 0, 0, 0);
                     }
                 }
+                // refill this register set with the chunk D further on
+                load_x(k0 + D * CHK, d);
+                load_t_kmajor(k0 + D * CHK, d);
+                load_t_nmajor(k0 + D * CHK, d);
             }
         }
     }
 
-    // lane holds row m = lane % 16, columns q = nb*16 + 4*(lane/16) + 0..3
+    // lane holds row m = 16 t + lane % 16, columns q = nb*16 + 4*(lane/16) + 0..3
     {
-        float *mine = red + (wave * 16 + l16) * C::RED_LD;
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-            *reinterpret_cast<floatx4 *>(mine + nb * 16 + kg * 4) = acc[nb];
+        for (int t = 0; t < RT; ++t) {
+            float *mine = red + (wave * ROWS + t * 16 + l16) * C::RED_LD;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                *reinterpret_cast<floatx4 *>(mine + nb * 16 + kg * 4) = acc[t][nb];
+        }
     }
     __syncthreads();
 
-    // sum over the waves in wave order, then write the fp32 copy (token-indexed h_save or
-    // row-indexed workspace) and the scaled copy in the element type
-    for (int idx = tid; idx < 16 * (RP / 4); idx += KW * 64) {
-        const int m = idx & 15, q = (idx >> 4) * 4;
+    // sum over the waves in wave order; with several K slices the sums go to the workspace and a
+    // second kernel adds the slices
+    const int n_quads = ROWS * (RP / 4);
+    for (int idx = tid; idx < n_quads; idx += KW * 64) {
+        const int m = idx % ROWS, q = (idx / ROWS) * 4;
         if (m >= it.n_rows || q >= rp) continue;
         floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int w = 0; w < KW; ++w) sum += *reinterpret_cast<const floatx4 *>(red + (w * 16 + m) * C::RED_LD + q);
-        float v[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (q + e < rank) ? sum[e] : 0.f;
-        const int row = it.row_lo + m;
-        const int tok = p.row_tok[row];
-        float *f32_row = nullptr;
-        if (p.f32_out) {
-            if (p.f32_by_token) {
-                if (p.tok_train[tok]) f32_row = p.f32_out + (int64_t)tok * p.f32_ld;
-            } else {
-                f32_row = p.f32_out + (int64_t)row * p.f32_ld;
-            }
-        }
-        if (f32_row) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (q + e < p.f32_cols) f32_row[q + e] = v[e] * p.f32_mult;
-            // zero fill beyond the padded rank (h_save rows are max_rank wide)
-            if (q + 4 == rp)
-                for (int z = rp; z < p.f32_cols; ++z) f32_row[z] = 0.f;
-        }
-        if (p.bf_out) {
-            uint16_t *bf_row = reinterpret_cast<uint16_t *>(p.bf_out) + (int64_t)row * p.bf_ld;
-            uint2 o;
-            o.x = pack_bf16(v[0] * p.bf_mult, v[1] * p.bf_mult);
-            o.y = pack_bf16(v[2] * p.bf_mult, v[3] * p.bf_mult);
-            *reinterpret_cast<uint2 *>(bf_row + q) = o;
-        }
+        for (int w = 0; w < KW; ++w) sum += *reinterpret_cast<const floatx4 *>(red + (w * ROWS + m) * C::RED_LD + q);
+        if (n_split > 1)
+            *reinterpret_cast<floatx4 *>(p.part + ((int64_t)split * p.part_rows + it.row_lo + m) * p.part_ld + q) = sum;
+        else
+            skinny_store(p, it, m, q, sum);
+    }
+}
+
+// adds the K slices of every item in slice order and writes the results
+__global__ void __launch_bounds__(256) skinny_finish_kernel(SkinnyArgs p, int n_split)
+{
+    const SkinnyItem it = p.items[blockIdx.x];
+    const int rp = (it.rank + 15) & ~15;
+    const int nq = rp >> 2;
+    for (int idx = threadIdx.x; idx < it.n_rows * nq; idx += 256) {
+        const int m = idx / nq, q = (idx - m * nq) * 4;
+        floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int sp = 0; sp < n_split; ++sp)
+            sum += *reinterpret_cast<const floatx4 *>(p.part + ((int64_t)sp * p.part_rows + it.row_lo + m) * p.part_ld + q);
+        skinny_store(p, it, m, q, sum);
     }
 }
 
@@ -1279,12 +1342,12 @@ hipError_t launch_gemm(const GemmArgs &a, int tile_cfg, bool b_kmajor, hipStream
 int gemm_tile_rows(int tile_cfg) { return tile_cfg == kTile128x128 ? 128 : 256; }
 int gemm_tile_cols(int tile_cfg) { return (tile_cfg == kTile256x256 || tile_cfg == kTile256x256w8) ? 256 : 128; }
 
-template <int RP, bool KM>
-static hipError_t launch_skinny_t(const SkinnyArgs &a, int n_items, hipStream_t st)
+template <int RP, bool KM, int RT>
+static hipError_t launch_skinny_t(const SkinnyArgs &a, int n_items, int n_split, hipStream_t st)
 {
     using C = SkinnyCfg<RP>;
-    constexpr int smem = C::RED_BYTES + (KM ? 0 : C::KW * C::STAGE_BYTES);
-    auto kern = skinny_kernel<RP, KM>;
+    constexpr int smem = C::KW * 16 * RT * C::RED_LD * 4 + (KM ? 0 : C::KW * C::STAGE_BYTES);
+    auto kern = skinny_kernel<RP, KM, RT>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -1292,15 +1355,32 @@ static hipError_t launch_skinny_t(const SkinnyArgs &a, int n_items, hipStream_t 
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(n_items), dim3(C::KW * 64), smem, st, a);
+    hipLaunchKernelGGL(kern, dim3(n_items, n_split), dim3(C::KW * 64), smem, st, a);
+    if (n_split > 1) hipLaunchKernelGGL(skinny_finish_kernel, dim3(n_items), dim3(256), 0, st, a, n_split);
     return hipGetLastError();
 }
 
-hipError_t launch_skinny(const SkinnyArgs &a, int n_items, int rpad, bool t_kmajor, hipStream_t st)
+template <int RP, bool KM>
+static hipError_t launch_skinny_rt(const SkinnyArgs &a, int n_items, int row_tiles, int n_split, hipStream_t st)
+{
+    constexpr int RTMAX = SkinnyCfg<RP>::RTMAX;
+    if (row_tiles > RTMAX) return hipErrorInvalidValue;
+    if constexpr (RTMAX >= 2)
+        if (row_tiles > 1) return launch_skinny_t<RP, KM, 2>(a, n_items, n_split, st);
+    return launch_skinny_t<RP, KM, 1>(a, n_items, n_split, st);
+}
+
+int skinny_max_row_tiles(int rpad) { return rpad <= 128 ? 2 : 1; }
+int skinny_waves(int rpad) { return rpad <= 32 ? 8 : 4; }
+
+hipError_t launch_skinny(const SkinnyArgs &a, int n_items, int rpad, int row_tiles, int n_split, bool t_kmajor,
+                         hipStream_t st)
 {
     if (n_items <= 0) return hipSuccess;
+    if (n_split < 1 || (n_split > 1 && !a.part)) return hipErrorInvalidValue;
 #define COLLM_SK(RP) \
-    return t_kmajor ? launch_skinny_t<RP, true>(a, n_items, st) : launch_skinny_t<RP, false>(a, n_items, st)
+    return t_kmajor ? launch_skinny_rt<RP, true>(a, n_items, row_tiles, n_split, st) \
+                    : launch_skinny_rt<RP, false>(a, n_items, row_tiles, n_split, st)
     if (rpad <= 16) { COLLM_SK(16); }
     if (rpad <= 32) { COLLM_SK(32); }
     if (rpad <= 64) { COLLM_SK(64); }

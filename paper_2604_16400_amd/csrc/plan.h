@@ -16,14 +16,15 @@ namespace collm {
 
 constexpr int kRowPad = 256;   // row orders are padded to a multiple of the largest GEMM tile
 constexpr int kMaxRank = 256;  // largest adapter rank the kernels accept
-constexpr int kSkinnyRows = 16;  // rows of one skinny work item (one MFMA tile)
+constexpr int kSkinnyRows = 16;  // rows of one MFMA tile of the skinny passes; an item holds 1 or 2 tiles
+constexpr int kSkinnyMaxSplit = 32;  // K slices a skinny pass may be cut into (partial sums in a workspace)
 constexpr int kKStep = 16;       // K extent of one low-rank extension step (one MFMA K)
 
 // Run of rows of one adapter inside a row order (never crosses an adapter boundary).
 struct SkinnyItem {
     int32_t adapter;
     int32_t row_lo;  // first row (index into the row order)
-    int32_t n_rows;  // 1..kSkinnyRows
+    int32_t n_rows;  // 1..item_rows of the row order
     int32_t rank;    // rank of the adapter
 };
 
@@ -50,6 +51,7 @@ struct RowOrderLayout {
     int32_t off_row_tok = 0;      // [n_rows_pad] token index or -1
     int32_t off_row_adapter = 0;  // [n_rows_pad] adapter or -1
     int32_t n_items = 0, off_items = 0;  // SkinnyItem[n_items]
+    int32_t item_rows = kSkinnyRows;     // most rows an item holds (16 or 32)
     int32_t bm = 0, n_tiles_m = 0;       // GEMM row tile the extension tables were built for
     int32_t off_ext_off = 0;             // [n_tiles_m + 1]
     int32_t off_ext = 0, n_ext = 0;      // ExtStep[n_ext]

@@ -31,6 +31,7 @@ struct PlanRequest {
     float *const *dB = nullptr;
     int bm_all = 256;    // GEMM row tile of the forward GEMM
     int bm_train = 256;  // GEMM row tile of the dX GEMM
+    int max_row_tiles = 1;  // most 16-row tiles a skinny item may hold (what the kernels for this rank width take)
 };
 
 // Builds the plan block for a batch that passed validate_batch.
