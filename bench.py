@@ -27,6 +27,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
+# HBM-side bytes of one forward-GEMM launch of configuration 2 (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by
+# what the same counters read for a plain 1 GiB copy; profiles/gemm_skinny_grad_config2_q_proj.txt).  Set to
+# None whenever gemm_lora_kernel changes until the counters have been taken again.
+ROOFLINE_TRAFFIC_BYTES = 153.7e6
 
 
 def _dev_tensors(w, proj_index, torch, exact=False):
@@ -231,7 +235,7 @@ def main():
     achieved = gemm_flops / (kt["gemm_fwd"] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "gemm_lora_kernel (forward: x W + fused expand)",
                 "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": ROOFLINE_TRAFFIC_BYTES,
                 "avg_launch_ms": kt["gemm_fwd"], "flops_per_launch": gemm_flops}
 
     all_cfg = [head]
