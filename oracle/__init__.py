@@ -172,3 +172,39 @@ def lora_linear_bwd(x, W, A, B, tok_adapter, tok_is_train, scale, dy, want_dx=Tr
         _ptr_table(dB) if want_dab else None,
     )
     return dx, dA, dB
+
+
+# ---------------------------------------------------------------------------------------------
+# The step after the backward pass: update of the trained adapter tables and their aggregation.
+# ---------------------------------------------------------------------------------------------
+def adapter_fedavg(copies) -> np.ndarray:
+    """Aggregation of the adapter copies of the |K| participating replicas (paper section 4.2, the
+    equation for the aggregated B and A): the element-wise mean, copies added in index order."""
+    copies = [_f64(c) for c in copies]
+    assert len(copies) >= 1 and all(c.shape == copies[0].shape for c in copies)
+    acc = np.zeros_like(copies[0])
+    for c in copies:
+        acc = acc + c
+    return acc / float(len(copies))
+
+
+def adamw_step(p, g, m, v, lr, beta1, beta2, eps, weight_decay, step):
+    """One AdamW update (Loshchilov & Hutter 2019, decoupled weight decay, bias-corrected moments) of
+    one adapter table in fp64.  The paper trains only the adapters (section 4.2) and keeps "gradients
+    and optimizer state" with the fine-tuning task (section 2.1) without naming the optimizer; AdamW
+    is this build's reading.  `step` counts from 1.  Returns (p, m, v)."""
+    p, g, m, v = _f64(p).copy(), _f64(g), _f64(m).copy(), _f64(v).copy()
+    assert step >= 1
+    it = np.nditer([p, g, m, v], op_flags=[["readwrite"], ["readonly"], ["readwrite"], ["readwrite"]])
+    c1 = 1.0 - beta1 ** step
+    c2 = 1.0 - beta2 ** step
+    for pi, gi, mi, vi in it:
+        gval = float(gi)
+        m_new = beta1 * float(mi) + (1.0 - beta1) * gval
+        v_new = beta2 * float(vi) + (1.0 - beta2) * gval * gval
+        p_dec = float(pi) * (1.0 - lr * weight_decay)
+        denom = (v_new ** 0.5) / (c2 ** 0.5) + eps
+        pi[...] = p_dec - (lr / c1) * m_new / denom
+        mi[...] = m_new
+        vi[...] = v_new
+    return p, m, v

@@ -267,3 +267,57 @@ def test_untrained_adapters_and_inference_rows_are_untouched():
     # skipping the W-sized contraction leaves the adapter gradients unchanged
     _, dA3, dB3 = oracle.lora_linear_bwd(t.x, None, t.A, t.B, ta, tt, w.scale, t.dy, want_dx=False)
     assert np.array_equal(dA3[1], dA[1]) and np.array_equal(dB3[1], dB[1])
+
+
+# ---------------------------------------------------------------------------------------------
+# adapter aggregation (paper section 4.2, aggregated B and A) and the AdamW update
+# ---------------------------------------------------------------------------------------------
+def test_fedavg_hand_example_and_mean():
+    # three copies, worked by hand: (1+3+2)/3, (2+2+2)/3, (3+1+2)/3, (0.5-1+2)/3
+    got = oracle.adapter_fedavg([[1.0, 2.0, 3.0, 0.5], [3.0, 2.0, 1.0, -1.0], [2.0, 2.0, 2.0, 2.0]])
+    assert np.array_equal(got, np.array([2.0, 2.0, 2.0, 0.5]))
+    rng = np.random.default_rng(5)
+    copies = [rng.normal(size=(37, 16)) for _ in range(5)]
+    got = oracle.adapter_fedavg(copies)
+    assert np.max(np.abs(got - np.mean(np.stack(copies), axis=0))) < 1e-15
+    # identical copies average to themselves; a constant shift of every copy shifts the mean
+    assert np.array_equal(oracle.adapter_fedavg([copies[0]] * 4), copies[0])
+    assert np.max(np.abs(oracle.adapter_fedavg([c + 0.25 for c in copies]) - (got + 0.25))) < 1e-15
+    # one copy is returned unchanged; the order of the copies does not matter beyond rounding
+    assert np.array_equal(oracle.adapter_fedavg(copies[:1]), copies[0])
+    assert np.max(np.abs(oracle.adapter_fedavg(copies[::-1]) - got)) < 1e-15
+
+
+def test_adamw_closed_forms():
+    p = np.array([1.0, -2.0, 0.5, 3.0])
+    g = np.array([0.1, -4.0, 0.0, 1e-3])
+    z = np.zeros(4)
+    lr, b1, b2, eps = 1e-2, 0.9, 0.999, 1e-8
+    # first step from zero moments, no decay: m^ = g, v^ = g^2, so p moves by lr g / (|g| + eps)
+    p1, m1, v1 = oracle.adamw_step(p, g, z, z, lr, b1, b2, eps, 0.0, 1)
+    assert np.max(np.abs(p1 - (p - lr * g / (np.abs(g) + eps)))) < 1e-15
+    assert np.max(np.abs(m1 - 0.1 * g)) < 1e-15 and np.max(np.abs(v1 - 1e-3 * g * g)) < 1e-15
+    assert p1[2] == p[2]  # zero gradient, zero decay: untouched
+    # decay alone (zero gradient): p (1 - lr wd), moments only shrink
+    p2, m2, v2 = oracle.adamw_step(p, z, m1, v1, lr, b1, b2, eps, 0.1, 2)
+    m_hat = b1 * m1 / (1 - b1 ** 2)
+    v_hat = b2 * v1 / (1 - b2 ** 2)
+    assert np.max(np.abs(p2 - (p * (1 - lr * 0.1) - lr * m_hat / (np.sqrt(v_hat) + eps)))) < 1e-15
+    assert np.max(np.abs(m2 - b1 * m1)) < 1e-15 and np.max(np.abs(v2 - b2 * v1)) < 1e-15
+
+
+def test_adamw_matches_library_optimizer():
+    import torch
+
+    rng = np.random.default_rng(11)
+    p0 = rng.normal(size=(24, 8))
+    grads = [rng.normal(size=(24, 8)) * s for s in (1.0, 0.1, 3.0, 1e-3, 0.5)]
+    lr, b1, b2, eps, wd = 3e-3, 0.9, 0.95, 1e-8, 0.05
+    tp = torch.tensor(p0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.AdamW([tp], lr=lr, betas=(b1, b2), eps=eps, weight_decay=wd)
+    p, m, v = p0, np.zeros_like(p0), np.zeros_like(p0)
+    for step, g in enumerate(grads, start=1):
+        tp.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        p, m, v = oracle.adamw_step(p, g, m, v, lr, b1, b2, eps, wd, step)
+        assert np.max(np.abs(p - tp.detach().numpy())) < 1e-13, step
