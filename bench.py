@@ -175,6 +175,45 @@ class Runner:
         self.ctx.close()
 
 
+def _adapter_update(torch, binding):
+    """The step after the backward pass at the size of configuration 5's gate/up adapters (128 adapters of rank
+    16, A 8192x16 and B 16x28672, stored back to back): aggregation of 4 replica copies and one AdamW step with an
+    fp32 master copy.  Element-wise and HBM-bound; bytes are what each call must read and write."""
+    n = 128 * 16 * (8192 + 28672)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(20260416)
+    copies = [(torch.randn(n, generator=g, device="cuda") * 0.02).to(torch.bfloat16) for _ in range(4)]
+    dst = torch.empty_like(copies[0])
+    tab = binding.PointerTable(copies)
+    grad = torch.randn(n, generator=g, device="cuda") * 1e-2
+    master = copies[0].float()
+    m, v = torch.zeros_like(master), torch.zeros_like(master)
+
+    def timed(fn, iters=20):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / iters
+
+    t_avg = timed(lambda: binding.collm_adapter_fedavg(tab, dst))
+    step = [0]
+
+    def adamw():
+        step[0] += 1
+        binding.collm_adapter_adamw(copies[0], grad, m, v, 1e-4, 0.9, 0.999, 1e-8, 0.01, step[0], master=master)
+
+    t_opt = timed(adamw)
+    b_avg = n * 2 * (len(copies) + 1)
+    b_opt = n * (4 + 4 + 4 + 4 + 4 + 4 + 4 + 2)  # grad, m and v read+written, master read+written, param written
+    return {"elements": n, "fedavg_copies": len(copies), "fedavg_ms": t_avg * 1e3, "fedavg_GBs": b_avg / t_avg / 1e9,
+            "fedavg_frac_hbm_peak": b_avg / t_avg / 1e9 / PEAK_HBM_GBS, "adamw_ms": t_opt * 1e3,
+            "adamw_GBs": b_opt / t_opt / 1e9, "adamw_frac_hbm_peak": b_opt / t_opt / 1e9 / PEAK_HBM_GBS}
+
+
 def _cpu_baseline(w, t):
     """The oracle as it stands, timed on the host cores on the same workload."""
     import numpy as np
@@ -261,6 +300,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    adapter_update = _adapter_update(torch, binding)
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = _cpu_baseline(w2, host_tensors)
@@ -280,6 +321,7 @@ def main():
         "cpu_baseline": cpu,
         "frac_mfma_peak_whole_step": (f_fwd + f_bwd) / sec / 1e12 / PEAK_BF16_TFLOPS,
         "all_configs": all_cfg,
+        "adapter_update": adapter_update,
         "device": {"name": props.name, "cus": props.multi_processor_count,
                    "peak_bf16_tflops_used": PEAK_BF16_TFLOPS, "peak_hbm_gbs_used": PEAK_HBM_GBS},
         "paper_context": "paper reports system-level gains only (up to 1.5x goodput, 2.2x quality-weighted "

@@ -179,6 +179,38 @@ int collm_debug_set_tiles(collm_ctx *ctx, int fwd_tile, int bwd_tile);
 int collm_profile_enable(collm_ctx *ctx, int enable);
 int collm_profile_read(collm_ctx *ctx, const char **names, float *ms, int cap);
 
+/*
+ * The step after the backward pass.  Both calls are element-wise over one adapter table of n_elems
+ * elements (A_i: d_in * rank, B_i: rank * d_out), asynchronous on `stream`, allocate nothing and need
+ * no context; `device` is made current.  Device buffers must be 16-byte aligned.
+ *
+ * collm_adapter_fedavg: aggregation of the adapter copies of the participating replicas (paper
+ * section 4.2, the equation for the aggregated B and A): dst[i] = (1/n_copies) sum_k src[k][i].
+ *   src       HOST array [n_copies] of dev pointers, element type `dtype`; 1 <= n_copies <= 16
+ *   dst       dev, element type `dtype`; may be one of the sources
+ * Sums are fp32 in copy order, one rounding to `dtype`.  COLLM_E_SHAPE for n_copies out of range.
+ *
+ * collm_adapter_adamw: one AdamW update (decoupled weight decay, bias-corrected moments; only the
+ * adapters train, paper section 4.2; the optimizer itself is this build's reading) from the fp32
+ * gradient that collm_lora_linear_bwd produced:
+ *   m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2
+ *   w = w (1 - lr wd) - lr / (1 - beta1^step) * m / (sqrt(v) / sqrt(1 - beta2^step) + eps)
+ *   param     dev, element type `dtype`: read (unless `master` is given) and written
+ *   master    dev fp32 copy of the parameters or NULL; when given it is the one updated and
+ *             `param` receives its rounded value
+ *   grad      dev fp32, read; m, v: dev fp32, updated in place
+ *   step      1 for the first update.  COLLM_E_SHAPE for step < 1 or n_elems < 0.
+ */
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay;
+    int32_t step;
+} collm_adamw;
+
+int collm_adapter_fedavg(int device, collm_dtype dtype, int32_t n_copies, const void *const *src, void *dst,
+                         int64_t n_elems, void *stream);
+int collm_adapter_adamw(int device, collm_dtype dtype, void *param, float *master, const float *grad,
+                        float *m, float *v, int64_t n_elems, const collm_adamw *hp, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

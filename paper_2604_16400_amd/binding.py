@@ -36,6 +36,13 @@ class collm_shape(ctypes.Structure):
     ]
 
 
+class collm_adamw(ctypes.Structure):
+    _fields_ = [
+        ("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
+        ("weight_decay", ctypes.c_float), ("step", ctypes.c_int32),
+    ]
+
+
 _lib = None
 _i32p = ctypes.POINTER(ctypes.c_int32)
 _u8p = ctypes.POINTER(ctypes.c_uint8)
@@ -86,6 +93,11 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.collm_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float),
                                        ctypes.c_int]
     lib.collm_profile_read.restype = ctypes.c_int
+    lib.collm_adapter_fedavg.argtypes = [ctypes.c_int, ctypes.c_int, i32, _vpp, vp, ctypes.c_int64, vp]
+    lib.collm_adapter_fedavg.restype = ctypes.c_int
+    lib.collm_adapter_adamw.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp, vp, vp, vp, ctypes.c_int64,
+                                        ctypes.POINTER(collm_adamw), vp]
+    lib.collm_adapter_adamw.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -241,3 +253,41 @@ class Context:
             ss.ctypes.data_as(_i32p), sa.ctypes.data_as(_i32p), st.ctypes.data_as(_u8p), dy.data_ptr(),
             None if h_save is None else h_save.data_ptr(), None if dx is None else dx.data_ptr(),
             dAt, dBt, 1 if accumulate else 0, self._stream(stream)), "collm_lora_linear_bwd")
+
+
+def _dtype_of(t):
+    import torch
+
+    if t.dtype == torch.bfloat16:
+        return COLLM_BF16
+    if t.dtype == torch.float32:
+        return COLLM_F32
+    raise TypeError("tensor must be bfloat16 or float32")
+
+
+def _stream_handle(stream):
+    import torch
+
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def collm_adapter_fedavg(copies: Sequence, dst, stream=None):
+    """dst <- mean of the adapter copies (same shape and element type), summed in list order."""
+    lib = load_library()
+    tab = copies if isinstance(copies, PointerTable) else PointerTable(copies)
+    _check(lib.collm_adapter_fedavg(dst.device.index or 0, _dtype_of(dst), len(tab), tab.array, dst.data_ptr(),
+                                    dst.numel(), _stream_handle(stream)), "collm_adapter_fedavg")
+    return dst
+
+
+def collm_adapter_adamw(param, grad, m, v, lr: float, beta1: float, beta2: float, eps: float,
+                        weight_decay: float, step: int, master=None, stream=None):
+    """One AdamW step on `param` (and its optional fp32 `master` copy) from the fp32 `grad`."""
+    lib = load_library()
+    hp = collm_adamw(lr, beta1, beta2, eps, weight_decay, int(step))
+    _check(lib.collm_adapter_adamw(param.device.index or 0, _dtype_of(param), param.data_ptr(),
+                                   None if master is None else master.data_ptr(), grad.data_ptr(), m.data_ptr(),
+                                   v.data_ptr(), param.numel(), ctypes.byref(hp), _stream_handle(stream)),
+           "collm_adapter_adamw")
+    return param

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcollm_lora.so")
-SOURCES = ["api.cpp", "planner.cpp", "kernels_bf16.hip", "kernels_f32.hip"]
+SOURCES = ["api.cpp", "planner.cpp", "kernels_bf16.hip", "kernels_f32.hip", "kernels_adapter.hip"]
 HEADERS = ["plan.h", "planner.h", "kernels.h"]
 
 FLAGS = [

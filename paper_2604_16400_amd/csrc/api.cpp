@@ -682,6 +682,56 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
     return COLLM_OK;
 }
 
+int collm_adapter_fedavg(int device, collm_dtype dtype, int32_t n_copies, const void *const *src, void *dst,
+                         int64_t n_elems, void *stream)
+{
+    if (dtype != COLLM_F32 && dtype != COLLM_BF16) return COLLM_E_DTYPE;
+    if (n_copies < 1 || n_copies > kMaxFedAvgCopies || n_elems < 0) return COLLM_E_SHAPE;
+    if (!src || (n_elems > 0 && !dst)) return COLLM_E_NULL;
+    if (!aligned16(dst)) return COLLM_E_ALIGN;
+    FedAvgArgs a{};
+    for (int k = 0; k < n_copies; ++k) {
+        if (n_elems > 0 && !src[k]) return COLLM_E_NULL;
+        if (!aligned16(src[k])) return COLLM_E_ALIGN;
+        a.src[k] = src[k];
+    }
+    if (n_elems == 0) return COLLM_OK;
+    a.dst = dst;
+    a.n = n_elems;
+    a.n_copies = n_copies;
+    HIP_TRY(hipSetDevice(device));
+    HIP_TRY(launch_fedavg(a, dtype == COLLM_BF16, (hipStream_t)stream));
+    return COLLM_OK;
+}
+
+int collm_adapter_adamw(int device, collm_dtype dtype, void *param, float *master, const float *grad,
+                        float *m, float *v, int64_t n_elems, const collm_adamw *hp, void *stream)
+{
+    if (dtype != COLLM_F32 && dtype != COLLM_BF16) return COLLM_E_DTYPE;
+    if (!hp) return COLLM_E_NULL;
+    if (n_elems < 0 || hp->step < 1) return COLLM_E_SHAPE;
+    if (n_elems == 0) return COLLM_OK;
+    if (!param || !grad || !m || !v) return COLLM_E_NULL;
+    if (!aligned16(param) || !aligned16(master) || !aligned16(grad) || !aligned16(m) || !aligned16(v)) return COLLM_E_ALIGN;
+    AdamWArgs a{};
+    a.param = param;
+    a.master = master;
+    a.grad = grad;
+    a.m = m;
+    a.v = v;
+    a.n = n_elems;
+    a.lr = hp->lr;
+    a.beta1 = hp->beta1;
+    a.beta2 = hp->beta2;
+    a.eps = hp->eps;
+    a.weight_decay = hp->weight_decay;
+    a.bias1 = (float)(1.0 - std::pow((double)hp->beta1, (double)hp->step));
+    a.rsqrt_bias2 = (float)(1.0 / std::sqrt(1.0 - std::pow((double)hp->beta2, (double)hp->step)));
+    HIP_TRY(hipSetDevice(device));
+    HIP_TRY(launch_adamw(a, dtype == COLLM_BF16, (hipStream_t)stream));
+    return COLLM_OK;
+}
+
 int collm_debug_device_token_map(collm_ctx *c, int32_t *tok_segment, int32_t *tok_adapter,
                                  uint8_t *tok_is_train)
 {

@@ -86,6 +86,28 @@ hipError_t launch_grad(const GradArgs &a, int n_grad, int rpad, hipStream_t st);
 hipError_t launch_plan_copy(const int32_t *src_pinned, int32_t *dst, size_t first_int, size_t n_ints, int *counter,
                             uint32_t *done_host_dev, uint32_t seq, hipStream_t st);
 
+// dst[i] = (1/n_copies) sum_k src[k][i]; element type bf16 or fp32, fp32 sums in copy order
+constexpr int kMaxFedAvgCopies = 16;
+struct FedAvgArgs {
+    const void *src[kMaxFedAvgCopies];
+    void *dst;
+    int64_t n;
+    int n_copies;
+};
+// one AdamW step: param (element type), optional fp32 master copy, fp32 grad and moments
+struct AdamWArgs {
+    void *param;
+    float *master;
+    const float *grad;
+    float *m, *v;
+    int64_t n;
+    float lr, beta1, beta2, eps, weight_decay;
+    float bias1;        // 1 - beta1^step
+    float rsqrt_bias2;  // 1 / sqrt(1 - beta2^step)
+};
+hipError_t launch_fedavg(const FedAvgArgs &a, bool bf16, hipStream_t st);
+hipError_t launch_adamw(const AdamWArgs &a, bool bf16, hipStream_t st);
+
 // fp32 element type: same argument blocks, plain fp32 FMA kernels
 hipError_t launch_gemm_f32(const GemmArgs &a, bool b_kmajor, hipStream_t st);
 hipError_t launch_skinny_f32(const SkinnyArgs &a, int n_items, bool t_kmajor, hipStream_t st);

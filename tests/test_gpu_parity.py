@@ -311,3 +311,86 @@ def test_error_statuses_touch_nothing():
                                                  [layer.dA[0], None], [layer.dB[0], None]))
     assert torch.isnan(layer.dx).all()
     ctx.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# the step after the backward pass: AdamW update of an adapter table, aggregation of the copies
+# ---------------------------------------------------------------------------------------------
+def _rounded(a, dtype):
+    return wl.bf16_round(a) if dtype == "bf16" else a
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("shape", [(4096, 16), (16, 4096), (1037, 5), (1, 3), (11008, 64)])
+def test_adapter_fedavg_matches_oracle(dtype, shape):
+    import torch
+
+    rng = np.random.default_rng(20260416 + shape[0])
+    K = 5 if shape[0] != 11008 else 16
+    host = [_rounded(rng.normal(0.0, 0.02, size=shape).astype(np.float32), dtype) for _ in range(K)]
+    ref = oracle.adapter_fedavg(host)
+    dev = [to_dev(h, dtype) for h in host]
+    dst = torch.full_like(dev[0], float("nan"))
+    binding.collm_adapter_fedavg(dev, dst)
+    torch.cuda.synchronize()
+    got = dst.float().cpu().numpy().astype(np.float64)
+    err = np.max(np.abs(got - ref)) / np.max(np.abs(ref))
+    assert err <= TOL[dtype], err
+    # in place (dst is one of the sources) gives the same bits
+    binding.collm_adapter_fedavg(dev, dev[2])
+    torch.cuda.synchronize()
+    assert torch.equal(dev[2].view(torch.int16 if dtype == "bf16" else torch.int32),
+                       dst.view(torch.int16 if dtype == "bf16" else torch.int32))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype,use_master", [("bf16", True), ("bf16", False), ("f32", False)])
+def test_adapter_adamw_matches_oracle(dtype, use_master):
+    import torch
+
+    rng = np.random.default_rng(7)
+    shape = (4099, 16)  # not a multiple of four elements: exercises the tail
+    p0 = _rounded(rng.normal(0.0, 0.02, size=shape).astype(np.float32), dtype)
+    # the C ABI takes fp32 hyper-parameters: the oracle gets exactly those values
+    lr, b1, b2, eps, wd = (float(np.float32(h)) for h in (1e-3, 0.9, 0.999, 1e-8, 0.01))
+    param = to_dev(p0, dtype)
+    master = torch.tensor(p0, dtype=torch.float32, device="cuda") if use_master else None
+    m = torch.zeros(shape, dtype=torch.float32, device="cuda")
+    v = torch.zeros(shape, dtype=torch.float32, device="cuda")
+    rp, rm, rv = p0.astype(np.float64), np.zeros(shape), np.zeros(shape)
+    for step in range(1, 4):
+        g = rng.normal(0.0, 1e-2, size=shape).astype(np.float32)
+        binding.collm_adapter_adamw(param, torch.tensor(g, device="cuda"), m, v, lr, b1, b2, eps, wd, step,
+                                    master=master)
+        torch.cuda.synchronize()
+        # without a master copy the parameter a step starts from is the rounded result of the step before
+        start = rp if (use_master or dtype == "f32" or step == 1) else param_prev
+        rp, rm, rv = oracle.adamw_step(start, g, rm, rv, lr, b1, b2, eps, wd, step)
+        param_prev = param.float().cpu().numpy().astype(np.float64)
+        ref_w = rp
+        got_w = (master if use_master else param).float().cpu().numpy().astype(np.float64)
+        tol_w = 1e-5 if (use_master or dtype == "f32") else TOL["bf16"]
+        assert np.max(np.abs(got_w - ref_w)) / np.max(np.abs(ref_w)) <= tol_w
+        assert np.max(np.abs(m.cpu().numpy() - rm)) / np.max(np.abs(rm)) <= 1e-5
+        assert np.max(np.abs(v.cpu().numpy() - rv)) / np.max(np.abs(rv)) <= 1e-5
+        # the element-type copy is the rounded master
+        if use_master:
+            assert torch.equal(param, master.to(torch.bfloat16))
+
+
+@pytest.mark.gpu
+def test_adapter_update_error_statuses():
+    import torch
+
+    a = torch.zeros(64, dtype=torch.bfloat16, device="cuda")
+    f = torch.zeros(64, dtype=torch.float32, device="cuda")
+    with pytest.raises(binding.CollmError) as e:
+        binding.collm_adapter_fedavg([a] * 17, a)
+    assert e.value.status == -2
+    with pytest.raises(binding.CollmError) as e:
+        binding.collm_adapter_adamw(a, f, f.clone(), f.clone(), 1e-3, 0.9, 0.999, 1e-8, 0.0, 0)
+    assert e.value.status == -2
+    with pytest.raises(binding.CollmError) as e:
+        binding.collm_adapter_fedavg([a, a[1:33]], a[:32])
+    assert e.value.status == -7
