@@ -208,3 +208,48 @@ def adamw_step(p, g, m, v, lr, beta1, beta2, eps, weight_decay, step):
         mi[...] = m_new
         vi[...] = v_new
     return p, m, v
+
+
+# ---------------------------------------------------------------------------------------------
+# The Coordinator's batch sizing (paper section 5), written out step by step.
+# ---------------------------------------------------------------------------------------------
+def fit_plane(B, b, T):
+    """Least-squares plane T ~ c0 B + c1 b + c2: normal equations solved by Gaussian elimination with
+    partial pivoting, in fp64 loops."""
+    B, b, T = [float(v) for v in B], [float(v) for v in b], [float(v) for v in T]
+    n = len(T)
+    cols = [B, b, [1.0] * n]
+    M = [[sum(cols[i][k] * cols[j][k] for k in range(n)) for j in range(3)] + [sum(cols[i][k] * T[k] for k in range(n))]
+         for i in range(3)]
+    for c in range(3):
+        piv = max(range(c, 3), key=lambda r: abs(M[r][c]))
+        M[c], M[piv] = M[piv], M[c]
+        for r in range(c + 1, 3):
+            f = M[r][c] / M[c][c]
+            for k in range(c, 4):
+                M[r][k] -= f * M[c][k]
+    sol = [0.0, 0.0, 0.0]
+    for c in (2, 1, 0):
+        sol[c] = (M[c][3] - sum(M[c][k] * sol[k] for k in range(c + 1, 3))) / M[c][c]
+    return tuple(sol)
+
+
+def coordinator_choice(train, infer, tau, B_grid, b_max, a, p, l, B0):
+    """(B*, b*, goodput) by brute force.  `train` = (coefficient of B, of b, constant) of T_train,
+    `infer` the same triple of T_infer (coefficient of B first).  For every B of the grid, b*(B) is found
+    by trying every b from b_max down to 0; GOODPUT = B / T_train(B, b*) * (a p l + B0) / (a p l + B);
+    the first B with the largest GOODPUT wins; None if no (B, b) meets the budget."""
+    best = None
+    for B in B_grid:
+        b_star = None
+        for b in range(int(b_max), -1, -1):
+            if infer[0] * B + infer[1] * b + infer[2] <= tau:
+                b_star = b
+                break
+        if b_star is None:
+            continue
+        t_train = train[0] * B + train[1] * b_star + train[2]
+        g = 0.0 if (B <= 0 or t_train <= 0) else (B / t_train) * (a * p * l + B0) / (a * p * l + B)
+        if best is None or g > best[2]:
+            best = (int(B), int(b_star), g)
+    return best
