@@ -188,6 +188,18 @@ def test_many_adapters_in_one_tile_and_large_rank():
     _run_full(w)
 
 
+def test_few_rows_long_contraction_and_many_trained_adapters_in_one_tile():
+    # 20 training rows against an 8192-long contraction: the rank-wide passes cut K into many slices
+    # across blocks (partial sums added by the second kernel); the dh pass (K = 64) uses a single one
+    _run_full(_adhoc("bf16", 8192, 64, [16, 8], [20, 3], [0, 1], [1, 0]))
+    _run_full(_adhoc("bf16", 64, 8192, [16, 8], [20, 3], [0, 1], [1, 0]))
+    # six trained adapters inside one GEMM row tile, ranks that are and are not multiples of 8: several
+    # batches of extension steps in the dX GEMM, some loaded element by element and some directly
+    w = _adhoc("bf16", 320, 192, [3, 16, 40, 16, 9, 64], [30, 20, 25, 35, 10, 40, 12], [0, 1, 2, 3, 4, 5, -1],
+               [1, 1, 1, 1, 1, 1, 0], scale=0.3)
+    _run_full(w)
+
+
 @pytest.mark.parametrize("tile", [binding.TILE_256x256, binding.TILE_256x128, binding.TILE_128x128,
                                   binding.TILE_256x256_W8])
 def test_every_gemm_tile_shape(tile):
