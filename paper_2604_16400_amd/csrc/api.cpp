@@ -577,7 +577,7 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
     // h of the training rows, if the forward call did not keep it
     if (!h_save && dA) {
         rc = run_skinny(c, s, L.train, x, s->d_in, L.off_A_ptr, false, c->d_h32, L.rpad, L.rpad, 0, 1.0f,
-                        nullptr, 0.f, "shrink_recompute", st);
+                        c->d_hs, s->scale, "shrink_recompute", st);
         if (rc != COLLM_OK) return rc;
     }
     // The adapter gradients depend on little (dB_a: h and dy; dA_a: dh and x) and are bound by memory
@@ -610,6 +610,16 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
             ga.small_by_token = 0;
         }
         ga.small_mult = s->scale;
+        if (!f32) {
+            // the small operand as a scaled bf16 copy in training row order (half the bytes of the fp32 one, no
+            // conversion in the kernel): left by the recomputing pass, or packed from h_save here.  The forward
+            // call's copy of s h (all rows) in the same buffer is dead once that call's GEMM has run.
+            if (h_save)
+                HIP_TRY(launch_pack_rows(h_save, c->max_rank, c->max_rank, c->d_plan + L.train.off_row_tok,
+                                         L.train.n_rows, s->scale, c->d_hs, L.rpad, gs));
+            ga.small_bf = c->d_hs;
+            ga.ld_small_bf = L.rpad;
+        }
         ga.out_tab = reinterpret_cast<const uint64_t *>(c->d_plan + L.off_dB_ptr);
         ga.out_transposed = 0;
         {
@@ -638,6 +648,10 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
         ga.ld_small = L.rpad;
         ga.small_by_token = 0;
         ga.small_mult = 1.0f;
+        if (!f32) {
+            ga.small_bf = c->d_dhs;  // dh in the element type, as the dh pass left it for the dX GEMM
+            ga.ld_small_bf = L.rpad;
+        }
         ga.out_tab = reinterpret_cast<const uint64_t *>(c->d_plan + L.off_dA_ptr);
         ga.out_transposed = 1;
         {

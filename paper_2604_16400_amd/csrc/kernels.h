@@ -63,6 +63,8 @@ struct GradArgs {
     int64_t ld_small;
     int small_by_token;
     float small_mult;
+    const void *small_bf;     // bf16 kernels: if set, the small operand as a bf16 copy [row order][ld_small_bf],
+    int ld_small_bf;          // already scaled, zeros from the rank up to the next multiple of 16 (fp32 one unused)
     const int32_t *row_tok;   // training row order
     const GradItem *items;    // one per trained adapter
     const uint64_t *out_tab;  // adapter -> fp32 output
@@ -79,6 +81,10 @@ hipError_t launch_skinny(const SkinnyArgs &a, int n_items, int rpad, int row_til
 int skinny_max_row_tiles(int rpad);
 int skinny_waves(int rpad);  // waves of a block, which split the block's K slice
 hipError_t launch_grad(const GradArgs &a, int n_grad, int rpad, hipStream_t st);
+// dst[t][q] = bf16(mult * src[row_tok[t]][q]) for n_rows rows and ld_dst (multiple of 8) columns; columns from
+// src_cols on are zero
+hipError_t launch_pack_rows(const float *src, int64_t ld_src, int src_cols, const int32_t *row_tok, int n_rows,
+                            float mult, void *dst, int ld_dst, hipStream_t st);
 
 // copies ints [first_int, first_int + n_ints) (rounded outwards to 16 bytes) of a pinned host
 // block into the device plan, in stream order, then stores `seq` to the pinned word

@@ -22,6 +22,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "kernels.h"
@@ -1146,11 +1147,13 @@ struct GradCfg {
     static constexpr int SROW = 64 * 4 / RP;       // rows advanced per piece index
 };
 
-template <int RP>
+template <int RP, bool SMALL_BF>
 __global__ void __launch_bounds__(GradCfg<RP>::KW * 64) grad_kernel(GradArgs p)
 {
     using C = GradCfg<RP>;
-    constexpr int KW = C::KW, MB = C::MB, SV = C::SV;
+    constexpr int KW = C::KW, MB = C::MB, SV = SMALL_BF ? 1 : C::SV;
+    constexpr int NP = RP / 16;   // 16-byte pieces of a bf16 `small` chunk per lane
+    constexpr int PPR = RP / 8;   // pieces per row
     extern __shared__ __align__(16) uint8_t smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint8_t *stage_b = smem + wave * C::STAGE_BYTES;
@@ -1172,6 +1175,8 @@ __global__ void __launch_bounds__(GradCfg<RP>::KW * 64) grad_kernel(GradArgs p)
     const __amdgpu_buffer_rsrc_t rbig = make_rsrc(p.big, p.big_bytes);
     const int32_t *__restrict__ row_tok = p.row_tok;
     const float *__restrict__ Small = p.small_;
+    const uint16_t *__restrict__ SmallB = reinterpret_cast<const uint16_t *>(p.small_bf);
+    const int rp_rank = (rank + 15) & ~15;  // the bf16 copy holds zeros from the rank up to here
 
     // big: lane copies chunk column c = lane % 8 of rows lane / 8 + 8 i
     const int bc = lane & 7, br = lane >> 3;
@@ -1187,18 +1192,35 @@ __global__ void __launch_bounds__(GradCfg<RP>::KW * 64) grad_kernel(GradArgs p)
             const int t = t0 + br + i * 8;
             tokb[i] = t < t_hi ? row_tok[t] : -1;
         }
+        if constexpr (!SMALL_BF) {
 #pragma unroll
-        for (int i = 0; i < SV; ++i) {
-            const int t = t0 + sr + i * C::SROW;
-            toks[i] = t < t_hi ? (p.small_by_token ? row_tok[t] : t) : -1;
+            for (int i = 0; i < SV; ++i) {
+                const int t = t0 + sr + i * C::SROW;
+                toks[i] = t < t_hi ? (p.small_by_token ? row_tok[t] : t) : -1;
+            }
         }
     };
     uint4 breg[4];
     floatx4 sreg[SV];
+    uint4 sbreg[SMALL_BF ? NP : 1];
+    int t_next = t_lo;  // first row of the chunk the next load_data fetches
     auto load_data = [&]() {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             breg[i] = buf16(rbig, (tokb[i] >= 0 && bcol != kOob) ? (uint32_t)tokb[i] * (uint32_t)p.ld_big * 2u + bcol : kOob);
+        if constexpr (SMALL_BF) {
+            // the bf16 copy is in row order and already scaled: 16-byte pieces as they lie in memory
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                const int c = lane + i * 64;
+                const int t = t_next + c / PPR, q = q0 + (c % PPR) * 8;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (t < t_hi && q < rp_rank) v = ldg16(SmallB + (int64_t)t * p.ld_small_bf + q);
+                sbreg[i] = v;
+            }
+            t_next += C::CHT;
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < SV; ++i) {
             floatx4 v = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -1222,6 +1244,14 @@ __global__ void __launch_bounds__(GradCfg<RP>::KW * 64) grad_kernel(GradArgs p)
     auto store_data = [&]() {
 #pragma unroll
         for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4 *>(stage_b + (br + i * 8) * C::BPITCH + bc * 16) = breg[i];
+        if constexpr (SMALL_BF) {
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                const int c = lane + i * 64;
+                *reinterpret_cast<uint4 *>(stage_s + (c / PPR) * C::SPITCH + (c % PPR) * 16) = sbreg[i];
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < SV; ++i) {
             uint2 o;
@@ -1389,11 +1419,11 @@ hipError_t launch_skinny(const SkinnyArgs &a, int n_items, int rpad, int row_til
 #undef COLLM_SK
 }
 
-template <int RP>
+template <int RP, bool SMALL_BF>
 static hipError_t launch_grad_t(const GradArgs &a, int n_grad, int rpad, hipStream_t st)
 {
     using C = GradCfg<RP>;
-    auto kern = grad_kernel<RP>;
+    auto kern = grad_kernel<RP, SMALL_BF>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -1409,10 +1439,45 @@ static hipError_t launch_grad_t(const GradArgs &a, int n_grad, int rpad, hipStre
 hipError_t launch_grad(const GradArgs &a, int n_grad, int rpad, hipStream_t st)
 {
     if (n_grad <= 0 || a.N <= 0) return hipSuccess;
-    if (rpad <= 16) return launch_grad_t<16>(a, n_grad, rpad, st);
-    if (rpad <= 32) return launch_grad_t<32>(a, n_grad, rpad, st);
-    if (rpad <= 64) return launch_grad_t<64>(a, n_grad, rpad, st);
-    return launch_grad_t<128>(a, n_grad, rpad, st);  // larger ranks: 128-wide slices on grid.z
+#define COLLM_GR(RP) return a.small_bf ? launch_grad_t<RP, true>(a, n_grad, rpad, st) : launch_grad_t<RP, false>(a, n_grad, rpad, st)
+    if (rpad <= 16) { COLLM_GR(16); }
+    if (rpad <= 32) { COLLM_GR(32); }
+    if (rpad <= 64) { COLLM_GR(64); }
+    COLLM_GR(128);  // larger ranks: 128-wide slices on grid.z
+#undef COLLM_GR
+}
+
+// dst[t][q] = bf16(mult * src[tok(t)][q]) for the rows t of a row order; columns beyond src_cols are zero
+__global__ void __launch_bounds__(256) pack_rows_kernel(const float *__restrict__ src, int64_t ld_src, int src_cols,
+                                                        const int32_t *__restrict__ row_tok, int n_rows, float mult,
+                                                        uint16_t *__restrict__ dst, int ld_dst)
+{
+    const int ppr = ld_dst / 8;
+    const int64_t n = (int64_t)n_rows * ppr;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        const int t = (int)(i / ppr), q = (int)(i % ppr) * 8;
+        const int tok = row_tok[t];
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (tok >= 0 && q + e < src_cols) ? src[(int64_t)tok * ld_src + q + e] * mult : 0.f;
+        uint4 o;
+        o.x = pack_bf16(v[0], v[1]);
+        o.y = pack_bf16(v[2], v[3]);
+        o.z = pack_bf16(v[4], v[5]);
+        o.w = pack_bf16(v[6], v[7]);
+        *reinterpret_cast<uint4 *>(dst + (int64_t)t * ld_dst + q) = o;
+    }
+}
+
+hipError_t launch_pack_rows(const float *src, int64_t ld_src, int src_cols, const int32_t *row_tok, int n_rows,
+                            float mult, void *dst, int ld_dst, hipStream_t st)
+{
+    if (n_rows <= 0) return hipSuccess;
+    const int64_t n = (int64_t)n_rows * (ld_dst / 8);
+    const int grid = (int)std::min<int64_t>((n + 255) / 256, 4096);
+    hipLaunchKernelGGL(pack_rows_kernel, dim3(grid), dim3(256), 0, st, src, ld_src, src_cols, row_tok, n_rows, mult,
+                       reinterpret_cast<uint16_t *>(dst), ld_dst);
+    return hipGetLastError();
 }
 
 }  // namespace collm
