@@ -224,8 +224,11 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
     const int bm_all = f32 ? 64 : gemm_tile_rows(tile_fwd);
     const int bm_train = f32 ? 64 : gemm_tile_rows(tile_bwd);
 
-    const bool reuse = allow_reuse && same_key(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train,
-                                               bm_all, bm_train);
+    // A batch whose segment table, ranks, adapter tables and sizes equal those of the plan the device holds
+    // reuses it (every layer and projection of a model sees the same batch): only a call on another stream
+    // than the one the plan was uploaded on builds it again, since nothing orders the two streams.
+    const bool reuse = allow_reuse && st == c->last_stream &&
+                       same_key(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, bm_all, bm_train);
     if (!reuse) {
         PlanRequest rq;
         rq.shape = s;
@@ -267,15 +270,20 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
         }
         c->plan_valid = true;
     } else if (dA || dB) {
-        // same batch as the forward call: only the gradient pointer tables are new
+        // same batch as the plan on the device: at most the gradient pointer tables are new
         const int N = s->n_adapters;
+        bool changed = false;
         for (int a = 0; a < N; ++a) {
             const uint64_t va = dA ? (uint64_t)(uintptr_t)dA[a] : 0, vb = dB ? (uint64_t)(uintptr_t)dB[a] : 0;
+            changed |= std::memcmp(c->plan.data() + c->L.off_dA_ptr + 2 * a, &va, 8) != 0;
+            changed |= std::memcmp(c->plan.data() + c->L.off_dB_ptr + 2 * a, &vb, 8) != 0;
             std::memcpy(c->plan.data() + c->L.off_dA_ptr + 2 * a, &va, 8);
             std::memcpy(c->plan.data() + c->L.off_dB_ptr + 2 * a, &vb, 8);
         }
-        int rc = upload(c, c->L.off_dA_ptr, (size_t)c->L.off_dB_ptr + 2 * (size_t)std::max(N, 1), st);
-        if (rc != COLLM_OK) return rc;
+        if (changed) {
+            int rc = upload(c, c->L.off_dA_ptr, (size_t)c->L.off_dB_ptr + 2 * (size_t)std::max(N, 1), st);
+            if (rc != COLLM_OK) return rc;
+        }
     }
     c->last_stream = st;
     return COLLM_OK;
@@ -305,18 +313,25 @@ int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, cons
     a.bf_out = bf_out;
     a.bf_ld = c->L.rpad;
     a.bf_mult = bf_mult;
-    // The pass is bound by memory latency unless thousands of waves are in flight: cut K into slices
-    // until there are about 8 waves per CU (each keeps several chunks in flight), as long as a wave
-    // keeps at least 64 K values and the partial sums stay well below the bytes streamed (and inside
-    // the workspace).  The second kernel that adds the slices costs a few microseconds.
+    // A wave keeps `depth` chunks of K in flight and so needs K / (waves * chunk * depth) round trips to
+    // memory; cutting K into slices across blocks shortens that chain at the price of a second kernel that
+    // adds the slices (about 6 us with its launch).  Cut only when the chain is longer than about six round
+    // trips and the items alone give fewer than 8 waves per CU (with more, the pass is bound by bandwidth and
+    // more, shorter blocks only scatter the stream), up to that many waves or down to about three trips, as
+    // long as a wave keeps one chunk and the partial sums stay well below the bytes streamed (and inside the
+    // workspace).
     int n_split = 1;
     if (s->dtype == COLLM_BF16) {
         const int kw = skinny_waves(c->L.rpad);
+        const int per_trip = kw * skinny_chunk(c->L.rpad) * skinny_depth(c->L.rpad, R.item_rows / kSkinnyRows);
+        const long trips = (K + per_trip - 1) / per_trip;
         const long per_split = (long)c->rows_cap * c->rpad_cap * 4;
         long lim = std::min<long>(kSkinnyMaxSplit, (long)c->part_bytes / per_split);
         lim = std::min<long>(lim, K / (4L * c->L.rpad));
-        lim = std::min<long>(lim, K / (64L * kw));
-        n_split = (int)std::max<long>(1, std::min<long>(lim, (2048 + (long)R.n_items * kw - 1) / ((long)R.n_items * kw)));
+        lim = std::min<long>(lim, K / ((long)skinny_chunk(c->L.rpad) * kw));
+        const long waves = (long)R.n_items * kw;
+        if (trips > 6 && waves < 2048)
+            n_split = (int)std::max<long>(1, std::min<long>({lim, (2048 + waves - 1) / waves, (trips + 2) / 3}));
     }
     a.part = c->d_part;
     a.part_rows = c->rows_cap;
@@ -501,7 +516,7 @@ int collm_lora_linear_fwd(collm_ctx *c, const collm_shape *s, const void *x, con
     hipStream_t st = (hipStream_t)stream;
     HIP_TRY(hipSetDevice(c->device));
     c->n_prof = 0;
-    rc = prepare_plan(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, nullptr, nullptr, false, st);
+    rc = prepare_plan(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, nullptr, nullptr, true, st);
     if (rc != COLLM_OK) return rc;
     const PlanLayout &L = c->L;
     const bool f32 = s->dtype == COLLM_F32;

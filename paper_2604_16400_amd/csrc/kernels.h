@@ -80,6 +80,8 @@ hipError_t launch_skinny(const SkinnyArgs &a, int n_items, int rpad, int row_til
                          hipStream_t st);
 int skinny_max_row_tiles(int rpad);
 int skinny_waves(int rpad);  // waves of a block, which split the block's K slice
+int skinny_chunk(int rpad);  // K values a wave fetches at a time
+int skinny_depth(int rpad, int row_tiles);  // chunks a wave keeps in flight
 hipError_t launch_grad(const GradArgs &a, int n_grad, int rpad, hipStream_t st);
 // dst[t][q] = bf16(mult * src[row_tok[t]][q]) for n_rows rows and ld_dst (multiple of 8) columns; columns from
 // src_cols on are zero

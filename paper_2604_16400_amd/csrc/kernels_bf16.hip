@@ -1402,6 +1402,14 @@ static hipError_t launch_skinny_rt(const SkinnyArgs &a, int n_items, int row_til
 
 int skinny_max_row_tiles(int rpad) { return rpad <= 128 ? 2 : 1; }
 int skinny_waves(int rpad) { return rpad <= 32 ? 8 : 4; }
+int skinny_chunk(int rpad) { return rpad <= 64 ? 64 : 32; }
+int skinny_depth(int rpad, int row_tiles)
+{
+    // as in skinny_kernel: four chunks in flight where a chunk needs few registers, else two
+    const int rp = rpad <= 16 ? 16 : (rpad <= 32 ? 32 : (rpad <= 64 ? 64 : (rpad <= 128 ? 128 : 256)));
+    const int steps = skinny_chunk(rpad) / 32, nb = rp / 16;
+    return (row_tiles * steps + steps * nb <= 8) ? 4 : 2;
+}
 
 hipError_t launch_skinny(const SkinnyArgs &a, int n_items, int rpad, int row_tiles, int n_split, bool t_kmajor,
                          hipStream_t st)

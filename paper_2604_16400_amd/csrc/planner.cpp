@@ -59,7 +59,7 @@ struct Builder {
 // Rows (token indices, already filtered) sorted by adapter, stable; items; extension tables.
 void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &tokens,
                      const int32_t *tok_adapter, const int32_t *rank, int n_adapters, int bm,
-                     const void *const *ext_tab, int max_row_tiles)
+                     const void *const *ext_tab, int max_row_tiles, int rpad)
 {
     const int n = (int)tokens.size();
     L.n_rows = n;
@@ -91,7 +91,8 @@ void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &
     // item halve the fetches of an adapter's table (which weigh as much as the rows for rank 16 and
     // several times as much for larger ranks) but also halve the waves in flight, and these passes are
     // bound by memory latency on small batches: measured, pairs pay from about 4096 rows on.
-    const int tiles = (max_row_tiles >= 2 && n >= 4096) ? 2 : 1;
+    // (for ranks above 64, where the table outweighs the rows eight times and more, from 2048 rows on)
+    const int tiles = (max_row_tiles >= 2 && (n >= 4096 || (rpad >= 128 && n >= 2048))) ? 2 : 1;
     L.item_rows = kSkinnyRows * tiles;
     std::vector<SkinnyItem> items;
     for (int a = 0; a < n_adapters; ++a) {
@@ -189,8 +190,8 @@ int build_plan(const PlanRequest &rq, std::vector<int32_t> &blk, PlanLayout &L)
     {
         std::vector<int32_t> tok_adapter(blk.begin() + L.off_tok_adapter,
                                          blk.begin() + L.off_tok_adapter + T);
-        build_row_order(b, L.all, all, tok_adapter.data(), rq.rank, N, rq.bm_all, rq.B, rq.max_row_tiles);
-        build_row_order(b, L.train, train, tok_adapter.data(), rq.rank, N, rq.bm_train, rq.A, rq.max_row_tiles);
+        build_row_order(b, L.all, all, tok_adapter.data(), rq.rank, N, rq.bm_all, rq.B, rq.max_row_tiles, L.rpad);
+        build_row_order(b, L.train, train, tok_adapter.data(), rq.rank, N, rq.bm_train, rq.A, rq.max_row_tiles, L.rpad);
     }
 
     // gradient items: one per trained adapter, rows contiguous in the training row order
