@@ -93,21 +93,76 @@ struct collm_ctx {
 
 namespace {
 
-int pick_tile(int rows, int cols)
+// How a GEMM's row tiles are cut: `tile` for the first `big_tiles_m` row tiles (all of them when
+// tail_tiles_m is 0), then 128x128 tiles for `tail_tiles_m` row tiles of 128 rows.
+struct Tiling {
+    int tile;
+    int big_tiles_m;
+    int tail_tiles_m;
+};
+
+Tiling pick_tiling(int rows, int cols)
 {
     // Two shapes are worth choosing between: 256x256 run by four waves (one block per CU, the most
-    // efficient inner loop) and 128x128 (two blocks per CU, about 0.85 of that efficiency, four
-    // times as many tiles).  The cost of a shape is the number of rounds its tiles take over the
-    // 256 CUs, in units of one round of 256x256 tiles, with two corrections read off measurements:
-    // a GPU that is not filled once clocks higher, and a last round of 128x128 tiles that leaves
-    // every CU at most one block runs faster than a full one.
+    // efficient inner loop) and 128x128 (two blocks per CU, four times as many tiles).  The cost of
+    // a choice is the time its tiles take over the 256 CUs in units of one full round of 256x256
+    // tiles; the constants are read off measurements on 4096- to 13824-wide layers:
+    //  - 256x256: a GPU that is not filled once clocks higher (0.5 + 0.5 x); after whole rounds a last
+    //    round that keeps a fraction f of the CUs busy costs 0.6 + 0.7 f, at most 1;
+    //  - 128x128: a round of 512 tiles costs 0.65, one that leaves every CU a single block 0.39; from
+    //    two rounds on the blocks' different speeds smooth the rounds out (0.62 per round, 0.3 for a
+    //    nearly empty last one);
+    //  - whole rounds of 256x256 tiles over the first rows and 128x128 tiles over the rest, as two
+    //    launches: the sum of both plus 0.1 for the idle CUs at the boundary between them.
+    auto cost_large = [](double tiles) {
+        const double x = tiles / 256.0, whole = std::floor(x), part = x - whole;
+        if (x <= 1.0) return 0.5 + 0.5 * x;
+        return whole + (part == 0.0 ? 0.0 : std::min(1.0, 0.6 + 0.7 * part));
+    };
+    auto cost_small = [](double tiles) {
+        const double x = tiles / 512.0, whole = std::floor(x), part = x - whole;
+        if (whole >= 2.0) return 0.62 * whole + (part == 0.0 ? 0.0 : (part <= 0.1 ? 0.3 : 0.62 * part + 0.1));
+        if (whole == 0.0) return part <= 0.5 ? 0.39 : 0.65;
+        return 0.65 + (part == 0.0 ? 0.0 : (part <= 0.1 ? 0.3 : 0.65));
+    };
     const int rp = round_up(std::max(rows, 1), kRowPad);
-    const double x256 = (double)(rp / 256) * ((cols + 255) / 256) / 256.0;
-    const double x128 = (double)(rp / 128) * ((cols + 127) / 128) / 512.0;
-    const double cost256 = x256 <= 1.0 ? 0.5 + 0.5 * x256 : std::ceil(x256);
-    const double whole = std::floor(x128), part = x128 - whole;
-    const double cost128 = 0.6 * (whole + (part == 0.0 ? 0.0 : (part <= 0.5 ? 0.6 : 1.0)));
-    return cost256 <= cost128 ? kTile256x256 : kTile128x128;
+    const int tm = rp / 256, tn = (cols + 255) / 256, tn128 = (cols + 127) / 128;
+    const int rows128 = (std::max(rows, 1) + 127) / 128;
+    const double cost256 = cost_large((double)tm * tn), cost128 = cost_small((double)rows128 * tn128);
+    Tiling best = cost256 <= cost128 ? Tiling{kTile256x256, tm, 0} : Tiling{kTile128x128, rows128, 0};
+    const double best_cost = std::min(cost256, cost128);
+    const int rounds = tm * tn / 256;
+    if (rounds >= 1 && (tm * tn) % 256 != 0) {
+        const int m = std::min(tm - 1, rounds * 256 / tn);
+        const int tail = (std::max(rows, 1) - 256 * m + 127) / 128;
+        if (m >= 1 && tail >= 1) {
+            const double cost = cost_large((double)m * tn) + cost_small((double)tail * tn128) + 0.1;
+            if (cost < best_cost) best = Tiling{kTile256x256, m, tail};
+        }
+    }
+    return best;
+}
+
+// One GEMM over the row order `R`: a single launch, or whole rounds of large tiles followed by
+// small tiles over the remaining rows.
+hipError_t run_gemm(collm_ctx *c, GemmArgs g, const RowOrderLayout &R, int rows, int cols, int forced_tile,
+                    bool b_kmajor, hipStream_t st)
+{
+    const Tiling t = forced_tile >= 0 ? Tiling{forced_tile, R.n_rows_pad / gemm_tile_rows(forced_tile), 0}
+                                      : pick_tiling(rows, cols);
+    g.tile_m_base = 0;
+    g.tiles_m = t.big_tiles_m;
+    g.tiles_n = (cols + gemm_tile_cols(t.tile) - 1) / gemm_tile_cols(t.tile);
+    g.ext_off = c->d_plan + R.off_ext_off;
+    g.ext = reinterpret_cast<const ExtStep *>(c->d_plan + R.off_ext);
+    hipError_t e = launch_gemm(g, t.tile, b_kmajor, st);
+    if (e != hipSuccess || t.tail_tiles_m == 0) return e;
+    g.tile_m_base = 2 * t.big_tiles_m;
+    g.tiles_m = t.tail_tiles_m;
+    g.tiles_n = (cols + gemm_tile_cols(kTile128x128) - 1) / gemm_tile_cols(kTile128x128);
+    g.ext_off = c->d_plan + R.off_ext_off_half;
+    g.ext = reinterpret_cast<const ExtStep *>(c->d_plan + R.off_ext_half);
+    return launch_gemm(g, kTile128x128, b_kmajor, st);
 }
 
 struct Prof {
@@ -219,8 +274,8 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
     int n_train = 0;
     for (int k = 0; k < s->n_segments; ++k)
         if (seg_is_train[k]) n_train += seg_start[k + 1] - seg_start[k];
-    const int tile_fwd = c->tile_fwd >= 0 ? c->tile_fwd : pick_tile(s->n_tokens, s->d_out);
-    const int tile_bwd = c->tile_bwd >= 0 ? c->tile_bwd : pick_tile(n_train, s->d_in);
+    const int tile_fwd = c->tile_fwd >= 0 ? c->tile_fwd : pick_tiling(s->n_tokens, s->d_out).tile;
+    const int tile_bwd = c->tile_bwd >= 0 ? c->tile_bwd : pick_tiling(n_train, s->d_in).tile;
     const int bm_all = f32 ? 64 : gemm_tile_rows(tile_fwd);
     const int bm_train = f32 ? 64 : gemm_tile_rows(tile_bwd);
 
@@ -551,9 +606,7 @@ int collm_lora_linear_fwd(collm_ctx *c, const collm_shape *s, const void *x, con
         if (f32) {
             HIP_TRY(launch_gemm_f32(g, false, st));
         } else {
-            const int tile = c->tile_fwd >= 0 ? c->tile_fwd : pick_tile(s->n_tokens, s->d_out);
-            g.tiles_n = (s->d_out + gemm_tile_cols(tile) - 1) / gemm_tile_cols(tile);
-            HIP_TRY(launch_gemm(g, tile, false, st));
+            HIP_TRY(run_gemm(c, g, L.all, s->n_tokens, s->d_out, c->tile_fwd, false, st));
         }
     }
     return COLLM_OK;
@@ -702,9 +755,7 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
         if (f32) {
             HIP_TRY(launch_gemm_f32(g, true, st));
         } else {
-            const int tile = c->tile_bwd >= 0 ? c->tile_bwd : pick_tile(n_train, s->d_in);
-            g.tiles_n = (s->d_in + gemm_tile_cols(tile) - 1) / gemm_tile_cols(tile);
-            HIP_TRY(launch_gemm(g, tile, true, st));
+            HIP_TRY(run_gemm(c, g, L.train, n_train, s->d_in, c->tile_bwd, true, st));
         }
     }
     if (overlap) HIP_TRY(hipStreamWaitEvent(st, c->ev_join, 0));

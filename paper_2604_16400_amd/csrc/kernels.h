@@ -20,6 +20,7 @@ struct GemmArgs {
     int N, K;
     uint32_t a_bytes, b_bytes;  // sizes of the two operand tensors (each below 2 GiB)
     int tiles_m, tiles_n;
+    int tile_m_base;          // first row tile of this launch (a GEMM may be split over launches by rows)
     const int32_t *row_tok;   // [tiles_m * BM]
     const int32_t *ext_off;   // [tiles_m + 1]
     const ExtStep *ext;

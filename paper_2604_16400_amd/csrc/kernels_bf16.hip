@@ -357,6 +357,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     const int wm = wave % WGM, wn = wave / WGM;
     int tile_m, tile_n;
     tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
+    tile_m += p.tile_m_base;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int K = p.K, N = p.N;
     const int32_t *__restrict__ row_tok = p.row_tok;

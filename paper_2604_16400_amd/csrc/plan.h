@@ -56,6 +56,9 @@ struct RowOrderLayout {
     int32_t off_ext_off = 0;             // [n_tiles_m + 1]
     int32_t off_ext = 0, n_ext = 0;      // ExtStep[n_ext]
     int32_t max_ext_per_tile = 0;
+    // the same for row tiles of half the size (built when bm is 256): a GEMM may run its last rows on
+    // smaller tiles
+    int32_t n_tiles_m_half = 0, off_ext_off_half = 0, off_ext_half = 0;
 };
 
 struct PlanLayout {

@@ -106,34 +106,40 @@ void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &
         std::memcpy(b.blk.data() + L.off_items, items.data(), items.size() * sizeof(SkinnyItem));
 
     // low-rank extension steps of every GEMM row tile
-    L.bm = bm;
-    L.n_tiles_m = L.n_rows_pad / bm;
-    std::vector<int32_t> ext_off(L.n_tiles_m + 1, 0);
-    std::vector<ExtStep> ext;
-    L.max_ext_per_tile = 0;
-    for (int t = 0; t < L.n_tiles_m; ++t) {
-        ext_off[t] = (int)ext.size();
-        const int r0 = t * bm, r1 = std::min(n, r0 + bm);
-        int r = r0;
-        while (r < r1) {
-            const int a = b.blk[L.off_row_adapter + r];
-            int e = r + 1;
-            while (e < r1 && b.blk[L.off_row_adapter + e] == a) ++e;
-            if (a >= 0) {
-                const uint64_t tab = ext_tab ? (uint64_t)(uintptr_t)ext_tab[a] : 0;
-                for (int k = 0; k < rank[a]; k += kKStep)
-                    ext.push_back({(uint32_t)k | ((uint32_t)rank[a] << 16), (uint32_t)(r - r0) | ((uint32_t)(e - r0) << 16), tab});
+    auto build_ext = [&](int tile_rows, int32_t &n_tiles, int32_t &off_ext_off, int32_t &off_ext, int32_t *n_ext,
+                         int32_t *max_per_tile) {
+        n_tiles = L.n_rows_pad / tile_rows;
+        std::vector<int32_t> ext_off(n_tiles + 1, 0);
+        std::vector<ExtStep> ext;
+        int most = 0;
+        for (int t = 0; t < n_tiles; ++t) {
+            ext_off[t] = (int)ext.size();
+            const int r0 = t * tile_rows, r1 = std::min(n, r0 + tile_rows);
+            int r = r0;
+            while (r < r1) {
+                const int a = b.blk[L.off_row_adapter + r];
+                int e = r + 1;
+                while (e < r1 && b.blk[L.off_row_adapter + e] == a) ++e;
+                if (a >= 0) {
+                    const uint64_t tab = ext_tab ? (uint64_t)(uintptr_t)ext_tab[a] : 0;
+                    for (int k = 0; k < rank[a]; k += kKStep)
+                        ext.push_back({(uint32_t)k | ((uint32_t)rank[a] << 16), (uint32_t)(r - r0) | ((uint32_t)(e - r0) << 16), tab});
+                }
+                r = e;
             }
-            r = e;
+            most = std::max(most, (int)ext.size() - ext_off[t]);
         }
-        L.max_ext_per_tile = std::max(L.max_ext_per_tile, (int)ext.size() - ext_off[t]);
-    }
-    ext_off[L.n_tiles_m] = (int)ext.size();
-    L.off_ext_off = b.alloc(ext_off.size());
-    std::memcpy(b.blk.data() + L.off_ext_off, ext_off.data(), ext_off.size() * 4);
-    L.n_ext = (int)ext.size();
-    L.off_ext = b.alloc((ext.size() + kExtBatch) * 4);  // padded: a kernel reads whole batches
-    if (!ext.empty()) std::memcpy(b.blk.data() + L.off_ext, ext.data(), ext.size() * sizeof(ExtStep));
+        ext_off[n_tiles] = (int)ext.size();
+        off_ext_off = b.alloc(ext_off.size());
+        std::memcpy(b.blk.data() + off_ext_off, ext_off.data(), ext_off.size() * 4);
+        off_ext = b.alloc((ext.size() + kExtBatch) * 4);  // padded: a kernel reads whole batches
+        if (!ext.empty()) std::memcpy(b.blk.data() + off_ext, ext.data(), ext.size() * sizeof(ExtStep));
+        if (n_ext) *n_ext = (int)ext.size();
+        if (max_per_tile) *max_per_tile = most;
+    };
+    L.bm = bm;
+    build_ext(bm, L.n_tiles_m, L.off_ext_off, L.off_ext, &L.n_ext, &L.max_ext_per_tile);
+    if (bm == 256) build_ext(128, L.n_tiles_m_half, L.off_ext_off_half, L.off_ext_half, nullptr, nullptr);
 }
 
 }  // namespace
@@ -232,8 +238,8 @@ size_t plan_ints_upper_bound(int max_tokens, int max_segments, int max_adapters,
     for (int k = 0; k < 2; ++k) {
         n += 2 * Tp;                     // row_tok, row_adapter
         n += 4 * (Tp / kSkinnyRows + N) + 8;          // skinny items
-        n += Tp / 64 + 8;                // ext_off (smallest tile 64 rows)
-        n += 4 * steps * (Tp / 64 + N) + 4 * kExtBatch + 8;  // ext steps: (tiles + adapter runs) x steps
+        n += 2 * (Tp / 64 + 8);          // ext_off (smallest tile 64 rows), two tile sizes
+        n += 2 * (4 * steps * (Tp / 64 + N) + 4 * kExtBatch + 8);  // ext steps: (tiles + adapter runs) x steps, two tile sizes
     }
     n += 4 * N + 8;                      // grad items
     return n + 1024;
