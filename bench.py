@@ -79,10 +79,11 @@ def _algorithmic_bytes(w, p):
 
 
 class Runner:
-    def __init__(self, w, proj_index, torch, exact=False):
+    def __init__(self, w, proj_index, torch, exact=False, transposed=False):
         from paper_2604_16400_amd import binding
 
         self.w, self.p, self.torch = w, w.projections[proj_index], torch
+        self.layout = binding.LAYOUT_OUT_IN if transposed else binding.LAYOUT_IN_OUT
         d = max(self.p.d_in, self.p.d_out)
         self.max_rank = int(w.ranks.max())
         self.ctx = binding.Context(w.n_tokens, w.n_segments, w.n_adapters, self.max_rank, d)
@@ -94,16 +95,21 @@ class Runner:
         self.h_save = torch.empty((T, self.max_rank), dtype=torch.float32, device="cuda")
         self.dA = [torch.empty((self.p.d_in, int(r)), dtype=torch.float32, device="cuda") for r in w.ranks]
         self.dB = [torch.empty((int(r), self.p.d_out), dtype=torch.float32, device="cuda") for r in w.ranks]
+        if transposed:  # module-weight convention: W [d_out, d_in], A [rank, d_in], B [d_out, rank], gradients alike
+            tp = lambda a: a.t().contiguous()
+            self.W, self.A, self.B = tp(self.W), [tp(a) for a in self.A], [tp(b) for b in self.B]
+            self.dA, self.dB = [tp(a) for a in self.dA], [tp(b) for b in self.dB]
         # the adapter pointer tables live as long as the adapters do: build them once
         self.A, self.B = binding.PointerTable(self.A), binding.PointerTable(self.B)
         self.dA, self.dB = binding.PointerTable(self.dA), binding.PointerTable(self.dB)
 
-    def step(self):
+    def step(self, accumulate=False):
         w, c = self.w, self.ctx
         c.collm_lora_linear_fwd(self.x, self.W, self.A, self.B, w.ranks, w.seg_start, w.seg_adapter,
-                                w.seg_is_train, w.scale, self.y, self.h_save)
+                                w.seg_is_train, w.scale, self.y, self.h_save, layout=self.layout)
         c.collm_lora_linear_bwd(self.x, self.W, self.A, self.B, w.ranks, w.seg_start, w.seg_adapter,
-                                w.seg_is_train, w.scale, self.dy, self.h_save, self.dx, self.dA, self.dB, False)
+                                w.seg_is_train, w.scale, self.dy, self.h_save, self.dx, self.dA, self.dB, accumulate,
+                                layout=self.layout)
 
     def prewarm(self, dispatches=1300):
         """The HIP runtime stalls once, for tens of milliseconds, at its 1024th kernel dispatch
@@ -214,6 +220,38 @@ def _adapter_update(torch, binding):
             "adamw_GBs": b_opt / t_opt / 1e9, "adamw_frac_hbm_peak": b_opt / t_opt / 1e9 / PEAK_HBM_GBS}
 
 
+def _variants(w, torch, steps, warmup):
+    """Configuration 2 again in the two other forms a caller may use: the module-weight layout (every table
+    transposed) and gradient accumulation over 8 micro-batches (the first overwrites dA/dB, seven add into
+    them; paper section 2.3 trains with 8 accumulation steps).  Same flops per step as the headline."""
+    p = w.projections[0]
+    f_fwd, f_bwd = w.flops(p)
+    out = {}
+    r = Runner(w, 0, torch, transposed=True)
+    sec = r.timed(steps, warmup)
+    out["layout_out_in"] = {"ms_per_step": sec * 1e3, "tflops": (f_fwd + f_bwd) / sec / 1e12}
+    r.close()
+    r = Runner(w, 0, torch)
+
+    def eight():
+        for k in range(8):
+            r.step(accumulate=k > 0)
+
+    for _ in range(max(1, warmup // 8)):
+        eight()
+    torch.cuda.synchronize()
+    n = max(1, steps // 8)
+    t0 = time.perf_counter()
+    for _ in range(n):
+        eight()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / (8 * n)
+    out["accumulate_x8"] = {"micro_batches": 8, "ms_per_micro_batch": sec * 1e3,
+                            "tflops": (f_fwd + f_bwd) / sec / 1e12}
+    r.close()
+    return out
+
+
 def _cpu_baseline(w, t):
     """The oracle as it stands, timed on the host cores on the same workload."""
     import numpy as np
@@ -301,6 +339,7 @@ def main():
         del src, dst
 
     adapter_update = _adapter_update(torch, binding)
+    variants = _variants(w2, torch, args.steps, args.warmup)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -322,6 +361,7 @@ def main():
         "frac_mfma_peak_whole_step": (f_fwd + f_bwd) / sec / 1e12 / PEAK_BF16_TFLOPS,
         "all_configs": all_cfg,
         "adapter_update": adapter_update,
+        "variants": variants,
         "device": {"name": props.name, "cus": props.multi_processor_count,
                    "peak_bf16_tflops_used": PEAK_BF16_TFLOPS, "peak_hbm_gbs_used": PEAK_HBM_GBS},
         "paper_context": "paper reports system-level gains only (up to 1.5x goodput, 2.2x quality-weighted "

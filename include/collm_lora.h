@@ -54,6 +54,20 @@ typedef struct collm_ctx collm_ctx; /* opaque: pinned staging, device plan and w
 
 typedef enum { COLLM_F32 = 0, COLLM_BF16 = 1 } collm_dtype;
 
+/*
+ * How the weight and the adapter tables lie in memory.  The mathematics is the same; with
+ * COLLM_LAYOUT_OUT_IN every one of them, and every adapter gradient, is the transpose of the
+ * array described at the calls below (the convention of module weights that store
+ * [out_features, in_features]):
+ *
+ *                           W               A[i]              B[i]              dA[i]  dB[i]
+ *   COLLM_LAYOUT_IN_OUT     [d_in, d_out]   [d_in, rank]      [rank, d_out]     as A   as B
+ *   COLLM_LAYOUT_OUT_IN     [d_out, d_in]   [rank, d_in]      [d_out, rank]     as A   as B
+ *
+ * x, y, dy, dx and h_save do not change.
+ */
+typedef enum { COLLM_LAYOUT_IN_OUT = 0, COLLM_LAYOUT_OUT_IN = 1 } collm_layout;
+
 enum {
     COLLM_OK = 0,
     COLLM_E_NULL = -1,     /* a required pointer is NULL                                    */
@@ -75,6 +89,7 @@ typedef struct {
     int32_t n_adapters; /* N */
     int32_t dtype;      /* collm_dtype */
     float scale;        /* multiplies the low-rank term */
+    int32_t layout;     /* collm_layout of W, A, B, dA, dB */
 } collm_shape;
 
 /* Create a context on GPU `device` able to serve calls with n_tokens <= max_tokens,
@@ -102,7 +117,7 @@ const char *collm_last_error(void);
  * K-steps before the single rounding of y.
  *
  *   x            dev  [T, d_in]
- *   W            dev  [d_in, d_out]
+ *   W            dev  [d_in, d_out]  (shapes of W, A, B as for COLLM_LAYOUT_IN_OUT; see collm_layout)
  *   A, B         HOST arrays [N] of dev pointers, A[i]: [d_in, rank[i]], B[i]: [rank[i], d_out];
  *                an entry may be NULL if no segment uses adapter i
  *   rank         HOST [N]

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libcollm_lora.so")
 
 COLLM_F32 = 0
 COLLM_BF16 = 1
+LAYOUT_IN_OUT, LAYOUT_OUT_IN = 0, 1  # W [d_in, d_out] (paper, row vectors) / W [d_out, d_in] (module weights)
 
 TILE_AUTO, TILE_256x256, TILE_256x128, TILE_128x128, TILE_256x256_W8 = -1, 0, 1, 2, 3
 
@@ -32,7 +33,7 @@ class collm_shape(ctypes.Structure):
     _fields_ = [
         ("d_in", ctypes.c_int32), ("d_out", ctypes.c_int32), ("n_tokens", ctypes.c_int32),
         ("n_segments", ctypes.c_int32), ("n_adapters", ctypes.c_int32), ("dtype", ctypes.c_int32),
-        ("scale", ctypes.c_float),
+        ("scale", ctypes.c_float), ("layout", ctypes.c_int32),
     ]
 
 
@@ -126,7 +127,7 @@ def collm_token_map(seg_start, seg_adapter, seg_is_train, n_tokens: Optional[int
     lib = load_library()
     ss, sa, st = _seg_arrays(seg_start, seg_adapter, seg_is_train)
     T = int(ss[-1]) if n_tokens is None else int(n_tokens)
-    sh = collm_shape(8, 8, T, len(sa), n_adapters, COLLM_BF16, 1.0)
+    sh = collm_shape(8, 8, T, len(sa), n_adapters, COLLM_BF16, 1.0, LAYOUT_IN_OUT)
     ts = np.full(max(T, 0), -9, np.int32)
     ta = np.full(max(T, 0), -9, np.int32)
     tt = np.full(max(T, 0), 9, np.uint8)
@@ -207,7 +208,7 @@ class Context:
         return ts, ta, tt
 
     # ------------------------------------------------------------------------------------
-    def _shape(self, x, d_out, n_seg, n_adapters, scale):
+    def _shape(self, x, W, n_seg, n_adapters, scale, layout):
         import torch
 
         if x.dtype == torch.bfloat16:
@@ -216,7 +217,9 @@ class Context:
             dt = COLLM_F32
         else:
             raise TypeError("x must be bfloat16 or float32")
-        return collm_shape(int(x.shape[1]), int(d_out), int(x.shape[0]), n_seg, n_adapters, dt, float(scale))
+        d_out = W.shape[0] if layout == LAYOUT_OUT_IN else W.shape[1]
+        return collm_shape(int(x.shape[1]), int(d_out), int(x.shape[0]), n_seg, n_adapters, dt, float(scale),
+                           int(layout))
 
     @staticmethod
     def _stream(stream):
@@ -226,11 +229,12 @@ class Context:
         return ctypes.c_void_p(s.cuda_stream)
 
     def collm_lora_linear_fwd(self, x, W, A: List, B: List, rank, seg_start, seg_adapter, seg_is_train,
-                              scale: float, y, h_save=None, stream=None):
-        """y <- x W + scale (x A_a) B_a per segment; h_save (optional) <- x A_a on training rows."""
+                              scale: float, y, h_save=None, stream=None, layout: int = 0):
+        """y <- x W + scale (x A_a) B_a per segment; h_save (optional) <- x A_a on training rows.
+        layout LAYOUT_OUT_IN: W, A_a, B_a are given transposed ([d_out, d_in], [rank, d_in], [d_out, rank])."""
         ss, sa, st = _seg_arrays(seg_start, seg_adapter, seg_is_train)
         rk = np.ascontiguousarray(rank, dtype=np.int32)
-        sh = self._shape(x, W.shape[1], len(sa), len(rk), scale)
+        sh = self._shape(x, W, len(sa), len(rk), scale, layout)
         At, Bt = _ptr_table(A, len(rk)), _ptr_table(B, len(rk))
         _check(self._lib.collm_lora_linear_fwd(
             self._h, ctypes.byref(sh), x.data_ptr(), W.data_ptr(), At, Bt, rk.ctypes.data_as(_i32p),
@@ -240,11 +244,12 @@ class Context:
 
     def collm_lora_linear_bwd(self, x, W, A: List, B: List, rank, seg_start, seg_adapter, seg_is_train,
                               scale: float, dy, h_save=None, dx=None, dA: Optional[List] = None,
-                              dB: Optional[List] = None, accumulate: bool = False, stream=None):
-        """Training rows: dx <- dy W^T + dh A_a^T; dA_a, dB_a (fp32) summed over the adapter's tokens."""
+                              dB: Optional[List] = None, accumulate: bool = False, stream=None, layout: int = 0):
+        """Training rows: dx <- dy W^T + dh A_a^T; dA_a, dB_a (fp32) summed over the adapter's tokens.
+        layout LAYOUT_OUT_IN: W, A_a, B_a, dA_a, dB_a are all transposed."""
         ss, sa, st = _seg_arrays(seg_start, seg_adapter, seg_is_train)
         rk = np.ascontiguousarray(rank, dtype=np.int32)
-        sh = self._shape(x, W.shape[1], len(sa), len(rk), scale)
+        sh = self._shape(x, W, len(sa), len(rk), scale, layout)
         At, Bt = _ptr_table(A, len(rk)), _ptr_table(B, len(rk))
         dAt = _ptr_table(dA, len(rk)) if dA is not None else None
         dBt = _ptr_table(dB, len(rk)) if dB is not None else None

@@ -191,6 +191,7 @@ int check_common(collm_ctx *ctx, const collm_shape *s, const void *x, const void
     if (s->dtype != COLLM_F32 && s->dtype != COLLM_BF16) return COLLM_E_DTYPE;
     const int q = s->dtype == COLLM_BF16 ? 8 : 4;
     if (s->d_in <= 0 || s->d_out <= 0 || s->d_in % q || s->d_out % q) return COLLM_E_SHAPE;
+    if (s->layout != COLLM_LAYOUT_IN_OUT && s->layout != COLLM_LAYOUT_OUT_IN) return COLLM_E_SHAPE;
     if (s->d_in > ctx->max_d || s->d_out > ctx->max_d) return COLLM_E_SHAPE;
     if (s->n_tokens < 0 || s->n_tokens > ctx->max_tokens) return COLLM_E_SHAPE;
     {
@@ -577,7 +578,10 @@ int collm_lora_linear_fwd(collm_ctx *c, const collm_shape *s, const void *x, con
     const bool f32 = s->dtype == COLLM_F32;
 
     // shrink: h = x A_a (fp32), kept as s*h in the element type for the GEMM's extra K-steps
-    rc = run_skinny(c, s, L.all, x, s->d_in, L.off_A_ptr, false, h_save, c->max_rank, c->max_rank, 1, 1.0f,
+    // COLLM_LAYOUT_OUT_IN: every table is the transpose, so each pass takes the kernel variant its
+    // counterpart in the other direction uses
+    const bool tr = s->layout == COLLM_LAYOUT_OUT_IN;
+    rc = run_skinny(c, s, L.all, x, s->d_in, L.off_A_ptr, tr, h_save, c->max_rank, c->max_rank, 1, 1.0f,
                     c->d_hs, s->scale, "shrink", st);
     if (rc != COLLM_OK) return rc;
 
@@ -585,7 +589,7 @@ int collm_lora_linear_fwd(collm_ctx *c, const collm_shape *s, const void *x, con
     g.a = x;
     g.lda = s->d_in;
     g.b = W;
-    g.ldb = s->d_out;
+    g.ldb = tr ? s->d_in : s->d_out;
     g.out = y;
     g.ldo = s->d_out;
     g.N = s->d_out;
@@ -599,14 +603,14 @@ int collm_lora_linear_fwd(collm_ctx *c, const collm_shape *s, const void *x, con
     g.hs = c->d_hs;
     g.hs_ld = L.rpad;
     g.hs_bytes = (uint32_t)((size_t)c->rows_cap * c->rpad_cap * 4);
-    g.ext_ld = s->d_out;
+    g.ext_ld = tr ? 0 : s->d_out;
     g.zeros = c->d_zeros;
     {
         Prof prof(c, st, "gemm_fwd");
         if (f32) {
-            HIP_TRY(launch_gemm_f32(g, false, st));
+            HIP_TRY(launch_gemm_f32(g, tr, st));
         } else {
-            HIP_TRY(run_gemm(c, g, L.all, s->n_tokens, s->d_out, c->tile_fwd, false, st));
+            HIP_TRY(run_gemm(c, g, L.all, s->n_tokens, s->d_out, c->tile_fwd, tr, st));
         }
     }
     return COLLM_OK;
@@ -641,10 +645,11 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
     if (rc != COLLM_OK) return rc;
     const PlanLayout &L = c->L;
     const bool f32 = s->dtype == COLLM_F32;
+    const bool tr = s->layout == COLLM_LAYOUT_OUT_IN;
 
     // h of the training rows, if the forward call did not keep it
     if (!h_save && dA) {
-        rc = run_skinny(c, s, L.train, x, s->d_in, L.off_A_ptr, false, c->d_h32, L.rpad, L.rpad, 0, 1.0f,
+        rc = run_skinny(c, s, L.train, x, s->d_in, L.off_A_ptr, tr, c->d_h32, L.rpad, L.rpad, 0, 1.0f,
                         c->d_hs, s->scale, "shrink_recompute", st);
         if (rc != COLLM_OK) return rc;
     }
@@ -689,7 +694,7 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
             ga.ld_small_bf = L.rpad;
         }
         ga.out_tab = reinterpret_cast<const uint64_t *>(c->d_plan + L.off_dB_ptr);
-        ga.out_transposed = 0;
+        ga.out_transposed = tr ? 1 : 0;
         {
             Prof prof(c, gs, "grad_dB");
             if (f32) HIP_TRY(launch_grad_f32(ga, L.n_grad, gs));
@@ -698,7 +703,7 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
     }
 
     // dh = s dy B_a^T: fp32 for dA, element type for the dX GEMM's extra K-steps
-    rc = run_skinny(c, s, L.train, dy, s->d_out, L.off_B_ptr, true, c->d_dh32, L.rpad, L.rpad, 0, s->scale,
+    rc = run_skinny(c, s, L.train, dy, s->d_out, L.off_B_ptr, !tr, c->d_dh32, L.rpad, L.rpad, 0, s->scale,
                     c->d_dhs, s->scale, "dh", st);
     if (rc != COLLM_OK) return rc;
 
@@ -721,7 +726,7 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
             ga.ld_small_bf = L.rpad;
         }
         ga.out_tab = reinterpret_cast<const uint64_t *>(c->d_plan + L.off_dA_ptr);
-        ga.out_transposed = 1;
+        ga.out_transposed = tr ? 0 : 1;
         {
             Prof prof(c, gs, "grad_dA");
             if (f32) HIP_TRY(launch_grad_f32(ga, L.n_grad, gs));
@@ -735,7 +740,7 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
         g.a = dy;
         g.lda = s->d_out;
         g.b = W;
-        g.ldb = s->d_out;
+        g.ldb = tr ? s->d_in : s->d_out;
         g.out = dx;
         g.ldo = s->d_in;
         g.N = s->d_in;
@@ -749,13 +754,13 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
         g.hs = c->d_dhs;
         g.hs_ld = L.rpad;
         g.hs_bytes = (uint32_t)((size_t)c->rows_cap * c->rpad_cap * 4);
-        g.ext_ld = 0;
+        g.ext_ld = tr ? s->d_in : 0;
         g.zeros = c->d_zeros;
         Prof prof(c, st, "gemm_dx");
         if (f32) {
-            HIP_TRY(launch_gemm_f32(g, true, st));
+            HIP_TRY(launch_gemm_f32(g, !tr, st));
         } else {
-            HIP_TRY(run_gemm(c, g, L.train, n_train, s->d_in, c->tile_bwd, true, st));
+            HIP_TRY(run_gemm(c, g, L.train, n_train, s->d_in, c->tile_bwd, !tr, st));
         }
     }
     if (overlap) HIP_TRY(hipStreamWaitEvent(st, c->ev_join, 0));

@@ -31,21 +31,25 @@ def maxrel(got, ref) -> float:
 
 
 class DeviceLayer:
-    """Inputs of one projection on the GPU plus the output buffers, sentinel-filled."""
+    """Inputs of one projection on the GPU plus the output buffers, sentinel-filled.  With
+    transposed=True the weight, the adapter tables and the adapter gradients live on the device as
+    transposes (LAYOUT_OUT_IN); the host-side tensors in `t` keep the paper's layout."""
 
     def __init__(self, w: wl.Workload, t: wl.Tensors, ctx: binding.Context, proj_index: int = 0,
-                 dy_poison_inference: bool = True):
+                 dy_poison_inference: bool = True, transposed: bool = False):
         import torch
 
         self.w, self.t, self.ctx = w, t, ctx
+        self.layout = binding.LAYOUT_OUT_IN if transposed else binding.LAYOUT_IN_OUT
+        tp = (lambda a: np.ascontiguousarray(np.asarray(a).T)) if transposed else (lambda a: a)
         p = w.projections[proj_index]
         self.p = p
         dt = w.dtype
         self.tdtype = torch.bfloat16 if dt == "bf16" else torch.float32
         self.x = to_dev(t.x, dt)
-        self.W = to_dev(t.W, dt)
-        self.A = [to_dev(a, dt) for a in t.A]
-        self.B = [to_dev(b, dt) for b in t.B]
+        self.W = to_dev(tp(t.W), dt)
+        self.A = [to_dev(tp(a), dt) for a in t.A]
+        self.B = [to_dev(tp(b), dt) for b in t.B]
         _, self.tok_adapter, self.tok_train = oracle.token_map(w.seg_start, w.seg_adapter, w.seg_is_train)
         dy = np.array(t.dy, dtype=np.float32)
         if dy_poison_inference:
@@ -55,20 +59,22 @@ class DeviceLayer:
         self.y = torch.full((T, p.d_out), float("nan"), dtype=self.tdtype, device="cuda")
         self.dx = torch.full((T, p.d_in), float("nan"), dtype=self.tdtype, device="cuda")
         self.h_save = torch.full((T, ctx.max_rank), float("nan"), dtype=torch.float32, device="cuda")
-        self.dA = [torch.full((p.d_in, int(r)), float("nan"), dtype=torch.float32, device="cuda") for r in w.ranks]
-        self.dB = [torch.full((int(r), p.d_out), float("nan"), dtype=torch.float32, device="cuda") for r in w.ranks]
+        sh = (lambda a, b: (b, a)) if transposed else (lambda a, b: (a, b))
+        self.dA = [torch.full(sh(p.d_in, int(r)), float("nan"), dtype=torch.float32, device="cuda") for r in w.ranks]
+        self.dB = [torch.full(sh(int(r), p.d_out), float("nan"), dtype=torch.float32, device="cuda") for r in w.ranks]
 
     def fwd(self, h_save=True):
         w = self.w
         self.ctx.collm_lora_linear_fwd(self.x, self.W, self.A, self.B, w.ranks, w.seg_start, w.seg_adapter,
-                                       w.seg_is_train, w.scale, self.y, self.h_save if h_save else None)
+                                       w.seg_is_train, w.scale, self.y, self.h_save if h_save else None,
+                                       layout=self.layout)
 
     def bwd(self, h_save=True, accumulate=False, dx=True, dab=True):
         w = self.w
         self.ctx.collm_lora_linear_bwd(self.x, self.W, self.A, self.B, w.ranks, w.seg_start, w.seg_adapter,
                                        w.seg_is_train, w.scale, self.dy, self.h_save if h_save else None,
                                        self.dx if dx else None, self.dA if dab else None,
-                                       self.dB if dab else None, accumulate)
+                                       self.dB if dab else None, accumulate, layout=self.layout)
 
 
 def make_ctx(w: wl.Workload, max_rank=None) -> binding.Context:
@@ -109,6 +115,8 @@ def check_full(layer: DeviceLayer, tol: float, check_h=True):
                 assert np.all(hs[tok, w.ranks[ta[tok]]:] == 0.0)
     for a in range(w.n_adapters):
         dA, dB = to_host(layer.dA[a]), to_host(layer.dB[a])
+        if layer.layout == binding.LAYOUT_OUT_IN:
+            dA, dB = dA.T, dB.T
         if dA_ref[a] is None:
             assert np.all(np.isnan(dA)) and np.all(np.isnan(dB)), f"untrained adapter {a} was written"
         else:

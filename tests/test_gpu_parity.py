@@ -15,10 +15,10 @@ from gpu_util import TOL, DeviceLayer, check_full, make_ctx, maxrel, to_dev, to_
 pytestmark = pytest.mark.gpu
 
 
-def _run_full(w, tol=None, h_save=True, **kw):
+def _run_full(w, tol=None, h_save=True, transposed=False, **kw):
     t = wl.make_tensors(w)
     ctx = make_ctx(w, **kw)
-    layer = DeviceLayer(w, t, ctx)
+    layer = DeviceLayer(w, t, ctx, transposed=transposed)
     layer.fwd(h_save=h_save)
     layer.bwd(h_save=h_save)
     errs = check_full(layer, TOL[w.dtype] if tol is None else tol, check_h=h_save)
@@ -216,6 +216,24 @@ def test_rows_split_between_large_and_small_tiles(wide_side):
     _run_full(w)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_transposed_weight_and_table_layout(dtype):
+    # W [d_out, d_in], A [rank, d_in], B [d_out, rank], gradients likewise: the same mathematics, so the
+    # oracle is fed the transposes back.  Ragged sizes, ranks that are and are not multiples of 8,
+    # decode and training rows sharing tiles; then config 2 (bf16) in full.
+    q = 8 if dtype == "bf16" else 4
+    w = _adhoc(dtype, 25 * q, 41 * q, [3, 5, 17, 8, 1, 24], [5, 0, 37, 1, 130, 0, 70, 2, 64, 301],
+               [0, 1, -1, 2, 2, 3, 5, -1, 4, 2], [0, 0, 0, 0, 1, 0, 1, 0, 0, 1], scale=0.3)
+    _run_full(w, transposed=True)
+    _run_full(w, transposed=True, h_save=False)
+    w = _adhoc(dtype, 64 * q, 24 * q, [16, 64, 40], [1] * 40 + [300, 200, 150], list(np.arange(40) % 3) + [0, 1, 2],
+               [0] * 40 + [1, 1, 0])
+    _run_full(w, transposed=True)
+    if dtype == "bf16":
+        errs = _run_full(wl.make_config(2), transposed=True)
+        assert errs["y"] < 6e-3 and errs["dx"] < 6e-3
+
+
 @pytest.mark.parametrize("tile", [binding.TILE_256x256, binding.TILE_256x128, binding.TILE_128x128,
                                   binding.TILE_256x256_W8])
 def test_every_gemm_tile_shape(tile):
@@ -331,6 +349,7 @@ def test_error_statuses_touch_nothing():
     big = torch.zeros((31, 64), dtype=torch.bfloat16, device="cuda")
     expect(-2, lambda: c(**args(x=big, seg_start=[0, 10, 31])))  # more tokens than the context holds
     expect(-2, lambda: c(**args(x=layer.x[:, :60].contiguous())))  # d_in not a multiple of 8
+    expect(-2, lambda: c(**args(layout=2)))                      # unknown layout
     torch.cuda.synchronize()
     assert torch.isnan(layer.y).all()
     # backward: trained adapter without gradient buffers
