@@ -185,6 +185,15 @@ int collm_debug_device_token_map(collm_ctx *ctx, int32_t *tok_segment, int32_t *
 int collm_debug_set_tiles(collm_ctx *ctx, int fwd_tile, int bwd_tile);
 
 /*
+ * Debug/tuning: which rows the rank-wide passes (h = x A, dh = dy B^T) run as 128-row tiles
+ * rather than 16-row items: runs of at least min_rows rows of one adapter whose rank is a
+ * multiple of 8.  0: never; -1: let the library choose (every such adapter when the widest
+ * rank of the batch is at least 49; for the training rows already from 17).  bf16 only.
+ * Affects only speed and rounding order.
+ */
+int collm_debug_set_wide_pass(collm_ctx *ctx, int min_rows);
+
+/*
  * Debug/profiling: average duration in milliseconds, measured with HIP events on the
  * call's own stream, of each kernel launched by the context's last compute call.
  * collm_profile_enable(ctx, 1) makes every later call record events around each launch;

@@ -89,6 +89,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.collm_debug_device_token_map.restype = ctypes.c_int
     lib.collm_debug_set_tiles.argtypes = [vp, ctypes.c_int, ctypes.c_int]
     lib.collm_debug_set_tiles.restype = ctypes.c_int
+    lib.collm_debug_set_wide_pass.argtypes = [vp, ctypes.c_int]
+    lib.collm_debug_set_wide_pass.restype = ctypes.c_int
     lib.collm_profile_enable.argtypes = [vp, ctypes.c_int]
     lib.collm_profile_enable.restype = ctypes.c_int
     lib.collm_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float),
@@ -186,6 +188,9 @@ class Context:
 
     def set_tiles(self, fwd_tile: int = TILE_AUTO, bwd_tile: int = TILE_AUTO):
         _check(self._lib.collm_debug_set_tiles(self._h, fwd_tile, bwd_tile), "collm_debug_set_tiles")
+
+    def set_wide_pass(self, min_rows: int = -1):
+        _check(self._lib.collm_debug_set_wide_pass(self._h, min_rows), "collm_debug_set_wide_pass")
 
     def profile_enable(self, on: bool):
         _check(self._lib.collm_profile_enable(self._h, 1 if on else 0), "collm_profile_enable")

@@ -79,6 +79,8 @@ struct collm_ctx {
     std::vector<uint64_t> key_A, key_B;
 
     int tile_fwd = -1, tile_bwd = -1;  // forced GEMM tile shapes (-1 = choose)
+    int wide_min_rows = -1;            // forced threshold of the tiled rank-wide pass (-1 = choose, 0 = never)
+    int key_wide = 0;
     hipStream_t last_stream = nullptr;
     // the adapter gradients run beside dh and the dX GEMM on a second stream
     hipStream_t side = nullptr;
@@ -219,14 +221,14 @@ int check_common(collm_ctx *ctx, const collm_shape *s, const void *x, const void
 
 bool same_key(collm_ctx *c, const collm_shape *s, const void *const *A, const void *const *B,
               const int32_t *rank, const int32_t *seg_start, const int32_t *seg_adapter,
-              const uint8_t *seg_is_train, int bm_all, int bm_train)
+              const uint8_t *seg_is_train, int bm_all, int bm_train, int wide)
 {
     if (!c->plan_valid) return false;
     const collm_shape &k = c->key_shape;
     if (k.d_in != s->d_in || k.d_out != s->d_out || k.n_tokens != s->n_tokens ||
         k.n_segments != s->n_segments || k.n_adapters != s->n_adapters || k.dtype != s->dtype)
         return false;
-    if (bm_all != c->key_bm_all || bm_train != c->key_bm_train) return false;
+    if (bm_all != c->key_bm_all || bm_train != c->key_bm_train || wide != c->key_wide) return false;
     const int S = s->n_segments, N = s->n_adapters;
     if (std::memcmp(c->key_seg_start.data(), seg_start, sizeof(int32_t) * (S + 1))) return false;
     if (S && std::memcmp(c->key_seg_adapter.data(), seg_adapter, sizeof(int32_t) * S)) return false;
@@ -279,12 +281,22 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
     const int tile_bwd = c->tile_bwd >= 0 ? c->tile_bwd : pick_tiling(n_train, s->d_in).tile;
     const int bm_all = f32 ? 64 : gemm_tile_rows(tile_fwd);
     const int bm_train = f32 ? 64 : gemm_tile_rows(tile_bwd);
+    int rmax = 1;
+    for (int a = 0; a < s->n_adapters; ++a) rmax = std::max(rmax, rank[a]);
+    // All rows of an adapter take the tiled rank-wide pass when ranks reach 64: there an adapter's table
+    // outweighs 16 or 32 rows of activations several times, and the tiled pass fetches it once per 128 rows.
+    // Narrow ranks waste its 128 columns of matrix work; measured, it still pays for the dh pass (tables
+    // with K contiguous) from rank 32 up.  Encoded as all-rows threshold + 65536 * training-rows threshold.
+    const int rpad_max = round_up(rmax, kKStep);
+    const int wide_all = f32 ? 0 : (c->wide_min_rows >= 0 ? c->wide_min_rows : (rpad_max >= 64 ? 1 : 0));
+    const int wide_train = f32 ? 0 : (c->wide_min_rows >= 0 ? c->wide_min_rows : (rpad_max >= 32 ? 1 : 0));
+    const int wide = wide_all + 65536 * wide_train;
 
     // A batch whose segment table, ranks, adapter tables and sizes equal those of the plan the device holds
     // reuses it (every layer and projection of a model sees the same batch): only a call on another stream
     // than the one the plan was uploaded on builds it again, since nothing orders the two streams.
     const bool reuse = allow_reuse && st == c->last_stream &&
-                       same_key(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, bm_all, bm_train);
+                       same_key(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, bm_all, bm_train, wide);
     if (!reuse) {
         PlanRequest rq;
         rq.shape = s;
@@ -298,11 +310,9 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
         rq.dB = dB;
         rq.bm_all = bm_all;
         rq.bm_train = bm_train;
-        {
-            int rmax = 1;
-            for (int a = 0; a < s->n_adapters; ++a) rmax = std::max(rmax, rank[a]);
-            rq.max_row_tiles = f32 ? 1 : skinny_max_row_tiles(round_up(rmax, kKStep));
-        }
+        rq.max_row_tiles = f32 ? 1 : skinny_max_row_tiles(round_up(rmax, kKStep));
+        rq.wide_min_rows_all = wide_all;
+        rq.wide_min_rows_train = wide_train;
         c->plan_valid = false;
         int rc = build_plan(rq, c->plan, c->L);
         if (rc != COLLM_OK) return rc;
@@ -314,6 +324,7 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
         c->key_shape = *s;
         c->key_bm_all = bm_all;
         c->key_bm_train = bm_train;
+        c->key_wide = wide;
         c->key_seg_start.assign(seg_start, seg_start + S + 1);
         c->key_seg_adapter.assign(seg_adapter, seg_adapter + S);
         c->key_seg_train.assign(seg_is_train, seg_is_train + S);
@@ -351,7 +362,7 @@ int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, cons
                int f32_by_token, float f32_mult, void *bf_out, float bf_mult, const char *name,
                hipStream_t st)
 {
-    if (R.n_items == 0) return COLLM_OK;
+    if (R.n_items == 0 && R.n_wide == 0) return COLLM_OK;
     SkinnyArgs a{};
     a.in = in;
     a.ld_in = K;
@@ -386,7 +397,7 @@ int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, cons
         lim = std::min<long>(lim, K / (4L * c->L.rpad));
         lim = std::min<long>(lim, K / ((long)skinny_chunk(c->L.rpad) * kw));
         const long waves = (long)R.n_items * kw;
-        if (trips > 6 && waves < 2048)
+        if (trips > 6 && waves > 0 && waves < 2048)
             n_split = (int)std::max<long>(1, std::min<long>({lim, (2048 + waves - 1) / waves, (trips + 2) / 3}));
     }
     a.part = c->d_part;
@@ -395,9 +406,37 @@ int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, cons
     Prof prof(c, st, name);
     if (s->dtype == COLLM_F32) {
         HIP_TRY(launch_skinny_f32(a, R.n_items, t_kmajor, st));
-    } else {
-        HIP_TRY(launch_skinny(a, R.n_items, c->L.rpad, R.item_rows / kSkinnyRows, n_split, t_kmajor, st));
+        return COLLM_OK;
     }
+    if (R.n_wide > 0) {
+        // Long runs: 128-row tiles through the GEMM machinery.  K is cut so that about two blocks per CU
+        // exist, as long as a slice keeps 512 K values and the partial sums fit the workspace; the small
+        // kernel that adds the slices also does this pass's stores.
+        GemmArgs g{};
+        g.a = in;
+        g.lda = K;
+        g.K = K;
+        g.a_bytes = a.in_bytes;
+        g.row_tok = a.row_tok;
+        g.items = reinterpret_cast<const SkinnyItem *>(c->d_plan + R.off_wide);
+        g.tab = a.tab;
+        g.part = a.part;
+        g.part_rows = a.part_rows;
+        g.part_ld = a.part_ld;
+        const long blocks = (long)R.n_wide * ((c->L.rpad + 127) / 128);
+        const long per_split = (long)c->rows_cap * c->rpad_cap * 4;
+        long ns = std::min<long>({(512 + blocks - 1) / blocks, std::max(1, K / 512), (long)c->part_bytes / per_split,
+                                  (long)kSkinnyMaxSplit});
+        ns = std::max<long>(ns, 1);
+        g.k_per_split = round_up((int)((K + ns - 1) / ns), 64);
+        const int n_wsplit = (K + g.k_per_split - 1) / g.k_per_split;
+        HIP_TRY(launch_wide(g, R.n_wide, c->L.rpad, n_wsplit, t_kmajor, st));
+        SkinnyArgs w = a;
+        w.items = g.items;
+        HIP_TRY(launch_skinny_finish(w, R.n_wide, kWideRows, n_wsplit, st));
+    }
+    if (R.n_items > 0)
+        HIP_TRY(launch_skinny(a, R.n_items, c->L.rpad, R.item_rows / kSkinnyRows, n_split, t_kmajor, st));
     return COLLM_OK;
 }
 
@@ -529,6 +568,14 @@ int collm_debug_set_tiles(collm_ctx *c, int fwd_tile, int bwd_tile)
     if (fwd_tile < -1 || fwd_tile >= kNumTiles || bwd_tile < -1 || bwd_tile >= kNumTiles) return COLLM_E_SHAPE;
     c->tile_fwd = fwd_tile;
     c->tile_bwd = bwd_tile;
+    return COLLM_OK;
+}
+
+int collm_debug_set_wide_pass(collm_ctx *c, int min_rows)
+{
+    if (!c) return COLLM_E_NULL;
+    if (min_rows < -1 || min_rows > 65535) return COLLM_E_SHAPE;
+    c->wide_min_rows = min_rows;
     return COLLM_OK;
 }
 

@@ -29,6 +29,14 @@ struct GemmArgs {
     uint32_t hs_bytes;        // size of hs
     int64_t ext_ld;           // row length of a [rank][N] table (forward)
     const void *zeros;        // at least 16 bytes of zeros, 16-byte aligned (source of masked 16-byte loads)
+    // rank-wide pass over long runs of one adapter (launch_wide): one row tile per item, second operand =
+    // the item's adapter table ([K][rank] or, K-major, [rank][K]), K cut into slices of k_per_split,
+    // fp32 sums of slice s for row r of the row order at part[(s * part_rows + r) * part_ld + q]
+    const SkinnyItem *items;
+    const uint64_t *tab;
+    float *part;
+    int part_rows, part_ld;
+    int k_per_split;          // multiple of 64
 };
 
 // out[m][q] = sum_k in[tok(m)][k] * tab_a(k, q), one SkinnyItem per blockIdx.x
@@ -74,6 +82,10 @@ struct GradArgs {
 };
 
 hipError_t launch_gemm(const GemmArgs &a, int tile_cfg, bool b_kmajor, hipStream_t st);
+// a, lda, K, a_bytes, row_tok and the fields of the rank-wide pass; everything else is ignored.  Items hold up
+// to kWideRows rows; ranks must be multiples of 8.  The caller adds the slices with launch_skinny_finish.
+hipError_t launch_wide(const GemmArgs &a, int n_items, int rpad, int n_split, bool t_kmajor, hipStream_t st);
+hipError_t launch_skinny_finish(const SkinnyArgs &a, int n_items, int item_rows, int n_split, hipStream_t st);
 int gemm_tile_rows(int tile_cfg);
 int gemm_tile_cols(int tile_cfg);
 // items hold up to 16 * row_tiles rows (row_tiles <= skinny_max_row_tiles(rpad)); n_split slices of K

@@ -327,7 +327,12 @@ struct DmaSlots {
     }
 };
 
-template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR, bool PINGPONG>
+// PARTIAL: the same tile machinery as a rank-wide pass over long runs of one adapter's rows.  A
+// block takes one item (up to BM rows of one adapter, blockIdx.x), BN of the adapter's rank
+// columns (blockIdx.y) and one slice of K (blockIdx.z); the second operand is the adapter's own
+// table; there are no extension steps, and the fp32 sums go to the workspace of partial sums that
+// skinny_finish_kernel adds up.
+template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR, bool PINGPONG, bool PARTIAL = false>
 __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 {
     constexpr int NT = WGM * WGN * 64;
@@ -356,18 +361,43 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WGM, wn = wave / WGM;
     int tile_m, tile_n;
-    tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
-    tile_m += p.tile_m_base;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
-    const int K = p.K, N = p.N;
+    int m0, K, N, rows_in = BM;
+    const void *a_base = p.a, *b_base = p.b;
+    uint32_t a_bytes = p.a_bytes, b_bytes = p.b_bytes, ldb = (uint32_t)p.ldb;
+    if constexpr (PARTIAL) {
+        const SkinnyItem it = p.items[blockIdx.x];
+        tile_m = blockIdx.x;
+        tile_n = blockIdx.y;
+        m0 = it.row_lo;
+        rows_in = it.n_rows;
+        N = it.rank;
+        // the block's slice of K: both operands start at its first K index, and the second one ends
+        // with the slice (its rows beyond it must read as zeros)
+        const int k_begin = blockIdx.z * p.k_per_split;
+        K = p.K - k_begin < p.k_per_split ? p.K - k_begin : p.k_per_split;
+        ldb = B_KMAJOR ? (uint32_t)p.K : (uint32_t)it.rank;
+        const uint32_t a_skip = (uint32_t)k_begin * 2u;
+        const uint32_t b_skip = B_KMAJOR ? (uint32_t)k_begin * 2u : (uint32_t)k_begin * ldb * 2u;
+        a_base = reinterpret_cast<const uint8_t *>(p.a) + a_skip;
+        a_bytes = p.a_bytes - a_skip;
+        b_base = reinterpret_cast<const uint8_t *>(p.tab[it.adapter]) + b_skip;
+        b_bytes = B_KMAJOR ? (uint32_t)it.rank * (uint32_t)p.K * 2u - b_skip : (uint32_t)K * ldb * 2u;
+    } else {
+        tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
+        tile_m += p.tile_m_base;
+        m0 = tile_m * BM;
+        K = p.K;
+        N = p.N;
+    }
+    const int n0 = tile_n * BN;
     const int32_t *__restrict__ row_tok = p.row_tok;
 
-    const __amdgpu_buffer_rsrc_t ra = make_rsrc(p.a, p.a_bytes);
-    const __amdgpu_buffer_rsrc_t rb = make_rsrc(p.b, p.b_bytes);
+    const __amdgpu_buffer_rsrc_t ra = make_rsrc(a_base, a_bytes);
+    const __amdgpu_buffer_rsrc_t rb = make_rsrc(b_base, b_bytes);
 
     // extension steps of this row tile; the first batch is fetched now, long before it is needed
-    const int e0 = __builtin_amdgcn_readfirstlane(p.ext_off[tile_m]);
-    const int e1 = __builtin_amdgcn_readfirstlane(p.ext_off[tile_m + 1]);
+    const int e0 = PARTIAL ? 0 : __builtin_amdgcn_readfirstlane(p.ext_off[tile_m]);
+    const int e1 = PARTIAL ? 0 : __builtin_amdgcn_readfirstlane(p.ext_off[tile_m + 1]);
     // The records of a batch come through the scalar cache (their own counter, so waiting for them
     // does not wait for the direct loads in flight).  Load and wait are one statement: registers
     // that a load is still writing must never be visible to the compiler, which may move or spill
@@ -390,7 +420,8 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         }
         return bt;
     };
-    const ExtBatch first_b = fetch_batch(e0);
+    ExtBatch first_b{};
+    if constexpr (!PARTIAL) first_b = fetch_batch(e0);
 
     // ---- per-thread source offsets (bytes) ------------------------------------------------
     // A thread owns fixed LDS positions: in K-major tiles row r8 + i NT/8, chunk position c8;
@@ -405,14 +436,15 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     uint32_t aoff[ACH];
 #pragma unroll
     for (int i = 0; i < ACH; ++i) {
-        const int tok = row_tok[m0 + r8 + i * (NT / 8)];
+        const int r = r8 + i * (NT / 8);
+        const int tok = (!PARTIAL || r < rows_in) ? row_tok[m0 + r] : -1;
         const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
         aoff[i] = tok >= 0 ? (uint32_t)tok * (uint32_t)p.lda * 2u + cl * 16u : kOob;
     }
     constexpr int NB = BCH;
     uint32_t boff[NB];
     uint32_t bstep = 0;  // N-major: advance of one K step, zero for columns beyond N
-    const uint32_t bstep_u = 64u * (uint32_t)p.ldb * 2u;  // the same as a wave-uniform value
+    const uint32_t bstep_u = 64u * ldb * 2u;  // the same as a wave-uniform value
     const int bng = tid % NG, bk0 = tid / NG;
     const int bcl = bng ^ ((bk0 & 3) << 2);  // N-major: source chunk of this thread (same for all i)
     if constexpr (B_KMAJOR) {
@@ -420,14 +452,14 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         for (int i = 0; i < NB; ++i) {
             const int n = n0 + r8 + i * (NT / 8);
             const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
-            boff[i] = n < N ? (uint32_t)n * (uint32_t)p.ldb * 2u + cl * 16u : kOob;
+            boff[i] = n < N ? (uint32_t)n * ldb * 2u + cl * 16u : kOob;
         }
     } else {
         const bool on = n0 + bcl * 8 < N;
-        bstep = on ? 64u * (uint32_t)p.ldb * 2u : 0u;
+        bstep = on ? 64u * ldb * 2u : 0u;
 #pragma unroll
         for (int i = 0; i < NB; ++i)
-            boff[i] = on ? ((uint32_t)(bk0 + i * (NT / NG)) * (uint32_t)p.ldb + n0 + bcl * 8) * 2u : kOob;
+            boff[i] = on ? ((uint32_t)(bk0 + i * (NT / NG)) * ldb + n0 + bcl * 8) * 2u : kOob;
     }
     // byte offset of the tile that starts at K index k0 = 64 kc, for chunk i; tiles that reach
     // beyond K mask their tail (K-major) or run off the end of the buffer (N-major rows)
@@ -486,7 +518,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     };
     // direct-to-LDS path: chunk idx (row chunks first, then the second operand's) of the tile that starts
     // at K index 64 kc goes to `stage`; the wave's 64 lanes fill the KiB (i NT/64 + wave) of the tile
-    const i32x4 ra_w = make_rsrc_words(p.a, p.a_bytes), rb_w = make_rsrc_words(p.b, p.b_bytes);
+    const i32x4 ra_w = make_rsrc_words(a_base, a_bytes), rb_w = make_rsrc_words(b_base, b_bytes);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
     const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds0 + wave * 1024);
     constexpr int ND = ACH + BCH;
@@ -714,7 +746,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     // of its loads, and those of the first batch before the main loop.  Rows of the tile outside a
     // step's row range, rank indices beyond the adapter's rank and columns beyond N are filled
     // with zeros (out-of-range buffer offsets, or the zero block).
-    if (e1 > e0) {
+    if (!PARTIAL && e1 > e0) {
         const i32x4 rh_w = make_rsrc_words(p.hs, p.hs_bytes);
         const uint64_t zeros = reinterpret_cast<uint64_t>(p.zeros);
         // per-lane choice among the four steps of a batch
@@ -823,7 +855,25 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     // with 8 bytes each.  Each wave instead writes its rounded tile to a private LDS area (row
     // pitch EP: the row, then its token index) and reads it back row by row, 16 bytes per lane,
     // so that a store instruction covers whole 128-byte lines of a few rows.
-    {
+    if constexpr (PARTIAL) {
+        // fp32 sums of the slice: a lane holds four consecutive rank columns of a row
+        const int q_hi = (N + 15) & ~15;
+        float *__restrict__ part = p.part + ((int64_t)blockIdx.z * p.part_rows + m0) * p.part_ld;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int r = wm * WM + mi * 32 + rl;
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int q = n0 + wn * WN + ni * 32 + g * 8 + kh * 4;
+                    if (r < rows_in && q < q_hi)
+                        *reinterpret_cast<floatx4 *>(part + (int64_t)r * p.part_ld + q) =
+                            floatx4{acc[ni][mi][g * 4 + 0], acc[ni][mi][g * 4 + 1], acc[ni][mi][g * 4 + 2], acc[ni][mi][g * 4 + 3]};
+                }
+            }
+        }
+    } else {
         constexpr int EP = WN * 2 + 16;          // bytes per staged row
         constexpr int LPR = WN / 8, RPI = 64 / LPR;  // lanes per row, rows per store instruction
         uint8_t *ep = smem + wave * (WM * EP);
@@ -1107,14 +1157,16 @@ __global__ void __launch_bounds__(SkinnyCfg<RP>::KW * 64) skinny_kernel(SkinnyAr
     }
 }
 
-// adds the K slices of every item in slice order and writes the results
+// adds the K slices of every item in slice order and writes the results; block (i, j) takes rows
+// 16 j .. 16 j + 15 of item i
 __global__ void __launch_bounds__(256) skinny_finish_kernel(SkinnyArgs p, int n_split)
 {
     const SkinnyItem it = p.items[blockIdx.x];
     const int rp = (it.rank + 15) & ~15;
     const int nq = rp >> 2;
-    for (int idx = threadIdx.x; idx < it.n_rows * nq; idx += 256) {
-        const int m = idx / nq, q = (idx - m * nq) * 4;
+    const int m_lo = blockIdx.y * 16, m_hi = it.n_rows < m_lo + 16 ? it.n_rows : m_lo + 16;
+    for (int idx = threadIdx.x; idx < (m_hi - m_lo) * nq; idx += 256) {
+        const int m = m_lo + idx / nq, q = (idx % nq) * 4;
         floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};
         for (int sp = 0; sp < n_split; ++sp)
             sum += *reinterpret_cast<const floatx4 *>(p.part + ((int64_t)sp * p.part_rows + it.row_lo + m) * p.part_ld + q);
@@ -1370,6 +1422,35 @@ hipError_t launch_gemm(const GemmArgs &a, int tile_cfg, bool b_kmajor, hipStream
     }
 }
 
+hipError_t launch_wide(const GemmArgs &a, int n_items, int rpad, int n_split, bool t_kmajor, hipStream_t st)
+{
+    static_assert(kWideRows == 128, "the rank-wide pass runs 128x128 tiles");
+    if (n_items <= 0) return hipSuccess;
+    if (n_split < 1 || !a.part || !a.items || !a.tab || a.k_per_split % 64 != 0) return hipErrorInvalidValue;
+    constexpr int smem = 2 * (128 + 128) * 128;
+    const dim3 grid(n_items, (rpad + 127) / 128, n_split);
+    auto launch = [&](auto kern) -> hipError_t {
+        static bool attr_done = false;
+        if (!attr_done) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+        hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, a);
+        return hipGetLastError();
+    };
+    return t_kmajor ? launch(gemm_lora_kernel<128, 128, 2, 2, true, false, true>)
+                    : launch(gemm_lora_kernel<128, 128, 2, 2, false, false, true>);
+}
+
+hipError_t launch_skinny_finish(const SkinnyArgs &a, int n_items, int item_rows, int n_split, hipStream_t st)
+{
+    if (n_items <= 0) return hipSuccess;
+    hipLaunchKernelGGL(skinny_finish_kernel, dim3(n_items, (item_rows + 15) / 16), dim3(256), 0, st, a, n_split);
+    return hipGetLastError();
+}
+
 int gemm_tile_rows(int tile_cfg) { return tile_cfg == kTile128x128 ? 128 : 256; }
 int gemm_tile_cols(int tile_cfg) { return (tile_cfg == kTile256x256 || tile_cfg == kTile256x256w8) ? 256 : 128; }
 
@@ -1387,7 +1468,7 @@ static hipError_t launch_skinny_t(const SkinnyArgs &a, int n_items, int n_split,
         attr_done = true;
     }
     hipLaunchKernelGGL(kern, dim3(n_items, n_split), dim3(C::KW * 64), smem, st, a);
-    if (n_split > 1) hipLaunchKernelGGL(skinny_finish_kernel, dim3(n_items), dim3(256), 0, st, a, n_split);
+    if (n_split > 1) hipLaunchKernelGGL(skinny_finish_kernel, dim3(n_items, RT), dim3(256), 0, st, a, n_split);
     return hipGetLastError();
 }
 

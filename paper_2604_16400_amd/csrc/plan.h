@@ -14,6 +14,7 @@
 
 namespace collm {
 
+constexpr int kWideRows = 128;  // rows of an item of the rank-wide pass for long runs of one adapter
 constexpr int kRowPad = 256;   // row orders are padded to a multiple of the largest GEMM tile
 constexpr int kMaxRank = 256;  // largest adapter rank the kernels accept
 constexpr int kSkinnyRows = 16;  // rows of one MFMA tile of the skinny passes; an item holds 1 or 2 tiles
@@ -52,6 +53,7 @@ struct RowOrderLayout {
     int32_t off_row_adapter = 0;  // [n_rows_pad] adapter or -1
     int32_t n_items = 0, off_items = 0;  // SkinnyItem[n_items]
     int32_t item_rows = kSkinnyRows;     // most rows an item holds (16 or 32)
+    int32_t n_wide = 0, off_wide = 0;    // SkinnyItem[n_wide] of up to kWideRows rows: long runs, taken by the tiled pass
     int32_t bm = 0, n_tiles_m = 0;       // GEMM row tile the extension tables were built for
     int32_t off_ext_off = 0;             // [n_tiles_m + 1]
     int32_t off_ext = 0, n_ext = 0;      // ExtStep[n_ext]

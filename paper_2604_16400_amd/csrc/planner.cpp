@@ -59,7 +59,7 @@ struct Builder {
 // Rows (token indices, already filtered) sorted by adapter, stable; items; extension tables.
 void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &tokens,
                      const int32_t *tok_adapter, const int32_t *rank, int n_adapters, int bm,
-                     const void *const *ext_tab, int max_row_tiles, int rpad)
+                     const void *const *ext_tab, int max_row_tiles, int rpad, int wide_min_rows)
 {
     const int n = (int)tokens.size();
     L.n_rows = n;
@@ -94,9 +94,19 @@ void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &
     // (for ranks above 64, where the table outweighs the rows eight times and more, from 2048 rows on)
     const int tiles = (max_row_tiles >= 2 && (n >= 4096 || (rpad >= 128 && n >= 2048))) ? 2 : 1;
     L.item_rows = kSkinnyRows * tiles;
-    std::vector<SkinnyItem> items;
+    // Long runs go to the tiled pass instead (items of up to kWideRows rows: an adapter's table is fetched
+    // once per 128 rows); what a run leaves over below the threshold stays a skinny item.
+    std::vector<SkinnyItem> items, wide;
     for (int a = 0; a < n_adapters; ++a) {
-        const int lo = start[a + 1], hi = start[a + 2];
+        int lo = start[a + 1];
+        const int hi = start[a + 2];
+        if (wide_min_rows > 0 && rank[a] % 8 == 0) {
+            while (hi - lo >= wide_min_rows) {
+                const int m = std::min(kWideRows, hi - lo);
+                wide.push_back({a, lo, m, rank[a]});
+                lo += m;
+            }
+        }
         for (int r = lo; r < hi; r += L.item_rows)
             items.push_back({a, r, std::min(L.item_rows, hi - r), rank[a]});
     }
@@ -104,6 +114,10 @@ void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &
     L.off_items = b.alloc(items.size() * 4 + 4);
     if (!items.empty())
         std::memcpy(b.blk.data() + L.off_items, items.data(), items.size() * sizeof(SkinnyItem));
+    L.n_wide = (int)wide.size();
+    L.off_wide = b.alloc(wide.size() * 4 + 4);
+    if (!wide.empty())
+        std::memcpy(b.blk.data() + L.off_wide, wide.data(), wide.size() * sizeof(SkinnyItem));
 
     // low-rank extension steps of every GEMM row tile
     auto build_ext = [&](int tile_rows, int32_t &n_tiles, int32_t &off_ext_off, int32_t &off_ext, int32_t *n_ext,
@@ -196,8 +210,8 @@ int build_plan(const PlanRequest &rq, std::vector<int32_t> &blk, PlanLayout &L)
     {
         std::vector<int32_t> tok_adapter(blk.begin() + L.off_tok_adapter,
                                          blk.begin() + L.off_tok_adapter + T);
-        build_row_order(b, L.all, all, tok_adapter.data(), rq.rank, N, rq.bm_all, rq.B, rq.max_row_tiles, L.rpad);
-        build_row_order(b, L.train, train, tok_adapter.data(), rq.rank, N, rq.bm_train, rq.A, rq.max_row_tiles, L.rpad);
+        build_row_order(b, L.all, all, tok_adapter.data(), rq.rank, N, rq.bm_all, rq.B, rq.max_row_tiles, L.rpad, rq.wide_min_rows_all);
+        build_row_order(b, L.train, train, tok_adapter.data(), rq.rank, N, rq.bm_train, rq.A, rq.max_row_tiles, L.rpad, rq.wide_min_rows_train);
     }
 
     // gradient items: one per trained adapter, rows contiguous in the training row order
@@ -238,6 +252,7 @@ size_t plan_ints_upper_bound(int max_tokens, int max_segments, int max_adapters,
     for (int k = 0; k < 2; ++k) {
         n += 2 * Tp;                     // row_tok, row_adapter
         n += 4 * (Tp / kSkinnyRows + N) + 8;          // skinny items
+        n += 4 * (Tp / 8 + N) + 8;                    // items of the tiled pass (runs of 8 rows at least)
         n += 2 * (Tp / 64 + 8);          // ext_off (smallest tile 64 rows), two tile sizes
         n += 2 * (4 * steps * (Tp / 64 + N) + 4 * kExtBatch + 8);  // ext steps: (tiles + adapter runs) x steps, two tile sizes
     }

@@ -32,6 +32,9 @@ struct PlanRequest {
     int bm_all = 256;    // GEMM row tile of the forward GEMM
     int bm_train = 256;  // GEMM row tile of the dX GEMM
     int max_row_tiles = 1;  // most 16-row tiles a skinny item may hold (what the kernels for this rank width take)
+    // > 0: runs of at least this many rows of an adapter whose rank is a multiple of 8 become items of up to
+    // kWideRows rows for the tiled rank-wide pass; one value for the order of all rows, one for the training rows
+    int wide_min_rows_all = 0, wide_min_rows_train = 0;
 };
 
 // Builds the plan block for a batch that passed validate_batch.

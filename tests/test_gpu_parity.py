@@ -15,9 +15,11 @@ from gpu_util import TOL, DeviceLayer, check_full, make_ctx, maxrel, to_dev, to_
 pytestmark = pytest.mark.gpu
 
 
-def _run_full(w, tol=None, h_save=True, transposed=False, **kw):
+def _run_full(w, tol=None, h_save=True, transposed=False, wide_min_rows=None, **kw):
     t = wl.make_tensors(w)
     ctx = make_ctx(w, **kw)
+    if wide_min_rows is not None:
+        ctx.set_wide_pass(wide_min_rows)
     layer = DeviceLayer(w, t, ctx, transposed=transposed)
     layer.fwd(h_save=h_save)
     layer.bwd(h_save=h_save)
@@ -214,6 +216,28 @@ def test_rows_split_between_large_and_small_tiles(wide_side):
         lens[4], lens[6], lens[7] = 30, 800, 297   # 2300 training rows beside 30 base-only ones
         w = _adhoc("bf16", 7424, 64, [16, 8, 12, 32], lens, ads, [1, 1, 1, 1, 0, 1, 1, 1], scale=0.5)
     _run_full(w)
+
+
+@pytest.mark.parametrize("transposed", [False, True])
+def test_rank_wide_passes_as_row_tiles(transposed):
+    # Runs of at least 8 rows of an adapter whose rank is a multiple of 8 go through the tiled pass (128-row
+    # items, K cut into slices, partial sums added by the second kernel); the other rows stay on the 16-row
+    # items.  Ragged everything: K = 200 and 328 (no multiple of 64), ranks 8..136 and two that are no
+    # multiple of 8, runs of 8, 129, 300 and 7 rows, an adapter shared by a decode token and a training run.
+    lens = [300, 1, 129, 7, 8, 40, 1, 1, 260, 33]
+    ads = [0, 0, 1, 2, 2, 3, 4, -1, 5, 6]
+    trn = [1, 0, 1, 0, 1, 0, 0, 0, 1, 1]
+    w = _adhoc("bf16", 200, 328, [64, 136, 8, 12, 16, 40, 3], lens, ads, trn, scale=0.3)
+    _run_full(w, transposed=transposed, wide_min_rows=8)
+    _run_full(w, transposed=transposed, wide_min_rows=8, h_save=False)
+    # many slices: 40 rows against K = 8192, both directions
+    _run_full(_adhoc("bf16", 8192, 64, [64, 16], [40, 3], [0, 1], [1, 0]), transposed=transposed, wide_min_rows=8)
+    _run_full(_adhoc("bf16", 64, 8192, [64, 16], [40, 3], [0, 1], [1, 0]), transposed=transposed, wide_min_rows=8)
+    # the choice the library makes by itself (ranks from 49 up) against the same batch with the pass off
+    w = _adhoc("bf16", 512, 384, [64, 128, 256, 56], [200, 1, 1, 90, 150, 31, 500], [0, 1, 2, 3, 1, 2, 2],
+               [1, 0, 0, 0, 1, 0, 1])
+    _run_full(w, transposed=transposed)
+    _run_full(w, transposed=transposed, wide_min_rows=0)
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
