@@ -177,6 +177,75 @@ def lora_linear_bwd(x, W, A, B, tok_adapter, tok_is_train, scale, dy, want_dx=Tr
 # ---------------------------------------------------------------------------------------------
 # The step after the backward pass: update of the trained adapter tables and their aggregation.
 # ---------------------------------------------------------------------------------------------
+def _sibling_slices(A, B, d_outs):
+    """Column ranges of the siblings in W / B_i, and for every sibling the adapters' own tables."""
+    P = len(d_outs)
+    cols = np.concatenate([[0], np.cumsum(d_outs)]).astype(int)
+    per = []
+    for j in range(P):
+        Aj, Bj = [], []
+        for a, b in zip(A, B):
+            r = b.shape[0]
+            assert a.shape[1] == P * r and b.shape[1] == cols[-1]
+            Aj.append(np.ascontiguousarray(a[:, j * r:(j + 1) * r]))
+            Bj.append(np.ascontiguousarray(b[:, cols[j]:cols[j + 1]]))
+        per.append((Aj, Bj))
+    return cols, per
+
+
+def lora_siblings_fwd(x, W, A, B, d_outs, tok_adapter, scale):
+    """Sibling projections of the same x stored side by side (W [d_in, D], A_i [d_in, P r_i], B_i [r_i, D]):
+    each sibling is a LoRA projection of its own (paper section 4.2, applied per projection), so the result
+    is the per-projection forward on the sibling's slices, written into its columns.  Returns
+    (y [T, D], h [T, P r_max]); a row of h holds sibling j's x A_j in columns j r_a .. (j + 1) r_a, r_a the
+    rank of the token's adapter, and zeros elsewhere."""
+    x, W = _f64(x), _f64(W)
+    A = [_f64(a) for a in A]
+    B = [_f64(b) for b in B]
+    cols, per = _sibling_slices(A, B, d_outs)
+    P, T = len(d_outs), x.shape[0]
+    rmax = max([b.shape[0] for b in B], default=1)
+    y = np.empty((T, cols[-1]))
+    h = np.zeros((T, P * rmax))
+    tok_adapter = np.asarray(tok_adapter)
+    for j, (Aj, Bj) in enumerate(per):
+        yj, hj = lora_linear_fwd(x, np.ascontiguousarray(W[:, cols[j]:cols[j + 1]]), Aj, Bj, tok_adapter, scale)
+        y[:, cols[j]:cols[j + 1]] = yj
+        for t in range(T):
+            a = tok_adapter[t]
+            if a >= 0:
+                r = B[a].shape[0]
+                h[t, j * r:(j + 1) * r] = hj[t, :r]
+    return y, h
+
+
+def lora_siblings_bwd(x, W, A, B, d_outs, tok_adapter, tok_is_train, scale, dy):
+    """Backward of lora_siblings_fwd: every sibling's per-projection backward on its slices; dx is the sum over
+    the siblings (x feeds all of them), dA_i and dB_i are assembled in the layout of A_i and B_i."""
+    x, W, dy = _f64(x), _f64(W), _f64(dy)
+    A = [_f64(a) for a in A]
+    B = [_f64(b) for b in B]
+    cols, per = _sibling_slices(A, B, d_outs)
+    dx = None
+    dA = [None] * len(A)
+    dB = [None] * len(B)
+    for j, (Aj, Bj) in enumerate(per):
+        sl = slice(cols[j], cols[j + 1])
+        dxj, dAj, dBj = lora_linear_bwd(x, np.ascontiguousarray(W[:, sl]), Aj, Bj, tok_adapter, tok_is_train, scale,
+                                        np.ascontiguousarray(dy[:, sl]))
+        dx = dxj if dx is None else dx + dxj
+        for i in range(len(A)):
+            if dAj[i] is None:
+                continue
+            r = B[i].shape[0]
+            if dA[i] is None:
+                dA[i] = np.zeros_like(A[i])
+                dB[i] = np.zeros_like(B[i])
+            dA[i][:, j * r:(j + 1) * r] = dAj[i]
+            dB[i][:, sl] = dBj[i]
+    return dx, dA, dB
+
+
 def adapter_fedavg(copies) -> np.ndarray:
     """Aggregation of the adapter copies of the |K| participating replicas (paper section 4.2, the
     equation for the aggregated B and A): the element-wise mean, copies added in index order."""

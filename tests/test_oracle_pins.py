@@ -321,3 +321,109 @@ def test_adamw_matches_library_optimizer():
         opt.step()
         p, m, v = oracle.adamw_step(p, g, m, v, lr, b1, b2, eps, wd, step)
         assert np.max(np.abs(p - tp.detach().numpy())) < 1e-13, step
+
+
+# ---------------------------------------------------------------------------------------------
+# sibling projections stored side by side
+# ---------------------------------------------------------------------------------------------
+def _sibling_case(seed, d_in=12, d_outs=(8, 16, 8), ranks=(8, 16, 8), T=23):
+    rng = np.random.default_rng(seed)
+    P, D = len(d_outs), sum(d_outs)
+    x = rng.standard_normal((T, d_in))
+    W = rng.standard_normal((d_in, D)) * 0.3
+    A = [rng.standard_normal((d_in, P * r)) * 0.3 for r in ranks]
+    B = [rng.standard_normal((r, D)) * 0.3 for r in ranks]
+    ta = rng.integers(-1, len(ranks), size=T).astype(np.int32)
+    tt = ((rng.random(T) < 0.5) & (ta >= 0)).astype(np.uint8)
+    dy = rng.standard_normal((T, D))
+    return x, W, A, B, list(d_outs), ta, tt, dy
+
+
+def _block_diagonal(B, d_outs):
+    """[r, D] side-by-side expand tables -> [P r, D] with sibling j's rows nonzero only in its columns."""
+    cols = np.concatenate([[0], np.cumsum(d_outs)])
+    out = []
+    for b in B:
+        r = b.shape[0]
+        bd = np.zeros((len(d_outs) * r, b.shape[1]))
+        for j in range(len(d_outs)):
+            bd[j * r:(j + 1) * r, cols[j]:cols[j + 1]] = b[:, cols[j]:cols[j + 1]]
+        out.append(bd)
+    return out
+
+
+def test_siblings_hand_example():
+    # two siblings of width 1, rank 1, one token on adapter 0: y = x W + s (x a_j) b_j per column
+    x = np.array([[1.0, 2.0]])
+    W = np.array([[1.0, 0.0], [0.0, 1.0]])
+    A = [np.array([[1.0, 0.0], [0.0, 1.0]])]       # a_0 = e_0, a_1 = e_1  ->  h = (1, 2)
+    B = [np.array([[10.0, 100.0]])]                # b_0 = 10 (column 0), b_1 = 100 (column 1)
+    y, h = oracle.lora_siblings_fwd(x, W, A, B, [1, 1], np.array([0], np.int32), 0.5)
+    assert np.array_equal(h, [[1.0, 2.0]])
+    assert np.array_equal(y, [[1.0 + 0.5 * 1.0 * 10.0, 2.0 + 0.5 * 2.0 * 100.0]])
+    dy = np.array([[1.0, -1.0]])
+    dx, dA, dB = oracle.lora_siblings_bwd(x, W, A, B, [1, 1], np.array([0], np.int32), np.array([1], np.uint8), 0.5, dy)
+    # dh_j = s dy_j b_j = (5, -50); dx = dy W^T + dh_0 a_0 + dh_1 a_1 = (1 + 5, -1 - 50)
+    assert np.array_equal(dx, [[6.0, -51.0]])
+    assert np.array_equal(dB[0], [[0.5 * 1.0 * 1.0, 0.5 * 2.0 * -1.0]])          # s h_j dy_j
+    assert np.array_equal(dA[0], [[1.0 * 5.0, 1.0 * -50.0], [2.0 * 5.0, 2.0 * -50.0]])  # x^T dh
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_siblings_equal_one_projection_with_block_diagonal_expand(seed):
+    # the side-by-side form is one projection whose adapter has rank P r, shrink table [A_0 | A_1 | ..] and a
+    # block-diagonal expand table: the single-projection oracle on those must give the same numbers
+    x, W, A, B, d_outs, ta, tt, dy = _sibling_case(seed)
+    Bd = _block_diagonal(B, d_outs)
+    y, h = oracle.lora_siblings_fwd(x, W, A, B, d_outs, ta, 0.7)
+    y1, h1 = oracle.lora_linear_fwd(x, W, A, Bd, ta, 0.7)
+    assert np.allclose(y, y1, rtol=0, atol=1e-12)
+    P = len(d_outs)
+    for t in range(len(ta)):
+        if ta[t] >= 0:
+            r = B[ta[t]].shape[0]
+            assert np.allclose(h[t, :P * r], h1[t, :P * r], rtol=0, atol=1e-12) and np.all(h[t, P * r:] == 0)
+        else:
+            assert np.all(h[t] == 0)
+    dx, dA, dB = oracle.lora_siblings_bwd(x, W, A, B, d_outs, ta, tt, 0.7, dy)
+    dx1, dA1, dB1 = oracle.lora_linear_bwd(x, W, A, Bd, ta, tt, 0.7, dy)
+    tr = tt != 0
+    assert np.allclose(dx[tr], dx1[tr], rtol=0, atol=1e-12) and np.all(np.isnan(dx[~tr]))
+    cols = np.concatenate([[0], np.cumsum(d_outs)])
+    for i in range(len(A)):
+        if dA1[i] is None:
+            assert dA[i] is None and dB[i] is None
+            continue
+        assert np.allclose(dA[i], dA1[i], rtol=0, atol=1e-12)
+        r = B[i].shape[0]
+        for j in range(P):  # the diagonal blocks of the block-diagonal table's gradient
+            assert np.allclose(dB[i][:, cols[j]:cols[j + 1]], dB1[i][j * r:(j + 1) * r, cols[j]:cols[j + 1]],
+                               rtol=0, atol=1e-12)
+
+
+def test_siblings_finite_differences():
+    x, W, A, B, d_outs, ta, tt, dy = _sibling_case(5, d_in=5, d_outs=(3, 2), ranks=(2, 1), T=6)
+    tt[:] = (ta >= 0)
+    s = 0.9
+    loss = lambda x_, A_, B_: float(np.sum(oracle.lora_siblings_fwd(x_, W, A_, B_, d_outs, ta, s)[0][tt != 0] * dy[tt != 0]))
+    dx, dA, dB = oracle.lora_siblings_bwd(x, W, A, B, d_outs, ta, tt, s, dy)
+    eps = 1e-6
+    for t in np.flatnonzero(tt):
+        for i in range(x.shape[1]):
+            xp, xm = x.copy(), x.copy()
+            xp[t, i] += eps
+            xm[t, i] -= eps
+            assert abs((loss(xp, A, B) - loss(xm, A, B)) / (2 * eps) - dx[t, i]) < 1e-6
+    for a in range(len(A)):
+        if dA[a] is None:
+            continue
+        for idx in np.ndindex(A[a].shape):
+            Ap, Am = [m.copy() for m in A], [m.copy() for m in A]
+            Ap[a][idx] += eps
+            Am[a][idx] -= eps
+            assert abs((loss(x, Ap, B) - loss(x, Am, B)) / (2 * eps) - dA[a][idx]) < 1e-6
+        for idx in np.ndindex(B[a].shape):
+            Bp, Bm = [m.copy() for m in B], [m.copy() for m in B]
+            Bp[a][idx] += eps
+            Bm[a][idx] -= eps
+            assert abs((loss(x, A, Bp) - loss(x, A, Bm)) / (2 * eps) - dB[a][idx]) < 1e-6
