@@ -252,6 +252,55 @@ def _variants(w, torch, steps, warmup):
     return out
 
 
+def _siblings(wl, torch, binding, steps, warmup):
+    """Sibling projections fused into one call (one pass over x for all shrink tables, one GEMM over the
+    concatenated weight, one dX GEMM over all output columns) on the batches of configurations 3 and 5:
+    gate+up 4096->22016 and q,k,v 8192->{8192,1024,1024}.  Same flops as the separate calls."""
+    out = []
+    for cfg, name, d_outs in ((3, "gate+up", (11008, 11008)), (5, "q+k+v", (8192, 1024, 1024))):
+        w = wl.make_config(cfg)
+        d_in = w.projections[0].d_in
+        P, D, T = len(d_outs), sum(d_outs), w.n_tokens
+        g = torch.Generator(device="cuda")
+        g.manual_seed(w.seed * 16 + 9)
+        rn = lambda shape, std: (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * std).to(torch.bfloat16)
+        x, W, dy = rn((T, d_in), w.std_x), rn((d_in, D), w.std_w), rn((T, D), w.std_dy)
+        A = binding.PointerTable([rn((d_in, P * int(r)), d_in ** -0.5) for r in w.ranks])
+        B = binding.PointerTable([rn((int(r), D), w.std_b) for r in w.ranks])
+        dA = binding.PointerTable([torch.empty((d_in, P * int(r)), dtype=torch.float32, device="cuda") for r in w.ranks])
+        dB = binding.PointerTable([torch.empty((int(r), D), dtype=torch.float32, device="cuda") for r in w.ranks])
+        mr = P * int(w.ranks.max())
+        ctx = binding.Context(T, w.n_segments, w.n_adapters, mr, max(d_in, D))
+        y = torch.empty((T, D), dtype=torch.bfloat16, device="cuda")
+        dx = torch.empty((T, d_in), dtype=torch.bfloat16, device="cuda")
+        hs = torch.empty((T, mr), dtype=torch.float32, device="cuda")
+        seg = (w.ranks, w.seg_start, w.seg_adapter, w.seg_is_train, w.scale)
+
+        def step():
+            ctx.collm_lora_siblings_fwd(d_outs, x, W, A, B, *seg, y, hs)
+            ctx.collm_lora_siblings_bwd(d_outs, x, W, A, B, *seg, dy, hs, dx, dA, dB, False)
+
+        n = max(5, min(steps, 30))
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            step()
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / n
+        flops = 0.0
+        for d_out in d_outs:
+            f_fwd, f_bwd = w.flops(type(w.projections[0])("sib", d_in, d_out))
+            flops += f_fwd + f_bwd
+        out.append({"workload": f"{w.name}/{name}", "d_in": d_in, "d_out": list(d_outs), "tokens": T,
+                    "ms_per_step": sec * 1e3, "tflops": flops / sec / 1e12})
+        ctx.close()
+        del x, W, dy, A, B, dA, dB, y, dx, hs
+        torch.cuda.empty_cache()
+    return out
+
+
 def _cpu_baseline(w, t):
     """The oracle as it stands, timed on the host cores on the same workload."""
     import numpy as np
@@ -340,6 +389,7 @@ def main():
 
     adapter_update = _adapter_update(torch, binding)
     variants = _variants(w2, torch, args.steps, args.warmup)
+    siblings = _siblings(wl, torch, binding, args.steps, args.warmup) if args.configs != "2" else None
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -362,6 +412,7 @@ def main():
         "all_configs": all_cfg,
         "adapter_update": adapter_update,
         "variants": variants,
+        "sibling_projections": siblings,
         "device": {"name": props.name, "cus": props.multi_processor_count,
                    "peak_bf16_tflops_used": PEAK_BF16_TFLOPS, "peak_hbm_gbs_used": PEAK_HBM_GBS},
         "paper_context": "paper reports system-level gains only (up to 1.5x goodput, 2.2x quality-weighted "

@@ -160,6 +160,46 @@ int collm_lora_linear_bwd(collm_ctx *ctx, const collm_shape *shape, const void *
                           void *stream);
 
 /*
+ * Sibling projections: several projections of the same x (gate and up of an MLP; q, k, v of an
+ * attention block), each with its own base weight and its own adapter pair of the same rank
+ * (paper section 4.2 parameterisation, applied per projection; the batch, the segments and the
+ * adapter of a token are shared).  The caller stores them side by side:
+ *
+ *   W     dev [d_in, D]          columns of sibling 0, then of sibling 1, ...; D = sum of d_out[j]
+ *   A[i]  dev [d_in, P rank[i]]  columns j rank[i] .. (j + 1) rank[i]: the shrink table of sibling j
+ *   B[i]  dev [rank[i], D]       columns as in W: the expand table of sibling j in its columns
+ *   y, dy dev [T, D]             dA[i], dB[i] fp32, shaped as A[i], B[i]
+ *   h_save dev fp32 [T, max_rank]: h of sibling j in columns j rank[a] .. of a row
+ *
+ * so that, for sibling j with columns C_j:  y[t, C_j] = x[t] W[:, C_j] + scale (x[t] A_j[a]) B[a][:, C_j].
+ * One pass over x serves all shrink tables, one GEMM all siblings (the backward GEMM contracts
+ * over all D columns at once, which also sums the siblings' contributions to dx).
+ *
+ * Limits: bf16, COLLM_LAYOUT_IN_OUT, shape->d_out = D, 1..COLLM_MAX_SIBLINGS siblings, every
+ * d_out[j] a multiple of 8 and all but the last multiples of 256; with more than one sibling
+ * every rank a multiple of 8; P * rank <= the context's max_rank (COLLM_E_RANK otherwise),
+ * D <= its max_d.  `activation` must be COLLM_ACT_NONE.  All other arguments, statuses and
+ * guarantees as for collm_lora_linear_fwd / collm_lora_linear_bwd.
+ */
+#define COLLM_MAX_SIBLINGS 4
+typedef enum { COLLM_ACT_NONE = 0 } collm_activation;
+typedef struct {
+    int32_t n_siblings;                 /* P */
+    int32_t d_out[COLLM_MAX_SIBLINGS];  /* output width of each sibling */
+    int32_t activation;                 /* collm_activation */
+} collm_siblings;
+
+int collm_lora_siblings_fwd(collm_ctx *ctx, const collm_shape *shape, const collm_siblings *siblings,
+                            const void *x, const void *W, const void *const *A, const void *const *B,
+                            const int32_t *rank, const int32_t *seg_start, const int32_t *seg_adapter,
+                            const uint8_t *seg_is_train, void *y, float *h_save, void *stream);
+int collm_lora_siblings_bwd(collm_ctx *ctx, const collm_shape *shape, const collm_siblings *siblings,
+                            const void *x, const void *W, const void *const *A, const void *const *B,
+                            const int32_t *rank, const int32_t *seg_start, const int32_t *seg_adapter,
+                            const uint8_t *seg_is_train, const void *dy, const float *h_save, void *dx,
+                            float *const *dA, float *const *dB, int accumulate, void *stream);
+
+/*
  * Integer bookkeeping on the host (no GPU needed): per-token segment index, adapter index
  * and training flag.  All pointers HOST; outputs have n_tokens entries.  Uses only
  * n_tokens, n_segments and n_adapters of `shape`.

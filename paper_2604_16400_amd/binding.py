@@ -37,6 +37,10 @@ class collm_shape(ctypes.Structure):
     ]
 
 
+class collm_siblings(ctypes.Structure):
+    _fields_ = [("n_siblings", ctypes.c_int32), ("d_out", ctypes.c_int32 * 4), ("activation", ctypes.c_int32)]
+
+
 class collm_adamw(ctypes.Structure):
     _fields_ = [
         ("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
@@ -83,6 +87,12 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.collm_lora_linear_bwd.argtypes = [vp, sp, vp, vp, _vpp, _vpp, _i32p, _i32p, _i32p, _u8p, vp, vp, vp,
                                           _vpp, _vpp, ctypes.c_int, vp]
     lib.collm_lora_linear_bwd.restype = ctypes.c_int
+    sbp = ctypes.POINTER(collm_siblings)
+    lib.collm_lora_siblings_fwd.argtypes = [vp, sp, sbp, vp, vp, _vpp, _vpp, _i32p, _i32p, _i32p, _u8p, vp, vp, vp]
+    lib.collm_lora_siblings_fwd.restype = ctypes.c_int
+    lib.collm_lora_siblings_bwd.argtypes = [vp, sp, sbp, vp, vp, _vpp, _vpp, _i32p, _i32p, _i32p, _u8p, vp, vp, vp,
+                                            _vpp, _vpp, ctypes.c_int, vp]
+    lib.collm_lora_siblings_bwd.restype = ctypes.c_int
     lib.collm_token_map.argtypes = [sp, _i32p, _i32p, _u8p, _i32p, _i32p, _u8p]
     lib.collm_token_map.restype = ctypes.c_int
     lib.collm_debug_device_token_map.argtypes = [vp, _i32p, _i32p, _u8p]
@@ -263,6 +273,52 @@ class Context:
             ss.ctypes.data_as(_i32p), sa.ctypes.data_as(_i32p), st.ctypes.data_as(_u8p), dy.data_ptr(),
             None if h_save is None else h_save.data_ptr(), None if dx is None else dx.data_ptr(),
             dAt, dBt, 1 if accumulate else 0, self._stream(stream)), "collm_lora_linear_bwd")
+
+
+    @staticmethod
+    def _siblings(d_outs, activation=0):
+        d = [int(v) for v in d_outs]
+        if not 1 <= len(d) <= 4:
+            raise ValueError("1 to 4 sibling projections")
+        sb = collm_siblings()
+        sb.n_siblings = len(d)
+        for j, v in enumerate(d):
+            sb.d_out[j] = v
+        sb.activation = int(activation)
+        return sb
+
+    def collm_lora_siblings_fwd(self, d_outs, x, W, A: List, B: List, rank, seg_start, seg_adapter, seg_is_train,
+                                scale: float, y, h_save=None, stream=None):
+        """Sibling projections of x stored side by side (W [d_in, sum d_outs], A_i [d_in, P rank_i],
+        B_i [rank_i, sum d_outs]): y[:, C_j] <- x W[:, C_j] + scale (x A_i,j) B_i[:, C_j]."""
+        ss, sa, st = _seg_arrays(seg_start, seg_adapter, seg_is_train)
+        rk = np.ascontiguousarray(rank, dtype=np.int32)
+        sh = self._shape(x, W, len(sa), len(rk), scale, LAYOUT_IN_OUT)
+        sb = self._siblings(d_outs)
+        At, Bt = _ptr_table(A, len(rk)), _ptr_table(B, len(rk))
+        _check(self._lib.collm_lora_siblings_fwd(
+            self._h, ctypes.byref(sh), ctypes.byref(sb), x.data_ptr(), W.data_ptr(), At, Bt,
+            rk.ctypes.data_as(_i32p), ss.ctypes.data_as(_i32p), sa.ctypes.data_as(_i32p), st.ctypes.data_as(_u8p),
+            y.data_ptr(), None if h_save is None else h_save.data_ptr(), self._stream(stream)),
+            "collm_lora_siblings_fwd")
+        return y
+
+    def collm_lora_siblings_bwd(self, d_outs, x, W, A: List, B: List, rank, seg_start, seg_adapter, seg_is_train,
+                                scale: float, dy, h_save=None, dx=None, dA: Optional[List] = None,
+                                dB: Optional[List] = None, accumulate: bool = False, stream=None):
+        """Backward of collm_lora_siblings_fwd; dA_i, dB_i (fp32) shaped as A_i, B_i."""
+        ss, sa, st = _seg_arrays(seg_start, seg_adapter, seg_is_train)
+        rk = np.ascontiguousarray(rank, dtype=np.int32)
+        sh = self._shape(x, W, len(sa), len(rk), scale, LAYOUT_IN_OUT)
+        sb = self._siblings(d_outs)
+        At, Bt = _ptr_table(A, len(rk)), _ptr_table(B, len(rk))
+        dAt = _ptr_table(dA, len(rk)) if dA is not None else None
+        dBt = _ptr_table(dB, len(rk)) if dB is not None else None
+        _check(self._lib.collm_lora_siblings_bwd(
+            self._h, ctypes.byref(sh), ctypes.byref(sb), x.data_ptr(), W.data_ptr(), At, Bt,
+            rk.ctypes.data_as(_i32p), ss.ctypes.data_as(_i32p), sa.ctypes.data_as(_i32p), st.ctypes.data_as(_u8p),
+            dy.data_ptr(), None if h_save is None else h_save.data_ptr(), None if dx is None else dx.data_ptr(),
+            dAt, dBt, 1 if accumulate else 0, self._stream(stream)), "collm_lora_siblings_bwd")
 
 
 def _dtype_of(t):

@@ -80,7 +80,8 @@ struct collm_ctx {
 
     int tile_fwd = -1, tile_bwd = -1;  // forced GEMM tile shapes (-1 = choose)
     int wide_min_rows = -1;            // forced threshold of the tiled rank-wide pass (-1 = choose, 0 = never)
-    int key_wide = 0;
+    int key_wide = 0, key_nsib = 0;
+    std::vector<int32_t> sum_rank;     // sibling calls: ranks summed over the siblings
     hipStream_t last_stream = nullptr;
     // the adapter gradients run beside dh and the dX GEMM on a second stream
     hipStream_t side = nullptr;
@@ -271,7 +272,7 @@ int upload(collm_ctx *c, size_t lo, size_t hi, hipStream_t st)
 int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const void *const *B,
                  const int32_t *rank, const int32_t *seg_start, const int32_t *seg_adapter,
                  const uint8_t *seg_is_train, float *const *dA, float *const *dB, bool allow_reuse,
-                 hipStream_t st)
+                 hipStream_t st, const int32_t *rank_ext_all = nullptr, int n_sib = 1)
 {
     const bool f32 = s->dtype == COLLM_F32;
     int n_train = 0;
@@ -295,12 +296,13 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
     // A batch whose segment table, ranks, adapter tables and sizes equal those of the plan the device holds
     // reuses it (every layer and projection of a model sees the same batch): only a call on another stream
     // than the one the plan was uploaded on builds it again, since nothing orders the two streams.
-    const bool reuse = allow_reuse && st == c->last_stream &&
+    const bool reuse = allow_reuse && st == c->last_stream && n_sib == c->key_nsib &&
                        same_key(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, bm_all, bm_train, wide);
     if (!reuse) {
         PlanRequest rq;
         rq.shape = s;
         rq.rank = rank;
+        rq.rank_ext_all = rank_ext_all;
         rq.seg_start = seg_start;
         rq.seg_adapter = seg_adapter;
         rq.seg_is_train = seg_is_train;
@@ -325,6 +327,7 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
         c->key_bm_all = bm_all;
         c->key_bm_train = bm_train;
         c->key_wide = wide;
+        c->key_nsib = n_sib;
         c->key_seg_start.assign(seg_start, seg_start + S + 1);
         c->key_seg_adapter.assign(seg_adapter, seg_adapter + S);
         c->key_seg_train.assign(seg_is_train, seg_is_train + S);
@@ -356,17 +359,36 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
     return COLLM_OK;
 }
 
+// A rank-wide pass restricted to one of several sibling projections that lie side by side in the columns of
+// dy and of the K-major tables: columns col0 .. col0 + K of rows of length ld.
+struct SiblingPass {
+    int n_sib = 0, sib = 0;
+    int64_t ld = 0, col0 = 0;
+    int rpad = 0;  // padded width of the widest single rank
+};
+
 // One skinny pass over a row order.
 int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, const void *in, int K,
                int32_t off_tab, bool t_kmajor, float *f32_out, int64_t f32_ld, int f32_cols,
                int f32_by_token, float f32_mult, void *bf_out, float bf_mult, const char *name,
-               hipStream_t st)
+               hipStream_t st, const SiblingPass *sp = nullptr)
 {
     if (R.n_items == 0 && R.n_wide == 0) return COLLM_OK;
     SkinnyArgs a{};
+    const int64_t esz = s->dtype == COLLM_BF16 ? 2 : 4;
     a.in = in;
     a.ld_in = K;
-    a.in_bytes = (uint32_t)((int64_t)s->n_tokens * K * (s->dtype == COLLM_BF16 ? 2 : 4));
+    a.in_bytes = (uint32_t)((int64_t)s->n_tokens * K * esz);
+    if (sp) {
+        a.in = reinterpret_cast<const uint8_t *>(in) + sp->col0 * esz;
+        a.ld_in = sp->ld;
+        a.in_bytes = (uint32_t)((int64_t)s->n_tokens * sp->ld * esz - sp->col0 * esz);
+        a.n_sib = sp->n_sib;
+        a.sib = sp->sib;
+        a.tab_ld = sp->ld;
+        a.tab_off = sp->col0;
+    }
+    const int rpad = sp ? sp->rpad : c->L.rpad;
     a.K = K;
     a.tab = reinterpret_cast<const uint64_t *>(c->d_plan + off_tab);
     a.items = reinterpret_cast<const SkinnyItem *>(c->d_plan + R.off_items);
@@ -389,13 +411,13 @@ int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, cons
     // workspace).
     int n_split = 1;
     if (s->dtype == COLLM_BF16) {
-        const int kw = skinny_waves(c->L.rpad);
-        const int per_trip = kw * skinny_chunk(c->L.rpad) * skinny_depth(c->L.rpad, R.item_rows / kSkinnyRows);
+        const int kw = skinny_waves(rpad);
+        const int per_trip = kw * skinny_chunk(rpad) * skinny_depth(rpad, R.item_rows / kSkinnyRows);
         const long trips = (K + per_trip - 1) / per_trip;
         const long per_split = (long)c->rows_cap * c->rpad_cap * 4;
         long lim = std::min<long>(kSkinnyMaxSplit, (long)c->part_bytes / per_split);
-        lim = std::min<long>(lim, K / (4L * c->L.rpad));
-        lim = std::min<long>(lim, K / ((long)skinny_chunk(c->L.rpad) * kw));
+        lim = std::min<long>(lim, K / (4L * rpad));
+        lim = std::min<long>(lim, K / ((long)skinny_chunk(rpad) * kw));
         const long waves = (long)R.n_items * kw;
         if (trips > 6 && waves > 0 && waves < 2048)
             n_split = (int)std::max<long>(1, std::min<long>({lim, (2048 + waves - 1) / waves, (trips + 2) / 3}));
@@ -413,8 +435,8 @@ int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, cons
         // exist, as long as a slice keeps 512 K values and the partial sums fit the workspace; the small
         // kernel that adds the slices also does this pass's stores.
         GemmArgs g{};
-        g.a = in;
-        g.lda = K;
+        g.a = a.in;
+        g.lda = a.ld_in;
         g.K = K;
         g.a_bytes = a.in_bytes;
         g.row_tok = a.row_tok;
@@ -423,20 +445,52 @@ int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, cons
         g.part = a.part;
         g.part_rows = a.part_rows;
         g.part_ld = a.part_ld;
-        const long blocks = (long)R.n_wide * ((c->L.rpad + 127) / 128);
+        g.part_n_sib = a.n_sib;
+        g.tab_ld = a.tab_ld;
+        g.tab_off = a.tab_off;
+        const long blocks = (long)R.n_wide * ((rpad + 127) / 128);
         const long per_split = (long)c->rows_cap * c->rpad_cap * 4;
         long ns = std::min<long>({(512 + blocks - 1) / blocks, std::max(1, K / 512), (long)c->part_bytes / per_split,
                                   (long)kSkinnyMaxSplit});
         ns = std::max<long>(ns, 1);
         g.k_per_split = round_up((int)((K + ns - 1) / ns), 64);
         const int n_wsplit = (K + g.k_per_split - 1) / g.k_per_split;
-        HIP_TRY(launch_wide(g, R.n_wide, c->L.rpad, n_wsplit, t_kmajor, st));
+        HIP_TRY(launch_wide(g, R.n_wide, rpad, n_wsplit, t_kmajor, st));
         SkinnyArgs w = a;
         w.items = g.items;
         HIP_TRY(launch_skinny_finish(w, R.n_wide, kWideRows, n_wsplit, st));
     }
     if (R.n_items > 0)
-        HIP_TRY(launch_skinny(a, R.n_items, c->L.rpad, R.item_rows / kSkinnyRows, n_split, t_kmajor, st));
+        HIP_TRY(launch_skinny(a, R.n_items, rpad, R.item_rows / kSkinnyRows, n_split, t_kmajor, st));
+    return COLLM_OK;
+}
+
+
+// Sibling projections (several projections of the same x side by side in the columns of W, y and dy).  Checks
+// the description and fills c->sum_rank with the ranks summed over the siblings, which is what the rank-wide
+// passes over all siblings, the plan and the context's limits see.
+int prepare_siblings(collm_ctx *c, const collm_shape *s, const collm_siblings *sib, const int32_t *rank)
+{
+    if (!c || !s || !sib) return COLLM_E_NULL;
+    if (s->dtype != COLLM_BF16) return COLLM_E_DTYPE;
+    if (s->layout != COLLM_LAYOUT_IN_OUT) return COLLM_E_SHAPE;
+    if (sib->activation != COLLM_ACT_NONE) return COLLM_E_SHAPE;
+    const int P = sib->n_siblings;
+    if (P < 1 || P > COLLM_MAX_SIBLINGS) return COLLM_E_SHAPE;
+    int64_t sum = 0;
+    for (int j = 0; j < P; ++j) {
+        if (sib->d_out[j] <= 0 || sib->d_out[j] % 8) return COLLM_E_SHAPE;
+        if (j + 1 < P && sib->d_out[j] % 256) return COLLM_E_SHAPE;  // a column tile belongs to one sibling
+        sum += sib->d_out[j];
+    }
+    if (sum != s->d_out) return COLLM_E_SHAPE;
+    if (s->n_adapters < 0 || s->n_adapters > c->max_adapters) return COLLM_E_SHAPE;
+    if (s->n_adapters > 0 && !rank) return COLLM_E_NULL;
+    c->sum_rank.resize((size_t)std::max(s->n_adapters, 1));
+    for (int a = 0; a < s->n_adapters; ++a) {
+        if (rank[a] < 1 || rank[a] > c->max_rank || (P > 1 && rank[a] % 8)) return COLLM_E_RANK;
+        c->sum_rank[a] = rank[a] * P;
+    }
     return COLLM_OK;
 }
 
@@ -606,12 +660,17 @@ int collm_profile_read(collm_ctx *c, const char **names, float *ms, int cap)
     return n;
 }
 
-int collm_lora_linear_fwd(collm_ctx *c, const collm_shape *s, const void *x, const void *W,
-                          const void *const *A, const void *const *B, const int32_t *rank,
-                          const int32_t *seg_start, const int32_t *seg_adapter,
-                          const uint8_t *seg_is_train, void *y, float *h_save, void *stream)
+static int fwd_impl(collm_ctx *c, const collm_shape *s, const collm_siblings *sib, const void *x, const void *W,
+                    const void *const *A, const void *const *B, const int32_t *rank1,
+                    const int32_t *seg_start, const int32_t *seg_adapter,
+                    const uint8_t *seg_is_train, void *y, float *h_save, void *stream)
 {
-    int rc = check_common(c, s, x, W, A, B, rank, seg_start, seg_adapter, seg_is_train);
+    // with siblings, `rank` is the sum over the siblings and rank1 the adapter's own
+    const int P = sib ? sib->n_siblings : 1;
+    int rc = sib ? prepare_siblings(c, s, sib, rank1) : COLLM_OK;
+    if (rc != COLLM_OK) return rc;
+    const int32_t *rank = P > 1 ? c->sum_rank.data() : rank1;
+    rc = check_common(c, s, x, W, A, B, rank, seg_start, seg_adapter, seg_is_train);
     if (rc != COLLM_OK) return rc;
     if (s->n_tokens > 0 && !y) return COLLM_E_NULL;
     if (!aligned16(y) || !aligned16(h_save)) return COLLM_E_ALIGN;
@@ -619,7 +678,8 @@ int collm_lora_linear_fwd(collm_ctx *c, const collm_shape *s, const void *x, con
     hipStream_t st = (hipStream_t)stream;
     HIP_TRY(hipSetDevice(c->device));
     c->n_prof = 0;
-    rc = prepare_plan(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, nullptr, nullptr, true, st);
+    rc = prepare_plan(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, nullptr, nullptr, true, st,
+                      P > 1 ? rank1 : nullptr, P);
     if (rc != COLLM_OK) return rc;
     const PlanLayout &L = c->L;
     const bool f32 = s->dtype == COLLM_F32;
@@ -652,6 +712,8 @@ int collm_lora_linear_fwd(collm_ctx *c, const collm_shape *s, const void *x, con
     g.hs_bytes = (uint32_t)((size_t)c->rows_cap * c->rpad_cap * 4);
     g.ext_ld = tr ? 0 : s->d_out;
     g.zeros = c->d_zeros;
+    g.n_sib = P;
+    for (int j = 0, col = 0; j + 1 < P; ++j) g.sib_col[j] = (col += sib->d_out[j]);
     {
         Prof prof(c, st, "gemm_fwd");
         if (f32) {
@@ -663,13 +725,34 @@ int collm_lora_linear_fwd(collm_ctx *c, const collm_shape *s, const void *x, con
     return COLLM_OK;
 }
 
-int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, const void *W,
+int collm_lora_linear_fwd(collm_ctx *c, const collm_shape *s, const void *x, const void *W,
                           const void *const *A, const void *const *B, const int32_t *rank,
                           const int32_t *seg_start, const int32_t *seg_adapter,
-                          const uint8_t *seg_is_train, const void *dy, const float *h_save, void *dx,
-                          float *const *dA, float *const *dB, int accumulate, void *stream)
+                          const uint8_t *seg_is_train, void *y, float *h_save, void *stream)
 {
-    int rc = check_common(c, s, x, W, A, B, rank, seg_start, seg_adapter, seg_is_train);
+    return fwd_impl(c, s, nullptr, x, W, A, B, rank, seg_start, seg_adapter, seg_is_train, y, h_save, stream);
+}
+
+int collm_lora_siblings_fwd(collm_ctx *c, const collm_shape *s, const collm_siblings *sib, const void *x,
+                            const void *W, const void *const *A, const void *const *B, const int32_t *rank,
+                            const int32_t *seg_start, const int32_t *seg_adapter, const uint8_t *seg_is_train,
+                            void *y, float *h_save, void *stream)
+{
+    if (!sib) return COLLM_E_NULL;
+    return fwd_impl(c, s, sib, x, W, A, B, rank, seg_start, seg_adapter, seg_is_train, y, h_save, stream);
+}
+
+static int bwd_impl(collm_ctx *c, const collm_shape *s, const collm_siblings *sib, const void *x, const void *W,
+                    const void *const *A, const void *const *B, const int32_t *rank1,
+                    const int32_t *seg_start, const int32_t *seg_adapter,
+                    const uint8_t *seg_is_train, const void *dy, const float *h_save, void *dx,
+                    float *const *dA, float *const *dB, int accumulate, void *stream)
+{
+    const int P = sib ? sib->n_siblings : 1;
+    int rc = sib ? prepare_siblings(c, s, sib, rank1) : COLLM_OK;
+    if (rc != COLLM_OK) return rc;
+    const int32_t *rank = P > 1 ? c->sum_rank.data() : rank1;
+    rc = check_common(c, s, x, W, A, B, rank, seg_start, seg_adapter, seg_is_train);
     if (rc != COLLM_OK) return rc;
     if ((dA == nullptr) != (dB == nullptr)) return COLLM_E_NULL;
     int n_train = 0;
@@ -688,8 +771,16 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
     hipStream_t st = (hipStream_t)stream;
     HIP_TRY(hipSetDevice(c->device));
     c->n_prof = 0;
-    rc = prepare_plan(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, dA, dB, true, st);
+    rc = prepare_plan(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, dA, dB, true, st,
+                      P > 1 ? rank1 : nullptr, P);
     if (rc != COLLM_OK) return rc;
+    // siblings: widest single rank, padded, for the passes that take one sibling at a time
+    int rpad1 = c->L.rpad;
+    if (P > 1) {
+        int r1 = 1;
+        for (int a = 0; a < s->n_adapters; ++a) r1 = std::max(r1, rank1[a]);
+        rpad1 = round_up(r1, kKStep);
+    }
     const PlanLayout &L = c->L;
     const bool f32 = s->dtype == COLLM_F32;
     const bool tr = s->layout == COLLM_LAYOUT_OUT_IN;
@@ -744,15 +835,46 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
         ga.out_transposed = tr ? 1 : 0;
         {
             Prof prof(c, gs, "grad_dB");
-            if (f32) HIP_TRY(launch_grad_f32(ga, L.n_grad, gs));
-            else HIP_TRY(launch_grad(ga, L.n_grad, L.rpad, gs));
+            if (f32) {
+                HIP_TRY(launch_grad_f32(ga, L.n_grad, gs));
+            } else if (P == 1) {
+                HIP_TRY(launch_grad(ga, L.n_grad, L.rpad, gs));
+            } else {
+                // one launch per sibling: its columns of dy against its columns of s h
+                for (int j = 0, col = 0; j < P; col += sib->d_out[j], ++j) {
+                    GradArgs gj = ga;
+                    gj.big = reinterpret_cast<const uint8_t *>(dy) + (int64_t)col * 2;
+                    gj.big_bytes = ga.big_bytes - (uint32_t)col * 2u;
+                    gj.N = sib->d_out[j];
+                    gj.n_sib = P;
+                    gj.sib = j;
+                    gj.ld_out = s->d_out;
+                    gj.out_off = col;
+                    HIP_TRY(launch_grad(gj, L.n_grad, rpad1, gs));
+                }
+            }
         }
     }
 
     // dh = s dy B_a^T: fp32 for dA, element type for the dX GEMM's extra K-steps
-    rc = run_skinny(c, s, L.train, dy, s->d_out, L.off_B_ptr, !tr, c->d_dh32, L.rpad, L.rpad, 0, s->scale,
-                    c->d_dhs, s->scale, "dh", st);
-    if (rc != COLLM_OK) return rc;
+    if (P == 1) {
+        rc = run_skinny(c, s, L.train, dy, s->d_out, L.off_B_ptr, !tr, c->d_dh32, L.rpad, L.rpad, 0, s->scale,
+                        c->d_dhs, s->scale, "dh", st);
+        if (rc != COLLM_OK) return rc;
+    } else {
+        // one pass per sibling over its columns of dy and of the tables, each writing its columns of dh
+        for (int j = 0, col = 0; j < P; col += sib->d_out[j], ++j) {
+            SiblingPass sp;
+            sp.n_sib = P;
+            sp.sib = j;
+            sp.ld = s->d_out;
+            sp.col0 = col;
+            sp.rpad = rpad1;
+            rc = run_skinny(c, s, L.train, dy, sib->d_out[j], L.off_B_ptr, true, c->d_dh32, L.rpad, L.rpad, 0,
+                            s->scale, c->d_dhs, s->scale, "dh", st, &sp);
+            if (rc != COLLM_OK) return rc;
+        }
+    }
 
     if (dA) {
         if (overlap) {
@@ -812,6 +934,27 @@ int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, con
     }
     if (overlap) HIP_TRY(hipStreamWaitEvent(st, c->ev_join, 0));
     return COLLM_OK;
+}
+
+int collm_lora_linear_bwd(collm_ctx *c, const collm_shape *s, const void *x, const void *W,
+                          const void *const *A, const void *const *B, const int32_t *rank,
+                          const int32_t *seg_start, const int32_t *seg_adapter,
+                          const uint8_t *seg_is_train, const void *dy, const float *h_save, void *dx,
+                          float *const *dA, float *const *dB, int accumulate, void *stream)
+{
+    return bwd_impl(c, s, nullptr, x, W, A, B, rank, seg_start, seg_adapter, seg_is_train, dy, h_save, dx, dA, dB,
+                    accumulate, stream);
+}
+
+int collm_lora_siblings_bwd(collm_ctx *c, const collm_shape *s, const collm_siblings *sib, const void *x,
+                            const void *W, const void *const *A, const void *const *B, const int32_t *rank,
+                            const int32_t *seg_start, const int32_t *seg_adapter, const uint8_t *seg_is_train,
+                            const void *dy, const float *h_save, void *dx, float *const *dA, float *const *dB,
+                            int accumulate, void *stream)
+{
+    if (!sib) return COLLM_E_NULL;
+    return bwd_impl(c, s, sib, x, W, A, B, rank, seg_start, seg_adapter, seg_is_train, dy, h_save, dx, dA, dB,
+                    accumulate, stream);
 }
 
 int collm_adapter_fedavg(int device, collm_dtype dtype, int32_t n_copies, const void *const *src, void *dst,

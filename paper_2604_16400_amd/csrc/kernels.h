@@ -29,6 +29,10 @@ struct GemmArgs {
     uint32_t hs_bytes;        // size of hs
     int64_t ext_ld;           // row length of a [rank][N] table (forward)
     const void *zeros;        // at least 16 bytes of zeros, 16-byte aligned (source of masked 16-byte loads)
+    // sibling projections side by side in the output columns (forward GEMM): a column tile of sibling j (columns
+    // from sib_col[j - 1] on) takes columns j * rank .. of hs for its extension steps, rank = that of the step
+    int n_sib;                // 0 or 1: a single projection
+    int sib_col[3];
     // rank-wide pass over long runs of one adapter (launch_wide): one row tile per item, second operand =
     // the item's adapter table ([K][rank] or, K-major, [rank][K]), K cut into slices of k_per_split,
     // fp32 sums of slice s for row r of the row order at part[(s * part_rows + r) * part_ld + q]
@@ -37,6 +41,8 @@ struct GemmArgs {
     float *part;
     int part_rows, part_ld;
     int k_per_split;          // multiple of 64
+    int part_n_sib;           // as SkinnyArgs::n_sib (0 or 1: ranks as the items give them)
+    int64_t tab_ld, tab_off;  // as SkinnyArgs
 };
 
 // out[m][q] = sum_k in[tok(m)][k] * tab_a(k, q), one SkinnyItem per blockIdx.x
@@ -60,6 +66,12 @@ struct SkinnyArgs {
     // K split over several blocks (bf16 kernels): sums of the slices, [slice][part_rows][part_ld]
     float *part;
     int part_rows, part_ld;
+    // One of n_sib sibling projections whose low-rank activations lie side by side (K-major tables only): the
+    // items' ranks are n_sib times the adapter's, the pass reads columns tab_off .. tab_off + K of table rows
+    // of length tab_ld and writes result columns sib * rank .. of each row; the last sibling also zero-fills
+    // the row from n_sib * rank on.  n_sib 0 or 1: none of this (tab_ld = K, tab_off = 0).
+    int n_sib, sib;
+    int64_t tab_ld, tab_off;
 };
 
 // out_a(q, n) = sum_t small[t][q] * big[tok(t)][n] over one adapter's training rows
@@ -79,6 +91,11 @@ struct GradArgs {
     const uint64_t *out_tab;  // adapter -> fp32 output
     int out_transposed;       // 0: out[q][n] (row length N); 1: out[n][q] (row length rank)
     int accumulate;
+    // one of n_sib sibling projections (bf16 copy of the small operand, out_transposed = 0 only): the items'
+    // ranks are n_sib times the adapter's, the small operand is columns sib * rank .. of the copy, and the
+    // result goes to out[q][out_off + n] with row length ld_out.  n_sib 0 or 1: none of this.
+    int n_sib, sib;
+    int64_t ld_out, out_off;
 };
 
 hipError_t launch_gemm(const GemmArgs &a, int tile_cfg, bool b_kmajor, hipStream_t st);

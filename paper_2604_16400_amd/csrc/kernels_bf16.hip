@@ -370,18 +370,18 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         tile_n = blockIdx.y;
         m0 = it.row_lo;
         rows_in = it.n_rows;
-        N = it.rank;
+        N = p.part_n_sib > 1 ? it.rank / p.part_n_sib : it.rank;
         // the block's slice of K: both operands start at its first K index, and the second one ends
         // with the slice (its rows beyond it must read as zeros)
         const int k_begin = blockIdx.z * p.k_per_split;
         K = p.K - k_begin < p.k_per_split ? p.K - k_begin : p.k_per_split;
-        ldb = B_KMAJOR ? (uint32_t)p.K : (uint32_t)it.rank;
+        ldb = B_KMAJOR ? (uint32_t)(p.tab_ld ? p.tab_ld : p.K) : (uint32_t)N;
         const uint32_t a_skip = (uint32_t)k_begin * 2u;
-        const uint32_t b_skip = B_KMAJOR ? (uint32_t)k_begin * 2u : (uint32_t)k_begin * ldb * 2u;
+        const uint32_t b_skip = B_KMAJOR ? (uint32_t)(k_begin + p.tab_off) * 2u : (uint32_t)k_begin * ldb * 2u;
         a_base = reinterpret_cast<const uint8_t *>(p.a) + a_skip;
         a_bytes = p.a_bytes - a_skip;
         b_base = reinterpret_cast<const uint8_t *>(p.tab[it.adapter]) + b_skip;
-        b_bytes = B_KMAJOR ? (uint32_t)it.rank * (uint32_t)p.K * 2u - b_skip : (uint32_t)K * ldb * 2u;
+        b_bytes = B_KMAJOR ? (uint32_t)N * ldb * 2u - b_skip : (uint32_t)K * ldb * 2u;
     } else {
         tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
         tile_m += p.tile_m_base;
@@ -391,6 +391,12 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     }
     const int n0 = tile_n * BN;
     const int32_t *__restrict__ row_tok = p.row_tok;
+    int sib = 0;  // which of the sibling projections this column tile belongs to
+    if constexpr (!PARTIAL) {
+#pragma unroll
+        for (int j = 0; j < 3; ++j)
+            if (j + 1 < p.n_sib && n0 >= p.sib_col[j]) sib = j + 1;
+    }
 
     const __amdgpu_buffer_rsrc_t ra = make_rsrc(a_base, a_bytes);
     const __amdgpu_buffer_rsrc_t rb = make_rsrc(b_base, b_bytes);
@@ -761,8 +767,10 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                 const int j = cl >> 1;
                 const uint32_t kr = pick(j, bt.kr[0], bt.kr[1], bt.kr[2], bt.kr[3]);
                 const uint32_t rows = pick(j, bt.rows[0], bt.rows[1], bt.rows[2], bt.rows[3]);
-                const bool in = r >= (int)(rows & 0xffffu) && r < (int)(rows >> 16);
-                const uint32_t off = in ? ((uint32_t)(m0 + r) * (uint32_t)p.hs_ld + (kr & 0xffffu) + (cl & 1) * 8u) * 2u : kOob;
+                // siblings: the columns after a sibling's own are the next sibling's, or were never written
+                const bool in = r >= (int)(rows & 0xffffu) && r < (int)(rows >> 16) &&
+                                (p.n_sib <= 1 || (kr & 0xffffu) + (cl & 1) * 8u < (kr >> 16));
+                const uint32_t off = in ? ((uint32_t)(m0 + r) * (uint32_t)p.hs_ld + (uint32_t)sib * (kr >> 16) + (kr & 0xffffu) + (cl & 1) * 8u) * 2u : kOob;
                 dma16(rh_w, off, lds_wave + (stage ? A_ST1 : 0) + i * (NT / 64) * 1024);
             }
             if constexpr (!B_KMAJOR) {
@@ -925,10 +933,6 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 // or row-indexed workspace) and the scaled copy in the element type.
 __device__ __forceinline__ void skinny_store(const SkinnyArgs &p, const SkinnyItem &it, int m, int q, floatx4 sum)
 {
-    const int rank = it.rank, rp = (rank + 15) & ~15;
-    float v[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] = (q + e < rank) ? sum[e] : 0.f;
     const int row = it.row_lo + m;
     const int tok = p.row_tok[row];
     float *f32_row = nullptr;
@@ -939,6 +943,32 @@ __device__ __forceinline__ void skinny_store(const SkinnyArgs &p, const SkinnyIt
             f32_row = p.f32_out + (int64_t)row * p.f32_ld;
         }
     }
+    uint16_t *bf_row = p.bf_out ? reinterpret_cast<uint16_t *>(p.bf_out) + (int64_t)row * p.bf_ld : nullptr;
+    if (p.n_sib > 1) {
+        // one sibling's columns of the row (ranks are multiples of 8 here); the last sibling clears the rest
+        const int rank = it.rank / p.n_sib, co = p.sib * rank;
+        if (q < rank) {
+            if (f32_row)
+                *reinterpret_cast<floatx4 *>(f32_row + co + q) = sum * p.f32_mult;
+            if (bf_row) {
+                uint2 o;
+                o.x = pack_bf16(sum[0] * p.bf_mult, sum[1] * p.bf_mult);
+                o.y = pack_bf16(sum[2] * p.bf_mult, sum[3] * p.bf_mult);
+                *reinterpret_cast<uint2 *>(bf_row + co + q) = o;
+            }
+        }
+        if (q == 0 && p.sib == p.n_sib - 1) {
+            if (f32_row)
+                for (int z = it.rank; z < p.f32_cols; ++z) f32_row[z] = 0.f;
+            if (bf_row)
+                for (int z = it.rank; z < p.bf_ld; ++z) bf_row[z] = 0;
+        }
+        return;
+    }
+    const int rank = it.rank, rp = (rank + 15) & ~15;
+    float v[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = (q + e < rank) ? sum[e] : 0.f;
     if (f32_row) {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
@@ -947,8 +977,7 @@ __device__ __forceinline__ void skinny_store(const SkinnyArgs &p, const SkinnyIt
         if (q + 4 == rp)
             for (int z = rp; z < p.f32_cols; ++z) f32_row[z] = 0.f;
     }
-    if (p.bf_out) {
-        uint16_t *bf_row = reinterpret_cast<uint16_t *>(p.bf_out) + (int64_t)row * p.bf_ld;
+    if (bf_row) {
         uint2 o;
         o.x = pack_bf16(v[0] * p.bf_mult, v[1] * p.bf_mult);
         o.y = pack_bf16(v[2] * p.bf_mult, v[3] * p.bf_mult);
@@ -981,10 +1010,11 @@ __global__ void __launch_bounds__(SkinnyCfg<RP>::KW * 64) skinny_kernel(SkinnyAr
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const SkinnyItem it = p.items[blockIdx.x];
-    const int K = p.K, rank = it.rank;
+    const int K = p.K, rank = p.n_sib > 1 ? it.rank / p.n_sib : it.rank;
     const int rp = (rank + 15) & ~15;
     const int l16 = lane & 15, kg = lane >> 4;
     const int n_rt = (it.n_rows + 15) >> 4;  // row tiles of this item
+    const uint32_t tld = T_KMAJOR && p.tab_ld ? (uint32_t)p.tab_ld : (uint32_t)K, toff = T_KMAJOR ? (uint32_t)p.tab_off : 0u;
 
     // K range of this wave: the slices of the blocks, cut again into the ranges of their waves
     const int n_split = gridDim.y, split = blockIdx.y;
@@ -994,7 +1024,7 @@ __global__ void __launch_bounds__(SkinnyCfg<RP>::KW * 64) skinny_kernel(SkinnyAr
 
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.in, p.in_bytes);
     const __amdgpu_buffer_rsrc_t rt = make_rsrc(reinterpret_cast<const void *>(p.tab[it.adapter]),
-                                                (uint32_t)rank * (uint32_t)K * 2u);
+                                                T_KMAJOR ? (uint32_t)rank * tld * 2u : (uint32_t)rank * (uint32_t)K * 2u);
     uint32_t xoff[RT];
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
@@ -1030,7 +1060,7 @@ __global__ void __launch_bounds__(SkinnyCfg<RP>::KW * 64) skinny_kernel(SkinnyAr
                 for (int nb = 0; nb < NB; ++nb) {
                     const int q = nb * 16 + l16;
                     treg[buf][s * NB + nb] =
-                        buf16(rt, (q < rank && k < k_hi) ? ((uint32_t)q * (uint32_t)K + (uint32_t)k) * 2u : kOob);
+                        buf16(rt, (q < rank && k < k_hi) ? ((uint32_t)q * tld + toff + (uint32_t)k) * 2u : kOob);
                 }
             }
         }
@@ -1162,7 +1192,7 @@ __global__ void __launch_bounds__(SkinnyCfg<RP>::KW * 64) skinny_kernel(SkinnyAr
 __global__ void __launch_bounds__(256) skinny_finish_kernel(SkinnyArgs p, int n_split)
 {
     const SkinnyItem it = p.items[blockIdx.x];
-    const int rp = (it.rank + 15) & ~15;
+    const int rp = ((p.n_sib > 1 ? it.rank / p.n_sib : it.rank) + 15) & ~15;
     const int nq = rp >> 2;
     const int m_lo = blockIdx.y * 16, m_hi = it.n_rows < m_lo + 16 ? it.n_rows : m_lo + 16;
     for (int idx = threadIdx.x; idx < (m_hi - m_lo) * nq; idx += 256) {
@@ -1216,7 +1246,7 @@ __global__ void __launch_bounds__(GradCfg<RP>::KW * 64) grad_kernel(GradArgs p)
     const int n0 = blockIdx.x * 64;
     const GradItem it = p.items[blockIdx.y];
     const int q0 = blockIdx.z * RP;
-    const int rank = it.rank;
+    const int rank = p.n_sib > 1 ? it.rank / p.n_sib : it.rank;
     const int N = p.N;
     const int l16 = lane & 15, kg = lane >> 4;
 
@@ -1229,7 +1259,10 @@ __global__ void __launch_bounds__(GradCfg<RP>::KW * 64) grad_kernel(GradArgs p)
     const int32_t *__restrict__ row_tok = p.row_tok;
     const float *__restrict__ Small = p.small_;
     const uint16_t *__restrict__ SmallB = reinterpret_cast<const uint16_t *>(p.small_bf);
-    const int rp_rank = (rank + 15) & ~15;  // the bf16 copy holds zeros from the rank up to here
+    // the bf16 copy holds zeros from the rank up to the next multiple of 16; with siblings (ranks are multiples
+    // of 8 then) the next sibling's columns follow at once
+    const int rp_rank = p.n_sib > 1 ? rank : (rank + 15) & ~15;
+    const int s_off = p.n_sib > 1 ? p.sib * rank : 0;
 
     // big: lane copies chunk column c = lane % 8 of rows lane / 8 + 8 i
     const int bc = lane & 7, br = lane >> 3;
@@ -1268,7 +1301,7 @@ __global__ void __launch_bounds__(GradCfg<RP>::KW * 64) grad_kernel(GradArgs p)
                 const int c = lane + i * 64;
                 const int t = t_next + c / PPR, q = q0 + (c % PPR) * 8;
                 uint4 v = make_uint4(0, 0, 0, 0);
-                if (t < t_hi && q < rp_rank) v = ldg16(SmallB + (int64_t)t * p.ld_small_bf + q);
+                if (t < t_hi && q < rp_rank) v = ldg16(SmallB + (int64_t)t * p.ld_small_bf + s_off + q);
                 sbreg[i] = v;
             }
             t_next += C::CHT;
@@ -1377,7 +1410,8 @@ __global__ void __launch_bounds__(GradCfg<RP>::KW * 64) grad_kernel(GradArgs p)
         float sum = 0.f;
 #pragma unroll
         for (int w = 0; w < KW; ++w) sum += red[(w * RP + q) * C::RED_LD + n];
-        float *dst = p.out_transposed ? out + (int64_t)(n0 + n) * rank + q0 + q : out + (int64_t)(q0 + q) * N + n0 + n;
+        float *dst = p.out_transposed ? out + (int64_t)(n0 + n) * rank + q0 + q
+                                      : out + (int64_t)(q0 + q) * (p.ld_out ? p.ld_out : (int64_t)N) + p.out_off + n0 + n;
         *dst = p.accumulate ? (*dst + sum) : sum;
     }
 }

@@ -59,7 +59,8 @@ struct Builder {
 // Rows (token indices, already filtered) sorted by adapter, stable; items; extension tables.
 void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &tokens,
                      const int32_t *tok_adapter, const int32_t *rank, int n_adapters, int bm,
-                     const void *const *ext_tab, int max_row_tiles, int rpad, int wide_min_rows)
+                     const void *const *ext_tab, int max_row_tiles, int rpad, int wide_min_rows,
+                     const int32_t *rank_ext)
 {
     const int n = (int)tokens.size();
     L.n_rows = n;
@@ -136,8 +137,8 @@ void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &
                 while (e < r1 && b.blk[L.off_row_adapter + e] == a) ++e;
                 if (a >= 0) {
                     const uint64_t tab = ext_tab ? (uint64_t)(uintptr_t)ext_tab[a] : 0;
-                    for (int k = 0; k < rank[a]; k += kKStep)
-                        ext.push_back({(uint32_t)k | ((uint32_t)rank[a] << 16), (uint32_t)(r - r0) | ((uint32_t)(e - r0) << 16), tab});
+                    for (int k = 0; k < rank_ext[a]; k += kKStep)
+                        ext.push_back({(uint32_t)k | ((uint32_t)rank_ext[a] << 16), (uint32_t)(r - r0) | ((uint32_t)(e - r0) << 16), tab});
                 }
                 r = e;
             }
@@ -210,8 +211,10 @@ int build_plan(const PlanRequest &rq, std::vector<int32_t> &blk, PlanLayout &L)
     {
         std::vector<int32_t> tok_adapter(blk.begin() + L.off_tok_adapter,
                                          blk.begin() + L.off_tok_adapter + T);
-        build_row_order(b, L.all, all, tok_adapter.data(), rq.rank, N, rq.bm_all, rq.B, rq.max_row_tiles, L.rpad, rq.wide_min_rows_all);
-        build_row_order(b, L.train, train, tok_adapter.data(), rq.rank, N, rq.bm_train, rq.A, rq.max_row_tiles, L.rpad, rq.wide_min_rows_train);
+        build_row_order(b, L.all, all, tok_adapter.data(), rq.rank, N, rq.bm_all, rq.B, rq.max_row_tiles, L.rpad, rq.wide_min_rows_all,
+                        rq.rank_ext_all ? rq.rank_ext_all : rq.rank);
+        build_row_order(b, L.train, train, tok_adapter.data(), rq.rank, N, rq.bm_train, rq.A, rq.max_row_tiles, L.rpad, rq.wide_min_rows_train,
+                        rq.rank);
     }
 
     // gradient items: one per trained adapter, rows contiguous in the training row order

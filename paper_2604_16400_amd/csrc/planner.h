@@ -22,6 +22,8 @@ void token_map(const collm_shape *s, const int32_t *seg_start, const int32_t *se
 struct PlanRequest {
     const collm_shape *shape = nullptr;
     const int32_t *rank = nullptr;
+    const int32_t *rank_ext_all = nullptr;  // ranks for the extension steps over all rows, if other than `rank`
+                                            // (sibling projections: `rank` holds the sum over the siblings)
     const int32_t *seg_start = nullptr;
     const int32_t *seg_adapter = nullptr;
     const uint8_t *seg_is_train = nullptr;

@@ -1,0 +1,171 @@
+"""GPU parity of the sibling-projection calls (several projections of the same x stored side by side)
+against the fp64 oracle, element by element.  Tolerance as for the single projection: 1e-2 of the
+largest reference entry per output tensor (bf16 inputs, fp32 accumulation)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2604_16400_amd import binding
+from paper_2604_16400_amd import workloads as wl
+
+from gpu_util import TOL, maxrel, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+class SiblingCase:
+    def __init__(self, d_in, d_outs, ranks, lens, adapters, train, scale=2.0, seed=11):
+        rng = np.random.default_rng(seed)
+        self.d_in, self.d_outs, self.scale = d_in, list(d_outs), scale
+        self.P, self.D = len(d_outs), int(sum(d_outs))
+        self.ranks = np.asarray(ranks, dtype=np.int32)
+        self.seg_start = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        self.seg_adapter = np.asarray(adapters, dtype=np.int32)
+        self.seg_is_train = np.asarray(train, dtype=np.uint8)
+        T = int(self.seg_start[-1])
+        self.T = T
+        r32 = lambda *s: rng.standard_normal(s).astype(np.float32)
+        self.x = wl.bf16_round(r32(T, d_in))
+        self.W = wl.bf16_round(r32(d_in, self.D) * 0.02)
+        self.A = [wl.bf16_round(r32(d_in, self.P * int(r)) * d_in ** -0.5) for r in ranks]
+        self.B = [wl.bf16_round(r32(int(r), self.D) * 0.05) for r in ranks]
+        self.dy = wl.bf16_round(r32(T, self.D))
+        _, self.tok_adapter, self.tok_train = oracle.token_map(self.seg_start, self.seg_adapter, self.seg_is_train)
+
+
+def _run(case: SiblingCase, h_save=True, accumulate=False):
+    import torch
+
+    P, T, D = case.P, case.T, case.D
+    max_rank = P * int(case.ranks.max())
+    ctx = binding.Context(max(T, 1), len(case.seg_adapter), len(case.ranks), max_rank, max(case.d_in, D))
+    nan = float("nan")
+    x, W, dy = to_dev(case.x, "bf16"), to_dev(case.W, "bf16"), to_dev(np.where(case.tok_train[:, None] != 0, case.dy, np.nan).astype(np.float32), "bf16")
+    A, B = [to_dev(a, "bf16") for a in case.A], [to_dev(b, "bf16") for b in case.B]
+    y = torch.full((T, D), nan, dtype=torch.bfloat16, device="cuda")
+    dx = torch.full((T, case.d_in), nan, dtype=torch.bfloat16, device="cuda")
+    hs = torch.full((T, max_rank), nan, dtype=torch.float32, device="cuda")
+    base = 1.5 if accumulate else nan
+    dA = [torch.full(a.shape, base, dtype=torch.float32, device="cuda") for a in case.A]
+    dB = [torch.full(b.shape, base, dtype=torch.float32, device="cuda") for b in case.B]
+    seg = (case.ranks, case.seg_start, case.seg_adapter, case.seg_is_train, case.scale)
+    ctx.collm_lora_siblings_fwd(case.d_outs, x, W, A, B, *seg, y, hs if h_save else None)
+    ctx.collm_lora_siblings_bwd(case.d_outs, x, W, A, B, *seg, dy, hs if h_save else None, dx, dA, dB, accumulate)
+    torch.cuda.synchronize()
+
+    ta, tt = case.tok_adapter, case.tok_train
+    y_ref, h_ref = oracle.lora_siblings_fwd(case.x, case.W, case.A, case.B, case.d_outs, ta, case.scale)
+    dx_ref, dA_ref, dB_ref = oracle.lora_siblings_bwd(case.x, case.W, case.A, case.B, case.d_outs, ta, tt, case.scale,
+                                                      case.dy)
+    errs = {}
+    yh = to_host(y)
+    assert np.all(np.isfinite(yh))
+    errs["y"] = maxrel(yh, y_ref)
+    tr = tt != 0
+    dxh = to_host(dx)
+    assert np.all(np.isnan(dxh[~tr]))
+    if tr.any():
+        assert np.all(np.isfinite(dxh[tr]))
+        errs["dx"] = maxrel(dxh[tr], dx_ref[tr])
+    if h_save:
+        hh = to_host(hs)
+        assert np.all(np.isnan(hh[~tr]))
+        if tr.any():
+            ref = np.zeros((int(tr.sum()), max_rank))
+            ref[:, : h_ref.shape[1]] = h_ref[tr]
+            errs["h"] = maxrel(hh[tr], ref)
+            for tok in np.flatnonzero(tr):  # zero beyond the P ranks of the token's adapter
+                assert np.all(hh[tok, P * case.ranks[ta[tok]]:] == 0.0)
+    for a in range(len(case.ranks)):
+        gA, gB = to_host(dA[a]), to_host(dB[a])
+        if dA_ref[a] is None:
+            if accumulate:
+                assert np.all(gA == 1.5) and np.all(gB == 1.5)
+            else:
+                assert np.all(np.isnan(gA)) and np.all(np.isnan(gB))
+        else:
+            off = 1.5 if accumulate else 0.0
+            errs[f"dA{a}"] = maxrel(gA - off, dA_ref[a])
+            errs[f"dB{a}"] = maxrel(gB - off, dB_ref[a])
+    ts, ta_d, tt_d = ctx.device_token_map(T)
+    rs, ra, rt = oracle.token_map(case.seg_start, case.seg_adapter, case.seg_is_train)
+    assert np.array_equal(ts, rs) and np.array_equal(ta_d, ra) and np.array_equal(tt_d, rt)
+    ctx.close()
+    bad = {k: v for k, v in errs.items() if not v <= TOL["bf16"]}
+    assert not bad, f"beyond tolerance: {bad} (all: {errs})"
+    return errs
+
+
+LENS = [5, 0, 37, 1, 130, 0, 70, 2, 64, 301]
+ADS = [0, 1, -1, 2, 2, 3, 3, -1, 1, 2]
+TRN = [0, 0, 0, 0, 1, 0, 1, 0, 0, 1]
+
+
+def test_two_siblings_ragged():
+    # gate/up-like pair; the second sibling's width is no multiple of a tile; ranks 8..64 (24 and 40 leave the
+    # last 16-wide step of a sibling half empty); decode, base-only, empty and training segments
+    c = SiblingCase(320, (256, 200), [8, 16, 24, 40], LENS, ADS, TRN, scale=0.3)
+    _run(c)
+    _run(c, h_save=False)
+    _run(c, accumulate=True)
+
+
+def test_three_siblings_qkv_like():
+    c = SiblingCase(512, (512, 256, 128), [16, 8, 32], [40, 1, 1, 1, 90, 33, 1, 260], [0, 1, 2, 0, 1, 2, 1, 0],
+                    [0, 0, 0, 0, 1, 0, 0, 1])
+    _run(c)
+    _run(c, h_save=False)
+
+
+def test_two_siblings_wide_ranks_and_large_tiles():
+    # rank 64 per sibling (128 side by side: the tiled rank-wide passes, per sibling on the dh side),
+    # enough rows and columns for 256x256 tiles, rows of several adapters inside one row tile
+    c = SiblingCase(1024, (1536, 1280), [64, 32, 64], [300, 1, 1, 200, 150, 9, 260], [0, 1, 2, 1, 2, -1, 0],
+                    [1, 0, 0, 1, 0, 0, 1])
+    _run(c)
+    _run(c, h_save=False)
+
+
+def test_one_sibling_equals_the_single_projection_call():
+    import torch
+
+    c = SiblingCase(256, (192,), [12, 16], [30, 50, 7], [0, 1, 0], [1, 0, 1], scale=0.5)
+    _run(c)  # ranks need not be multiples of 8 with a single sibling
+    ctx = binding.Context(c.T, 3, 2, 16, 256)
+    x, W = to_dev(c.x, "bf16"), to_dev(c.W, "bf16")
+    A, B = [to_dev(a, "bf16") for a in c.A], [to_dev(b, "bf16") for b in c.B]
+    seg = (c.ranks, c.seg_start, c.seg_adapter, c.seg_is_train, c.scale)
+    y1 = torch.empty((c.T, 192), dtype=torch.bfloat16, device="cuda")
+    y2 = torch.empty_like(y1)
+    ctx.collm_lora_siblings_fwd((192,), x, W, A, B, *seg, y1)
+    ctx.collm_lora_linear_fwd(x, W, A, B, *seg, y2)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2)
+    ctx.close()
+
+
+def test_sibling_error_statuses():
+    import torch
+
+    c = SiblingCase(64, (256, 64), [8, 16], [10, 20], [0, 1], [0, 1])
+    ctx = binding.Context(c.T, 2, 2, 32, 320)
+    x, W = to_dev(c.x, "bf16"), to_dev(c.W, "bf16")
+    A, B = [to_dev(a, "bf16") for a in c.A], [to_dev(b, "bf16") for b in c.B]
+    y = torch.full((c.T, c.D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    seg = [c.ranks, c.seg_start, c.seg_adapter, c.seg_is_train, c.scale]
+
+    def expect(status, fn):
+        with pytest.raises(binding.CollmError) as e:
+            fn()
+        assert e.value.status == status, e.value
+
+    f = ctx.collm_lora_siblings_fwd
+    expect(-2, lambda: f((256, 32), x, W, A, B, *seg, y))            # widths do not add up to W's columns
+    expect(-2, lambda: f((64, 256), x, W, A, B, *seg, y))            # a sibling but the last is no multiple of 256
+    expect(-5, lambda: f((256, 64), x, W, A, B, [8, 12], *seg[1:], y))   # rank no multiple of 8
+    expect(-5, lambda: f((256, 64), x, W, A, B, [8, 24], *seg[1:], y))   # 2 x 24 beyond the context's max_rank
+    xf = torch.zeros((c.T, 64), dtype=torch.float32, device="cuda")
+    expect(-6, lambda: f((256, 64), xf, W, A, B, *seg, y))           # fp32 is not served
+    torch.cuda.synchronize()
+    assert torch.isnan(y).all()
+    ctx.close()
