@@ -246,6 +246,26 @@ def lora_siblings_bwd(x, W, A, B, d_outs, tok_adapter, tok_is_train, scale, dy):
     return dx, dA, dB
 
 
+def swiglu(pre):
+    """Gated activation of a gate/up pair stored side by side (pre [T, 2 d_ff]: gate columns, then up columns):
+    out[t, j] = silu(g) u with silu(g) = g / (1 + exp(-g)) (Shazeer 2020, the SwiGLU feed-forward variant of the
+    Llama models the paper serves)."""
+    pre = _f64(pre)
+    d = pre.shape[1] // 2
+    g, u = pre[:, :d], pre[:, d:]
+    return g / (1.0 + np.exp(-g)) * u
+
+
+def swiglu_bwd(pre, dout):
+    """Gradient of swiglu with respect to pre: [dL/dg | dL/du] from dout = dL/dout, term by term:
+    d silu / dg = sigma(g) (1 + g (1 - sigma(g)))."""
+    pre, dout = _f64(pre), _f64(dout)
+    d = pre.shape[1] // 2
+    g, u = pre[:, :d], pre[:, d:]
+    sg = 1.0 / (1.0 + np.exp(-g))
+    return np.concatenate([dout * u * sg * (1.0 + g * (1.0 - sg)), dout * g * sg], axis=1)
+
+
 def adapter_fedavg(copies) -> np.ndarray:
     """Aggregation of the adapter copies of the |K| participating replicas (paper section 4.2, the
     equation for the aggregated B and A): the element-wise mean, copies added in index order."""

@@ -427,3 +427,23 @@ def test_siblings_finite_differences():
             Bp[a][idx] += eps
             Bm[a][idx] -= eps
             assert abs((loss(x, A, Bp) - loss(x, A, Bm)) / (2 * eps) - dB[a][idx]) < 1e-6
+
+
+def test_swiglu_closed_forms_and_library():
+    import torch
+
+    # g = 0: silu = 0, slope 1/2; large |g|: silu -> g or -> 0
+    pre = np.array([[0.0, 3.0], [40.0, 2.0], [-40.0, 2.0]])
+    out = oracle.swiglu(pre)
+    assert out[0, 0] == 0.0 and abs(out[1, 0] - 80.0) < 1e-12 and abs(out[2, 0]) < 1e-12
+    d = oracle.swiglu_bwd(pre, np.ones((3, 1)))
+    assert np.allclose(d[0], [1.5, 0.0], atol=1e-15) and np.allclose(d[1], [2.0, 40.0], atol=1e-12)
+    # against the library's silu and its automatic differentiation, fp64
+    rng = np.random.default_rng(2)
+    pre = rng.standard_normal((7, 10)) * 3
+    dout = rng.standard_normal((7, 5))
+    t = torch.tensor(pre, dtype=torch.float64, requires_grad=True)
+    ref = torch.nn.functional.silu(t[:, :5]) * t[:, 5:]
+    ref.backward(torch.tensor(dout, dtype=torch.float64))
+    assert np.allclose(oracle.swiglu(pre), ref.detach().numpy(), rtol=0, atol=1e-14)
+    assert np.allclose(oracle.swiglu_bwd(pre, dout), t.grad.numpy(), rtol=0, atol=1e-13)
