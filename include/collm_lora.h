@@ -178,16 +178,38 @@ int collm_lora_linear_bwd(collm_ctx *ctx, const collm_shape *shape, const void *
  * Limits: bf16, COLLM_LAYOUT_IN_OUT, shape->d_out = D, 1..COLLM_MAX_SIBLINGS siblings, every
  * d_out[j] a multiple of 8 and all but the last multiples of 256; with more than one sibling
  * every rank a multiple of 8; P * rank <= the context's max_rank (COLLM_E_RANK otherwise),
- * D <= its max_d.  `activation` must be COLLM_ACT_NONE.  All other arguments, statuses and
- * guarantees as for collm_lora_linear_fwd / collm_lora_linear_bwd.
+ * D <= its max_d.  All other arguments, statuses and guarantees as for collm_lora_linear_fwd /
+ * collm_lora_linear_bwd.
+ *
+ * activation = COLLM_ACT_SWIGLU (forward call; two siblings of equal width d_ff, gate then up;
+ * ranks multiples of 16): the forward call combines the pair before its single rounding,
+ *     y[t, j] = silu(g) u,  g = y_gate[t, j], u = y_up[t, j], silu(g) = g / (1 + exp(-g)),
+ * and y is dev [T, d_ff].  If pre_act (dev [T, D]) is not NULL, rows of training tokens receive
+ * both pre-activations (g in columns 0 .. d_ff, u after them, each rounded to bf16): what
+ * collm_swiglu_bwd needs; rows of inference tokens are not touched.  The backward call ignores
+ * `activation` and pre_act: its dy is the gradient with respect to the pre-activations.
  */
 #define COLLM_MAX_SIBLINGS 4
-typedef enum { COLLM_ACT_NONE = 0 } collm_activation;
+typedef enum { COLLM_ACT_NONE = 0, COLLM_ACT_SWIGLU = 1 } collm_activation;
 typedef struct {
     int32_t n_siblings;                 /* P */
     int32_t d_out[COLLM_MAX_SIBLINGS];  /* output width of each sibling */
     int32_t activation;                 /* collm_activation */
+    void *pre_act;                      /* COLLM_ACT_SWIGLU: dev [T, D] or NULL (see above) */
 } collm_siblings;
+
+/*
+ * Backward of y = silu(g) u for the rows of training tokens (bf16): from dout = dL/dy, dev
+ * [T, d_ff], and the pre-activations the forward call kept (pre_act, dev [T, 2 d_ff]),
+ *     dy[t, j]        = dout[t, j] u sigma(g) (1 + g (1 - sigma(g)))      (dL/dg)
+ *     dy[t, d_ff + j] = dout[t, j] g sigma(g)                              (dL/du)
+ * in fp32, rounded once.  dy is dev [T, 2 d_ff]: the dy of collm_lora_siblings_bwd.  Rows of
+ * inference tokens are neither read nor written.  seg_start, seg_is_train: HOST, as in the
+ * other calls (checked the same way); d_ff a multiple of 8; pointers 16-byte aligned.
+ */
+int collm_swiglu_bwd(int device, int32_t n_tokens, int32_t d_ff, int32_t n_segments,
+                     const int32_t *seg_start, const uint8_t *seg_is_train, const void *pre_act,
+                     const void *dout, void *dy, void *stream);
 
 int collm_lora_siblings_fwd(collm_ctx *ctx, const collm_shape *shape, const collm_siblings *siblings,
                             const void *x, const void *W, const void *const *A, const void *const *B,

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libcollm_lora.so")
 
 COLLM_F32 = 0
 COLLM_BF16 = 1
+ACT_NONE, ACT_SWIGLU = 0, 1
 LAYOUT_IN_OUT, LAYOUT_OUT_IN = 0, 1  # W [d_in, d_out] (paper, row vectors) / W [d_out, d_in] (module weights)
 
 TILE_AUTO, TILE_256x256, TILE_256x128, TILE_128x128, TILE_256x256_W8 = -1, 0, 1, 2, 3
@@ -38,7 +39,8 @@ class collm_shape(ctypes.Structure):
 
 
 class collm_siblings(ctypes.Structure):
-    _fields_ = [("n_siblings", ctypes.c_int32), ("d_out", ctypes.c_int32 * 4), ("activation", ctypes.c_int32)]
+    _fields_ = [("n_siblings", ctypes.c_int32), ("d_out", ctypes.c_int32 * 4), ("activation", ctypes.c_int32),
+                ("pre_act", ctypes.c_void_p)]
 
 
 class collm_adamw(ctypes.Structure):
@@ -93,6 +95,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.collm_lora_siblings_bwd.argtypes = [vp, sp, sbp, vp, vp, _vpp, _vpp, _i32p, _i32p, _i32p, _u8p, vp, vp, vp,
                                             _vpp, _vpp, ctypes.c_int, vp]
     lib.collm_lora_siblings_bwd.restype = ctypes.c_int
+    lib.collm_swiglu_bwd.argtypes = [ctypes.c_int, i32, i32, i32, _i32p, _u8p, vp, vp, vp, vp]
+    lib.collm_swiglu_bwd.restype = ctypes.c_int
     lib.collm_token_map.argtypes = [sp, _i32p, _i32p, _u8p, _i32p, _i32p, _u8p]
     lib.collm_token_map.restype = ctypes.c_int
     lib.collm_debug_device_token_map.argtypes = [vp, _i32p, _i32p, _u8p]
@@ -276,7 +280,7 @@ class Context:
 
 
     @staticmethod
-    def _siblings(d_outs, activation=0):
+    def _siblings(d_outs, activation=0, pre_act=None):
         d = [int(v) for v in d_outs]
         if not 1 <= len(d) <= 4:
             raise ValueError("1 to 4 sibling projections")
@@ -285,16 +289,19 @@ class Context:
         for j, v in enumerate(d):
             sb.d_out[j] = v
         sb.activation = int(activation)
+        sb.pre_act = None if pre_act is None else pre_act.data_ptr()
         return sb
 
     def collm_lora_siblings_fwd(self, d_outs, x, W, A: List, B: List, rank, seg_start, seg_adapter, seg_is_train,
-                                scale: float, y, h_save=None, stream=None):
+                                scale: float, y, h_save=None, stream=None, activation: int = ACT_NONE, pre_act=None):
         """Sibling projections of x stored side by side (W [d_in, sum d_outs], A_i [d_in, P rank_i],
-        B_i [rank_i, sum d_outs]): y[:, C_j] <- x W[:, C_j] + scale (x A_i,j) B_i[:, C_j]."""
+        B_i [rank_i, sum d_outs]): y[:, C_j] <- x W[:, C_j] + scale (x A_i,j) B_i[:, C_j].
+        activation ACT_SWIGLU (gate, up): y [T, d_ff] <- silu(gate) * up; pre_act (optional, [T, 2 d_ff])
+        keeps both pre-activations of training rows."""
         ss, sa, st = _seg_arrays(seg_start, seg_adapter, seg_is_train)
         rk = np.ascontiguousarray(rank, dtype=np.int32)
         sh = self._shape(x, W, len(sa), len(rk), scale, LAYOUT_IN_OUT)
-        sb = self._siblings(d_outs)
+        sb = self._siblings(d_outs, activation, pre_act)
         At, Bt = _ptr_table(A, len(rk)), _ptr_table(B, len(rk))
         _check(self._lib.collm_lora_siblings_fwd(
             self._h, ctypes.byref(sh), ctypes.byref(sb), x.data_ptr(), W.data_ptr(), At, Bt,
@@ -336,6 +343,18 @@ def _stream_handle(stream):
 
     s = torch.cuda.current_stream() if stream is None else stream
     return ctypes.c_void_p(s.cuda_stream)
+
+
+def collm_swiglu_bwd(seg_start, seg_is_train, pre_act, dout, dy, stream=None):
+    """Training rows: dy [T, 2 d_ff] <- gradient of silu(gate) * up with respect to the pre-activations pre_act,
+    from dout [T, d_ff]."""
+    lib = load_library()
+    ss = np.ascontiguousarray(seg_start, dtype=np.int32)
+    st = np.ascontiguousarray(seg_is_train, dtype=np.uint8)
+    _check(lib.collm_swiglu_bwd(dout.device.index or 0, int(dout.shape[0]), int(dout.shape[1]), len(st),
+                                ss.ctypes.data_as(_i32p), st.ctypes.data_as(_u8p), pre_act.data_ptr(),
+                                dout.data_ptr(), dy.data_ptr(), _stream_handle(stream)), "collm_swiglu_bwd")
+    return dy
 
 
 def collm_adapter_fedavg(copies: Sequence, dst, stream=None):

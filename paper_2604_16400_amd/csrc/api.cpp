@@ -149,23 +149,26 @@ Tiling pick_tiling(int rows, int cols)
 // One GEMM over the row order `R`: a single launch, or whole rounds of large tiles followed by
 // small tiles over the remaining rows.
 hipError_t run_gemm(collm_ctx *c, GemmArgs g, const RowOrderLayout &R, int rows, int cols, int forced_tile,
-                    bool b_kmajor, hipStream_t st)
+                    bool b_kmajor, hipStream_t st, bool swiglu = false)
 {
+    // SwiGLU epilogue: `cols` counts gate and up columns; a tile holds half as many output columns as it is wide
+    auto launch = [&](int tile) {
+        g.tiles_n = (cols + gemm_tile_cols(tile) - 1) / gemm_tile_cols(tile);
+        return swiglu ? launch_gemm_swiglu(g, tile, st) : launch_gemm(g, tile, b_kmajor, st);
+    };
     const Tiling t = forced_tile >= 0 ? Tiling{forced_tile, R.n_rows_pad / gemm_tile_rows(forced_tile), 0}
                                       : pick_tiling(rows, cols);
     g.tile_m_base = 0;
     g.tiles_m = t.big_tiles_m;
-    g.tiles_n = (cols + gemm_tile_cols(t.tile) - 1) / gemm_tile_cols(t.tile);
     g.ext_off = c->d_plan + R.off_ext_off;
     g.ext = reinterpret_cast<const ExtStep *>(c->d_plan + R.off_ext);
-    hipError_t e = launch_gemm(g, t.tile, b_kmajor, st);
+    hipError_t e = launch(t.tile);
     if (e != hipSuccess || t.tail_tiles_m == 0) return e;
     g.tile_m_base = 2 * t.big_tiles_m;
     g.tiles_m = t.tail_tiles_m;
-    g.tiles_n = (cols + gemm_tile_cols(kTile128x128) - 1) / gemm_tile_cols(kTile128x128);
     g.ext_off = c->d_plan + R.off_ext_off_half;
     g.ext = reinterpret_cast<const ExtStep *>(c->d_plan + R.off_ext_half);
-    return launch_gemm(g, kTile128x128, b_kmajor, st);
+    return launch(kTile128x128);
 }
 
 struct Prof {
@@ -474,9 +477,12 @@ int prepare_siblings(collm_ctx *c, const collm_shape *s, const collm_siblings *s
     if (!c || !s || !sib) return COLLM_E_NULL;
     if (s->dtype != COLLM_BF16) return COLLM_E_DTYPE;
     if (s->layout != COLLM_LAYOUT_IN_OUT) return COLLM_E_SHAPE;
-    if (sib->activation != COLLM_ACT_NONE) return COLLM_E_SHAPE;
+    const bool swiglu = sib->activation == COLLM_ACT_SWIGLU;
+    if (sib->activation != COLLM_ACT_NONE && !swiglu) return COLLM_E_SHAPE;
     const int P = sib->n_siblings;
     if (P < 1 || P > COLLM_MAX_SIBLINGS) return COLLM_E_SHAPE;
+    if (swiglu && (P != 2 || sib->d_out[0] != sib->d_out[1])) return COLLM_E_SHAPE;
+    if (!aligned16(sib->pre_act)) return COLLM_E_ALIGN;
     int64_t sum = 0;
     for (int j = 0; j < P; ++j) {
         if (sib->d_out[j] <= 0 || sib->d_out[j] % 8) return COLLM_E_SHAPE;
@@ -488,7 +494,8 @@ int prepare_siblings(collm_ctx *c, const collm_shape *s, const collm_siblings *s
     if (s->n_adapters > 0 && !rank) return COLLM_E_NULL;
     c->sum_rank.resize((size_t)std::max(s->n_adapters, 1));
     for (int a = 0; a < s->n_adapters; ++a) {
-        if (rank[a] < 1 || rank[a] > c->max_rank || (P > 1 && rank[a] % 8)) return COLLM_E_RANK;
+        if (rank[a] < 1 || rank[a] > c->max_rank || (P > 1 && rank[a] % 8) || (swiglu && rank[a] % 16))
+            return COLLM_E_RANK;
         c->sum_rank[a] = rank[a] * P;
     }
     return COLLM_OK;
@@ -670,6 +677,7 @@ static int fwd_impl(collm_ctx *c, const collm_shape *s, const collm_siblings *si
     int rc = sib ? prepare_siblings(c, s, sib, rank1) : COLLM_OK;
     if (rc != COLLM_OK) return rc;
     const int32_t *rank = P > 1 ? c->sum_rank.data() : rank1;
+    const bool swiglu = sib && sib->activation == COLLM_ACT_SWIGLU;
     rc = check_common(c, s, x, W, A, B, rank, seg_start, seg_adapter, seg_is_train);
     if (rc != COLLM_OK) return rc;
     if (s->n_tokens > 0 && !y) return COLLM_E_NULL;
@@ -678,8 +686,9 @@ static int fwd_impl(collm_ctx *c, const collm_shape *s, const collm_siblings *si
     hipStream_t st = (hipStream_t)stream;
     HIP_TRY(hipSetDevice(c->device));
     c->n_prof = 0;
+    // (with the SwiGLU epilogue the extension steps run over both siblings' ranks, as in the backward GEMM)
     rc = prepare_plan(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, nullptr, nullptr, true, st,
-                      P > 1 ? rank1 : nullptr, P);
+                      P > 1 && !swiglu ? rank1 : nullptr, swiglu ? 16 + P : P);
     if (rc != COLLM_OK) return rc;
     const PlanLayout &L = c->L;
     const bool f32 = s->dtype == COLLM_F32;
@@ -712,14 +721,22 @@ static int fwd_impl(collm_ctx *c, const collm_shape *s, const collm_siblings *si
     g.hs_bytes = (uint32_t)((size_t)c->rows_cap * c->rpad_cap * 4);
     g.ext_ld = tr ? 0 : s->d_out;
     g.zeros = c->d_zeros;
-    g.n_sib = P;
+    g.n_sib = swiglu ? 0 : P;
     for (int j = 0, col = 0; j + 1 < P; ++j) g.sib_col[j] = (col += sib->d_out[j]);
+    if (swiglu) {
+        // y is [T, d_ff]; W and the expand tables keep their 2 d_ff columns
+        g.N = g.ldo = g.act_col = sib->d_out[0];
+        g.pre_act = sib->pre_act;
+        g.pre_ld = s->d_out;
+        g.tok_train = c->d_plan + L.off_tok_train;
+    }
     {
         Prof prof(c, st, "gemm_fwd");
         if (f32) {
             HIP_TRY(launch_gemm_f32(g, tr, st));
         } else {
-            HIP_TRY(run_gemm(c, g, L.all, s->n_tokens, s->d_out, c->tile_fwd, tr, st));
+            const int forced = swiglu && c->tile_fwd != kTile256x256 && c->tile_fwd != kTile128x128 ? -1 : c->tile_fwd;
+            HIP_TRY(run_gemm(c, g, L.all, s->n_tokens, s->d_out, forced, tr, st, swiglu));
         }
     }
     return COLLM_OK;
@@ -955,6 +972,44 @@ int collm_lora_siblings_bwd(collm_ctx *c, const collm_shape *s, const collm_sibl
     if (!sib) return COLLM_E_NULL;
     return bwd_impl(c, s, sib, x, W, A, B, rank, seg_start, seg_adapter, seg_is_train, dy, h_save, dx, dA, dB,
                     accumulate, stream);
+}
+
+int collm_swiglu_bwd(int device, int32_t n_tokens, int32_t d_ff, int32_t n_segments, const int32_t *seg_start,
+                     const uint8_t *seg_is_train, const void *pre_act, const void *dout, void *dy, void *stream)
+{
+    if (n_tokens < 0 || n_segments < 0 || d_ff <= 0 || d_ff % 8) return COLLM_E_SHAPE;
+    if (n_segments > 0 && (!seg_start || !seg_is_train)) return COLLM_E_NULL;
+    if (n_segments > 0 && seg_start[0] != 0) return COLLM_E_SEGMENTS;
+    bool any = false;
+    for (int k = 0; k < n_segments; ++k) {
+        if (seg_start[k + 1] < seg_start[k]) return COLLM_E_SEGMENTS;
+        any = any || (seg_is_train[k] && seg_start[k + 1] > seg_start[k]);
+    }
+    if (n_segments > 0 && seg_start[n_segments] != n_tokens) return COLLM_E_SEGMENTS;
+    if (!any) return COLLM_OK;
+    if (!pre_act || !dout || !dy) return COLLM_E_NULL;
+    if (!aligned16(pre_act) || !aligned16(dout) || !aligned16(dy)) return COLLM_E_ALIGN;
+    HIP_TRY(hipSetDevice(device));
+    SwigluBwdArgs a{};
+    a.pre = pre_act;
+    a.dout = dout;
+    a.dy = dy;
+    a.d_ff = d_ff;
+    a.ld_pre = a.ld_dy = 2 * (int64_t)d_ff;
+    a.ld_dout = d_ff;
+    for (int k = 0; k < n_segments; ++k) {
+        const int n = seg_start[k + 1] - seg_start[k];
+        if (seg_is_train[k] && n > 0) {
+            a.tok0[a.n_seg] = seg_start[k];
+            a.row0[a.n_seg + 1] = a.row0[a.n_seg] + n;
+            ++a.n_seg;
+        }
+        if (a.n_seg == kSwigluSegs || (k + 1 == n_segments && a.n_seg > 0)) {
+            HIP_TRY(launch_swiglu_bwd(a, (hipStream_t)stream));
+            a.n_seg = 0;
+        }
+    }
+    return COLLM_OK;
 }
 
 int collm_adapter_fedavg(int device, collm_dtype dtype, int32_t n_copies, const void *const *src, void *dst,

@@ -33,6 +33,13 @@ struct GemmArgs {
     // from sib_col[j - 1] on) takes columns j * rank .. of hs for its extension steps, rank = that of the step
     int n_sib;                // 0 or 1: a single projection
     int sib_col[3];
+    // gate/up pair with the SwiGLU epilogue (launch_gemm_swiglu): N = d_ff output columns; the up sibling's columns
+    // of b and of the expand tables start at act_col; pre_act (optional, [tokens][pre_ld]) receives both
+    // pre-activations of the rows of training tokens (tok_train: token -> 0/1)
+    int act_col;
+    void *pre_act;
+    int64_t pre_ld;
+    const int32_t *tok_train;
     // rank-wide pass over long runs of one adapter (launch_wide): one row tile per item, second operand =
     // the item's adapter table ([K][rank] or, K-major, [rank][K]), K cut into slices of k_per_split,
     // fp32 sums of slice s for row r of the row order at part[(s * part_rows + r) * part_ld + q]
@@ -99,6 +106,8 @@ struct GradArgs {
 };
 
 hipError_t launch_gemm(const GemmArgs &a, int tile_cfg, bool b_kmajor, hipStream_t st);
+// tile_cfg kTile256x256 or kTile128x128; tiles_n counts tiles of half as many output columns as the tile has
+hipError_t launch_gemm_swiglu(const GemmArgs &a, int tile_cfg, hipStream_t st);
 // a, lda, K, a_bytes, row_tok and the fields of the rank-wide pass; everything else is ignored.  Items hold up
 // to kWideRows rows; ranks must be multiples of 8.  The caller adds the slices with launch_skinny_finish.
 hipError_t launch_wide(const GemmArgs &a, int n_items, int rpad, int n_split, bool t_kmajor, hipStream_t st);
@@ -143,6 +152,20 @@ struct AdamWArgs {
     float bias1;        // 1 - beta1^step
     float rsqrt_bias2;  // 1 / sqrt(1 - beta2^step)
 };
+// Backward of out = silu(g) * u for the rows of up to kSwigluSegs training segments: pre holds g in columns
+// 0 .. d_ff and u in columns d_ff .. 2 d_ff of a row, dy receives d out / d g and d out / d u in the same places.
+constexpr int kSwigluSegs = 64;
+struct SwigluBwdArgs {
+    const void *pre;
+    const void *dout;
+    void *dy;
+    int d_ff;
+    int64_t ld_pre, ld_dout, ld_dy;
+    int n_seg;
+    int32_t row0[kSwigluSegs + 1];  // rows of the launch before segment k
+    int32_t tok0[kSwigluSegs];      // first token of segment k
+};
+hipError_t launch_swiglu_bwd(const SwigluBwdArgs &a, hipStream_t st);
 hipError_t launch_fedavg(const FedAvgArgs &a, bool bf16, hipStream_t st);
 hipError_t launch_adamw(const AdamWArgs &a, bool bf16, hipStream_t st);
 

@@ -1,8 +1,8 @@
 // Adapter update kernels: the step after the backward pass of the mixed-batch LoRA layer.
 //   fedavg   dst = (1/K) sum_k src_k        aggregation of the replicas' adapter copies
 //   adamw    one AdamW step on an adapter table from its fp32 gradient
-// Both are element-wise and HBM-bound: 16-byte loads and stores, a grid that covers the array a
-// few times over, no shared memory.
+//   swiglu_bwd  gradient of silu(gate) * up with respect to both pre-activations, training rows only
+// All are element-wise and HBM-bound: 16-byte loads and stores, no shared memory.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -130,7 +130,49 @@ int grid_for(int64_t work_items)
     return (int)(blocks < 1 ? 1 : (blocks > 256 * 16 ? 256 * 16 : blocks));  // at most 16 blocks per CU
 }
 
+// one block row = one training row, 8 columns per lane
+__global__ void __launch_bounds__(256) swiglu_bwd_kernel(SwigluBwdArgs p)
+{
+    int k = 0;
+    while (k + 1 < p.n_seg && (int)blockIdx.y >= p.row0[k + 1]) ++k;
+    const int64_t tok = p.tok0[k] + ((int)blockIdx.y - p.row0[k]);
+    const int j = (blockIdx.x * 256 + threadIdx.x) * 8;
+    if (j >= p.d_ff) return;
+    const uint16_t *pre = reinterpret_cast<const uint16_t *>(p.pre) + tok * p.ld_pre;
+    const uint4 gv = *reinterpret_cast<const uint4 *>(pre + j);
+    const uint4 uv = *reinterpret_cast<const uint4 *>(pre + p.d_ff + j);
+    const uint4 dv = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(p.dout) + tok * p.ld_dout + j);
+    const uint32_t gw[4] = {gv.x, gv.y, gv.z, gv.w}, uw[4] = {uv.x, uv.y, uv.z, uv.w}, dw[4] = {dv.x, dv.y, dv.z, dv.w};
+    uint32_t og[4], ou[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        uint16_t rg[2], ru[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const float g = bf16_to_f32((uint16_t)(gw[e] >> (16 * h)));
+            const float u = bf16_to_f32((uint16_t)(uw[e] >> (16 * h)));
+            const float d = bf16_to_f32((uint16_t)(dw[e] >> (16 * h)));
+            const float sg = 1.f / (1.f + __expf(-g));
+            rg[h] = f32_to_bf16(d * u * sg * (1.f + g * (1.f - sg)));
+            ru[h] = f32_to_bf16(d * g * sg);
+        }
+        og[e] = (uint32_t)rg[0] | ((uint32_t)rg[1] << 16);
+        ou[e] = (uint32_t)ru[0] | ((uint32_t)ru[1] << 16);
+    }
+    uint16_t *dy = reinterpret_cast<uint16_t *>(p.dy) + tok * p.ld_dy;
+    *reinterpret_cast<uint4 *>(dy + j) = make_uint4(og[0], og[1], og[2], og[3]);
+    *reinterpret_cast<uint4 *>(dy + p.d_ff + j) = make_uint4(ou[0], ou[1], ou[2], ou[3]);
+}
+
 }  // namespace
+
+hipError_t launch_swiglu_bwd(const SwigluBwdArgs &a, hipStream_t st)
+{
+    const int rows = a.row0[a.n_seg];
+    if (rows <= 0 || a.d_ff <= 0) return hipSuccess;
+    hipLaunchKernelGGL(swiglu_bwd_kernel, dim3((a.d_ff / 8 + 255) / 256, rows), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
 
 hipError_t launch_fedavg(const FedAvgArgs &a, bool bf16, hipStream_t st)
 {

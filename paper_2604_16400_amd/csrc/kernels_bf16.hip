@@ -332,9 +332,16 @@ struct DmaSlots {
 // columns (blockIdx.y) and one slice of K (blockIdx.z); the second operand is the adapter's own
 // table; there are no extension steps, and the fp32 sums go to the workspace of partial sums that
 // skinny_finish_kernel adds up.
-template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR, bool PINGPONG, bool PARTIAL = false>
+// SWIGLU (N-major second operand, WGN = 2): a column tile holds BN / 2 gate columns j0 .. and the BN / 2 up
+// columns act_col + j0 .. of the same outputs; the waves of the left half hold the gate values, those
+// of the right half the up values of the same rows.  The extension steps run over both siblings' ranks
+// (rank r each, multiples of 16): a step of the first r multiplies into the gate half only, one of the
+// second r into the up half only.  The epilogue passes the up values through LDS and stores
+// silu(gate) * up, rounded once, as [rows][N = d_ff]; training rows also keep both pre-activations.
+template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR, bool PINGPONG, bool PARTIAL = false, bool SWIGLU = false>
 __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 {
+    static_assert(!SWIGLU || (!B_KMAJOR && !PINGPONG && !PARTIAL && WGN == 2), "SwiGLU epilogue: N-major, two wave columns");
     constexpr int NT = WGM * WGN * 64;
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int MI = WM / 32, NI = WN / 32;
@@ -389,7 +396,17 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         K = p.K;
         N = p.N;
     }
-    const int n0 = tile_n * BN;
+    const int n0 = SWIGLU ? tile_n * (BN / 2) : tile_n * BN;
+    // tile column c (a multiple of 8) -> column of the second operand and of the expand tables
+    auto src_col = [&](int c) -> int {
+        if constexpr (SWIGLU) return c < BN / 2 ? n0 + c : p.act_col + n0 + c - BN / 2;
+        return n0 + c;
+    };
+    // ... and whether that column exists (N: columns of the output)
+    auto col_on = [&](int c) -> bool {
+        if constexpr (SWIGLU) return n0 + (c < BN / 2 ? c : c - BN / 2) < N;
+        return n0 + c < N;
+    };
     const int32_t *__restrict__ row_tok = p.row_tok;
     int sib = 0;  // which of the sibling projections this column tile belongs to
     if constexpr (!PARTIAL) {
@@ -461,11 +478,11 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
             boff[i] = n < N ? (uint32_t)n * ldb * 2u + cl * 16u : kOob;
         }
     } else {
-        const bool on = n0 + bcl * 8 < N;
+        const bool on = col_on(bcl * 8);
         bstep = on ? 64u * ldb * 2u : 0u;
 #pragma unroll
         for (int i = 0; i < NB; ++i)
-            boff[i] = on ? ((uint32_t)(bk0 + i * (NT / NG)) * ldb + n0 + bcl * 8) * 2u : kOob;
+            boff[i] = on ? ((uint32_t)(bk0 + i * (NT / NG)) * ldb + src_col(bcl * 8)) * 2u : kOob;
     }
     // byte offset of the tile that starts at K index k0 = 64 kc, for chunk i; tiles that reach
     // beyond K mask their tail (K-major) or run off the end of the buffer (N-major rows)
@@ -782,9 +799,17 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                 for (int i = 0; i < BCH; ++i) {
                     const int j = (i * (NT / NG)) >> 4;
                     const int k = bk0 + i * (NT / NG);
-                    const uint32_t rk = bt.kr[j] >> 16, koff = bt.kr[j] & 0xffffu;
+                    uint32_t rk = bt.kr[j] >> 16, koff = bt.kr[j] & 0xffffu;
+                    bool mine = true;
+                    if constexpr (SWIGLU) {
+                        // the step belongs to the gate sibling (first half of the ranks) or the up sibling
+                        rk >>= 1;
+                        const bool up = koff >= rk;
+                        koff -= up ? rk : 0u;
+                        mine = (bcl * 8 >= BN / 2) == up;
+                    }
                     const i32x4 rt = make_rsrc_words(reinterpret_cast<const void *>(bt.tab[j]), rk * (uint32_t)p.ext_ld * 2u);
-                    const uint32_t off = (n0 + bcl * 8 < N) ? ((koff + (uint32_t)(k & 15)) * (uint32_t)p.ext_ld + (uint32_t)(n0 + bcl * 8)) * 2u : kOob;
+                    const uint32_t off = (mine && col_on(bcl * 8)) ? ((koff + (uint32_t)(k & 15)) * (uint32_t)p.ext_ld + (uint32_t)src_col(bcl * 8)) * 2u : kOob;
                     dma16(rt, off, lds_wave + (stage ? B_ST1 : B_ST0) + i * (NT / 64) * 1024);
                 }
             } else {
@@ -885,6 +910,60 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         constexpr int EP = WN * 2 + 16;          // bytes per staged row
         constexpr int LPR = WN / 8, RPI = 64 / LPR;  // lanes per row, rows per store instruction
         uint8_t *ep = smem + wave * (WM * EP);
+        if constexpr (SWIGLU) {
+            // pre-activations of training rows, as they are (8 bytes per lane: few rows need them)
+            if (p.pre_act) {
+                uint16_t *__restrict__ Pre = reinterpret_cast<uint16_t *>(p.pre_act);
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi) {
+                    const int tok = row_tok[m0 + wm * WM + mi * 32 + rl];
+                    if (tok < 0 || !p.tok_train[tok]) continue;
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            const int c = ni * 32 + g * 8 + kh * 4;
+                            if (n0 + c >= N) continue;
+                            uint2 v;
+                            v.x = pack_bf16(acc[ni][mi][g * 4 + 0], acc[ni][mi][g * 4 + 1]);
+                            v.y = pack_bf16(acc[ni][mi][g * 4 + 2], acc[ni][mi][g * 4 + 3]);
+                            *reinterpret_cast<uint2 *>(Pre + (int64_t)tok * p.pre_ld + (wn ? p.act_col : 0) + n0 + c) = v;
+                        }
+                }
+            }
+            // the up values of a wave's rows go to the area of its pair, lane for lane as the gate wave holds them
+            floatx4 *xch = reinterpret_cast<floatx4 *>(smem + wm * (WM * WN * 4));
+            if (wn == 1) {
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                        for (int g = 0; g < 4; ++g)
+                            xch[((mi * NI + ni) * 4 + g) * 64 + lane] =
+                                floatx4{acc[ni][mi][g * 4 + 0], acc[ni][mi][g * 4 + 1], acc[ni][mi][g * 4 + 2], acc[ni][mi][g * 4 + 3]};
+            }
+            __syncthreads();
+            if (wn == 1) return;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const floatx4 u = xch[((mi * NI + ni) * 4 + g) * 64 + lane];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float a = acc[ni][mi][g * 4 + e];
+                            acc[ni][mi][g * 4 + e] = a / (1.f + __expf(-a)) * u[e];
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);  // one block of 16 at a time: few registers in flight
+                }
+            // the pair's area is free again (this wave has read all of it): stage the rows there
+            __builtin_amdgcn_wave_barrier();
+            ep = smem + wm * (WM * WN * 4);
+        }
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
             uint8_t *erow = ep + (mi * 32 + rl) * EP;
@@ -1419,14 +1498,15 @@ __global__ void __launch_bounds__(GradCfg<RP>::KW * 64) grad_kernel(GradArgs p)
 // =========================================================================================
 // launchers
 // =========================================================================================
-template <int BM, int BN, int WGM, int WGN, bool KM, bool PP>
+template <int BM, int BN, int WGM, int WGN, bool KM, bool PP, bool SWIGLU = false>
 static hipError_t launch_gemm_t(const GemmArgs &a, hipStream_t st)
 {
     constexpr int NT = WGM * WGN * 64;
     constexpr int stage_bytes = 2 * (BM + BN) * 128;
     constexpr int epi_bytes = BM * BN * 2 + BM * WGN * 16;  // per wave (BM/WGM) rows of (BN/WGN) * 2 + 16 bytes
     constexpr int smem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
-    auto kern = gemm_lora_kernel<BM, BN, WGM, WGN, KM, PP>;
+    static_assert(!SWIGLU || smem >= BM * (BN / 2) * 4, "the up halves of all rows pass through LDS as fp32");
+    auto kern = gemm_lora_kernel<BM, BN, WGM, WGN, KM, PP, false, SWIGLU>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -1483,6 +1563,18 @@ hipError_t launch_skinny_finish(const SkinnyArgs &a, int n_items, int item_rows,
     if (n_items <= 0) return hipSuccess;
     hipLaunchKernelGGL(skinny_finish_kernel, dim3(n_items, (item_rows + 15) / 16), dim3(256), 0, st, a, n_split);
     return hipGetLastError();
+}
+
+hipError_t launch_gemm_swiglu(const GemmArgs &a, int tile_cfg, hipStream_t st)
+{
+    switch (tile_cfg) {
+    case kTile256x256:
+        return launch_gemm_t<256, 256, 2, 2, false, false, true>(a, st);
+    case kTile128x128:
+        return launch_gemm_t<128, 128, 2, 2, false, false, true>(a, st);
+    default:
+        return hipErrorInvalidValue;
+    }
 }
 
 int gemm_tile_rows(int tile_cfg) { return tile_cfg == kTile128x128 ? 128 : 256; }

@@ -169,3 +169,129 @@ def test_sibling_error_statuses():
     torch.cuda.synchronize()
     assert torch.isnan(y).all()
     ctx.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# gate/up pair with the SwiGLU epilogue, and the gradient through it
+# ---------------------------------------------------------------------------------------------
+def _run_swiglu(case: SiblingCase, tile=None, keep_pre=True):
+    import torch
+
+    assert case.P == 2 and case.d_outs[0] == case.d_outs[1]
+    T, D, d_ff = case.T, case.D, case.d_outs[0]
+    max_rank = 2 * int(case.ranks.max())
+    ctx = binding.Context(max(T, 1), len(case.seg_adapter), len(case.ranks), max_rank, max(case.d_in, D))
+    if tile is not None:
+        ctx.set_tiles(tile, tile)
+    x, W = to_dev(case.x, "bf16"), to_dev(case.W, "bf16")
+    A, B = [to_dev(a, "bf16") for a in case.A], [to_dev(b, "bf16") for b in case.B]
+    y = torch.full((T, d_ff), float("nan"), dtype=torch.bfloat16, device="cuda")
+    pre = torch.full((T, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    hs = torch.full((T, max_rank), float("nan"), dtype=torch.float32, device="cuda")
+    seg = (case.ranks, case.seg_start, case.seg_adapter, case.seg_is_train, case.scale)
+    ctx.collm_lora_siblings_fwd(case.d_outs, x, W, A, B, *seg, y, hs, activation=binding.ACT_SWIGLU,
+                                pre_act=pre if keep_pre else None)
+    torch.cuda.synchronize()
+    y_pre_ref, h_ref = oracle.lora_siblings_fwd(case.x, case.W, case.A, case.B, case.d_outs, case.tok_adapter, case.scale)
+    out_ref = oracle.swiglu(y_pre_ref)
+    yh = to_host(y)
+    assert np.all(np.isfinite(yh))
+    errs = {"y": maxrel(yh, out_ref)}
+    tr = case.tok_train != 0
+    ph = to_host(pre)
+    if keep_pre:
+        assert np.all(np.isnan(ph[~tr]))
+        if tr.any():
+            assert np.all(np.isfinite(ph[tr]))
+            errs["pre"] = maxrel(ph[tr], y_pre_ref[tr])
+    else:
+        assert np.all(np.isnan(ph))
+    hh = to_host(hs)
+    if tr.any():
+        ref = np.zeros((int(tr.sum()), max_rank))
+        ref[:, : h_ref.shape[1]] = h_ref[tr]
+        errs["h"] = maxrel(hh[tr], ref)
+    ctx.close()
+    bad = {k: v for k, v in errs.items() if not v <= TOL["bf16"]}
+    assert not bad, f"beyond tolerance: {bad} (all: {errs})"
+    return pre
+
+
+@pytest.mark.parametrize("tile", [None, binding.TILE_256x256, binding.TILE_128x128])
+def test_swiglu_epilogue(tile):
+    # d_ff = 256 + 40 columns per sibling would break the multiple-of-256 rule for the first sibling, so: 512
+    # (two 256-wide or four 128-wide column pairs); ranks 16..64; decode, base-only and training rows mixed
+    c = SiblingCase(320, (512, 512), [16, 32, 48, 64], LENS, ADS, TRN, scale=0.3)
+    _run_swiglu(c, tile)
+    _run_swiglu(c, tile, keep_pre=False)
+
+
+def test_swiglu_epilogue_large_tiles_and_tail():
+    # 2300 rows x (2 x 3840) columns: whole rounds of 256x256 tiles, then 128x128 tiles over the last rows
+    lens = [700, 1, 1, 500, 300, 1, 600, 197]
+    ads = [0, 1, 2, 1, -1, 0, 2, 2]
+    c = SiblingCase(64, (3840, 3840), [16, 32, 16], lens, ads, [1, 0, 0, 1, 0, 0, 1, 0], scale=0.5)
+    _run_swiglu(c)
+
+
+def test_swiglu_backward_kernel_and_chain():
+    import torch
+
+    # the gradient kernel alone, then the chain: forward with epilogue -> gradient kernel -> sibling backward
+    c = SiblingCase(320, (512, 512), [16, 32, 48, 64], LENS, ADS, TRN, scale=0.3)
+    pre = _run_swiglu(c)
+    rng = np.random.default_rng(3)
+    d_ff, T = 512, c.T
+    dout_h = wl.bf16_round(rng.standard_normal((T, d_ff)).astype(np.float32))
+    tr = c.tok_train != 0
+    dout = to_dev(np.where(tr[:, None], dout_h, np.nan).astype(np.float32), "bf16")  # inference rows must not be read
+    dy = torch.full((T, 2 * d_ff), float("nan"), dtype=torch.bfloat16, device="cuda")
+    binding.collm_swiglu_bwd(c.seg_start, c.seg_is_train, pre, dout, dy)
+    torch.cuda.synchronize()
+    dyh, preh = to_host(dy), to_host(pre)
+    assert np.all(np.isnan(dyh[~tr])) and np.all(np.isfinite(dyh[tr]))
+    ref = oracle.swiglu_bwd(preh[tr], dout_h[tr])
+    assert maxrel(dyh[tr], ref) <= TOL["bf16"]
+    # chain: the sibling backward on that dy against the oracle's backward on the oracle's own dy
+    y_pre_ref, _ = oracle.lora_siblings_fwd(c.x, c.W, c.A, c.B, c.d_outs, c.tok_adapter, c.scale)
+    dy_ref = np.zeros((T, 2 * d_ff))
+    dy_ref[tr] = oracle.swiglu_bwd(y_pre_ref[tr], dout_h[tr])
+    dx_ref, dA_ref, dB_ref = oracle.lora_siblings_bwd(c.x, c.W, c.A, c.B, c.d_outs, c.tok_adapter, c.tok_train, c.scale, dy_ref)
+    ctx = binding.Context(T, len(c.seg_adapter), len(c.ranks), 128, 1024)
+    x, W = to_dev(c.x, "bf16"), to_dev(c.W, "bf16")
+    A, B = [to_dev(a, "bf16") for a in c.A], [to_dev(b, "bf16") for b in c.B]
+    dx = torch.full((T, c.d_in), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dA = [torch.full(a.shape, float("nan"), dtype=torch.float32, device="cuda") for a in c.A]
+    dB = [torch.full(b.shape, float("nan"), dtype=torch.float32, device="cuda") for b in c.B]
+    ctx.collm_lora_siblings_bwd(c.d_outs, x, W, A, B, c.ranks, c.seg_start, c.seg_adapter, c.seg_is_train, c.scale,
+                                dy, None, dx, dA, dB)
+    torch.cuda.synchronize()
+    errs = {"dx": maxrel(to_host(dx)[tr], dx_ref[tr])}
+    for a in range(len(c.ranks)):
+        if dA_ref[a] is not None:
+            errs[f"dA{a}"] = maxrel(to_host(dA[a]), dA_ref[a])
+            errs[f"dB{a}"] = maxrel(to_host(dB[a]), dB_ref[a])
+    ctx.close()
+    # two bf16 roundings (pre-activations, dy) lie between the oracle's chain and this one
+    bad = {k: v for k, v in errs.items() if not v <= 2e-2}
+    assert not bad, f"beyond tolerance: {bad} (all: {errs})"
+
+
+def test_swiglu_error_statuses():
+    import torch
+
+    c = SiblingCase(64, (256, 256), [16, 8], [10, 20], [0, 1], [0, 1])
+    ctx = binding.Context(c.T, 2, 2, 64, 512)
+    x, W = to_dev(c.x, "bf16"), to_dev(c.W, "bf16")
+    A, B = [to_dev(a, "bf16") for a in c.A], [to_dev(b, "bf16") for b in c.B]
+    y = torch.full((c.T, 256), float("nan"), dtype=torch.bfloat16, device="cuda")
+    seg = [c.ranks, c.seg_start, c.seg_adapter, c.seg_is_train, c.scale]
+    with pytest.raises(binding.CollmError) as e:   # rank 8 is no multiple of 16
+        ctx.collm_lora_siblings_fwd((256, 256), x, W, A, B, *seg, y, activation=binding.ACT_SWIGLU)
+    assert e.value.status == -5
+    with pytest.raises(binding.CollmError) as e:   # unknown activation
+        ctx.collm_lora_siblings_fwd((256, 256), x, W, A, B, *seg, y, activation=7)
+    assert e.value.status == -2
+    torch.cuda.synchronize()
+    assert torch.isnan(y).all()
+    ctx.close()
