@@ -293,8 +293,34 @@ def _siblings(wl, torch, binding, steps, warmup):
         for d_out in d_outs:
             f_fwd, f_bwd = w.flops(type(w.projections[0])("sib", d_in, d_out))
             flops += f_fwd + f_bwd
-        out.append({"workload": f"{w.name}/{name}", "d_in": d_in, "d_out": list(d_outs), "tokens": T,
-                    "ms_per_step": sec * 1e3, "tflops": flops / sec / 1e12})
+        rec = {"workload": f"{w.name}/{name}", "d_in": d_in, "d_out": list(d_outs), "tokens": T,
+               "ms_per_step": sec * 1e3, "tflops": flops / sec / 1e12}
+        if P == 2 and d_outs[0] == d_outs[1]:
+            # gate/up pair: the forward call alone, plain and with the SwiGLU epilogue (y [T, d_ff], both
+            # pre-activations of training rows kept), and the gradient kernel through the activation
+            d_ff = d_outs[0]
+            ya = torch.empty((T, d_ff), dtype=torch.bfloat16, device="cuda")
+            dout = rn((T, d_ff), 1.0)
+
+            def timed(fn):
+                for _ in range(3):
+                    fn()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(n):
+                    fn()
+                torch.cuda.synchronize()
+                return (time.perf_counter() - t0) / n
+
+            t_plain = timed(lambda: ctx.collm_lora_siblings_fwd(d_outs, x, W, A, B, *seg, y, hs))
+            t_act = timed(lambda: ctx.collm_lora_siblings_fwd(d_outs, x, W, A, B, *seg, ya, hs,
+                                                              activation=binding.ACT_SWIGLU, pre_act=y))
+            t_gb = timed(lambda: binding.collm_swiglu_bwd(w.seg_start, w.seg_is_train, y, dout, dy))
+            by = w.n_train_tokens * d_ff * 2 * 5  # reads g, u, dout; writes two gradients
+            rec.update({"fwd_ms": t_plain * 1e3, "fwd_swiglu_ms": t_act * 1e3, "swiglu_bwd_ms": t_gb * 1e3,
+                        "swiglu_bwd_GBs": by / t_gb / 1e9})
+            del ya, dout
+        out.append(rec)
         ctx.close()
         del x, W, dy, A, B, dA, dB, y, dx, hs
         torch.cuda.empty_cache()

@@ -931,38 +931,80 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                         }
                 }
             }
-            // the up values of a wave's rows go to the area of its pair, lane for lane as the gate wave holds them
-            floatx4 *xch = reinterpret_cast<floatx4 *>(smem + wm * (WM * WN * 4));
-            if (wn == 1) {
+            // Each wave of a pair finishes half of the pair's rows: the gate wave the first half (it receives
+            // their up values), the up wave the second half (it receives their gate values), lane for lane as
+            // the sender holds them.  Area of the pair: [gate values of the second half | up values of the first].
+            static_assert(MI % 2 == 0, "the rows of a wave pair are split in two");
+            constexpr int MH = MI / 2;
+            floatx4 *xg = reinterpret_cast<floatx4 *>(smem + wm * (WM * WN * 4));
+            floatx4 *xu = xg + MH * NI * 4 * 64;
+            auto send = [&](auto lo_c, floatx4 *dst) {
+                constexpr int LO = decltype(lo_c)::value;
 #pragma unroll
-                for (int mi = 0; mi < MI; ++mi)
+                for (int mh = 0; mh < MH; ++mh)
 #pragma unroll
                     for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
                         for (int g = 0; g < 4; ++g)
-                            xch[((mi * NI + ni) * 4 + g) * 64 + lane] =
-                                floatx4{acc[ni][mi][g * 4 + 0], acc[ni][mi][g * 4 + 1], acc[ni][mi][g * 4 + 2], acc[ni][mi][g * 4 + 3]};
-            }
+                            dst[((mh * NI + ni) * 4 + g) * 64 + lane] =
+                                floatx4{acc[ni][LO + mh][g * 4 + 0], acc[ni][LO + mh][g * 4 + 1], acc[ni][LO + mh][g * 4 + 2],
+                                        acc[ni][LO + mh][g * 4 + 3]};
+            };
+            if (wn == 0) send(std::integral_constant<int, MH>{}, xg);
+            else send(std::integral_constant<int, 0>{}, xu);
             __syncthreads();
-            if (wn == 1) return;
+            // silu(g) u = g u / (1 + exp(-g)); stage the rounded rows in the area just read; store whole lines
+            auto finish = [&](auto lo_c, auto gate_c, const floatx4 *src) {
+                constexpr int LO = decltype(lo_c)::value;
+                constexpr bool OWN_GATE = decltype(gate_c)::value;
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
+                for (int mh = 0; mh < MH; ++mh) {
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni) {
+                    for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const floatx4 u = xch[((mi * NI + ni) * 4 + g) * 64 + lane];
+                        for (int g = 0; g < 4; ++g) {
+                            const floatx4 o = src[((mh * NI + ni) * 4 + g) * 64 + lane];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const float a = acc[ni][mi][g * 4 + e];
-                            acc[ni][mi][g * 4 + e] = a / (1.f + __expf(-a)) * u[e];
+                            for (int e = 0; e < 4; ++e) {
+                                const float own = acc[ni][LO + mh][g * 4 + e];
+                                const float gt = OWN_GATE ? own : o[e], up = OWN_GATE ? o[e] : own;
+                                acc[ni][LO + mh][g * 4 + e] = gt * up * __builtin_amdgcn_rcpf(1.f + __expf(-gt));
+                            }
                         }
+                        __builtin_amdgcn_sched_barrier(0);  // one block of 16 at a time: few registers in flight
                     }
-                    __builtin_amdgcn_sched_barrier(0);  // one block of 16 at a time: few registers in flight
                 }
-            // the pair's area is free again (this wave has read all of it): stage the rows there
-            __builtin_amdgcn_wave_barrier();
-            ep = smem + wm * (WM * WN * 4);
+                __builtin_amdgcn_wave_barrier();
+                uint8_t *area = reinterpret_cast<uint8_t *>(const_cast<floatx4 *>(src));
+#pragma unroll
+                for (int mh = 0; mh < MH; ++mh) {
+                    uint8_t *erow = area + (mh * 32 + rl) * EP;
+                    if (kh == 0) *reinterpret_cast<int32_t *>(erow + WN * 2) = row_tok[m0 + wm * WM + (LO + mh) * 32 + rl];
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            uint2 v;
+                            v.x = pack_bf16(acc[ni][LO + mh][g * 4 + 0], acc[ni][LO + mh][g * 4 + 1]);
+                            v.y = pack_bf16(acc[ni][LO + mh][g * 4 + 2], acc[ni][LO + mh][g * 4 + 3]);
+                            *reinterpret_cast<uint2 *>(erow + (ni * 32 + g * 8 + kh * 4) * 2) = v;
+                        }
+                }
+                __builtin_amdgcn_wave_barrier();
+                uint16_t *__restrict__ Out = reinterpret_cast<uint16_t *>(p.out);
+                const int rr = lane / LPR, cc = lane % LPR;
+                const int n = n0 + cc * 8;
+#pragma unroll 4
+                for (int it = 0; it < (WM / 2) / RPI; ++it) {
+                    const uint8_t *erow = area + (it * RPI + rr) * EP;
+                    const uint4 v = *reinterpret_cast<const uint4 *>(erow + cc * 16);
+                    const int tok = *reinterpret_cast<const int32_t *>(erow + WN * 2);
+                    if (tok >= 0 && n < N) *reinterpret_cast<uint4 *>(Out + (int64_t)tok * p.ldo + n) = v;
+                }
+            };
+            if (wn == 0) finish(std::integral_constant<int, 0>{}, std::true_type{}, xu);
+            else finish(std::integral_constant<int, MH>{}, std::false_type{}, xg);
+            return;
         }
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
