@@ -239,6 +239,17 @@ int collm_debug_device_token_map(collm_ctx *ctx, int32_t *tok_segment, int32_t *
                                  uint8_t *tok_is_train);
 
 /*
+ * Debug, HOST only (no GPU): the order in which the plan lists the rows of a batch for the GEMM
+ * over all rows (training_rows_only = 0) or over the training rows (1), and the number of
+ * 16-wide low-rank K-steps every row tile of tile_rows (64, 128 or 256) rows carries.
+ * row_tok receives the token of every row (n_tokens entries at most), tile_steps one entry per
+ * row tile.  Returns the number of rows (>= 0) or a negative status.
+ */
+int collm_debug_host_row_order(const collm_shape *shape, const int32_t *rank, const int32_t *seg_start,
+                               const int32_t *seg_adapter, const uint8_t *seg_is_train, int tile_rows,
+                               int training_rows_only, int32_t *row_tok, int32_t *tile_steps);
+
+/*
  * Debug/tuning: force the tile shape of the forward GEMM and of the dX GEMM
  * (0: 256x256, 1: 256x128, 2: 128x128 rows x columns of the output, 3: 256x256 run by eight
  * waves instead of four; -1: let the library

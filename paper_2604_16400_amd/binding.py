@@ -101,6 +101,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.collm_token_map.restype = ctypes.c_int
     lib.collm_debug_device_token_map.argtypes = [vp, _i32p, _i32p, _u8p]
     lib.collm_debug_device_token_map.restype = ctypes.c_int
+    lib.collm_debug_host_row_order.argtypes = [sp, _i32p, _i32p, _i32p, _u8p, ctypes.c_int, ctypes.c_int, _i32p, _i32p]
+    lib.collm_debug_host_row_order.restype = ctypes.c_int
     lib.collm_debug_set_tiles.argtypes = [vp, ctypes.c_int, ctypes.c_int]
     lib.collm_debug_set_tiles.restype = ctypes.c_int
     lib.collm_debug_set_wide_pass.argtypes = [vp, ctypes.c_int]
@@ -151,6 +153,23 @@ def collm_token_map(seg_start, seg_adapter, seg_is_train, n_tokens: Optional[int
                                st.ctypes.data_as(_u8p), ts.ctypes.data_as(_i32p), ta.ctypes.data_as(_i32p),
                                tt.ctypes.data_as(_u8p)), "collm_token_map")
     return ts, ta, tt
+
+
+def host_row_order(rank, seg_start, seg_adapter, seg_is_train, tile_rows: int = 256, training_rows_only: bool = False):
+    """(row_tok, tile_steps) of the plan for this batch, built on the host (no GPU needed)."""
+    lib = load_library()
+    ss, sa, st = _seg_arrays(seg_start, seg_adapter, seg_is_train)
+    rk = np.ascontiguousarray(rank, dtype=np.int32)
+    T = int(ss[-1])
+    sh = collm_shape(8, 8, T, len(sa), len(rk), COLLM_BF16, 1.0, LAYOUT_IN_OUT)
+    row_tok = np.full(max(T, 1), -7, np.int32)
+    steps = np.full((T + tile_rows - 1) // tile_rows + 1, -7, np.int32)
+    n = lib.collm_debug_host_row_order(ctypes.byref(sh), rk.ctypes.data_as(_i32p), ss.ctypes.data_as(_i32p),
+                                       sa.ctypes.data_as(_i32p), st.ctypes.data_as(_u8p), tile_rows,
+                                       1 if training_rows_only else 0, row_tok.ctypes.data_as(_i32p),
+                                       steps.ctypes.data_as(_i32p))
+    _check(min(n, 0), "collm_debug_host_row_order")
+    return row_tok[:n], steps[: (n + tile_rows - 1) // tile_rows]
 
 
 class PointerTable:

@@ -623,6 +623,32 @@ int collm_ctx_destroy(collm_ctx *c)
 
 int64_t collm_ctx_workspace_bytes(const collm_ctx *c) { return c ? c->workspace_bytes : 0; }
 
+int collm_debug_host_row_order(const collm_shape *s, const int32_t *rank, const int32_t *seg_start,
+                               const int32_t *seg_adapter, const uint8_t *seg_is_train, int tile_rows,
+                               int training_rows_only, int32_t *row_tok, int32_t *tile_steps)
+{
+    if (!s || !seg_start || !row_tok || !tile_steps) return COLLM_E_NULL;
+    if (tile_rows != 64 && tile_rows != 128 && tile_rows != 256) return COLLM_E_SHAPE;
+    int rc = validate_batch(s, rank, seg_start, seg_adapter, seg_is_train, 256);
+    if (rc != COLLM_OK) return rc;
+    PlanRequest rq;
+    rq.shape = s;
+    rq.rank = rank;
+    rq.seg_start = seg_start;
+    rq.seg_adapter = seg_adapter;
+    rq.seg_is_train = seg_is_train;
+    rq.bm_all = rq.bm_train = tile_rows;
+    std::vector<int32_t> plan;
+    PlanLayout L;
+    rc = build_plan(rq, plan, L);
+    if (rc != COLLM_OK) return rc;
+    const RowOrderLayout &R = training_rows_only ? L.train : L.all;
+    for (int i = 0; i < R.n_rows; ++i) row_tok[i] = plan[R.off_row_tok + i];
+    const int n_tiles = (R.n_rows + tile_rows - 1) / tile_rows;
+    for (int t = 0; t < n_tiles; ++t) tile_steps[t] = plan[R.off_ext_off + t + 1] - plan[R.off_ext_off + t];
+    return R.n_rows;
+}
+
 int collm_debug_set_tiles(collm_ctx *c, int fwd_tile, int bwd_tile)
 {
     if (!c) return COLLM_E_NULL;

@@ -443,8 +443,31 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         }
         return bt;
     };
-    ExtBatch first_b{};
-    if constexpr (!PARTIAL) first_b = fetch_batch(e0);
+    // The first 64 step records of the tile are fetched once, one per lane, before any direct load is in
+    // flight; a batch then comes out of the lanes with readlane.  (Tiles with more steps fetch the later
+    // batches through the scalar cache.)
+    uint4 rec = make_uint4(0u, 0u, 0u, 0u);
+    if constexpr (!PARTIAL) {
+        if (e0 + lane < e1) rec = *reinterpret_cast<const uint4 *>(p.ext + e0 + lane);
+        asm volatile("" : "+v"(rec.x), "+v"(rec.y), "+v"(rec.z), "+v"(rec.w));  // the load completes here
+    }
+    auto get_batch = [&](int eb) {
+        const int rel = eb - e0;
+        if (rel + kExtBatch > 64) return fetch_batch(eb);
+        ExtBatch bt;
+#pragma unroll
+        for (int j = 0; j < kExtBatch; ++j) {
+            const bool on = eb + j < e1;
+            const uint32_t kr = (uint32_t)__builtin_amdgcn_readlane((int)rec.x, rel + j);
+            const uint32_t rows = (uint32_t)__builtin_amdgcn_readlane((int)rec.y, rel + j);
+            const uint32_t tlo = (uint32_t)__builtin_amdgcn_readlane((int)rec.z, rel + j);
+            const uint32_t thi = (uint32_t)__builtin_amdgcn_readlane((int)rec.w, rel + j);
+            bt.kr[j] = on ? kr : 0u;
+            bt.rows[j] = on ? rows : 0u;
+            bt.tab[j] = ((uint64_t)thi << 32) | tlo;
+        }
+        return bt;
+    };
 
     // ---- per-thread source offsets (bytes) ------------------------------------------------
     // A thread owns fixed LDS positions: in K-major tiles row r8 + i NT/8, chunk position c8;
@@ -774,112 +797,141 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         const uint64_t zeros = reinterpret_cast<uint64_t>(p.zeros);
         // per-lane choice among the four steps of a batch
         auto pick = [](int j, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3) { return j == 0 ? v0 : (j == 1 ? v1 : (j == 2 ? v2 : v3)); };
-        auto issue_batch = [&](int stage, const ExtBatch &bt) {
-            // rows: position c8 of row r holds chunk cl; chunk cl belongs to step cl / 2, rank
-            // indices koff + 8 (cl % 2) ..
-#pragma unroll
-            for (int i = 0; i < ACH; ++i) {
+        constexpr int ND = ACH + BCH;  // direct loads (16 bytes per lane each) of a batch per wave
+        // piece d of a batch: chunk d of the rows' operand, or chunk d - ACH of the tables'
+        // (called with d known after unrolling: the branches and the step index fold away)
+        // live = false: the piece only fills its place with zeros (no memory is read)
+        auto issue_piece = [&](int stage, const ExtBatch &bt, const int D, const bool live) {
+            if (D < ACH) {
+                // rows: position c8 of row r holds chunk cl; chunk cl belongs to step cl / 2, rank
+                // indices koff + 8 (cl % 2) ..
+                const int i = D;
                 const int r = r8 + i * (NT / 8);
                 const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
                 const int j = cl >> 1;
                 const uint32_t kr = pick(j, bt.kr[0], bt.kr[1], bt.kr[2], bt.kr[3]);
                 const uint32_t rows = pick(j, bt.rows[0], bt.rows[1], bt.rows[2], bt.rows[3]);
                 // siblings: the columns after a sibling's own are the next sibling's, or were never written
-                const bool in = r >= (int)(rows & 0xffffu) && r < (int)(rows >> 16) &&
+                const bool in = live && r >= (int)(rows & 0xffffu) && r < (int)(rows >> 16) &&
                                 (p.n_sib <= 1 || (kr & 0xffffu) + (cl & 1) * 8u < (kr >> 16));
                 const uint32_t off = in ? ((uint32_t)(m0 + r) * (uint32_t)p.hs_ld + (uint32_t)sib * (kr >> 16) + (kr & 0xffffu) + (cl & 1) * 8u) * 2u : kOob;
                 dma16(rh_w, off, lds_wave + (stage ? A_ST1 : 0) + i * (NT / 64) * 1024);
-            }
-            if constexpr (!B_KMAJOR) {
+            } else if constexpr (!B_KMAJOR) {
                 // table rows are rank indices: B_a[q][n]; tile row 16 j + i is rank index koff_j + i.
                 // All lanes of a load belong to one step, whose table is the load's buffer: rank
                 // indices beyond the rank lie beyond it.
                 static_assert(16 % (NT / NG) == 0 || (NT / NG) % 16 == 0, "a direct load must not straddle two steps");
-#pragma unroll
-                for (int i = 0; i < BCH; ++i) {
-                    const int j = (i * (NT / NG)) >> 4;
-                    const int k = bk0 + i * (NT / NG);
-                    uint32_t rk = bt.kr[j] >> 16, koff = bt.kr[j] & 0xffffu;
-                    bool mine = true;
-                    if constexpr (SWIGLU) {
-                        // the step belongs to the gate sibling (first half of the ranks) or the up sibling
-                        rk >>= 1;
-                        const bool up = koff >= rk;
-                        koff -= up ? rk : 0u;
-                        mine = (bcl * 8 >= BN / 2) == up;
-                    }
-                    const i32x4 rt = make_rsrc_words(reinterpret_cast<const void *>(bt.tab[j]), rk * (uint32_t)p.ext_ld * 2u);
-                    const uint32_t off = (mine && col_on(bcl * 8)) ? ((koff + (uint32_t)(k & 15)) * (uint32_t)p.ext_ld + (uint32_t)src_col(bcl * 8)) * 2u : kOob;
-                    dma16(rt, off, lds_wave + (stage ? B_ST1 : B_ST0) + i * (NT / 64) * 1024);
+                const int i = D - ACH;
+                const int j = (i * (NT / NG)) >> 4;
+                const int k = bk0 + i * (NT / NG);
+                uint32_t rk = bt.kr[j] >> 16, koff = bt.kr[j] & 0xffffu;
+                bool mine = true;
+                if constexpr (SWIGLU) {
+                    // the step belongs to the gate sibling (first half of the ranks) or the up sibling
+                    rk >>= 1;
+                    const bool up = koff >= rk;
+                    koff -= up ? rk : 0u;
+                    mine = (bcl * 8 >= BN / 2) == up;
                 }
+                const i32x4 rt = make_rsrc_words(reinterpret_cast<const void *>(bt.tab[j]), rk * (uint32_t)p.ext_ld * 2u);
+                const uint32_t off = (live && mine && col_on(bcl * 8)) ? ((koff + (uint32_t)(k & 15)) * (uint32_t)p.ext_ld + (uint32_t)src_col(bcl * 8)) * 2u : kOob;
+                dma16(rt, off, lds_wave + (stage ? B_ST1 : B_ST0) + i * (NT / 64) * 1024);
             } else {
                 // table rows are output columns: A_a[n][q], row length rank.  The four steps of a
                 // batch may have four tables, so every lane forms its own 64-bit address.
+                const int i = D - ACH;
                 const bool all8 = (((bt.kr[0] | bt.kr[1] | bt.kr[2] | bt.kr[3]) >> 16) & 7u) == 0;
+                const int r = r8 + i * (NT / 8);
+                const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
+                const int j = cl >> 1;
+                const uint32_t kr = pick(j, bt.kr[0], bt.kr[1], bt.kr[2], bt.kr[3]);
+                const uint32_t tlo = pick(j, (uint32_t)bt.tab[0], (uint32_t)bt.tab[1], (uint32_t)bt.tab[2], (uint32_t)bt.tab[3]);
+                const uint32_t thi = pick(j, (uint32_t)(bt.tab[0] >> 32), (uint32_t)(bt.tab[1] >> 32), (uint32_t)(bt.tab[2] >> 32), (uint32_t)(bt.tab[3] >> 32));
                 if (all8) {
-#pragma unroll
-                    for (int i = 0; i < BCH; ++i) {
-                        const int r = r8 + i * (NT / 8);
-                        const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
-                        const int j = cl >> 1;
-                        const uint32_t kr = pick(j, bt.kr[0], bt.kr[1], bt.kr[2], bt.kr[3]);
-                        const uint32_t tlo = pick(j, (uint32_t)bt.tab[0], (uint32_t)bt.tab[1], (uint32_t)bt.tab[2], (uint32_t)bt.tab[3]);
-                        const uint32_t thi = pick(j, (uint32_t)(bt.tab[0] >> 32), (uint32_t)(bt.tab[1] >> 32), (uint32_t)(bt.tab[2] >> 32), (uint32_t)(bt.tab[3] >> 32));
-                        const uint32_t rk = kr >> 16, q0 = (kr & 0xffffu) + (cl & 1) * 8u;
-                        const bool in = n0 + r < N && q0 < rk;
-                        const uint64_t addr = in ? (((uint64_t)thi << 32) | tlo) + ((uint64_t)(n0 + r) * rk + q0) * 2u : zeros;
-                        dma16g(addr, lds_wave + (stage ? B_ST1 : B_ST0) + i * (NT / 64) * 1024);
-                    }
+                    const uint32_t rk = kr >> 16, q0 = (kr & 0xffffu) + (cl & 1) * 8u;
+                    const bool in = live && n0 + r < N && q0 < rk;
+                    const uint64_t addr = in ? (((uint64_t)thi << 32) | tlo) + ((uint64_t)(n0 + r) * rk + q0) * 2u : zeros;
+                    dma16g(addr, lds_wave + (stage ? B_ST1 : B_ST0) + i * (NT / 64) * 1024);
                 } else {
                     // some rank is no multiple of 8: table rows are not 16-byte aligned; element by element
                     uint8_t *tb = smem + (stage ? B_ST1 : B_ST0);
+                    const int rk = (int)(kr >> 16), q0 = (int)(kr & 0xffffu) + (cl & 1) * 8;
+                    uint16_t e[8];
 #pragma unroll
-                    for (int i = 0; i < BCH; ++i) {
-                        const int r = r8 + i * (NT / 8);
-                        const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
-                        const int j = cl >> 1;
-                        const uint32_t kr = pick(j, bt.kr[0], bt.kr[1], bt.kr[2], bt.kr[3]);
-                        const uint32_t tlo = pick(j, (uint32_t)bt.tab[0], (uint32_t)bt.tab[1], (uint32_t)bt.tab[2], (uint32_t)bt.tab[3]);
-                        const uint32_t thi = pick(j, (uint32_t)(bt.tab[0] >> 32), (uint32_t)(bt.tab[1] >> 32), (uint32_t)(bt.tab[2] >> 32), (uint32_t)(bt.tab[3] >> 32));
-                        const int rk = (int)(kr >> 16), q0 = (int)(kr & 0xffffu) + (cl & 1) * 8;
-                        uint16_t e[8];
+                    for (int q = 0; q < 8; ++q) e[q] = 0;
+                    if (live && n0 + r < N) {
+                        const uint16_t *src = reinterpret_cast<const uint16_t *>(((uint64_t)thi << 32) | tlo) + (int64_t)(n0 + r) * rk + q0;
 #pragma unroll
-                        for (int q = 0; q < 8; ++q) e[q] = 0;
-                        if (n0 + r < N) {
-                            const uint16_t *src = reinterpret_cast<const uint16_t *>(((uint64_t)thi << 32) | tlo) + (int64_t)(n0 + r) * rk + q0;
-#pragma unroll
-                            for (int q = 0; q < 8; ++q)
-                                if (q0 + q < rk) e[q] = src[q];
-                        }
-                        uint4 v;
-                        v.x = e[0] | ((uint32_t)e[1] << 16);
-                        v.y = e[2] | ((uint32_t)e[3] << 16);
-                        v.z = e[4] | ((uint32_t)e[5] << 16);
-                        v.w = e[6] | ((uint32_t)e[7] << 16);
-                        *reinterpret_cast<uint4 *>(tb + (r8 + i * (NT / 8)) * 128 + c8 * 16) = v;
+                        for (int q = 0; q < 8; ++q)
+                            if (q0 + q < rk) e[q] = src[q];
                     }
+                    uint4 v;
+                    v.x = e[0] | ((uint32_t)e[1] << 16);
+                    v.y = e[2] | ((uint32_t)e[3] << 16);
+                    v.z = e[4] | ((uint32_t)e[5] << 16);
+                    v.w = e[6] | ((uint32_t)e[7] << 16);
+                    *reinterpret_cast<uint4 *>(tb + (r8 + i * (NT / 8)) * 128 + c8 * 16) = v;
                 }
             }
         };
+        auto issue_batch = [&](int stage, const ExtBatch &bt) {
+#pragma unroll
+            for (int d = 0; d < ND; ++d) issue_piece(stage, bt, d, true);
+        };
 
-        issue_batch(0, first_b);
-        ExtBatch nxt_b = fetch_batch(e0 + kExtBatch);
+        // A step touches only the rows of its adapter: a wave multiplies only those of its 32-row blocks that
+        // the step's row range reaches (the others would add zeros).  `rows` = lo | hi << 16, uniform.
+        const int wrow0 = __builtin_amdgcn_readfirstlane(wm * WM);
+        auto block_on = [&](uint32_t rows, int mi) {
+            const int lo = (int)(rows & 0xffffu), hi = (int)(rows >> 16);
+            return lo < wrow0 + mi * 32 + 32 && hi > wrow0 + mi * 32;
+        };
+        auto mma_rows = [&](int buf, uint32_t rows) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                if (block_on(rows, mi)) {
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni)
+                        acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[buf][ni], af[buf][mi], acc[ni][mi], 0, 0, 0);
+                }
+            }
+        };
+        ExtBatch cur_b = get_batch(e0);
+        issue_batch(0, cur_b);
+        ExtBatch nxt_b = get_batch(e0 + kExtBatch);
         int stage = 0;
         for (int eb = e0; eb < e1; eb += kExtBatch, stage ^= 1) {
             drain_and_barrier();  // this batch has landed; the stage of the batch before it is free
             const int nsteps = (e1 - eb) < kExtBatch ? (e1 - eb) : kExtBatch;
-            if (eb + kExtBatch < e1) issue_batch(stage ^ 1, nxt_b);
-            nxt_b = fetch_batch(eb + 2 * kExtBatch);  // a short wait, in the shadow of the loads just issued
             read_frags(stage, 0, 0);
+            if (nsteps > 1) read_frags(stage, 1, 1);
+            {
+                // step 0, with the loads of the next batch (addresses and all) riding behind its MFMAs; after
+                // the last batch they only write zeros into the stage that is free
+                const bool more = eb + kExtBatch < e1;
+                constexpr int NM = MI * NI;
 #pragma unroll
-            for (int ks = 0; ks < kExtBatch; ++ks) {
-                if (ks < nsteps) {
-                    if (ks + 1 < nsteps) read_frags(stage, ks + 1, (ks + 1) & 1);
-                    mma(ks & 1);
+                for (int mi = 0; mi < MI; ++mi) {
+                    if (block_on(cur_b.rows[0], mi)) {
+#pragma unroll
+                        for (int ni = 0; ni < NI; ++ni)
+                            acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[0][ni], af[0][mi], acc[ni][mi], 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int d = mi * ND / MI; d < (mi + 1) * ND / MI; ++d) issue_piece(stage ^ 1, nxt_b, d, more);
                 }
             }
+#pragma unroll
+            for (int ks = 1; ks < kExtBatch; ++ks) {
+                if (ks < nsteps) {
+                    if (ks + 1 < nsteps) read_frags(stage, ks + 1, (ks + 1) & 1);
+                    mma_rows(ks & 1, cur_b.rows[ks]);
+                }
+            }
+            cur_b = nxt_b;
+            nxt_b = get_batch(eb + 2 * kExtBatch);
         }
-        __syncthreads();
+        drain_and_barrier();  // the zero fills behind the last batch have landed: LDS is free for the epilogue
     }
 
     // ---- epilogue: one rounding to bf16, rows scattered back to their tokens --------------

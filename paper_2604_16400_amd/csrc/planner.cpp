@@ -60,7 +60,7 @@ struct Builder {
 void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &tokens,
                      const int32_t *tok_adapter, const int32_t *rank, int n_adapters, int bm,
                      const void *const *ext_tab, int max_row_tiles, int rpad, int wide_min_rows,
-                     const int32_t *rank_ext)
+                     const int32_t *rank_ext, bool split_runs)
 {
     const int n = (int)tokens.size();
     L.n_rows = n;
@@ -68,19 +68,78 @@ void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &
     L.off_row_tok = b.alloc(L.n_rows_pad);
     L.off_row_adapter = b.alloc(L.n_rows_pad);
 
-    // counting sort by key = adapter + 1 (base-only rows first), stable in token order
-    std::vector<int32_t> start(n_adapters + 2, 0);
-    for (int i = 0; i < n; ++i) start[tok_adapter[tokens[i]] + 2]++;
-    for (int k = 1; k < n_adapters + 2; ++k) start[k] += start[k - 1];
+    // Rows in runs of one adapter, stable in token order inside an adapter; base-only rows first.  Where the
+    // runs lie is free, and it decides how the extension steps spread over the GEMM row tiles: every adapter
+    // that reaches into a tile costs that tile its K-steps, and the tiles with the most steps finish last.
+    // With adapters of very different popularity, listing them by index would pile the many rare ones into
+    // the last tiles.  So (split_runs): the adapters with less than a tile of rows are dealt out over the
+    // tiles in proportion to the rows passed, each as one run, and the rows of the larger adapters fill
+    // what is left of every tile (they reach into several tiles anyway).  Without split_runs every adapter
+    // is one run (what the gradient items need), larger adapters first.
+    std::vector<int32_t> count(n_adapters + 1, 0);  // [0]: base-only rows
+    for (int i = 0; i < n; ++i) count[tok_adapter[tokens[i]] + 1]++;
+    struct Run {
+        int32_t adapter, lo, len;
+    };
+    std::vector<Run> runs;  // in row order
+    {
+        std::vector<int32_t> big, small_;
+        for (int a = 0; a < n_adapters; ++a) {
+            if (count[a + 1] >= bm) big.push_back(a);
+            else if (count[a + 1] > 0) small_.push_back(a);
+        }
+        auto larger = [&](int32_t x, int32_t y) { return count[x + 1] > count[y + 1]; };
+        std::stable_sort(big.begin(), big.end(), larger);
+        std::stable_sort(small_.begin(), small_.end(), larger);
+        int32_t pos = count[0];
+        const int64_t adapter_rows = n - count[0];
+        size_t dealt = 0, bi = 0;
+        int32_t rem = big.empty() ? 0 : count[big[0] + 1];
+        auto put = [&](int32_t a, int32_t len) {
+            if (!runs.empty() && runs.back().adapter == a) runs.back().len += len;
+            else runs.push_back({a, pos, len});
+            pos += len;
+        };
+        while (pos < n) {
+            const int32_t tile_end = std::min(n, (pos / bm + 1) * bm);
+            size_t due = bi < big.size() ? (size_t)((int64_t)small_.size() * (tile_end - count[0]) / adapter_rows)
+                                         : small_.size();
+            if (!split_runs) due = bi < big.size() ? 0 : small_.size();
+            while (dealt < due && dealt < small_.size()) {
+                put(small_[dealt], count[small_[dealt] + 1]);
+                ++dealt;
+            }
+            const int32_t fill_end = split_runs ? tile_end : n;
+            while (pos < fill_end && bi < big.size()) {
+                const int32_t take = std::min(rem, fill_end - pos);
+                put(big[bi], take);
+                rem -= take;
+                if (rem == 0 && ++bi < big.size()) rem = count[big[bi] + 1];
+            }
+        }
+    }
     {
         int32_t *row_tok = b.blk.data() + L.off_row_tok;
         int32_t *row_ad = b.blk.data() + L.off_row_adapter;
-        std::vector<int32_t> cur(start.begin(), start.end() - 1);
+        // the tokens of an adapter fill its runs in row order
+        std::vector<std::vector<int32_t>> runs_of(n_adapters);
+        for (size_t k = 0; k < runs.size(); ++k) runs_of[runs[k].adapter].push_back((int32_t)k);
+        std::vector<int32_t> which(n_adapters, 0), used(n_adapters, 0);
+        int32_t base_pos = 0;
         for (int i = 0; i < n; ++i) {
             const int a = tok_adapter[tokens[i]];
-            const int pos = cur[a + 1]++;
-            row_tok[pos] = tokens[i];
-            row_ad[pos] = a;
+            int32_t pos_i;
+            if (a < 0) {
+                pos_i = base_pos++;
+            } else {
+                if (used[a] == runs[runs_of[a][which[a]]].len) {
+                    ++which[a];
+                    used[a] = 0;
+                }
+                pos_i = runs[runs_of[a][which[a]]].lo + used[a]++;
+            }
+            row_tok[pos_i] = tokens[i];
+            row_ad[pos_i] = a;
         }
         for (int i = n; i < L.n_rows_pad; ++i) {
             row_tok[i] = -1;
@@ -98,9 +157,10 @@ void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &
     // Long runs go to the tiled pass instead (items of up to kWideRows rows: an adapter's table is fetched
     // once per 128 rows); what a run leaves over below the threshold stays a skinny item.
     std::vector<SkinnyItem> items, wide;
-    for (int a = 0; a < n_adapters; ++a) {
-        int lo = start[a + 1];
-        const int hi = start[a + 2];
+    for (const Run &run : runs) {
+        const int32_t a = run.adapter;
+        int lo = run.lo;
+        const int hi = run.lo + run.len;
         if (wide_min_rows > 0 && rank[a] % 8 == 0) {
             while (hi - lo >= wide_min_rows) {
                 const int m = std::min(kWideRows, hi - lo);
@@ -212,9 +272,9 @@ int build_plan(const PlanRequest &rq, std::vector<int32_t> &blk, PlanLayout &L)
         std::vector<int32_t> tok_adapter(blk.begin() + L.off_tok_adapter,
                                          blk.begin() + L.off_tok_adapter + T);
         build_row_order(b, L.all, all, tok_adapter.data(), rq.rank, N, rq.bm_all, rq.B, rq.max_row_tiles, L.rpad, rq.wide_min_rows_all,
-                        rq.rank_ext_all ? rq.rank_ext_all : rq.rank);
+                        rq.rank_ext_all ? rq.rank_ext_all : rq.rank, true);
         build_row_order(b, L.train, train, tok_adapter.data(), rq.rank, N, rq.bm_train, rq.A, rq.max_row_tiles, L.rpad, rq.wide_min_rows_train,
-                        rq.rank);
+                        rq.rank, false);
     }
 
     // gradient items: one per trained adapter, rows contiguous in the training row order

@@ -79,3 +79,56 @@ def test_token_map_rejects_bad_tables():
     with pytest.raises(binding.CollmError) as e:
         f([0, 3], [-2], [0], n_adapters=5)
     assert e.value.status == -4
+
+
+# ---------------------------------------------------------------------------------------------
+# the plan's row order (host logic): rows in runs of one adapter, low-rank K-steps per row tile
+# ---------------------------------------------------------------------------------------------
+def _steps_from_rows(row_tok, tok_adapter, ranks, tile_rows):
+    """K-steps per row tile, counted from the row order: every maximal run of one adapter inside a
+    tile costs ceil(rank / 16) steps."""
+    out = []
+    for t0 in range(0, len(row_tok), tile_rows):
+        ads = tok_adapter[row_tok[t0:t0 + tile_rows]]
+        n = 0
+        for i, a in enumerate(ads):
+            if a >= 0 and (i == 0 or ads[i - 1] != a):
+                n += (int(ranks[a]) + 15) // 16
+        out.append(n)
+    return np.array(out, dtype=np.int32)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("tile_rows", [128, 256])
+def test_plan_row_order_is_a_grouping_and_counts_its_steps(cfg, tile_rows):
+    w = wl.make_config(cfg)
+    _, ta, tt = oracle.token_map(w.seg_start, w.seg_adapter, w.seg_is_train)
+    row_tok, steps = binding.host_row_order(w.ranks, w.seg_start, w.seg_adapter, w.seg_is_train, tile_rows)
+    assert sorted(row_tok.tolist()) == list(range(w.n_tokens))           # every token exactly once
+    ads = ta[row_tok]
+    n_base = int((ta < 0).sum())
+    assert np.all(ads[:n_base] < 0) and np.all(ads[n_base:] >= 0)        # base-only rows first
+    for a in range(w.n_adapters):                                         # token order kept inside an adapter
+        toks = row_tok[ads == a]
+        assert np.all(np.diff(toks) > 0)
+    assert np.array_equal(steps, _steps_from_rows(row_tok, ta, w.ranks, tile_rows))
+    # training rows: one run per adapter (the gradient items are runs)
+    row_tr, steps_tr = binding.host_row_order(w.ranks, w.seg_start, w.seg_adapter, w.seg_is_train, tile_rows, True)
+    assert sorted(row_tr.tolist()) == np.flatnonzero(tt).tolist()
+    ads_tr = ta[row_tr]
+    changes = int((np.diff(ads_tr) != 0).sum()) + 1 if len(ads_tr) else 0
+    assert changes == len(np.unique(ads_tr))
+    assert np.array_equal(steps_tr, _steps_from_rows(row_tr, ta, w.ranks, tile_rows))
+
+
+def test_plan_spreads_rare_adapters_over_the_row_tiles():
+    # configuration 3: 32 adapters of rank 64 with Zipf popularity.  Listed by adapter index, the rare ones
+    # would share the last tiles (11 adapters = 44 steps in one of them); dealt out, no tile carries more than
+    # a few adapters beside the large ones that fill it.
+    w = wl.make_config(3)
+    _, ta, _ = oracle.token_map(w.seg_start, w.seg_adapter, w.seg_is_train)
+    _, steps = binding.host_row_order(w.ranks, w.seg_start, w.seg_adapter, w.seg_is_train, 256)
+    by_index = _steps_from_rows(np.argsort(ta, kind="stable").astype(np.int32), ta, w.ranks, 256)
+    assert by_index.max() >= 40
+    assert steps.max() <= 20 and steps.max() <= by_index.max() // 2
+    assert steps.sum() <= by_index.sum() + 4 * len(steps)   # at most one more run per tile, of rank 64
