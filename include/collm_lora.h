@@ -258,6 +258,14 @@ int collm_debug_host_row_order(const collm_shape *shape, const int32_t *rank, co
 int collm_debug_set_tiles(collm_ctx *ctx, int fwd_tile, int bwd_tile);
 
 /*
+ * Debug/tuning: into how many slices of K a GEMM with few rows (fewer than 256 tiles of
+ * 128x128) is cut across blocks; the slices' fp32 sums are added by a second kernel before the
+ * single rounding.  -1: let the library choose; 1: never; 2..64: that many (as far as K and
+ * the workspace allow).  bf16 only.  Affects only speed and rounding order.
+ */
+int collm_debug_set_gemm_split(collm_ctx *ctx, int n_slices);
+
+/*
  * Debug/tuning: which rows the rank-wide passes (h = x A, dh = dy B^T) run as 128-row tiles
  * rather than 16-row items: runs of at least min_rows rows of one adapter whose rank is a
  * multiple of 8.  0: never; -1: let the library choose (every such adapter when the widest

@@ -105,6 +105,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.collm_debug_host_row_order.restype = ctypes.c_int
     lib.collm_debug_set_tiles.argtypes = [vp, ctypes.c_int, ctypes.c_int]
     lib.collm_debug_set_tiles.restype = ctypes.c_int
+    lib.collm_debug_set_gemm_split.argtypes = [vp, ctypes.c_int]
+    lib.collm_debug_set_gemm_split.restype = ctypes.c_int
     lib.collm_debug_set_wide_pass.argtypes = [vp, ctypes.c_int]
     lib.collm_debug_set_wide_pass.restype = ctypes.c_int
     lib.collm_profile_enable.argtypes = [vp, ctypes.c_int]
@@ -221,6 +223,9 @@ class Context:
 
     def set_tiles(self, fwd_tile: int = TILE_AUTO, bwd_tile: int = TILE_AUTO):
         _check(self._lib.collm_debug_set_tiles(self._h, fwd_tile, bwd_tile), "collm_debug_set_tiles")
+
+    def set_gemm_split(self, n_slices: int = -1):
+        _check(self._lib.collm_debug_set_gemm_split(self._h, n_slices), "collm_debug_set_gemm_split")
 
     def set_wide_pass(self, min_rows: int = -1):
         _check(self._lib.collm_debug_set_wide_pass(self._h, min_rows), "collm_debug_set_wide_pass")

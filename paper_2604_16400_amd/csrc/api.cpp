@@ -80,6 +80,7 @@ struct collm_ctx {
 
     int tile_fwd = -1, tile_bwd = -1;  // forced GEMM tile shapes (-1 = choose)
     int wide_min_rows = -1;            // forced threshold of the tiled rank-wide pass (-1 = choose, 0 = never)
+    int gemm_split = -1;               // forced number of K slices of a GEMM with few rows (-1 = choose, 1 = never)
     int key_wide = 0, key_nsib = 0;
     std::vector<int32_t> sum_rank;     // sibling calls: ranks summed over the siblings
     hipStream_t last_stream = nullptr;
@@ -162,6 +163,28 @@ hipError_t run_gemm(collm_ctx *c, GemmArgs g, const RowOrderLayout &R, int rows,
     g.tiles_m = t.big_tiles_m;
     g.ext_off = c->d_plan + R.off_ext_off;
     g.ext = reinterpret_cast<const ExtStep *>(c->d_plan + R.off_ext);
+    if (!swiglu && forced_tile < 0 && c->gemm_split != 1 && t.tile == kTile128x128 && t.tail_tiles_m == 0) {
+        // Few rows against a long contraction (decode-sized batches): too few tiles to fill the GPU, each walking all
+        // of K with one tile of loads in flight.  Cut K into slices so that up to two blocks per CU exist, as long as a
+        // slice keeps 512 K values and the fp32 partial sums fit the workspace; a second kernel adds the slices.
+        const int tiles_n = (cols + 127) / 128;
+        const long tiles = (long)t.big_tiles_m * tiles_n;
+        const long per_slice = (long)t.big_tiles_m * 128 * cols * 4;
+        long want = c->gemm_split > 1 ? c->gemm_split : (tiles <= 256 ? (448 + tiles - 1) / tiles : 1);
+        want = std::min<long>({want, c->gemm_split > 1 ? g.K / 64 : g.K / 512, (long)c->part_bytes / per_slice, 64L});
+        if (want >= 2) {
+            g.tiles_n = tiles_n;
+            g.k_per_split = round_up((int)((g.K + want - 1) / want), 64);
+            const int n_split = (g.K + g.k_per_split - 1) / g.k_per_split;
+            g.part = c->d_part;
+            g.part_rows = t.big_tiles_m * 128;
+            g.part_ld = cols;
+            g.n_rows = rows;
+            hipError_t e = launch_gemm_splitk(g, n_split, b_kmajor, st);
+            if (e != hipSuccess) return e;
+            return launch_gemm_finish(g, n_split, st);
+        }
+    }
     hipError_t e = launch(t.tile);
     if (e != hipSuccess || t.tail_tiles_m == 0) return e;
     g.tile_m_base = 2 * t.big_tiles_m;
@@ -577,6 +600,8 @@ int collm_ctx_create(collm_ctx **out, int device, int32_t max_tokens, int32_t ma
     const size_t act = (size_t)c->rows_cap * c->rpad_cap;
     // partial sums of the K slices: room for kSkinnyMaxSplit slices, but no more than 64 MiB (at least one)
     c->part_bytes = std::max(act * 4, std::min(act * 4 * kSkinnyMaxSplit, (size_t)64 << 20));
+    // ... and of a GEMM with few rows: up to 8 slices of 512 rows of the widest output
+    c->part_bytes = std::max(c->part_bytes, std::min((size_t)std::min(c->rows_cap, 512) * (size_t)max_d * 4 * 8, (size_t)64 << 20));
     if (dev_alloc((void **)&c->d_plan, c->plan_cap * sizeof(int32_t)) != hipSuccess ||
         dev_alloc(&c->d_hs, act * 4) != hipSuccess || dev_alloc(&c->d_dhs, act * 4) != hipSuccess ||
         dev_alloc((void **)&c->d_h32, act * 4) != hipSuccess ||
@@ -655,6 +680,14 @@ int collm_debug_set_tiles(collm_ctx *c, int fwd_tile, int bwd_tile)
     if (fwd_tile < -1 || fwd_tile >= kNumTiles || bwd_tile < -1 || bwd_tile >= kNumTiles) return COLLM_E_SHAPE;
     c->tile_fwd = fwd_tile;
     c->tile_bwd = bwd_tile;
+    return COLLM_OK;
+}
+
+int collm_debug_set_gemm_split(collm_ctx *c, int n_slices)
+{
+    if (!c) return COLLM_E_NULL;
+    if (n_slices < -1 || n_slices == 0 || n_slices > 64) return COLLM_E_SHAPE;
+    c->gemm_split = n_slices;
     return COLLM_OK;
 }
 

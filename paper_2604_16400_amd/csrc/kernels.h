@@ -48,6 +48,7 @@ struct GemmArgs {
     float *part;
     int part_rows, part_ld;
     int k_per_split;          // multiple of 64
+    int n_rows;               // launch_gemm_splitk: rows of the row order (part rows beyond them are not written)
     int part_n_sib;           // as SkinnyArgs::n_sib (0 or 1: ranks as the items give them)
     int64_t tab_ld, tab_off;  // as SkinnyArgs
 };
@@ -106,6 +107,11 @@ struct GradArgs {
 };
 
 hipError_t launch_gemm(const GemmArgs &a, int tile_cfg, bool b_kmajor, hipStream_t st);
+// The GEMM with K cut into n_split slices of k_per_split (128x128 tiles): fp32 sums of slice s for row r of the row order at
+// part[(s * part_rows + r) * part_ld + n] (part_ld >= N, a multiple of 4), then launch_gemm_finish adds the slices, rounds
+// and scatters the rows through row_tok.
+hipError_t launch_gemm_splitk(const GemmArgs &a, int n_split, bool b_kmajor, hipStream_t st);
+hipError_t launch_gemm_finish(const GemmArgs &a, int n_split, hipStream_t st);
 // tile_cfg kTile256x256 or kTile128x128; tiles_n counts tiles of half as many output columns as the tile has
 hipError_t launch_gemm_swiglu(const GemmArgs &a, int tile_cfg, hipStream_t st);
 // a, lda, K, a_bytes, row_tok and the fields of the rank-wide pass; everything else is ignored.  Items hold up

@@ -338,10 +338,15 @@ struct DmaSlots {
 // (rank r each, multiples of 16): a step of the first r multiplies into the gate half only, one of the
 // second r into the up half only.  The epilogue passes the up values through LDS and stores
 // silu(gate) * up, rounded once, as [rows][N = d_ff]; training rows also keep both pre-activations.
-template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR, bool PINGPONG, bool PARTIAL = false, bool SWIGLU = false>
+// SPLITK: the GEMM itself with K cut into gridDim.y slices (few rows against a long contraction: too few tiles to
+// fill the GPU).  A block takes one tile and one slice; slice 0 also runs the tile's extension steps; the fp32
+// sums go to the workspace and gemm_finish_kernel adds the slices, rounds once and scatters the rows.
+template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR, bool PINGPONG, bool PARTIAL = false, bool SWIGLU = false,
+          bool SPLITK = false>
 __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 {
     static_assert(!SWIGLU || (!B_KMAJOR && !PINGPONG && !PARTIAL && WGN == 2), "SwiGLU epilogue: N-major, two wave columns");
+    static_assert(!SPLITK || (!PARTIAL && !SWIGLU && !PINGPONG), "K slices: plain tiles only");
     constexpr int NT = WGM * WGN * 64;
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int MI = WM / 32, NI = WN / 32;
@@ -395,6 +400,17 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         m0 = tile_m * BM;
         K = p.K;
         N = p.N;
+        if constexpr (SPLITK) {
+            // the block's slice of K, as above
+            const int k_begin = blockIdx.y * p.k_per_split;
+            K = p.K - k_begin < p.k_per_split ? p.K - k_begin : p.k_per_split;
+            const uint32_t a_skip = (uint32_t)k_begin * 2u;
+            const uint32_t b_skip = B_KMAJOR ? (uint32_t)k_begin * 2u : (uint32_t)k_begin * ldb * 2u;
+            a_base = reinterpret_cast<const uint8_t *>(p.a) + a_skip;
+            a_bytes = p.a_bytes - a_skip;
+            b_base = reinterpret_cast<const uint8_t *>(p.b) + b_skip;
+            b_bytes = B_KMAJOR ? p.b_bytes - b_skip : (uint32_t)K * ldb * 2u;
+        }
     }
     const int n0 = SWIGLU ? tile_n * (BN / 2) : tile_n * BN;
     // tile column c (a multiple of 8) -> column of the second operand and of the expand tables
@@ -420,7 +436,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 
     // extension steps of this row tile; the first batch is fetched now, long before it is needed
     const int e0 = PARTIAL ? 0 : __builtin_amdgcn_readfirstlane(p.ext_off[tile_m]);
-    const int e1 = PARTIAL ? 0 : __builtin_amdgcn_readfirstlane(p.ext_off[tile_m + 1]);
+    const int e1 = PARTIAL ? 0 : ((SPLITK && blockIdx.y != 0) ? e0 : __builtin_amdgcn_readfirstlane(p.ext_off[tile_m + 1]));
     // The records of a batch come through the scalar cache (their own counter, so waiting for them
     // does not wait for the direct loads in flight).  Load and wait are one statement: registers
     // that a load is still writing must never be visible to the compiler, which may move or spill
@@ -940,10 +956,11 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     // with 8 bytes each.  Each wave instead writes its rounded tile to a private LDS area (row
     // pitch EP: the row, then its token index) and reads it back row by row, 16 bytes per lane,
     // so that a store instruction covers whole 128-byte lines of a few rows.
-    if constexpr (PARTIAL) {
-        // fp32 sums of the slice: a lane holds four consecutive rank columns of a row
-        const int q_hi = (N + 15) & ~15;
-        float *__restrict__ part = p.part + ((int64_t)blockIdx.z * p.part_rows + m0) * p.part_ld;
+    if constexpr (PARTIAL || SPLITK) {
+        // fp32 sums of the slice: a lane holds four consecutive (rank) columns of a row
+        const int q_hi = SPLITK ? N : (N + 15) & ~15;
+        if constexpr (SPLITK) rows_in = p.n_rows - m0;  // rows of the order beyond the last are padding
+        float *__restrict__ part = p.part + ((int64_t)(SPLITK ? blockIdx.y : blockIdx.z) * p.part_rows + m0) * p.part_ld;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
             const int r = wm * WM + mi * 32 + rl;
@@ -1656,6 +1673,51 @@ hipError_t launch_skinny_finish(const SkinnyArgs &a, int n_items, int item_rows,
 {
     if (n_items <= 0) return hipSuccess;
     hipLaunchKernelGGL(skinny_finish_kernel, dim3(n_items, (item_rows + 15) / 16), dim3(256), 0, st, a, n_split);
+    return hipGetLastError();
+}
+
+// adds the K slices of a split GEMM in slice order, rounds once and writes the rows to their tokens;
+// block row = row of the order, 4 columns per thread
+__global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p, int n_split)
+{
+    const int r = blockIdx.y;
+    const int tok = p.row_tok[r];
+    const int n = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (tok < 0 || n >= p.N) return;
+    floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int sp = 0; sp < n_split; ++sp)
+        sum += *reinterpret_cast<const floatx4 *>(p.part + ((int64_t)sp * p.part_rows + r) * p.part_ld + n);
+    uint2 v;
+    v.x = pack_bf16(sum[0], sum[1]);
+    v.y = pack_bf16(sum[2], sum[3]);
+    *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(p.out) + (int64_t)tok * p.ldo + n) = v;
+}
+
+hipError_t launch_gemm_splitk(const GemmArgs &a, int n_split, bool b_kmajor, hipStream_t st)
+{
+    if (n_split < 1 || !a.part || a.k_per_split % 64 != 0 || a.part_ld < a.N || a.part_ld % 4 != 0) return hipErrorInvalidValue;
+    constexpr int smem = 2 * (128 + 128) * 128;
+    const int tiles = a.tiles_m * a.tiles_n;
+    if (tiles <= 0) return hipSuccess;
+    auto launch = [&](auto kern) -> hipError_t {
+        static bool attr_done = false;
+        if (!attr_done) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+        hipLaunchKernelGGL(kern, dim3(tiles, n_split), dim3(256), smem, st, a);
+        return hipGetLastError();
+    };
+    return b_kmajor ? launch(gemm_lora_kernel<128, 128, 2, 2, true, false, false, false, true>)
+                    : launch(gemm_lora_kernel<128, 128, 2, 2, false, false, false, false, true>);
+}
+
+hipError_t launch_gemm_finish(const GemmArgs &a, int n_split, hipStream_t st)
+{
+    if (a.n_rows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(gemm_finish_kernel, dim3((a.N / 4 + 255) / 256, a.n_rows), dim3(256), 0, st, a, n_split);
     return hipGetLastError();
 }
 

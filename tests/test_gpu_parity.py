@@ -15,11 +15,13 @@ from gpu_util import TOL, DeviceLayer, check_full, make_ctx, maxrel, to_dev, to_
 pytestmark = pytest.mark.gpu
 
 
-def _run_full(w, tol=None, h_save=True, transposed=False, wide_min_rows=None, **kw):
+def _run_full(w, tol=None, h_save=True, transposed=False, wide_min_rows=None, gemm_split=None, **kw):
     t = wl.make_tensors(w)
     ctx = make_ctx(w, **kw)
     if wide_min_rows is not None:
         ctx.set_wide_pass(wide_min_rows)
+    if gemm_split is not None:
+        ctx.set_gemm_split(gemm_split)
     layer = DeviceLayer(w, t, ctx, transposed=transposed)
     layer.fwd(h_save=h_save)
     layer.bwd(h_save=h_save)
@@ -216,6 +218,24 @@ def test_rows_split_between_large_and_small_tiles(wide_side):
         lens[4], lens[6], lens[7] = 30, 800, 297   # 2300 training rows beside 30 base-only ones
         w = _adhoc("bf16", 7424, 64, [16, 8, 12, 32], lens, ads, [1, 1, 1, 1, 0, 1, 1, 1], scale=0.5)
     _run_full(w)
+
+
+@pytest.mark.parametrize("transposed", [False, True])
+def test_gemm_with_few_rows_cut_into_k_slices(transposed):
+    # decode-sized batches: the library cuts K of both GEMMs into slices by itself (forward: 37 rows against
+    # K = 2048; dX: 21 training rows against K = 1536), partial sums added by the second kernel before the one rounding
+    lens = [1] * 16 + [9, 12]
+    ads = list(np.arange(16) % 3) + [1, 2]
+    w = _adhoc("bf16", 2048, 1536, [16, 8, 24], lens, ads, [0] * 16 + [1, 1], scale=0.5)
+    _run_full(w, transposed=transposed)
+    _run_full(w, transposed=transposed, gemm_split=1)      # and the same batch without slices
+    # forced: 3 slices of a K that is no multiple of 3 x 64, ragged everything, rows of several adapters and
+    # base-only rows in one tile, more than one row tile
+    w = _adhoc("bf16", 328, 200, [16, 5, 40], [60, 1, 130, 0, 70, 2, 64], [0, 1, 2, 2, -1, 1, 0], [1, 0, 1, 0, 0, 0, 1],
+               scale=0.3)
+    _run_full(w, transposed=transposed, gemm_split=3)
+    _run_full(w, transposed=transposed, gemm_split=64)     # clamped to one K tile per slice
+    _run_full(_adhoc("bf16", 8192, 64, [16], [1], [0], [0]), transposed=transposed)   # one token
 
 
 @pytest.mark.parametrize("transposed", [False, True])
