@@ -457,9 +457,9 @@ int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, cons
         return COLLM_OK;
     }
     if (R.n_wide > 0) {
-        // Long runs: 128-row tiles through the GEMM machinery.  K is cut so that about two blocks per CU
-        // exist, as long as a slice keeps 512 K values and the partial sums fit the workspace; the small
-        // kernel that adds the slices also does this pass's stores.
+        // Long runs: 128-row tiles through the GEMM machinery.  A block fills a CU (four LDS stages), so K is cut
+        // so that at most one block per CU exists, as long as a slice keeps 512 K values and the partial sums fit
+        // the workspace; the small kernel that adds the slices also does this pass's stores.
         GemmArgs g{};
         g.a = a.in;
         g.lda = a.ld_in;
@@ -476,7 +476,7 @@ int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, cons
         g.tab_off = a.tab_off;
         const long blocks = (long)R.n_wide * ((rpad + 127) / 128);
         const long per_split = (long)c->rows_cap * c->rpad_cap * 4;
-        long ns = std::min<long>({(512 + blocks - 1) / blocks, std::max(1, K / 512), (long)c->part_bytes / per_split,
+        long ns = std::min<long>({256 / blocks, std::max(1, K / 512), (long)c->part_bytes / per_split,
                                   (long)kSkinnyMaxSplit});
         ns = std::max<long>(ns, 1);
         g.k_per_split = round_up((int)((K + ns - 1) / ns), 64);

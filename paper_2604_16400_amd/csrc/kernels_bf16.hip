@@ -341,6 +341,7 @@ struct DmaSlots {
 // SPLITK: the GEMM itself with K cut into gridDim.y slices (few rows against a long contraction: too few tiles to
 // fill the GPU).  A block takes one tile and one slice; slice 0 also runs the tile's extension steps; the fp32
 // sums go to the workspace and gemm_finish_kernel adds the slices, rounds once and scatters the rows.
+constexpr int kWideStages = 4;  // LDS stages of the PARTIAL loop (128x128 tiles: 32 KiB each)
 template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR, bool PINGPONG, bool PARTIAL = false, bool SWIGLU = false,
           bool SPLITK = false>
 __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
@@ -377,8 +378,11 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     const void *a_base = p.a, *b_base = p.b;
     uint32_t a_bytes = p.a_bytes, b_bytes = p.b_bytes, ldb = (uint32_t)p.ldb;
     if constexpr (PARTIAL) {
-        const SkinnyItem it = p.items[blockIdx.x];
-        tile_m = blockIdx.x;
+        // consecutive items mostly belong to one adapter; blocks go round-robin to the 8 XCDs, so give every XCD a
+        // contiguous run of the items: an adapter's table then comes through one L2 instead of eight
+        const int n_it = gridDim.x, per = n_it >> 3, rem = n_it & 7, xc = blockIdx.x & 7;
+        tile_m = xc * per + (xc < rem ? xc : rem) + (blockIdx.x >> 3);
+        const SkinnyItem it = p.items[tile_m];
         tile_n = blockIdx.y;
         m0 = it.row_lo;
         rows_in = it.n_rows;
@@ -684,7 +688,63 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     };
 
     // ---- main K loop ----------------------------------------------------------------------
-    if (nk > 0) {
+    if constexpr (PARTIAL) {
+        // Rank-wide pass: bound by memory, not by the matrix pipe, so what counts is bytes in flight.  kWideStages LDS
+        // stages of [rows tile | table tile]; the loads of kWideStages - 1 tiles are in flight while one is multiplied.
+        // One barrier per tile: before it every wave has received its own loads of tile kc, after it all of the tile
+        // is in LDS and every wave is done with tile kc - 1, whose stage the loads of tile kc + kWideStages - 1 may fill.
+        constexpr int NS = kWideStages;
+        static_assert((NS - 2) * ND <= 63, "outstanding loads must fit the counter");
+        auto issue_tile = [&](int kc) {
+            const uint32_t base = lds_wave + (uint32_t)(kc % NS) * STAGE;
+            const int k0 = kc << 6;
+            const i32x4 ra_t = tile_rsrc(ra_w, kc), rb_t = tile_rsrc(rb_w, kc);
+#pragma unroll
+            for (int i = 0; i < ACH; ++i) dma16(ra_t, a_src(i, k0, false), base + i * (NT / 64) * 1024);
+#pragma unroll
+            for (int i = 0; i < BCH; ++i) dma16(rb_t, b_src(i, k0, kc, false), base + ATILE + i * (NT / 64) * 1024);
+        };
+        auto read_frags_at = [&](const uint8_t *ta, int ks, int buf) {
+            const uint8_t *tb = ta + ATILE;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) af[buf][mi] = lds_frag(ta, wm * WM + mi * 32 + rl, ks * 2 + kh);
+            if constexpr (B_KMAJOR) {
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) bf[buf][ni] = lds_frag(tb, wn * WN + ni * 32 + rl, ks * 2 + kh);
+            } else {
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) {
+                    const uint8_t *src = tb + btr[ni] + ks * 16 * BPITCH;
+                    const bf16x4 lo = lds_tr(src);
+                    const bf16x4 hi = lds_tr(src + 4 * BPITCH);
+                    bf[buf][ni] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                }
+            }
+        };
+#pragma unroll
+        for (int t = 0; t < NS - 1; ++t) issue_tile(t);
+        for (int kc = 0; kc < nk; ++kc) {
+            wait_dma_but<(NS - 2) * ND>();
+            __syncthreads();
+            issue_tile(kc + NS - 1);
+            const uint8_t *ta = smem + (kc % NS) * STAGE;
+            read_frags_at(ta, 0, 0);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                if (ks + 1 < 4) read_frags_at(ta, ks + 1, (ks + 1) & 1);
+                // only the 32-column blocks the adapter's rank reaches
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) {
+                    if (n0 + wn * WN + ni * 32 < N) {
+#pragma unroll
+                        for (int mi = 0; mi < MI; ++mi)
+                            acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[ks & 1][ni], af[ks & 1][mi], acc[ni][mi], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        wait_dma();  // loads of tiles beyond the last one (they fetch nothing)
+    } else if (nk > 0) {
         if constexpr (!PINGPONG) {
             // One wave per SIMD; tiles travel global -> LDS without touching registers.  A K tile is
             // four MFMA steps.  Everything else a wave has to issue rides behind single MFMAs, one
@@ -1652,7 +1712,7 @@ hipError_t launch_wide(const GemmArgs &a, int n_items, int rpad, int n_split, bo
     static_assert(kWideRows == 128, "the rank-wide pass runs 128x128 tiles");
     if (n_items <= 0) return hipSuccess;
     if (n_split < 1 || !a.part || !a.items || !a.tab || a.k_per_split % 64 != 0) return hipErrorInvalidValue;
-    constexpr int smem = 2 * (128 + 128) * 128;
+    constexpr int smem = kWideStages * (128 + 128) * 128;
     const dim3 grid(n_items, (rpad + 127) / 128, n_split);
     auto launch = [&](auto kern) -> hipError_t {
         static bool attr_done = false;
@@ -1665,8 +1725,9 @@ hipError_t launch_wide(const GemmArgs &a, int n_items, int rpad, int n_split, bo
         hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, a);
         return hipGetLastError();
     };
-    return t_kmajor ? launch(gemm_lora_kernel<128, 128, 2, 2, true, false, true>)
-                    : launch(gemm_lora_kernel<128, 128, 2, 2, false, false, true>);
+    // four waves side by side in the rows (32 rows x 128 rank columns each): the work of a wave shrinks with the rank
+    return t_kmajor ? launch(gemm_lora_kernel<128, 128, 4, 1, true, false, true>)
+                    : launch(gemm_lora_kernel<128, 128, 4, 1, false, false, true>);
 }
 
 hipError_t launch_skinny_finish(const SkinnyArgs &a, int n_items, int item_rows, int n_split, hipStream_t st)
