@@ -105,7 +105,9 @@ struct Tiling {
     int tail_tiles_m;
 };
 
-Tiling pick_tiling(int rows, int cols)
+// can_split: the 128x128 tiles behind the large ones may have K cut into slices (see run_gemm), which lets a few
+// such tiles use the whole GPU
+Tiling pick_tiling(int rows, int cols, int K, bool can_split)
 {
     // Two shapes are worth choosing between: 256x256 run by four waves (one block per CU, the most
     // efficient inner loop) and 128x128 (two blocks per CU, four times as many tiles).  The cost of
@@ -117,7 +119,8 @@ Tiling pick_tiling(int rows, int cols)
     //    two rounds on the blocks' different speeds smooth the rounds out (0.62 per round, 0.3 for a
     //    nearly empty last one);
     //  - whole rounds of 256x256 tiles over the first rows and 128x128 tiles over the rest, as two
-    //    launches: the sum of both plus 0.1 for the idle CUs at the boundary between them.
+    //    launches: the sum of both plus 0.1 for the idle CUs at the boundary between them; fewer than 448
+    //    small tiles with K in slices cost their share of a full round plus the kernel that adds the slices.
     auto cost_large = [](double tiles) {
         const double x = tiles / 256.0, whole = std::floor(x), part = x - whole;
         if (x <= 1.0) return 0.5 + 0.5 * x;
@@ -140,7 +143,10 @@ Tiling pick_tiling(int rows, int cols)
         const int m = std::min(tm - 1, rounds * 256 / tn);
         const int tail = (std::max(rows, 1) - 256 * m + 127) / 128;
         if (m >= 1 && tail >= 1) {
-            const double cost = cost_large((double)m * tn) + cost_small((double)tail * tn128) + 0.1;
+            const double tail_tiles = (double)tail * tn128;
+            const double tail_cost = (can_split && K >= 1024 && tail_tiles < 448) ? 0.65 * tail_tiles / 512.0 + 0.05
+                                                                                 : cost_small(tail_tiles);
+            const double cost = cost_large((double)m * tn) + tail_cost + 0.1;
             if (cost < best_cost) best = Tiling{kTile256x256, m, tail};
         }
     }
@@ -157,40 +163,48 @@ hipError_t run_gemm(collm_ctx *c, GemmArgs g, const RowOrderLayout &R, int rows,
         g.tiles_n = (cols + gemm_tile_cols(tile) - 1) / gemm_tile_cols(tile);
         return swiglu ? launch_gemm_swiglu(g, tile, st) : launch_gemm(g, tile, b_kmajor, st);
     };
+    const bool can_split = !swiglu && c->gemm_split != 1;
     const Tiling t = forced_tile >= 0 ? Tiling{forced_tile, R.n_rows_pad / gemm_tile_rows(forced_tile), 0}
-                                      : pick_tiling(rows, cols);
+                                      : pick_tiling(rows, cols, g.K, can_split);
     g.tile_m_base = 0;
     g.tiles_m = t.big_tiles_m;
     g.ext_off = c->d_plan + R.off_ext_off;
     g.ext = reinterpret_cast<const ExtStep *>(c->d_plan + R.off_ext);
-    if (!swiglu && forced_tile < 0 && c->gemm_split != 1 && t.tile == kTile128x128 && t.tail_tiles_m == 0) {
-        // Few rows against a long contraction (decode-sized batches): too few tiles to fill the GPU, each walking all
-        // of K with one tile of loads in flight.  Cut K into slices so that up to two blocks per CU exist, as long as a
-        // slice keeps 512 K values and the fp32 partial sums fit the workspace; a second kernel adds the slices.
+    // Few tiles against a long contraction (decode-sized batches, or the small tiles behind whole rounds of large
+    // ones): too few blocks to fill the GPU, each walking all of K with one tile of loads in flight.  Cut K into
+    // slices so that up to two blocks per CU exist, as long as a slice keeps 512 K values and the fp32 partial sums
+    // fit the workspace; a second kernel adds the slices.  Returns false if the launch should be a plain one.
+    auto try_split = [&](int tiles_m, int row_base, int n_rows_here, hipError_t &err) -> bool {
+        if (!can_split || forced_tile >= 0) return false;
         const int tiles_n = (cols + 127) / 128;
-        const long tiles = (long)t.big_tiles_m * tiles_n;
-        const long per_slice = (long)t.big_tiles_m * 128 * cols * 4;
-        long want = c->gemm_split > 1 ? c->gemm_split : (tiles <= 256 ? (448 + tiles - 1) / tiles : 1);
+        const long tiles = (long)tiles_m * tiles_n;
+        const long per_slice = (long)tiles_m * 128 * cols * 4;
+        long want = c->gemm_split > 1 ? c->gemm_split : (tiles < 448 ? (448 + tiles - 1) / tiles : 1);
         want = std::min<long>({want, c->gemm_split > 1 ? g.K / 64 : g.K / 512, (long)c->part_bytes / per_slice, 64L});
-        if (want >= 2) {
-            g.tiles_n = tiles_n;
-            g.k_per_split = round_up((int)((g.K + want - 1) / want), 64);
-            const int n_split = (g.K + g.k_per_split - 1) / g.k_per_split;
-            g.part = c->d_part;
-            g.part_rows = t.big_tiles_m * 128;
-            g.part_ld = cols;
-            g.n_rows = rows;
-            hipError_t e = launch_gemm_splitk(g, n_split, b_kmajor, st);
-            if (e != hipSuccess) return e;
-            return launch_gemm_finish(g, n_split, st);
-        }
-    }
-    hipError_t e = launch(t.tile);
+        if (want < 2) return false;
+        GemmArgs gs = g;
+        gs.tiles_m = tiles_m;
+        gs.tiles_n = tiles_n;
+        gs.k_per_split = round_up((int)((g.K + want - 1) / want), 64);
+        const int n_split = (g.K + gs.k_per_split - 1) / gs.k_per_split;
+        gs.part = c->d_part;
+        gs.part_rows = tiles_m * 128;
+        gs.part_ld = cols;
+        gs.row_base = row_base;
+        gs.n_rows = n_rows_here;
+        err = launch_gemm_splitk(gs, n_split, b_kmajor, st);
+        if (err == hipSuccess) err = launch_gemm_finish(gs, n_split, st);
+        return true;
+    };
+    hipError_t e = hipSuccess;
+    if (t.tile == kTile128x128 && t.tail_tiles_m == 0 && try_split(t.big_tiles_m, 0, rows, e)) return e;
+    e = launch(t.tile);
     if (e != hipSuccess || t.tail_tiles_m == 0) return e;
     g.tile_m_base = 2 * t.big_tiles_m;
     g.tiles_m = t.tail_tiles_m;
     g.ext_off = c->d_plan + R.off_ext_off_half;
     g.ext = reinterpret_cast<const ExtStep *>(c->d_plan + R.off_ext_half);
+    if (try_split(t.tail_tiles_m, 256 * t.big_tiles_m, rows - 256 * t.big_tiles_m, e)) return e;
     return launch(kTile128x128);
 }
 
@@ -304,8 +318,9 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
     int n_train = 0;
     for (int k = 0; k < s->n_segments; ++k)
         if (seg_is_train[k]) n_train += seg_start[k + 1] - seg_start[k];
-    const int tile_fwd = c->tile_fwd >= 0 ? c->tile_fwd : pick_tiling(s->n_tokens, s->d_out).tile;
-    const int tile_bwd = c->tile_bwd >= 0 ? c->tile_bwd : pick_tiling(n_train, s->d_in).tile;
+    const bool can_split = !f32 && c->gemm_split != 1;
+    const int tile_fwd = c->tile_fwd >= 0 ? c->tile_fwd : pick_tiling(s->n_tokens, s->d_out, s->d_in, can_split && n_sib < 16).tile;
+    const int tile_bwd = c->tile_bwd >= 0 ? c->tile_bwd : pick_tiling(n_train, s->d_in, s->d_out, can_split).tile;
     const int bm_all = f32 ? 64 : gemm_tile_rows(tile_fwd);
     const int bm_train = f32 ? 64 : gemm_tile_rows(tile_bwd);
     int rmax = 1;

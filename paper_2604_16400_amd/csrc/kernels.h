@@ -48,7 +48,8 @@ struct GemmArgs {
     float *part;
     int part_rows, part_ld;
     int k_per_split;          // multiple of 64
-    int n_rows;               // launch_gemm_splitk: rows of the row order (part rows beyond them are not written)
+    int n_rows, row_base;     // launch_gemm_splitk: the launch covers rows row_base .. row_base + n_rows of the row order
+                              // (row_base = 128 tile_m_base); part row = row - row_base
     int part_n_sib;           // as SkinnyArgs::n_sib (0 or 1: ranks as the items give them)
     int64_t tab_ld, tab_off;  // as SkinnyArgs
 };

@@ -1019,8 +1019,9 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     if constexpr (PARTIAL || SPLITK) {
         // fp32 sums of the slice: a lane holds four consecutive (rank) columns of a row
         const int q_hi = SPLITK ? N : (N + 15) & ~15;
-        if constexpr (SPLITK) rows_in = p.n_rows - m0;  // rows of the order beyond the last are padding
-        float *__restrict__ part = p.part + ((int64_t)(SPLITK ? blockIdx.y : blockIdx.z) * p.part_rows + m0) * p.part_ld;
+        if constexpr (SPLITK) rows_in = p.row_base + p.n_rows - m0;  // rows of the order beyond the last are padding
+        float *__restrict__ part =
+            p.part + ((int64_t)(SPLITK ? blockIdx.y : blockIdx.z) * p.part_rows + m0 - (SPLITK ? p.row_base : 0)) * p.part_ld;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
             const int r = wm * WM + mi * 32 + rl;
@@ -1741,8 +1742,8 @@ hipError_t launch_skinny_finish(const SkinnyArgs &a, int n_items, int item_rows,
 // block row = row of the order, 4 columns per thread
 __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p, int n_split)
 {
-    const int r = blockIdx.y;
-    const int tok = p.row_tok[r];
+    const int r = blockIdx.y;  // row of the launch; row p.row_base + r of the order
+    const int tok = p.row_tok[p.row_base + r];
     const int n = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (tok < 0 || n >= p.N) return;
     floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};

@@ -204,7 +204,7 @@ def test_few_rows_long_contraction_and_many_trained_adapters_in_one_tile():
     _run_full(w)
 
 
-@pytest.mark.parametrize("wide_side", ["d_out", "d_in"])
+@pytest.mark.parametrize("wide_side", ["d_out", "d_in", "d_out_long_k"])
 def test_rows_split_between_large_and_small_tiles(wide_side):
     # 2300 rows x 7424 columns is 9 x 29 tiles of 256x256, five more than one round over 256 CUs: the
     # first 8 row tiles run as 256x256, rows 2048.. as 128x128 tiles in a second launch.  Segments and
@@ -212,7 +212,10 @@ def test_rows_split_between_large_and_small_tiles(wide_side):
     # is compared.  d_out wide: the forward GEMM is the split one; d_in wide: the dX GEMM.
     lens = [700, 1, 1, 500, 300, 1, 600, 197]
     ads = [0, 1, 2, 1, -1, 0, 2, 3]
-    if wide_side == "d_out":
+    if wide_side == "d_out_long_k":
+        # K = 1024: the small tiles of the last rows also cut K into slices (second kernel adds them)
+        w = _adhoc("bf16", 1024, 7424, [16, 8, 12, 32], lens, ads, [1, 0, 0, 1, 0, 0, 1, 0], scale=0.5)
+    elif wide_side == "d_out":
         w = _adhoc("bf16", 64, 7424, [16, 8, 12, 32], lens, ads, [1, 0, 0, 1, 0, 0, 1, 0], scale=0.5)
     else:
         lens[4], lens[6], lens[7] = 30, 800, 297   # 2300 training rows beside 30 base-only ones
