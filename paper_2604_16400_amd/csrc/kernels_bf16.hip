@@ -336,8 +336,9 @@ struct DmaSlots {
 // columns act_col + j0 .. of the same outputs; the waves of the left half hold the gate values, those
 // of the right half the up values of the same rows.  The extension steps run over both siblings' ranks
 // (rank r each, multiples of 16): a step of the first r multiplies into the gate half only, one of the
-// second r into the up half only.  The epilogue passes the up values through LDS and stores
-// silu(gate) * up, rounded once, as [rows][N = d_ff]; training rows also keep both pre-activations.
+// second r into the up half only.  In the epilogue the two waves that hold the gate and the up values of the
+// same rows swap halves through LDS, each finishes half of the rows: silu(gate) * up, rounded once, stored as
+// [rows][N = d_ff]; training rows also keep both pre-activations.
 // SPLITK: the GEMM itself with K cut into gridDim.y slices (few rows against a long contraction: too few tiles to
 // fill the GPU).  A block takes one tile and one slice; slice 0 also runs the tile's extension steps; the fp32
 // sums go to the workspace and gemm_finish_kernel adds the slices, rounds once and scatters the rows.
