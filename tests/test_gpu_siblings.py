@@ -295,3 +295,35 @@ def test_swiglu_error_statuses():
     torch.cuda.synchronize()
     assert torch.isnan(y).all()
     ctx.close()
+
+
+def test_sibling_edge_batches():
+    import torch
+
+    # one token; inference only (the backward call is a no-op); training only; widest rank the context takes
+    _run(SiblingCase(256, (256, 64), [8], [1], [0], [1]))
+    c = SiblingCase(256, (256, 64), [8, 16], [3, 40, 9], [0, 1, -1], [0, 0, 0])
+    _run(c)
+    _run(SiblingCase(256, (256, 64), [8, 16], [30, 41], [1, 0], [1, 1]))
+    _run(SiblingCase(128, (256, 256), [128], [70, 9], [0, 0], [1, 0]))   # 2 x 128 = 256 rank columns side by side
+    # empty batch
+    ctx = binding.Context(8, 2, 1, 16, 512)
+    e = SiblingCase(64, (256, 64), [8], [0, 0], [0, -1], [0, 0])
+    x = torch.zeros((0, 64), dtype=torch.bfloat16, device="cuda")
+    W = to_dev(e.W, "bf16")
+    y = torch.zeros((0, 320), dtype=torch.bfloat16, device="cuda")
+    ctx.collm_lora_siblings_fwd((256, 64), x, W, [to_dev(e.A[0], "bf16")], [to_dev(e.B[0], "bf16")], e.ranks, e.seg_start,
+                                e.seg_adapter, e.seg_is_train, 1.0, y)
+    ctx.close()
+
+
+def test_swiglu_single_token_and_decode_batch():
+    # decode-sized batches take the K-sliced GEMM in the plain sibling call; the epilogue version keeps whole tiles
+    c = SiblingCase(2048, (256, 256), [16, 32], [1], [1], [0])
+    _run_swiglu(c)
+    _run(c)
+    lens = [1] * 24 + [8]
+    c = SiblingCase(2048, (512, 512), [16, 32, 16], lens, list(np.arange(24) % 3) + [2], [0] * 24 + [1], scale=0.5)
+    _run_swiglu(c)
+    _run(c)
+    _run(c, h_save=False)
