@@ -663,6 +663,18 @@ int collm_ctx_destroy(collm_ctx *c)
 
 int64_t collm_ctx_workspace_bytes(const collm_ctx *c) { return c ? c->workspace_bytes : 0; }
 
+int collm_debug_host_tiling(int rows, int cols, int K, int can_split, int32_t *tile, int32_t *big_tiles_m,
+                            int32_t *tail_tiles_m)
+{
+    if (!tile || !big_tiles_m || !tail_tiles_m) return COLLM_E_NULL;
+    if (rows < 0 || cols <= 0 || K <= 0) return COLLM_E_SHAPE;
+    const Tiling t = pick_tiling(rows, cols, K, can_split != 0);
+    *tile = t.tile;
+    *big_tiles_m = t.big_tiles_m;
+    *tail_tiles_m = t.tail_tiles_m;
+    return COLLM_OK;
+}
+
 int collm_debug_host_row_order(const collm_shape *s, const int32_t *rank, const int32_t *seg_start,
                                const int32_t *seg_adapter, const uint8_t *seg_is_train, int tile_rows,
                                int training_rows_only, int32_t *row_tok, int32_t *tile_steps)

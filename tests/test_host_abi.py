@@ -132,3 +132,25 @@ def test_plan_spreads_rare_adapters_over_the_row_tiles():
     assert by_index.max() >= 40
     assert steps.max() <= 20 and steps.max() <= by_index.max() // 2
     assert steps.sum() <= by_index.sum() + 4 * len(steps)   # at most one more run per tile, of rank 64
+
+
+def test_gemm_tiling_covers_the_rows_and_matches_the_measured_choices():
+    rng = np.random.default_rng(5)
+    for _ in range(2000):
+        rows = int(rng.integers(1, 40000))
+        cols = int(rng.integers(1, 4000)) * 8
+        K = int(rng.integers(1, 2000)) * 8
+        tile, big, tail = binding.host_tiling(rows, cols, K, bool(rng.integers(0, 2)))
+        assert tile in (binding.TILE_256x256, binding.TILE_128x128) and big >= 1 and tail >= 0
+        tr = 256 if tile == binding.TILE_256x256 else 128
+        assert tr * big + 128 * tail >= rows                      # every row is in some tile
+        if tail:
+            assert tile == binding.TILE_256x256 and 256 * big < rows          # the tail starts inside the rows
+            assert 256 * big + 128 * (tail - 1) < rows                        # and has no empty row tile
+        else:
+            assert tr * (big - 1) < rows or rows <= tr
+    # choices the measurements on the five configurations gave
+    assert binding.host_tiling(2048, 4096, 4096) == (binding.TILE_128x128, 16, 0)       # c2 forward: one round of 512 small tiles
+    assert binding.host_tiling(16384, 8192, 8192) == (binding.TILE_256x256, 64, 0)      # c5: whole rounds of large tiles
+    assert binding.host_tiling(3277, 5120, 5120) == (binding.TILE_256x256, 12, 2)       # c4 dX: 240 large tiles + the last 205 rows
+    assert binding.host_tiling(64, 4096, 4096)[0] == binding.TILE_128x128               # decode-sized
