@@ -175,6 +175,9 @@ class Runner:
         if "gemm_fwd" in kt:
             out["gemm_fwd_tflops"] = gemm_fwd_flops / (kt["gemm_fwd"] * 1e-3) / 1e12
             out["gemm_fwd_frac_mfma_peak"] = out["gemm_fwd_tflops"] / PEAK_BF16_TFLOPS
+            # yardstick, not part of the library: the vendor GEMM on the base term alone (no adapters, no row
+            # gather/scatter), same device, same shape
+            out["vendor_gemm_fwd_tflops"] = gemm_fwd_flops / self.vendor_gemm_seconds() / 1e12
         if "gemm_dx" in kt:
             out["gemm_dx_tflops"] = gemm_dx_flops / (kt["gemm_dx"] * 1e-3) / 1e12
             out["gemm_dx_frac_mfma_peak"] = out["gemm_dx_tflops"] / PEAK_BF16_TFLOPS
@@ -184,6 +187,18 @@ class Runner:
                 out[f"{k}_GBs"] = gbs
                 out[f"{k}_frac_hbm_peak"] = gbs / PEAK_HBM_GBS
         return out, sec, kt
+
+    def vendor_gemm_seconds(self, iters=20):
+        torch = self.torch
+        W = self.W if self.layout == 0 else self.W.t()
+        for _ in range(3):
+            torch.matmul(self.x, W)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            torch.matmul(self.x, W)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / iters
 
     def close(self):
         self.ctx.close()
