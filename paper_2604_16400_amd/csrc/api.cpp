@@ -275,9 +275,38 @@ bool same_key(collm_ctx *c, const collm_shape *s, const void *const *A, const vo
     if (S && std::memcmp(c->key_seg_adapter.data(), seg_adapter, sizeof(int32_t) * S)) return false;
     if (S && std::memcmp(c->key_seg_train.data(), seg_is_train, S)) return false;
     if (N && std::memcmp(c->key_rank.data(), rank, sizeof(int32_t) * N)) return false;
+    (void)A;
+    (void)B;
+    return true;
+}
+
+bool same_tables(collm_ctx *c, int N, const void *const *A, const void *const *B)
+{
     for (int a = 0; a < N; ++a)
         if (c->key_A[a] != (uint64_t)(uintptr_t)A[a] || c->key_B[a] != (uint64_t)(uintptr_t)B[a]) return false;
     return true;
+}
+
+// Same batch, other adapter tables (another layer or projection of the model): the plan keeps its shape; the
+// two pointer tables and the table address inside every extension step are replaced.
+void patch_tables(collm_ctx *c, int N, const void *const *A, const void *const *B)
+{
+    PlanLayout &L = c->L;
+    for (int a = 0; a < N; ++a) {
+        const uint64_t va = (uint64_t)(uintptr_t)A[a], vb = (uint64_t)(uintptr_t)B[a];
+        std::memcpy(c->plan.data() + L.off_A_ptr + 2 * a, &va, 8);
+        std::memcpy(c->plan.data() + L.off_B_ptr + 2 * a, &vb, 8);
+        c->key_A[a] = va;
+        c->key_B[a] = vb;
+    }
+    auto patch = [&](int32_t off_ext, const std::vector<int32_t> &step_adapter, const void *const *tab) {
+        ExtStep *ext = reinterpret_cast<ExtStep *>(c->plan.data() + off_ext);
+        for (size_t k = 0; k < step_adapter.size(); ++k) ext[k].tab = (uint64_t)(uintptr_t)tab[step_adapter[k]];
+    };
+    patch(L.all.off_ext, L.all.ext_adapter, B);            // forward: expand tables
+    patch(L.all.off_ext_half, L.all.ext_adapter_half, B);
+    patch(L.train.off_ext, L.train.ext_adapter, A);        // backward: shrink tables
+    patch(L.train.off_ext_half, L.train.ext_adapter_half, A);
 }
 
 // Copy ints [lo, hi) of the host plan to the device plan through a pinned staging slot.
@@ -339,6 +368,11 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
     // than the one the plan was uploaded on builds it again, since nothing orders the two streams.
     const bool reuse = allow_reuse && st == c->last_stream && n_sib == c->key_nsib &&
                        same_key(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, bm_all, bm_train, wide);
+    bool upload_all = false;
+    if (reuse && !same_tables(c, s->n_adapters, A, B)) {
+        patch_tables(c, s->n_adapters, A, B);
+        upload_all = true;
+    }
     if (!reuse) {
         PlanRequest rq;
         rq.shape = s;
@@ -380,8 +414,8 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
             c->key_B[a] = (uint64_t)(uintptr_t)B[a];
         }
         c->plan_valid = true;
-    } else if (dA || dB) {
-        // same batch as the plan on the device: at most the gradient pointer tables are new
+    } else if (dA || dB || upload_all) {
+        // same batch as the plan on the device: at most the pointer tables are new
         const int N = s->n_adapters;
         bool changed = false;
         for (int a = 0; a < N; ++a) {
@@ -391,7 +425,10 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
             std::memcpy(c->plan.data() + c->L.off_dA_ptr + 2 * a, &va, 8);
             std::memcpy(c->plan.data() + c->L.off_dB_ptr + 2 * a, &vb, 8);
         }
-        if (changed) {
+        if (upload_all) {
+            int rc = upload(c, 0, c->L.total_ints, st);
+            if (rc != COLLM_OK) return rc;
+        } else if (changed) {
             int rc = upload(c, c->L.off_dA_ptr, (size_t)c->L.off_dB_ptr + 2 * (size_t)std::max(N, 1), st);
             if (rc != COLLM_OK) return rc;
         }

@@ -12,6 +12,8 @@
 #pragma once
 #include <stdint.h>
 
+#include <vector>
+
 namespace collm {
 
 constexpr int kWideRows = 128;  // rows of an item of the rank-wide pass for long runs of one adapter
@@ -61,6 +63,9 @@ struct RowOrderLayout {
     // the same for row tiles of half the size (built when bm is 256): a GEMM may run its last rows on
     // smaller tiles
     int32_t n_tiles_m_half = 0, off_ext_off_half = 0, off_ext_half = 0;
+    // host only: the adapter of every extension step (both tables), so that the table addresses inside the
+    // steps can be replaced when only the adapter tables of a batch change
+    std::vector<int32_t> ext_adapter, ext_adapter_half;
 };
 
 struct PlanLayout {

@@ -182,7 +182,8 @@ void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &
 
     // low-rank extension steps of every GEMM row tile
     auto build_ext = [&](int tile_rows, int32_t &n_tiles, int32_t &off_ext_off, int32_t &off_ext, int32_t *n_ext,
-                         int32_t *max_per_tile) {
+                         int32_t *max_per_tile, std::vector<int32_t> &step_adapter) {
+        step_adapter.clear();
         n_tiles = L.n_rows_pad / tile_rows;
         std::vector<int32_t> ext_off(n_tiles + 1, 0);
         std::vector<ExtStep> ext;
@@ -197,8 +198,10 @@ void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &
                 while (e < r1 && b.blk[L.off_row_adapter + e] == a) ++e;
                 if (a >= 0) {
                     const uint64_t tab = ext_tab ? (uint64_t)(uintptr_t)ext_tab[a] : 0;
-                    for (int k = 0; k < rank_ext[a]; k += kKStep)
+                    for (int k = 0; k < rank_ext[a]; k += kKStep) {
                         ext.push_back({(uint32_t)k | ((uint32_t)rank_ext[a] << 16), (uint32_t)(r - r0) | ((uint32_t)(e - r0) << 16), tab});
+                        step_adapter.push_back(a);
+                    }
                 }
                 r = e;
             }
@@ -213,8 +216,9 @@ void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &
         if (max_per_tile) *max_per_tile = most;
     };
     L.bm = bm;
-    build_ext(bm, L.n_tiles_m, L.off_ext_off, L.off_ext, &L.n_ext, &L.max_ext_per_tile);
-    if (bm == 256) build_ext(128, L.n_tiles_m_half, L.off_ext_off_half, L.off_ext_half, nullptr, nullptr);
+    build_ext(bm, L.n_tiles_m, L.off_ext_off, L.off_ext, &L.n_ext, &L.max_ext_per_tile, L.ext_adapter);
+    L.ext_adapter_half.clear();
+    if (bm == 256) build_ext(128, L.n_tiles_m_half, L.off_ext_off_half, L.off_ext_half, nullptr, nullptr, L.ext_adapter_half);
 }
 
 }  // namespace

@@ -296,6 +296,31 @@ def test_every_gemm_tile_shape(tile):
     ctx.close()
 
 
+def test_same_batch_other_adapter_tables_reuses_the_plan():
+    # Every layer and projection of a model sees the same batch with its own weight and adapter tables: the plan
+    # on the device keeps its shape and only the table addresses inside it are replaced.  Two sets of tensors
+    # (same segments, different values and buffers) through one context, calls interleaved; each checked in full.
+    for shape in ((512, 384, [16, 64, 8], [40, 1, 1, 1, 300, 90, 33, 1, 260], [0, 1, 2, 0, 1, 1, 2, 1, 0],
+                   [0, 0, 0, 0, 1, 1, 0, 0, 1]),
+                  (64, 7424, [16, 8, 12, 32], [700, 1, 1, 500, 300, 1, 600, 197], [0, 1, 2, 1, -1, 0, 2, 3],
+                   [1, 0, 0, 1, 0, 0, 1, 0])):
+        d_in, d_out, ranks, lens, ads, trn = shape
+        w1 = _adhoc("bf16", d_in, d_out, ranks, lens, ads, trn, scale=0.5, seed=7)
+        w2 = _adhoc("bf16", d_in, d_out, ranks, lens, ads, trn, scale=0.5, seed=8)
+        ctx = make_ctx(w1)
+        l1 = DeviceLayer(w1, wl.make_tensors(w1), ctx)
+        l2 = DeviceLayer(w2, wl.make_tensors(w2), ctx)
+        l1.fwd()
+        l2.fwd()
+        l1.fwd()
+        l2.bwd()
+        l1.bwd()
+        l2.fwd()
+        check_full(l1, TOL["bf16"])
+        check_full(l2, TOL["bf16"])
+        ctx.close()
+
+
 # ------------------------------------------------------------------ contracts
 def test_recompute_h_and_accumulate_and_run_to_run():
     import torch
