@@ -614,6 +614,100 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         }
     };
 
+    // ---- loads of the low-rank extension (used from the last tiles of the main loop on) ------
+    // The extension steps after the main loop are taken four at a time (one 64-wide K tile); the operands of
+    // such a batch travel global -> LDS like the tiles of the main loop and take the same places in a stage.
+    const i32x4 rh_w = make_rsrc_words(p.hs, p.hs_bytes);
+    const uint64_t zeros = reinterpret_cast<uint64_t>(p.zeros);
+    // per-lane choice among the four steps of a batch
+    auto pick = [](int j, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3) { return j == 0 ? v0 : (j == 1 ? v1 : (j == 2 ? v2 : v3)); };
+    // piece d of a batch: chunk d of the rows' operand, or chunk d - ACH of the tables'
+    // (called with d known after unrolling: the branches and the step index fold away)
+    auto issue_piece = [&](int stage, const ExtBatch &bt, const int D) {
+        if (D < ACH) {
+            // rows: position c8 of row r holds chunk cl; chunk cl belongs to step cl / 2, rank
+            // indices koff + 8 (cl % 2) ..
+            const int i = D;
+            const int r = r8 + i * (NT / 8);
+            const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
+            const int j = cl >> 1;
+            const uint32_t kr = pick(j, bt.kr[0], bt.kr[1], bt.kr[2], bt.kr[3]);
+            const uint32_t rows = pick(j, bt.rows[0], bt.rows[1], bt.rows[2], bt.rows[3]);
+            // siblings: the columns after a sibling's own are the next sibling's, or were never written
+            const bool in = r >= (int)(rows & 0xffffu) && r < (int)(rows >> 16) &&
+                            (p.n_sib <= 1 || (kr & 0xffffu) + (cl & 1) * 8u < (kr >> 16));
+            const uint32_t off = in ? ((uint32_t)(m0 + r) * (uint32_t)p.hs_ld + (uint32_t)sib * (kr >> 16) + (kr & 0xffffu) + (cl & 1) * 8u) * 2u : kOob;
+            dma16(rh_w, off, lds_wave + (stage ? A_ST1 : 0) + i * (NT / 64) * 1024);
+        } else if constexpr (!B_KMAJOR) {
+            // table rows are rank indices: B_a[q][n]; tile row 16 j + i is rank index koff_j + i.
+            // All lanes of a load belong to one step, whose table is the load's buffer: rank
+            // indices beyond the rank lie beyond it.
+            static_assert(16 % (NT / NG) == 0 || (NT / NG) % 16 == 0, "a direct load must not straddle two steps");
+            const int i = D - ACH;
+            const int j = (i * (NT / NG)) >> 4;
+            const int k = bk0 + i * (NT / NG);
+            uint32_t rk = bt.kr[j] >> 16, koff = bt.kr[j] & 0xffffu;
+            bool mine = true;
+            if constexpr (SWIGLU) {
+                // the step belongs to the gate sibling (first half of the ranks) or the up sibling
+                rk >>= 1;
+                const bool up = koff >= rk;
+                koff -= up ? rk : 0u;
+                mine = (bcl * 8 >= BN / 2) == up;
+            }
+            const i32x4 rt = make_rsrc_words(reinterpret_cast<const void *>(bt.tab[j]), rk * (uint32_t)p.ext_ld * 2u);
+            const uint32_t off = (mine && col_on(bcl * 8)) ? ((koff + (uint32_t)(k & 15)) * (uint32_t)p.ext_ld + (uint32_t)src_col(bcl * 8)) * 2u : kOob;
+            dma16(rt, off, lds_wave + (stage ? B_ST1 : B_ST0) + i * (NT / 64) * 1024);
+        } else {
+            // table rows are output columns: A_a[n][q], row length rank.  The four steps of a
+            // batch may have four tables, so every lane forms its own 64-bit address.
+            const int i = D - ACH;
+            const bool all8 = (((bt.kr[0] | bt.kr[1] | bt.kr[2] | bt.kr[3]) >> 16) & 7u) == 0;
+            const int r = r8 + i * (NT / 8);
+            const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
+            const int j = cl >> 1;
+            const uint32_t kr = pick(j, bt.kr[0], bt.kr[1], bt.kr[2], bt.kr[3]);
+            const uint32_t tlo = pick(j, (uint32_t)bt.tab[0], (uint32_t)bt.tab[1], (uint32_t)bt.tab[2], (uint32_t)bt.tab[3]);
+            const uint32_t thi = pick(j, (uint32_t)(bt.tab[0] >> 32), (uint32_t)(bt.tab[1] >> 32), (uint32_t)(bt.tab[2] >> 32), (uint32_t)(bt.tab[3] >> 32));
+            if (all8) {
+                const uint32_t rk = kr >> 16, q0 = (kr & 0xffffu) + (cl & 1) * 8u;
+                const bool in = n0 + r < N && q0 < rk;
+                const uint64_t addr = in ? (((uint64_t)thi << 32) | tlo) + ((uint64_t)(n0 + r) * rk + q0) * 2u : zeros;
+                dma16g(addr, lds_wave + (stage ? B_ST1 : B_ST0) + i * (NT / 64) * 1024);
+            } else {
+                // some rank is no multiple of 8: table rows are not 16-byte aligned; element by element
+                uint8_t *tb = smem + (stage ? B_ST1 : B_ST0);
+                const int rk = (int)(kr >> 16), q0 = (int)(kr & 0xffffu) + (cl & 1) * 8;
+                uint16_t e[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) e[q] = 0;
+                if (n0 + r < N) {
+                    const uint16_t *src = reinterpret_cast<const uint16_t *>(((uint64_t)thi << 32) | tlo) + (int64_t)(n0 + r) * rk + q0;
+#pragma unroll
+                    for (int q = 0; q < 8; ++q)
+                        if (q0 + q < rk) e[q] = src[q];
+                }
+                uint4 v;
+                v.x = e[0] | ((uint32_t)e[1] << 16);
+                v.y = e[2] | ((uint32_t)e[3] << 16);
+                v.z = e[4] | ((uint32_t)e[5] << 16);
+                v.w = e[6] | ((uint32_t)e[7] << 16);
+                *reinterpret_cast<uint4 *>(tb + (r8 + i * (NT / 8)) * 128 + c8 * 16) = v;
+            }
+        }
+    };
+
+    // Whether the first batch is loaded from inside the main loop (see k_tile): the hand-scheduled loop with at
+    // least two tiles, and every piece of the batch one direct load (tables with K contiguous: ranks in eights).
+    // Not for 256x256 tiles: their main loop leaves no registers for the address arithmetic of these loads.
+    constexpr bool CAN_PRE = !PINGPONG && !PARTIAL && BM * BN < 256 * 256;
+    bool pre = false;
+    if constexpr (CAN_PRE) {
+        uint32_t kr_or = 0;  // lanes beyond the tile's steps hold zeros
+#pragma unroll
+        for (int j = 0; j < kExtBatch; ++j) kr_or |= (uint32_t)__builtin_amdgcn_readlane((int)rec.x, j);
+        pre = e1 > e0 && nk >= 2 && (!B_KMAJOR || ((kr_or >> 16) & 7u) == 0);
+    }
     // acc[ni][mi] holds the transposed 32x32 block: lane = row m, registers = columns n
     floatx16 acc[NI][MI];
 #pragma unroll
@@ -781,8 +875,11 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 #pragma unroll
             for (int j = 0; j < NRD; ++j) read_one(0, 0, 0, j);
 
-            auto k_tile = [&](auto cur_c, int kc) {
-                constexpr int cur = decltype(cur_c)::value, nxt = cur ^ 1;
+            // tail_c: 0 = a tile of the loop proper.  With `pre`, the first batch of the extension takes the place of the
+            // tile after the last one: the second-last tile (2) issues its first loads where it would issue those of
+            // that tile, the last tile (1) the others, and its latency hides behind the last tile's MFMAs.
+            auto k_tile = [&](auto cur_c, auto tail_c, int kc, const ExtBatch &b0) {
+                constexpr int cur = decltype(cur_c)::value, nxt = cur ^ 1, tail = decltype(tail_c)::value;
                 // steps 0..2: MFMAs of step s, fragment reads of step s+1, direct loads of tile kc+1
 #pragma unroll
                 for (int st = 0; st < 3; ++st) {
@@ -792,7 +889,10 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 #pragma unroll
                         for (int j = m * RPS; j < (m + 1) * RPS; ++j)
                             if (j < NRD) read_one(cur, st + 1, (st + 1) & 1, j);
-                        if (st < 2 && SL.slot[st + 1][m] >= 0) dma_chunk(even_c, SL.slot[st + 1][m], nxt, kc + 1, ra_t, rb_t);
+                        if (st < 2 && SL.slot[st + 1][m] >= 0) {
+                            if constexpr (tail == 1) issue_piece(nxt, b0, SL.slot[st + 1][m]);
+                            else dma_chunk(even_c, SL.slot[st + 1][m], nxt, kc + 1, ra_t, rb_t);
+                        }
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
@@ -810,13 +910,35 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 #pragma unroll
                     for (int j = (m - PRE) * RPS3; j < (m - PRE + 1) * RPS3; ++j)
                         if (j < NRD) read_one(nxt, 0, 0, j);
-                    if (SL.slot[0][m] >= 0) dma_chunk(even_c, SL.slot[0][m], cur, kc + 2, ra_t, rb_t);
+                    if (SL.slot[0][m] >= 0) {
+                        if constexpr (tail == 2) issue_piece(cur, b0, SL.slot[0][m]);
+                        else if constexpr (tail == 0) dma_chunk(even_c, SL.slot[0][m], cur, kc + 2, ra_t, rb_t);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             };
-            for (int kc = 0; kc < nk; kc += 2) {
-                k_tile(std::integral_constant<int, 0>{}, kc);
-                if (kc + 1 < nk) k_tile(std::integral_constant<int, 1>{}, kc + 1);
+            using I0 = std::integral_constant<int, 0>;
+            using I1 = std::integral_constant<int, 1>;
+            using I2 = std::integral_constant<int, 2>;
+            const int n_loop = pre ? nk - 2 : nk;  // tiles of the loop proper
+            const ExtBatch no_batch{};
+            int kc = 0;
+            for (; kc + 1 < n_loop; kc += 2) {
+                k_tile(I0{}, I0{}, kc, no_batch);
+                k_tile(I1{}, I0{}, kc + 1, no_batch);
+            }
+            if (kc < n_loop) k_tile(I0{}, I0{}, kc++, no_batch);
+            if constexpr (CAN_PRE) {
+                if (pre) {
+                    const ExtBatch b0 = get_batch(e0);
+                    if (kc & 1) {
+                        k_tile(I1{}, I2{}, kc, b0);
+                        k_tile(I0{}, I1{}, kc + 1, b0);
+                    } else {
+                        k_tile(I0{}, I2{}, kc, b0);
+                        k_tile(I1{}, I1{}, kc + 1, b0);
+                    }
+                }
             }
             wait_dma();  // loads of tiles beyond the last one fetch nothing but still signal completion
             };
@@ -870,90 +992,9 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     // step's row range, rank indices beyond the adapter's rank and columns beyond N are filled
     // with zeros (out-of-range buffer offsets, or the zero block).
     if (!PARTIAL && e1 > e0) {
-        const i32x4 rh_w = make_rsrc_words(p.hs, p.hs_bytes);
-        const uint64_t zeros = reinterpret_cast<uint64_t>(p.zeros);
-        // per-lane choice among the four steps of a batch
-        auto pick = [](int j, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3) { return j == 0 ? v0 : (j == 1 ? v1 : (j == 2 ? v2 : v3)); };
-        constexpr int ND = ACH + BCH;  // direct loads (16 bytes per lane each) of a batch per wave
-        // piece d of a batch: chunk d of the rows' operand, or chunk d - ACH of the tables'
-        // (called with d known after unrolling: the branches and the step index fold away)
-        // live = false: the piece only fills its place with zeros (no memory is read)
-        auto issue_piece = [&](int stage, const ExtBatch &bt, const int D, const bool live) {
-            if (D < ACH) {
-                // rows: position c8 of row r holds chunk cl; chunk cl belongs to step cl / 2, rank
-                // indices koff + 8 (cl % 2) ..
-                const int i = D;
-                const int r = r8 + i * (NT / 8);
-                const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
-                const int j = cl >> 1;
-                const uint32_t kr = pick(j, bt.kr[0], bt.kr[1], bt.kr[2], bt.kr[3]);
-                const uint32_t rows = pick(j, bt.rows[0], bt.rows[1], bt.rows[2], bt.rows[3]);
-                // siblings: the columns after a sibling's own are the next sibling's, or were never written
-                const bool in = live && r >= (int)(rows & 0xffffu) && r < (int)(rows >> 16) &&
-                                (p.n_sib <= 1 || (kr & 0xffffu) + (cl & 1) * 8u < (kr >> 16));
-                const uint32_t off = in ? ((uint32_t)(m0 + r) * (uint32_t)p.hs_ld + (uint32_t)sib * (kr >> 16) + (kr & 0xffffu) + (cl & 1) * 8u) * 2u : kOob;
-                dma16(rh_w, off, lds_wave + (stage ? A_ST1 : 0) + i * (NT / 64) * 1024);
-            } else if constexpr (!B_KMAJOR) {
-                // table rows are rank indices: B_a[q][n]; tile row 16 j + i is rank index koff_j + i.
-                // All lanes of a load belong to one step, whose table is the load's buffer: rank
-                // indices beyond the rank lie beyond it.
-                static_assert(16 % (NT / NG) == 0 || (NT / NG) % 16 == 0, "a direct load must not straddle two steps");
-                const int i = D - ACH;
-                const int j = (i * (NT / NG)) >> 4;
-                const int k = bk0 + i * (NT / NG);
-                uint32_t rk = bt.kr[j] >> 16, koff = bt.kr[j] & 0xffffu;
-                bool mine = true;
-                if constexpr (SWIGLU) {
-                    // the step belongs to the gate sibling (first half of the ranks) or the up sibling
-                    rk >>= 1;
-                    const bool up = koff >= rk;
-                    koff -= up ? rk : 0u;
-                    mine = (bcl * 8 >= BN / 2) == up;
-                }
-                const i32x4 rt = make_rsrc_words(reinterpret_cast<const void *>(bt.tab[j]), rk * (uint32_t)p.ext_ld * 2u);
-                const uint32_t off = (live && mine && col_on(bcl * 8)) ? ((koff + (uint32_t)(k & 15)) * (uint32_t)p.ext_ld + (uint32_t)src_col(bcl * 8)) * 2u : kOob;
-                dma16(rt, off, lds_wave + (stage ? B_ST1 : B_ST0) + i * (NT / 64) * 1024);
-            } else {
-                // table rows are output columns: A_a[n][q], row length rank.  The four steps of a
-                // batch may have four tables, so every lane forms its own 64-bit address.
-                const int i = D - ACH;
-                const bool all8 = (((bt.kr[0] | bt.kr[1] | bt.kr[2] | bt.kr[3]) >> 16) & 7u) == 0;
-                const int r = r8 + i * (NT / 8);
-                const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
-                const int j = cl >> 1;
-                const uint32_t kr = pick(j, bt.kr[0], bt.kr[1], bt.kr[2], bt.kr[3]);
-                const uint32_t tlo = pick(j, (uint32_t)bt.tab[0], (uint32_t)bt.tab[1], (uint32_t)bt.tab[2], (uint32_t)bt.tab[3]);
-                const uint32_t thi = pick(j, (uint32_t)(bt.tab[0] >> 32), (uint32_t)(bt.tab[1] >> 32), (uint32_t)(bt.tab[2] >> 32), (uint32_t)(bt.tab[3] >> 32));
-                if (all8) {
-                    const uint32_t rk = kr >> 16, q0 = (kr & 0xffffu) + (cl & 1) * 8u;
-                    const bool in = live && n0 + r < N && q0 < rk;
-                    const uint64_t addr = in ? (((uint64_t)thi << 32) | tlo) + ((uint64_t)(n0 + r) * rk + q0) * 2u : zeros;
-                    dma16g(addr, lds_wave + (stage ? B_ST1 : B_ST0) + i * (NT / 64) * 1024);
-                } else {
-                    // some rank is no multiple of 8: table rows are not 16-byte aligned; element by element
-                    uint8_t *tb = smem + (stage ? B_ST1 : B_ST0);
-                    const int rk = (int)(kr >> 16), q0 = (int)(kr & 0xffffu) + (cl & 1) * 8;
-                    uint16_t e[8];
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) e[q] = 0;
-                    if (live && n0 + r < N) {
-                        const uint16_t *src = reinterpret_cast<const uint16_t *>(((uint64_t)thi << 32) | tlo) + (int64_t)(n0 + r) * rk + q0;
-#pragma unroll
-                        for (int q = 0; q < 8; ++q)
-                            if (q0 + q < rk) e[q] = src[q];
-                    }
-                    uint4 v;
-                    v.x = e[0] | ((uint32_t)e[1] << 16);
-                    v.y = e[2] | ((uint32_t)e[3] << 16);
-                    v.z = e[4] | ((uint32_t)e[5] << 16);
-                    v.w = e[6] | ((uint32_t)e[7] << 16);
-                    *reinterpret_cast<uint4 *>(tb + (r8 + i * (NT / 8)) * 128 + c8 * 16) = v;
-                }
-            }
-        };
         auto issue_batch = [&](int stage, const ExtBatch &bt) {
 #pragma unroll
-            for (int d = 0; d < ND; ++d) issue_piece(stage, bt, d, true);
+            for (int d = 0; d < ND; ++d) issue_piece(stage, bt, d);
         };
 
         // A step touches only the rows of its adapter: a wave multiplies only those of its 32-row blocks that
@@ -974,17 +1015,16 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
             }
         };
         ExtBatch cur_b = get_batch(e0);
-        issue_batch(0, cur_b);
+        if (!pre) issue_batch(0, cur_b);
         ExtBatch nxt_b = get_batch(e0 + kExtBatch);
-        int stage = 0;
+        int stage = pre ? (nk & 1) : 0;  // with `pre` the batch lies where the tile after the last would
         for (int eb = e0; eb < e1; eb += kExtBatch, stage ^= 1) {
             drain_and_barrier();  // this batch has landed; the stage of the batch before it is free
             const int nsteps = (e1 - eb) < kExtBatch ? (e1 - eb) : kExtBatch;
             read_frags(stage, 0, 0);
             if (nsteps > 1) read_frags(stage, 1, 1);
             {
-                // step 0, with the loads of the next batch (addresses and all) riding behind its MFMAs; after
-                // the last batch they only write zeros into the stage that is free
+                // step 0, with the loads of the next batch (addresses and all) riding behind its MFMAs
                 const bool more = eb + kExtBatch < e1;
                 constexpr int NM = MI * NI;
 #pragma unroll
@@ -994,8 +1034,10 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                         for (int ni = 0; ni < NI; ++ni)
                             acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[0][ni], af[0][mi], acc[ni][mi], 0, 0, 0);
                     }
+                    if (more) {
 #pragma unroll
-                    for (int d = mi * ND / MI; d < (mi + 1) * ND / MI; ++d) issue_piece(stage ^ 1, nxt_b, d, more);
+                        for (int d = mi * ND / MI; d < (mi + 1) * ND / MI; ++d) issue_piece(stage ^ 1, nxt_b, d);
+                    }
                 }
             }
 #pragma unroll
@@ -1008,7 +1050,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
             cur_b = nxt_b;
             nxt_b = get_batch(eb + 2 * kExtBatch);
         }
-        drain_and_barrier();  // the zero fills behind the last batch have landed: LDS is free for the epilogue
+        drain_and_barrier();  // every wave has its last fragments: LDS is free for the epilogue
     }
 
     // ---- epilogue: one rounding to bf16, rows scattered back to their tokens --------------
