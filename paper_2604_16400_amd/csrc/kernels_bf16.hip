@@ -1481,6 +1481,26 @@ __global__ void __launch_bounds__(SkinnyCfg<RP>::KW * 64) skinny_kernel(SkinnyAr
     }
 }
 
+// Sum of n values that lie `stride` floats apart, added in index order; four loads are in flight at a time
+// (the kernels that add K slices are bound by the latency of these loads, not by their bytes).
+__device__ __forceinline__ floatx4 sum_slices(const float *first, int64_t stride, int n)
+{
+    floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};
+    int i = 0;
+    for (; i + 4 <= n; i += 4) {
+        const floatx4 v0 = *reinterpret_cast<const floatx4 *>(first + (i + 0) * stride);
+        const floatx4 v1 = *reinterpret_cast<const floatx4 *>(first + (i + 1) * stride);
+        const floatx4 v2 = *reinterpret_cast<const floatx4 *>(first + (i + 2) * stride);
+        const floatx4 v3 = *reinterpret_cast<const floatx4 *>(first + (i + 3) * stride);
+        sum += v0;
+        sum += v1;
+        sum += v2;
+        sum += v3;
+    }
+    for (; i < n; ++i) sum += *reinterpret_cast<const floatx4 *>(first + i * stride);
+    return sum;
+}
+
 // adds the K slices of every item in slice order and writes the results; block (i, j) takes rows
 // 16 j .. 16 j + 15 of item i
 __global__ void __launch_bounds__(256) skinny_finish_kernel(SkinnyArgs p, int n_split)
@@ -1491,9 +1511,7 @@ __global__ void __launch_bounds__(256) skinny_finish_kernel(SkinnyArgs p, int n_
     const int m_lo = blockIdx.y * 16, m_hi = it.n_rows < m_lo + 16 ? it.n_rows : m_lo + 16;
     for (int idx = threadIdx.x; idx < (m_hi - m_lo) * nq; idx += 256) {
         const int m = m_lo + idx / nq, q = (idx % nq) * 4;
-        floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};
-        for (int sp = 0; sp < n_split; ++sp)
-            sum += *reinterpret_cast<const floatx4 *>(p.part + ((int64_t)sp * p.part_rows + it.row_lo + m) * p.part_ld + q);
+        const floatx4 sum = sum_slices(p.part + (int64_t)(it.row_lo + m) * p.part_ld + q, (int64_t)p.part_rows * p.part_ld, n_split);
         skinny_store(p, it, m, q, sum);
     }
 }
@@ -1789,9 +1807,7 @@ __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p, int n_spli
     const int tok = p.row_tok[p.row_base + r];
     const int n = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (tok < 0 || n >= p.N) return;
-    floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};
-    for (int sp = 0; sp < n_split; ++sp)
-        sum += *reinterpret_cast<const floatx4 *>(p.part + ((int64_t)sp * p.part_rows + r) * p.part_ld + n);
+    const floatx4 sum = sum_slices(p.part + (int64_t)r * p.part_ld + n, (int64_t)p.part_rows * p.part_ld, n_split);
     uint2 v;
     v.x = pack_bf16(sum[0], sum[1]);
     v.y = pack_bf16(sum[2], sum[3]);
