@@ -301,7 +301,8 @@ void patch_tables(collm_ctx *c, int N, const void *const *A, const void *const *
     }
     auto patch = [&](int32_t off_ext, const std::vector<int32_t> &step_adapter, const void *const *tab) {
         ExtStep *ext = reinterpret_cast<ExtStep *>(c->plan.data() + off_ext);
-        for (size_t k = 0; k < step_adapter.size(); ++k) ext[k].tab = (uint64_t)(uintptr_t)tab[step_adapter[k]];
+        for (size_t k = 0; k < step_adapter.size(); ++k)
+            if (step_adapter[k] >= 0) ext[k].tab = (uint64_t)(uintptr_t)tab[step_adapter[k]];  // (empty steps have no table)
     };
     patch(L.all.off_ext, L.all.ext_adapter, B);            // forward: expand tables
     patch(L.all.off_ext_half, L.all.ext_adapter_half, B);

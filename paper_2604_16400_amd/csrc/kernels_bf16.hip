@@ -344,7 +344,7 @@ struct DmaSlots {
 // sums go to the workspace and gemm_finish_kernel adds the slices, rounds once and scatters the rows.
 constexpr int kWideStages = 4;  // LDS stages of the PARTIAL loop (128x128 tiles: 32 KiB each)
 template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR, bool PINGPONG, bool PARTIAL = false, bool SWIGLU = false,
-          bool SPLITK = false>
+          bool SPLITK = false, bool SIBS = false>
 __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 {
     static_assert(!SWIGLU || (!B_KMAJOR && !PINGPONG && !PARTIAL && WGN == 2), "SwiGLU epilogue: N-major, two wave columns");
@@ -621,10 +621,19 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     const uint64_t zeros = reinterpret_cast<uint64_t>(p.zeros);
     // per-lane choice among the four steps of a batch
     auto pick = [](int j, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3) { return j == 0 ? v0 : (j == 1 ? v1 : (j == 2 ? v2 : v3)); };
-    // piece d of a batch: chunk d of the rows' operand, or chunk d - ACH of the tables'
-    // (called with d known after unrolling: the branches and the step index fold away)
-    auto issue_piece = [&](int stage, const ExtBatch &bt, const int D) {
-        if (D < ACH) {
+    // piece d of a batch: chunk d of the rows' operand (into the LDS area at byte a_base), or chunk d - ACH of
+    // the tables' (area at b_base); called with d known after unrolling: the branches and the step index fold away.
+    // once: the rows' operand is not that of the batch but rank indices 64 g .. 64 g + 63 of every row's own s h
+    // (or dh), whatever its adapter: it is loaded once for the whole tile and masked per step when it is used.
+    auto issue_piece = [&](uint32_t a_base, uint32_t b_base, const ExtBatch &bt, const int D, const bool once, const int g) {
+        if (D < ACH && once) {
+            const int i = D;
+            const int r = r8 + i * (NT / 8);
+            const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
+            const int k = 64 * g + cl * 8;
+            const uint32_t off = k < p.hs_ld ? ((uint32_t)(m0 + r) * (uint32_t)p.hs_ld + (uint32_t)k) * 2u : kOob;
+            dma16(rh_w, off, lds_wave + a_base + i * (NT / 64) * 1024);
+        } else if (D < ACH) {
             // rows: position c8 of row r holds chunk cl; chunk cl belongs to step cl / 2, rank
             // indices koff + 8 (cl % 2) ..
             const int i = D;
@@ -637,7 +646,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
             const bool in = r >= (int)(rows & 0xffffu) && r < (int)(rows >> 16) &&
                             (p.n_sib <= 1 || (kr & 0xffffu) + (cl & 1) * 8u < (kr >> 16));
             const uint32_t off = in ? ((uint32_t)(m0 + r) * (uint32_t)p.hs_ld + (uint32_t)sib * (kr >> 16) + (kr & 0xffffu) + (cl & 1) * 8u) * 2u : kOob;
-            dma16(rh_w, off, lds_wave + (stage ? A_ST1 : 0) + i * (NT / 64) * 1024);
+            dma16(rh_w, off, lds_wave + a_base + i * (NT / 64) * 1024);
         } else if constexpr (!B_KMAJOR) {
             // table rows are rank indices: B_a[q][n]; tile row 16 j + i is rank index koff_j + i.
             // All lanes of a load belong to one step, whose table is the load's buffer: rank
@@ -657,7 +666,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
             }
             const i32x4 rt = make_rsrc_words(reinterpret_cast<const void *>(bt.tab[j]), rk * (uint32_t)p.ext_ld * 2u);
             const uint32_t off = (mine && col_on(bcl * 8)) ? ((koff + (uint32_t)(k & 15)) * (uint32_t)p.ext_ld + (uint32_t)src_col(bcl * 8)) * 2u : kOob;
-            dma16(rt, off, lds_wave + (stage ? B_ST1 : B_ST0) + i * (NT / 64) * 1024);
+            dma16(rt, off, lds_wave + b_base + i * (NT / 64) * 1024);
         } else {
             // table rows are output columns: A_a[n][q], row length rank.  The four steps of a
             // batch may have four tables, so every lane forms its own 64-bit address.
@@ -673,10 +682,10 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                 const uint32_t rk = kr >> 16, q0 = (kr & 0xffffu) + (cl & 1) * 8u;
                 const bool in = n0 + r < N && q0 < rk;
                 const uint64_t addr = in ? (((uint64_t)thi << 32) | tlo) + ((uint64_t)(n0 + r) * rk + q0) * 2u : zeros;
-                dma16g(addr, lds_wave + (stage ? B_ST1 : B_ST0) + i * (NT / 64) * 1024);
+                dma16g(addr, lds_wave + b_base + i * (NT / 64) * 1024);
             } else {
                 // some rank is no multiple of 8: table rows are not 16-byte aligned; element by element
-                uint8_t *tb = smem + (stage ? B_ST1 : B_ST0);
+                uint8_t *tb = smem + b_base;
                 const int rk = (int)(kr >> 16), q0 = (int)(kr & 0xffffu) + (cl & 1) * 8;
                 uint16_t e[8];
 #pragma unroll
@@ -700,7 +709,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     // Whether the first batch is loaded from inside the main loop (see k_tile): the hand-scheduled loop with at
     // least two tiles, and every piece of the batch one direct load (tables with K contiguous: ranks in eights).
     // Not for 256x256 tiles: their main loop leaves no registers for the address arithmetic of these loads.
-    constexpr bool CAN_PRE = !PINGPONG && !PARTIAL && BM * BN < 256 * 256;
+    constexpr bool CAN_PRE = !PINGPONG && !PARTIAL && !SIBS && BM * BN < 256 * 256;
     bool pre = false;
     if constexpr (CAN_PRE) {
         uint32_t kr_or = 0;  // lanes beyond the tile's steps hold zeros
@@ -890,7 +899,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                         for (int j = m * RPS; j < (m + 1) * RPS; ++j)
                             if (j < NRD) read_one(cur, st + 1, (st + 1) & 1, j);
                         if (st < 2 && SL.slot[st + 1][m] >= 0) {
-                            if constexpr (tail == 1) issue_piece(nxt, b0, SL.slot[st + 1][m]);
+                            if constexpr (tail == 1) issue_piece(nxt ? A_ST1 : 0, nxt ? B_ST1 : B_ST0, b0, SL.slot[st + 1][m], true, 0);
                             else dma_chunk(even_c, SL.slot[st + 1][m], nxt, kc + 1, ra_t, rb_t);
                         }
                         __builtin_amdgcn_sched_barrier(0);
@@ -911,7 +920,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                     for (int j = (m - PRE) * RPS3; j < (m - PRE + 1) * RPS3; ++j)
                         if (j < NRD) read_one(nxt, 0, 0, j);
                     if (SL.slot[0][m] >= 0) {
-                        if constexpr (tail == 2) issue_piece(cur, b0, SL.slot[0][m]);
+                        if constexpr (tail == 2) issue_piece(cur ? A_ST1 : 0, cur ? B_ST1 : B_ST0, b0, SL.slot[0][m], true, 0);
                         else if constexpr (tail == 0) dma_chunk(even_c, SL.slot[0][m], cur, kc + 2, ra_t, rb_t);
                     }
                     __builtin_amdgcn_sched_barrier(0);
@@ -991,10 +1000,10 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     // of its loads, and those of the first batch before the main loop.  Rows of the tile outside a
     // step's row range, rank indices beyond the adapter's rank and columns beyond N are filled
     // with zeros (out-of-range buffer offsets, or the zero block).
-    if (!PARTIAL && e1 > e0) {
+    if (SIBS && !PARTIAL && e1 > e0) {
         auto issue_batch = [&](int stage, const ExtBatch &bt) {
 #pragma unroll
-            for (int d = 0; d < ND; ++d) issue_piece(stage, bt, d);
+            for (int d = 0; d < ND; ++d) issue_piece(stage ? A_ST1 : 0, stage ? B_ST1 : B_ST0, bt, d, false, 0);
         };
 
         // A step touches only the rows of its adapter: a wave multiplies only those of its 32-row blocks that
@@ -1036,7 +1045,8 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                     }
                     if (more) {
 #pragma unroll
-                        for (int d = mi * ND / MI; d < (mi + 1) * ND / MI; ++d) issue_piece(stage ^ 1, nxt_b, d);
+                        for (int d = mi * ND / MI; d < (mi + 1) * ND / MI; ++d)
+                            issue_piece(stage ? 0 : A_ST1, stage ? B_ST0 : B_ST1, nxt_b, d, false, 0);
                     }
                 }
             }
@@ -1049,6 +1059,122 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
             }
             cur_b = nxt_b;
             nxt_b = get_batch(eb + 2 * kExtBatch);
+        }
+        drain_and_barrier();  // every wave has its last fragments: LDS is free for the epilogue
+    } else if (!SIBS && !PARTIAL && e1 > e0) {
+        // One projection (or the SwiGLU pair, whose s h rows hold gate and up ranks side by side).  A batch of
+        // the scheme above is bound by latency: its loads have only the batch before it to land.  Here the rows'
+        // operand is loaded once for the tile: one LDS area holds rank indices 64 g .. 64 g + 63 of every row's
+        // own s h (rows of different adapters side by side, what lies beyond a row's rank is never used), a step
+        // reads its fragments at its own rank offset and clears the rows outside its row range in registers.
+        // Only the tables stream: three areas, the loads of two batches in flight while one multiplies.
+        static_assert(ATILE >= BTILE, "a table area must fit the place of a row area");
+        const int par = pre ? (nk & 1) : 0;  // with `pre` the first batch lies where the tile after the last would
+        const uint32_t xa = par ? A_ST1 : 0;
+        uint32_t t_cur = par ? B_ST1 : B_ST0, t_nxt = par ? B_ST0 : B_ST1, t_far = par ? 0 : A_ST1;
+        const int wrow0 = __builtin_amdgcn_readfirstlane(wm * WM);
+        auto block_on = [&](uint32_t rows, int mi) {
+            const int lo = (int)(rows & 0xffffu), hi = (int)(rows >> 16);
+            return lo < wrow0 + mi * 32 + 32 && hi > wrow0 + mi * 32;
+        };
+        auto issue_rows = [&](int g) {
+#pragma unroll
+            for (int d = 0; d < ACH; ++d) issue_piece(xa, 0u, ExtBatch{}, d, true, g);
+        };
+        // true if every piece was one direct load (what the waits below count)
+        auto issue_tab = [&](uint32_t base, const ExtBatch &bt) -> bool {
+#pragma unroll
+            for (int d = ACH; d < ND; ++d) issue_piece(0u, base, bt, d, false, 0);
+            return !B_KMAJOR || (((bt.kr[0] | bt.kr[1] | bt.kr[2] | bt.kr[3]) >> 16) & 7u) == 0;
+        };
+        // fragments of step j of the batch in the table area `base`: rank offset koff, rows [lo, hi)
+        auto read_step = [&](uint32_t base, int j, uint32_t kr, uint32_t rows, int buf) {
+            const int c0 = (int)((kr & 63u) >> 3) + kh;
+            const int lo = (int)(rows & 0xffffu), hi = (int)(rows >> 16);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                if (block_on(rows, mi)) {
+                    const int row = wm * WM + mi * 32 + rl;
+                    uint4 v = __builtin_bit_cast(uint4, lds_frag(smem + xa, row, c0));
+                    const bool in = row >= lo && row < hi;
+                    v.x = in ? v.x : 0u;
+                    v.y = in ? v.y : 0u;
+                    v.z = in ? v.z : 0u;
+                    v.w = in ? v.w : 0u;
+                    af[buf][mi] = __builtin_bit_cast(bf16x8, v);
+                }
+            }
+            const uint8_t *tb = smem + base;
+            if constexpr (B_KMAJOR) {
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) bf[buf][ni] = lds_frag(tb, wn * WN + ni * 32 + rl, j * 2 + kh);
+            } else {
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) {
+                    const uint8_t *src = tb + btr[ni] + j * 16 * BPITCH;
+                    const bf16x4 lo4 = lds_tr(src);
+                    const bf16x4 hi4 = lds_tr(src + 4 * BPITCH);
+                    bf[buf][ni] = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+                }
+            }
+        };
+        auto mma_rows = [&](int buf, uint32_t rows) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                if (block_on(rows, mi)) {
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni)
+                        acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[buf][ni], af[buf][mi], acc[ni][mi], 0, 0, 0);
+                }
+            }
+        };
+        auto lds_done_and_barrier = [] { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+
+        ExtBatch cur_b = get_batch(e0);
+        ExtBatch nxt_b = get_batch(e0 + kExtBatch);
+        int g_cur = pre ? 0 : (int)((cur_b.kr[0] & 0xffffu) >> 6);  // (what the main loop's last tiles loaded: 0)
+        if (!pre) {
+            issue_rows(g_cur);
+            issue_tab(t_cur, cur_b);
+        }
+        bool nxt_direct = true;
+        if (e0 + kExtBatch < e1) nxt_direct = issue_tab(t_nxt, nxt_b);
+        for (int eb = e0; eb < e1; eb += kExtBatch) {
+            const bool has1 = eb + kExtBatch < e1, has2 = eb + 2 * kExtBatch < e1;
+            // this batch has landed (loads complete in order; those of the batch after it may still be on their way)
+            if (has1 && nxt_direct) wait_dma_but<BCH>();
+            else wait_dma();
+            lds_done_and_barrier();  // ... in every wave, and the area of the batch before it is free
+            const ExtBatch far_b = get_batch(eb + 2 * kExtBatch);
+            bool far_direct = true;
+            if (has2) far_direct = issue_tab(t_far, far_b);
+            const int nsteps = (e1 - eb) < kExtBatch ? (e1 - eb) : kExtBatch;
+            {
+                // the steps of a batch lie inside one group of 64 rank indices (the planner sees to that); when the
+                // group changes, the rows' area is loaded again (ranks above 64 only, once per tile and group)
+                const int g = (int)((cur_b.kr[0] & 0xffffu) >> 6);
+                if (g != g_cur) {
+                    issue_rows(g);  // every wave is past the barrier above: none reads the old rows any more
+                    wait_dma();
+                    lds_done_and_barrier();
+                    g_cur = g;
+                }
+            }
+            read_step(t_cur, 0, cur_b.kr[0], cur_b.rows[0], 0);
+#pragma unroll
+            for (int j = 0; j < kExtBatch; ++j) {
+                if (j < nsteps) {
+                    if (j + 1 < nsteps) read_step(t_cur, j + 1, cur_b.kr[(j + 1) & 3], cur_b.rows[(j + 1) & 3], (j + 1) & 1);
+                    mma_rows(j & 1, cur_b.rows[j]);
+                }
+            }
+            const uint32_t t = t_cur;
+            t_cur = t_nxt;
+            t_nxt = t_far;
+            t_far = t;
+            cur_b = nxt_b;
+            nxt_b = far_b;
+            nxt_direct = far_direct;
         }
         drain_and_barrier();  // every wave has its last fragments: LDS is free for the epilogue
     }
@@ -1731,7 +1857,7 @@ __global__ void __launch_bounds__(GradCfg<RP>::KW * 64) grad_kernel(GradArgs p)
 // =========================================================================================
 // launchers
 // =========================================================================================
-template <int BM, int BN, int WGM, int WGN, bool KM, bool PP, bool SWIGLU = false>
+template <int BM, int BN, int WGM, int WGN, bool KM, bool PP, bool SWIGLU = false, bool SIBS = false>
 static hipError_t launch_gemm_t(const GemmArgs &a, hipStream_t st)
 {
     constexpr int NT = WGM * WGN * 64;
@@ -1739,7 +1865,7 @@ static hipError_t launch_gemm_t(const GemmArgs &a, hipStream_t st)
     constexpr int epi_bytes = BM * BN * 2 + BM * WGN * 16;  // per wave (BM/WGM) rows of (BN/WGN) * 2 + 16 bytes
     constexpr int smem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
     static_assert(!SWIGLU || smem >= BM * (BN / 2) * 4, "the up halves of all rows pass through LDS as fp32");
-    auto kern = gemm_lora_kernel<BM, BN, WGM, WGN, KM, PP, false, SWIGLU>;
+    auto kern = gemm_lora_kernel<BM, BN, WGM, WGN, KM, PP, false, SWIGLU, false, SIBS>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -1755,6 +1881,23 @@ static hipError_t launch_gemm_t(const GemmArgs &a, hipStream_t st)
 
 hipError_t launch_gemm(const GemmArgs &a, int tile_cfg, bool b_kmajor, hipStream_t st)
 {
+    if (a.n_sib > 1) {
+        // sibling projections side by side (forward only, second operand [K][N]): the kernels whose extension
+        // loads the rows' operand per batch, at the sibling's offset inside each adapter's ranks
+        if (b_kmajor) return hipErrorInvalidValue;
+        switch (tile_cfg) {
+        case kTile256x256:
+            return launch_gemm_t<256, 256, 2, 2, false, false, false, true>(a, st);
+        case kTile256x128:
+            return launch_gemm_t<256, 128, 2, 2, false, false, false, true>(a, st);
+        case kTile128x128:
+            return launch_gemm_t<128, 128, 2, 2, false, false, false, true>(a, st);
+        case kTile256x256w8:
+            return launch_gemm_t<256, 256, 2, 4, false, true, false, true>(a, st);
+        default:
+            return hipErrorInvalidValue;
+        }
+    }
     switch (tile_cfg) {
     case kTile256x256:
         return b_kmajor ? launch_gemm_t<256, 256, 2, 2, true, false>(a, st) : launch_gemm_t<256, 256, 2, 2, false, false>(a, st);
@@ -1831,6 +1974,7 @@ hipError_t launch_gemm_splitk(const GemmArgs &a, int n_split, bool b_kmajor, hip
         hipLaunchKernelGGL(kern, dim3(tiles, n_split), dim3(256), smem, st, a);
         return hipGetLastError();
     };
+    if (a.n_sib > 1) return b_kmajor ? hipErrorInvalidValue : launch(gemm_lora_kernel<128, 128, 2, 2, false, false, false, false, true, true>);
     return b_kmajor ? launch(gemm_lora_kernel<128, 128, 2, 2, true, false, false, false, true>)
                     : launch(gemm_lora_kernel<128, 128, 2, 2, false, false, false, false, true>);
 }

@@ -40,6 +40,7 @@ struct ExtStep {
     uint64_t tab;        // device address of the adapter's table for this GEMM (B_a forward, A_a backward)
 };
 constexpr int kExtBatch = 4;  // steps a kernel fetches at a time; the step array is padded by as many
+constexpr int kExtGroup = 64;  // rank indices of a group (kExtBatch steps): the steps of a tile are listed group by group
 
 // Training rows of one trained adapter inside the training row order.
 struct GradItem {

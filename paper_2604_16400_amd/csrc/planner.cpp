@@ -191,19 +191,32 @@ void build_row_order(Builder &b, RowOrderLayout &L, const std::vector<int32_t> &
         for (int t = 0; t < n_tiles; ++t) {
             ext_off[t] = (int)ext.size();
             const int r0 = t * tile_rows, r1 = std::min(n, r0 + tile_rows);
-            int r = r0;
-            while (r < r1) {
-                const int a = b.blk[L.off_row_adapter + r];
-                int e = r + 1;
-                while (e < r1 && b.blk[L.off_row_adapter + e] == a) ++e;
-                if (a >= 0) {
-                    const uint64_t tab = ext_tab ? (uint64_t)(uintptr_t)ext_tab[a] : 0;
-                    for (int k = 0; k < rank_ext[a]; k += kKStep) {
-                        ext.push_back({(uint32_t)k | ((uint32_t)rank_ext[a] << 16), (uint32_t)(r - r0) | ((uint32_t)(e - r0) << 16), tab});
-                        step_adapter.push_back(a);
+            // The steps of a tile are listed by 64-wide groups of rank indices (all runs' steps below 64, then
+            // those of 64..127, ...), and a group that is not the tile's last is filled up to whole batches with
+            // empty steps: a batch then lies inside one group, which is what a kernel that keeps one group of
+            // every row's low-rank activations in LDS needs.  (Ranks up to 64: one group, nothing changes.)
+            for (int g0 = 0, more = 1; more; g0 += kExtGroup) {
+                more = 0;
+                if (g0 > 0)
+                    while (((int)ext.size() - ext_off[t]) % kExtBatch != 0) {
+                        ext.push_back({0u, 0u, 0});
+                        step_adapter.push_back(-1);
                     }
+                int r = r0;
+                while (r < r1) {
+                    const int a = b.blk[L.off_row_adapter + r];
+                    int e = r + 1;
+                    while (e < r1 && b.blk[L.off_row_adapter + e] == a) ++e;
+                    if (a >= 0) {
+                        const uint64_t tab = ext_tab ? (uint64_t)(uintptr_t)ext_tab[a] : 0;
+                        for (int k = g0; k < std::min(rank_ext[a], g0 + kExtGroup); k += kKStep) {
+                            ext.push_back({(uint32_t)k | ((uint32_t)rank_ext[a] << 16), (uint32_t)(r - r0) | ((uint32_t)(e - r0) << 16), tab});
+                            step_adapter.push_back(a);
+                        }
+                        if (rank_ext[a] > g0 + kExtGroup) more = 1;
+                    }
+                    r = e;
                 }
-                r = e;
             }
             most = std::max(most, (int)ext.size() - ext_off[t]);
         }

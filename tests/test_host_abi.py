@@ -86,14 +86,19 @@ def test_token_map_rejects_bad_tables():
 # ---------------------------------------------------------------------------------------------
 def _steps_from_rows(row_tok, tok_adapter, ranks, tile_rows):
     """K-steps per row tile, counted from the row order: every maximal run of one adapter inside a
-    tile costs ceil(rank / 16) steps."""
+    tile costs ceil(rank / 16) steps; the steps are listed by groups of 64 rank indices, and every group
+    but the tile's last is filled up to a multiple of four steps."""
     out = []
     for t0 in range(0, len(row_tok), tile_rows):
         ads = tok_adapter[row_tok[t0:t0 + tile_rows]]
-        n = 0
-        for i, a in enumerate(ads):
-            if a >= 0 and (i == 0 or ads[i - 1] != a):
-                n += (int(ranks[a]) + 15) // 16
+        run_ranks = [int(ranks[a]) for i, a in enumerate(ads) if a >= 0 and (i == 0 or ads[i - 1] != a)]
+        n, g = 0, 0
+        while True:
+            n += sum((min(r, g + 64) - g + 15) // 16 for r in run_ranks if r > g)
+            g += 64
+            if not any(r > g for r in run_ranks):
+                break
+            n = (n + 3) // 4 * 4
         out.append(n)
     return np.array(out, dtype=np.int32)
 
