@@ -710,6 +710,16 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     // least two tiles, and every piece of the batch one direct load (tables with K contiguous: ranks in eights).
     // Not for 256x256 tiles: their main loop leaves no registers for the address arithmetic of these loads.
     constexpr bool CAN_PRE = !PINGPONG && !PARTIAL && !SIBS && BM * BN < 256 * 256;
+    // The 256x256 tiles instead use what the main loop's two stages leave of the LDS (32 KiB of 160): the rows' area of
+    // the extension lies behind them and is loaded before the main loop starts.
+    constexpr bool ROWS_EARLY = !PINGPONG && !PARTIAL && !SIBS && !CAN_PRE;
+    constexpr uint32_t XA_EARLY = 2 * STAGE;
+    if constexpr (ROWS_EARLY) {
+        if (e1 > e0) {
+#pragma unroll
+            for (int d = 0; d < ACH; ++d) issue_piece(XA_EARLY, 0u, ExtBatch{}, d, true, 0);
+        }
+    }
     bool pre = false;
     if constexpr (CAN_PRE) {
         uint32_t kr_or = 0;  // lanes beyond the tile's steps hold zeros
@@ -1070,7 +1080,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         // Only the tables stream: three areas, the loads of two batches in flight while one multiplies.
         static_assert(ATILE >= BTILE, "a table area must fit the place of a row area");
         const int par = pre ? (nk & 1) : 0;  // with `pre` the first batch lies where the tile after the last would
-        const uint32_t xa = par ? A_ST1 : 0;
+        const uint32_t xa = ROWS_EARLY ? XA_EARLY : (par ? A_ST1 : 0);
         uint32_t t_cur = par ? B_ST1 : B_ST0, t_nxt = par ? B_ST0 : B_ST1, t_far = par ? 0 : A_ST1;
         const int wrow0 = __builtin_amdgcn_readfirstlane(wm * WM);
         auto block_on = [&](uint32_t rows, int mi) {
@@ -1132,9 +1142,9 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 
         ExtBatch cur_b = get_batch(e0);
         ExtBatch nxt_b = get_batch(e0 + kExtBatch);
-        int g_cur = pre ? 0 : (int)((cur_b.kr[0] & 0xffffu) >> 6);  // (what the main loop's last tiles loaded: 0)
+        int g_cur = (pre || ROWS_EARLY) ? 0 : (int)((cur_b.kr[0] & 0xffffu) >> 6);  // (what was loaded earlier: 0)
         if (!pre) {
-            issue_rows(g_cur);
+            if (!ROWS_EARLY) issue_rows(g_cur);
             issue_tab(t_cur, cur_b);
         }
         bool nxt_direct = true;
@@ -1861,7 +1871,8 @@ template <int BM, int BN, int WGM, int WGN, bool KM, bool PP, bool SWIGLU = fals
 static hipError_t launch_gemm_t(const GemmArgs &a, hipStream_t st)
 {
     constexpr int NT = WGM * WGN * 64;
-    constexpr int stage_bytes = 2 * (BM + BN) * 128;
+    // two stages; the 256x256 tiles of the direct-load pipeline keep the rows' area of the extension behind them
+    constexpr int stage_bytes = 2 * (BM + BN) * 128 + ((!PP && !SIBS && BM * BN == 256 * 256) ? BM * 128 : 0);
     constexpr int epi_bytes = BM * BN * 2 + BM * WGN * 16;  // per wave (BM/WGM) rows of (BN/WGN) * 2 + 16 bytes
     constexpr int smem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
     static_assert(!SWIGLU || smem >= BM * (BN / 2) * 4, "the up halves of all rows pass through LDS as fp32");
