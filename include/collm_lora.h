@@ -242,10 +242,12 @@ int collm_debug_device_token_map(collm_ctx *ctx, int32_t *tok_segment, int32_t *
  * Debug, HOST only (no GPU): how the library would cut a GEMM of `rows` x `cols` outputs with
  * contraction length K into tiles: *tile = 0 (256x256) or 2 (128x128) for the first
  * *big_tiles_m row tiles, then *tail_tiles_m row tiles of 128 rows as 128x128 tiles (0: none).
+ * *tail_cols (0: none; only with 256x256 tiles and no row tail): that many 256-wide tile columns
+ * at the right edge run as 128x128 tiles over all rows in a second launch.
  * can_split: whether few 128x128 tiles may cut K into slices (see collm_debug_set_gemm_split).
  */
 int collm_debug_host_tiling(int rows, int cols, int K, int can_split, int32_t *tile, int32_t *big_tiles_m,
-                            int32_t *tail_tiles_m);
+                            int32_t *tail_tiles_m, int32_t *tail_cols);
 
 /*
  * Debug, HOST only (no GPU): the order in which the plan lists the rows of a batch for the GEMM

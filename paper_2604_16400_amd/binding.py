@@ -101,7 +101,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.collm_token_map.restype = ctypes.c_int
     lib.collm_debug_device_token_map.argtypes = [vp, _i32p, _i32p, _u8p]
     lib.collm_debug_device_token_map.restype = ctypes.c_int
-    lib.collm_debug_host_tiling.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, _i32p, _i32p, _i32p]
+    lib.collm_debug_host_tiling.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, _i32p, _i32p, _i32p,
+                                            _i32p]
     lib.collm_debug_host_tiling.restype = ctypes.c_int
     lib.collm_debug_host_row_order.argtypes = [sp, _i32p, _i32p, _i32p, _u8p, ctypes.c_int, ctypes.c_int, _i32p, _i32p]
     lib.collm_debug_host_row_order.restype = ctypes.c_int
@@ -160,9 +161,10 @@ def collm_token_map(seg_start, seg_adapter, seg_is_train, n_tokens: Optional[int
 
 
 def host_tiling(rows: int, cols: int, K: int, can_split: bool = True):
-    """(tile, big_tiles_m, tail_tiles_m) the library would use for a GEMM of this size (host logic, no GPU)."""
+    """(tile, big_tiles_m, tail_tiles_m, tail_cols) the library would use for a GEMM of this size (host logic,
+    no GPU)."""
     lib = load_library()
-    out = [ctypes.c_int32(-9) for _ in range(3)]
+    out = [ctypes.c_int32(-9) for _ in range(4)]
     _check(lib.collm_debug_host_tiling(rows, cols, K, 1 if can_split else 0, *[ctypes.byref(o) for o in out]),
            "collm_debug_host_tiling")
     return tuple(o.value for o in out)

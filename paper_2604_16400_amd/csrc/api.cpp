@@ -97,12 +97,14 @@ struct collm_ctx {
 
 namespace {
 
-// How a GEMM's row tiles are cut: `tile` for the first `big_tiles_m` row tiles (all of them when
-// tail_tiles_m is 0), then 128x128 tiles for `tail_tiles_m` row tiles of 128 rows.
+// How a GEMM's tiles are cut: `tile` for the first `big_tiles_m` row tiles (all of them when
+// tail_tiles_m is 0), then 128x128 tiles for `tail_tiles_m` row tiles of 128 rows.  Or (tail_cols > 0, 256x256
+// tiles, no row tail): the last tail_cols tile columns of all rows run as 128x128 tiles in a second launch.
 struct Tiling {
     int tile;
     int big_tiles_m;
     int tail_tiles_m;
+    int tail_cols = 0;
 };
 
 // can_split: the 128x128 tiles behind the large ones may have K cut into slices (see run_gemm), which lets a few
@@ -137,7 +139,7 @@ Tiling pick_tiling(int rows, int cols, int K, bool can_split)
     const int rows128 = (std::max(rows, 1) + 127) / 128;
     const double cost256 = cost_large((double)tm * tn), cost128 = cost_small((double)rows128 * tn128);
     Tiling best = cost256 <= cost128 ? Tiling{kTile256x256, tm, 0} : Tiling{kTile128x128, rows128, 0};
-    const double best_cost = std::min(cost256, cost128);
+    double best_cost = std::min(cost256, cost128);
     const int rounds = tm * tn / 256;
     if (rounds >= 1 && (tm * tn) % 256 != 0) {
         const int m = std::min(tm - 1, rounds * 256 / tn);
@@ -147,7 +149,22 @@ Tiling pick_tiling(int rows, int cols, int K, bool can_split)
             const double tail_cost = (can_split && K >= 1024 && tail_tiles < 448) ? 0.65 * tail_tiles / 512.0 + 0.05
                                                                                  : cost_small(tail_tiles);
             const double cost = cost_large((double)m * tn) + tail_cost + 0.1;
-            if (cost < best_cost) best = Tiling{kTile256x256, m, tail};
+            if (cost < best_cost) {
+                best = Tiling{kTile256x256, m, tail};
+                best_cost = cost;
+            }
+        }
+    }
+    // ... or whole rounds over the first tile columns and the last columns of all rows as at most one round of
+    // 128x128 tiles (two per CU) in a second launch: a last round that fills part of the CUs with large tiles
+    // costs most of a round, 512 small tiles cost 0.65.
+    if (rounds >= 1 && (tm * tn) % 256 != 0) {
+        const int c = tn - rounds * 256 / tm;  // tile columns that do not fit the whole rounds
+        const int cols_tail = cols - 256 * (tn - c);
+        const long small = (long)rows128 * ((cols_tail + 127) / 128);
+        if (c >= 1 && c < tn && small <= 512) {
+            const double cost = cost_large((double)tm * (tn - c)) + cost_small((double)small) + 0.05;
+            if (cost < best_cost - 0.05) best = Tiling{kTile256x256, tm, 0, c};
         }
     }
     return best;
@@ -198,6 +215,19 @@ hipError_t run_gemm(collm_ctx *c, GemmArgs g, const RowOrderLayout &R, int rows,
     };
     hipError_t e = hipSuccess;
     if (t.tile == kTile128x128 && t.tail_tiles_m == 0 && try_split(t.big_tiles_m, 0, rows, e)) return e;
+    if (t.tail_cols > 0 && !swiglu) {
+        // whole rounds of large tiles over the first columns, small tiles over the other columns of all rows
+        const int tn_big = (cols + 255) / 256 - t.tail_cols;
+        g.tiles_n = tn_big;
+        e = launch_gemm(g, kTile256x256, b_kmajor, st);
+        if (e != hipSuccess) return e;
+        g.n_base = 256 * tn_big;
+        g.tiles_n = (cols - g.n_base + 127) / 128;
+        g.tiles_m = (rows + 127) / 128;
+        g.ext_off = c->d_plan + R.off_ext_off_half;
+        g.ext = reinterpret_cast<const ExtStep *>(c->d_plan + R.off_ext_half);
+        return launch_gemm(g, kTile128x128, b_kmajor, st);
+    }
     e = launch(t.tile);
     if (e != hipSuccess || t.tail_tiles_m == 0) return e;
     g.tile_m_base = 2 * t.big_tiles_m;
@@ -702,14 +732,15 @@ int collm_ctx_destroy(collm_ctx *c)
 int64_t collm_ctx_workspace_bytes(const collm_ctx *c) { return c ? c->workspace_bytes : 0; }
 
 int collm_debug_host_tiling(int rows, int cols, int K, int can_split, int32_t *tile, int32_t *big_tiles_m,
-                            int32_t *tail_tiles_m)
+                            int32_t *tail_tiles_m, int32_t *tail_cols)
 {
-    if (!tile || !big_tiles_m || !tail_tiles_m) return COLLM_E_NULL;
+    if (!tile || !big_tiles_m || !tail_tiles_m || !tail_cols) return COLLM_E_NULL;
     if (rows < 0 || cols <= 0 || K <= 0) return COLLM_E_SHAPE;
     const Tiling t = pick_tiling(rows, cols, K, can_split != 0);
     *tile = t.tile;
     *big_tiles_m = t.big_tiles_m;
     *tail_tiles_m = t.tail_tiles_m;
+    *tail_cols = t.tail_cols;
     return COLLM_OK;
 }
 

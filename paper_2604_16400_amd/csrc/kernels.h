@@ -21,6 +21,7 @@ struct GemmArgs {
     uint32_t a_bytes, b_bytes;  // sizes of the two operand tensors (each below 2 GiB)
     int tiles_m, tiles_n;
     int tile_m_base;          // first row tile of this launch (a GEMM may be split over launches by rows)
+    int n_base;               // first output column of this launch (... or by columns); a multiple of 8
     const int32_t *row_tok;   // [tiles_m * BM]
     const int32_t *ext_off;   // [tiles_m + 1]
     const ExtStep *ext;

@@ -417,7 +417,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
             b_bytes = B_KMAJOR ? p.b_bytes - b_skip : (uint32_t)K * ldb * 2u;
         }
     }
-    const int n0 = SWIGLU ? tile_n * (BN / 2) : tile_n * BN;
+    const int n0 = SWIGLU ? tile_n * (BN / 2) : (PARTIAL ? 0 : p.n_base) + tile_n * BN;
     // tile column c (a multiple of 8) -> column of the second operand and of the expand tables
     auto src_col = [&](int c) -> int {
         if constexpr (SWIGLU) return c < BN / 2 ? n0 + c : p.act_col + n0 + c - BN / 2;

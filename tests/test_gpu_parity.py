@@ -223,6 +223,23 @@ def test_rows_split_between_large_and_small_tiles(wide_side):
     _run_full(w)
 
 
+@pytest.mark.parametrize("wide_side", ["d_out", "d_in"])
+def test_columns_split_between_large_and_small_tiles(wide_side):
+    # 5000 rows x 7000 columns is 20 x 28 tiles of 256x256, 48 more than two rounds over 256 CUs: the first 25
+    # tile columns run as 256x256 tiles, columns 6400.. of all rows as 128x128 tiles in a second launch (five
+    # tile columns, the last 88 columns wide; the last row tile 8 rows high).  Adapters with ranks that are and
+    # are not multiples of 8, one above 64 (two groups of extension steps); every element is compared.
+    assert binding.host_tiling(5000, 7000, 64) == (binding.TILE_256x256, 20, 0, 3)
+    lens = [1500, 1, 1, 1100, 400, 1, 1300, 697]
+    ads = [0, 1, 2, 1, -1, 0, 2, 3]
+    if wide_side == "d_out":
+        w = _adhoc("bf16", 64, 7000, [16, 8, 12, 72], lens, ads, [1, 0, 0, 1, 0, 0, 1, 0], scale=0.5)
+    else:
+        lens[4], lens[7] = 30, 1097    # 5000 training rows beside 30 base-only ones
+        w = _adhoc("bf16", 7000, 64, [16, 8, 12, 72], lens, ads, [1, 1, 1, 1, 0, 1, 1, 1], scale=0.5)
+    _run_full(w)
+
+
 @pytest.mark.parametrize("transposed", [False, True])
 def test_gemm_with_few_rows_cut_into_k_slices(transposed):
     # decode-sized batches: the library cuts K of both GEMMs into slices by itself (forward: 37 rows against

@@ -145,8 +145,8 @@ def test_gemm_tiling_covers_the_rows_and_matches_the_measured_choices():
         rows = int(rng.integers(1, 40000))
         cols = int(rng.integers(1, 4000)) * 8
         K = int(rng.integers(1, 2000)) * 8
-        tile, big, tail = binding.host_tiling(rows, cols, K, bool(rng.integers(0, 2)))
-        assert tile in (binding.TILE_256x256, binding.TILE_128x128) and big >= 1 and tail >= 0
+        tile, big, tail, tail_cols = binding.host_tiling(rows, cols, K, bool(rng.integers(0, 2)))
+        assert tile in (binding.TILE_256x256, binding.TILE_128x128) and big >= 1 and tail >= 0 and tail_cols >= 0
         tr = 256 if tile == binding.TILE_256x256 else 128
         assert tr * big + 128 * tail >= rows                      # every row is in some tile
         if tail:
@@ -154,8 +154,16 @@ def test_gemm_tiling_covers_the_rows_and_matches_the_measured_choices():
             assert 256 * big + 128 * (tail - 1) < rows                        # and has no empty row tile
         else:
             assert tr * (big - 1) < rows or rows <= tr
+        if tail_cols:
+            # large tiles over whole rounds of the 256 CUs, then at most one round of small tiles (two per CU)
+            tn = (cols + 255) // 256
+            assert tile == binding.TILE_256x256 and tail == 0 and 0 < tail_cols < tn
+            assert big * (tn - tail_cols) <= 256 * (big * tn // 256)
+            assert ((rows + 127) // 128) * ((cols - 256 * (tn - tail_cols) + 127) // 128) <= 512
     # choices the measurements on the five configurations gave
-    assert binding.host_tiling(2048, 4096, 4096) == (binding.TILE_128x128, 16, 0)       # c2 forward: one round of 512 small tiles
-    assert binding.host_tiling(16384, 8192, 8192) == (binding.TILE_256x256, 64, 0)      # c5: whole rounds of large tiles
-    assert binding.host_tiling(3277, 5120, 5120) == (binding.TILE_256x256, 12, 2)       # c4 dX: 240 large tiles + the last 205 rows
+    assert binding.host_tiling(2048, 4096, 4096) == (binding.TILE_128x128, 16, 0, 0)    # c2 forward: one round of 512 small tiles
+    assert binding.host_tiling(16384, 8192, 8192) == (binding.TILE_256x256, 64, 0, 0)   # c5: whole rounds of large tiles
+    assert binding.host_tiling(3277, 5120, 5120) == (binding.TILE_256x256, 12, 2, 0)    # c4 dX: 240 large tiles + the last 205 rows
+    assert binding.host_tiling(8192, 5120, 5120) == (binding.TILE_256x256, 32, 0, 4)    # c4 forward: 2 rounds + 512 tiles of 128x128
+    assert binding.host_tiling(4096, 11008, 4096) == (binding.TILE_256x256, 16, 0, 0)   # c3 forward: 2.7 rounds, no split pays
     assert binding.host_tiling(64, 4096, 4096)[0] == binding.TILE_128x128               # decode-sized
