@@ -339,6 +339,8 @@ struct DmaSlots {
 // second r into the up half only.  In the epilogue the two waves that hold the gate and the up values of the
 // same rows swap halves through LDS, each finishes half of the rows: silu(gate) * up, rounded once, stored as
 // [rows][N = d_ff]; training rows also keep both pre-activations.
+// SIBS: sibling projections side by side in the columns; the low-rank extension then loads the rows' operand per
+// batch at the sibling's offset inside each adapter's ranks (see the extension below).
 // SPLITK: the GEMM itself with K cut into gridDim.y slices (few rows against a long contraction: too few tiles to
 // fill the GPU).  A block takes one tile and one slice; slice 0 also runs the tile's extension steps; the fp32
 // sums go to the workspace and gemm_finish_kernel adds the slices, rounds once and scatters the rows.
@@ -1004,12 +1006,12 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     }
 
     // ---- low-rank extension: K-steps [s h | dh] x [B_a | A_a^T] of the tile's adapters ----
-    // The steps are taken four at a time (one 64-wide K tile).  The operands of a batch travel
-    // global -> LDS like the tiles of the main loop, into the stage the batch before it does not
-    // use, while that batch multiplies; the step records of a batch are fetched one batch ahead
-    // of its loads, and those of the first batch before the main loop.  Rows of the tile outside a
-    // step's row range, rank indices beyond the adapter's rank and columns beyond N are filled
-    // with zeros (out-of-range buffer offsets, or the zero block).
+    // The steps are taken four at a time (one 64-wide K tile); the step records of a batch are fetched ahead of
+    // its loads, those of the first batch before the main loop.  Rank indices beyond an adapter's rank and
+    // columns beyond N are filled with zeros (out-of-range buffer offsets, or the zero block).
+    // SIBS (sibling projections side by side): both operands of a batch travel global -> LDS like the tiles of
+    // the main loop, into the stage the batch before it does not use, while that batch multiplies; rows of the
+    // tile outside a step's row range are filled with zeros.
     if (SIBS && !PARTIAL && e1 > e0) {
         auto issue_batch = [&](int stage, const ExtBatch &bt) {
 #pragma unroll
