@@ -280,6 +280,39 @@ def test_rank_wide_passes_as_row_tiles(transposed):
     _run_full(w, transposed=transposed, wide_min_rows=0)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_batches_every_element(seed):
+    # Seeded random batches through every path at once: ranks 1..256 (multiples of 8 or not, above 64: several
+    # groups of extension steps), up to 40 adapters with skewed popularity, decode tokens, long and empty segments,
+    # base-only segments, either layout, every tile shape, with and without h_save.  Every element is compared.
+    rng = np.random.default_rng(1000 + seed)
+    n_ad = int(rng.integers(1, 41))
+    top = [16, 64, 128, 256][seed % 4]
+    ranks = [int(rng.integers(1, top + 1)) if rng.random() < 0.4 else int(rng.integers(1, top // 8 + 1)) * 8 for _ in range(n_ad)]
+    n_seg = int(rng.integers(1, 60))
+    lens, ads, trn = [], [], []
+    for _ in range(n_seg):
+        kind = rng.random()
+        lens.append(0 if kind < 0.05 else (1 if kind < 0.5 else int(rng.integers(2, 400 if kind > 0.9 else 60))))
+        a = -1 if rng.random() < 0.1 else int(min(n_ad - 1, rng.zipf(1.5) - 1))
+        ads.append(a)
+        trn.append(int(a >= 0 and rng.random() < 0.4))
+    if sum(lens) == 0:
+        lens[0] = 5
+    d_in, d_out = int(rng.integers(1, 80)) * 8, int(rng.integers(1, 80)) * 8
+    w = _adhoc("bf16", d_in, d_out, ranks, lens, ads, trn, scale=0.3, seed=seed)
+    tile = [None, 0, 1, 2, 3][seed % 5]
+    t = wl.make_tensors(w)
+    ctx = make_ctx(w)
+    if tile is not None:
+        ctx.set_tiles(tile, tile)
+    layer = DeviceLayer(w, t, ctx, transposed=bool(seed % 2))
+    layer.fwd(h_save=seed % 3 != 0)
+    layer.bwd(h_save=seed % 3 != 0)
+    check_full(layer, TOL[w.dtype], check_h=seed % 3 != 0)
+    ctx.close()
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_transposed_weight_and_table_layout(dtype):
     # W [d_out, d_in], A [rank, d_in], B [d_out, rank], gradients likewise: the same mathematics, so the
