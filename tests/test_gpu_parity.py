@@ -280,6 +280,31 @@ def test_rank_wide_passes_as_row_tiles(transposed):
     _run_full(w, transposed=transposed, wide_min_rows=0)
 
 
+@pytest.mark.parametrize("transposed", [False, True])
+def test_many_extension_steps_in_one_row_tile(transposed):
+    # Twelve adapters of ranks 128 and 256 with 20 rows each share one 256-row tile: 144 extension steps in four
+    # groups of 64 rank indices, more than the 64 step records a kernel keeps in registers (the later batches come
+    # through the scalar cache), the rows' operand loaded again for every group; forward (all rows) and backward
+    # (the training rows of eight of the adapters), every tile shape.
+    ranks = [128, 256] * 6
+    lens = [20] * 12 + [9]
+    ads = list(range(12)) + [-1]
+    trn = [1, 1, 0, 1, 1, 0, 1, 1, 0, 1, 1, 0, 0]
+    w = _adhoc("bf16", 256, 320, ranks, lens, ads, trn, scale=0.2)
+    _, steps = binding.host_row_order(w.ranks, w.seg_start, w.seg_adapter, w.seg_is_train, 256)
+    assert steps.max() >= 144
+    for tile in (None, 0, 1, 2, 3):
+        t = wl.make_tensors(w)
+        ctx = make_ctx(w)
+        if tile is not None:
+            ctx.set_tiles(tile, tile)
+        layer = DeviceLayer(w, t, ctx, transposed=transposed)
+        layer.fwd(h_save=True)
+        layer.bwd(h_save=True)
+        check_full(layer, TOL[w.dtype])
+        ctx.close()
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_random_batches_every_element(seed):
     # Seeded random batches through every path at once: ranks 1..256 (multiples of 8 or not, above 64: several
