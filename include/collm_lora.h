@@ -286,11 +286,14 @@ int collm_debug_set_gemm_split(collm_ctx *ctx, int n_slices);
 int collm_debug_set_wide_pass(collm_ctx *ctx, int min_rows);
 
 /*
- * Debug/profiling: average duration in milliseconds, measured with HIP events on the
- * call's own stream, of each kernel launched by the context's last compute call.
- * collm_profile_enable(ctx, 1) makes every later call record events around each launch;
+ * Debug/profiling: duration in milliseconds of each pass (one kernel, or the few kernels of
+ * a pass) launched by the context's last compute call, from the start of its first kernel to
+ * the end of its last by the kernels' own time stamps (HIP events attached to the launches on
+ * the call's own stream; no event latency inside the interval; 0 for a pass that launched
+ * nothing).  collm_profile_enable(ctx, 1) makes every later call time its passes this way,
+ * all on the call's stream, one after the other;
  * collm_profile_read synchronises, fills names[i] (static strings) and ms[i] for up to
- * `cap` kernels and returns how many there were (or a negative status).
+ * `cap` passes and returns how many there were (or a negative status).
  */
 int collm_profile_enable(collm_ctx *ctx, int enable);
 int collm_profile_read(collm_ctx *ctx, const char **names, float *ms, int cap);

@@ -16,6 +16,10 @@
 
 using namespace collm;
 
+namespace collm {
+thread_local LaunchEvents g_launch_events;
+}
+
 namespace {
 
 thread_local std::string g_last_error;
@@ -92,6 +96,7 @@ struct collm_ctx {
     int n_prof = 0;
     const char *prof_name[kMaxProfile] = {};
     hipEvent_t prof_ev[kMaxProfile][2] = {};
+    int prof_launches[kMaxProfile] = {};  // kernels each entry timed (0: nothing ran, the events were not recorded)
     bool prof_ev_made = false;
 };
 
@@ -238,22 +243,29 @@ hipError_t run_gemm(collm_ctx *c, GemmArgs g, const RowOrderLayout &R, int rows,
     return launch(kTile128x128);
 }
 
+// Times the kernels launched while it lives (profile mode): from the start of the first to the end of the last,
+// by the kernels' own time stamps (see LaunchEvents).
 struct Prof {
     collm_ctx *c;
-    hipStream_t st;
     int idx = -1;
-    Prof(collm_ctx *c_, hipStream_t st_, const char *name) : c(c_), st(st_)
+    Prof(collm_ctx *c_, hipStream_t, const char *name) : c(c_)
     {
         if (c->profile && c->n_prof < kMaxProfile) {
             idx = c->n_prof++;
             c->prof_name[idx] = name;
-            (void)hipEventRecord(c->prof_ev[idx][0], st);
+            c->prof_launches[idx] = 0;
+            g_launch_events = LaunchEvents{c->prof_ev[idx][0], c->prof_ev[idx][1], 0};
         }
     }
     ~Prof()
     {
-        if (idx >= 0) (void)hipEventRecord(c->prof_ev[idx][1], st);
+        if (idx >= 0) {
+            c->prof_launches[idx] = g_launch_events.launches;
+            g_launch_events = LaunchEvents{};
+        }
     }
+    Prof(const Prof &) = delete;
+    Prof &operator=(const Prof &) = delete;
 };
 
 int check_common(collm_ctx *ctx, const collm_shape *s, const void *x, const void *W,
@@ -815,8 +827,10 @@ int collm_profile_read(collm_ctx *c, const char **names, float *ms, int cap)
     if (!c || !names || !ms) return COLLM_E_NULL;
     const int n = std::min(c->n_prof, cap);
     for (int i = 0; i < n; ++i) {
-        HIP_TRY(hipEventSynchronize(c->prof_ev[i][1]));
         names[i] = c->prof_name[i];
+        ms[i] = 0.f;
+        if (c->prof_launches[i] == 0) continue;
+        HIP_TRY(hipEventSynchronize(c->prof_ev[i][1]));
         HIP_TRY(hipEventElapsedTime(&ms[i], c->prof_ev[i][0], c->prof_ev[i][1]));
     }
     return n;

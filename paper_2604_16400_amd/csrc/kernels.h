@@ -1,11 +1,32 @@
 // Kernel argument blocks and launchers (device side of the library).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "plan.h"
 
 namespace collm {
+
+// Timing of the calling thread's next launches through COLLM_LAUNCH: `start` is recorded when the first of them
+// begins on the GPU, `stop` when the last one launched so far ends (the kernels' own time stamps, as a profiler
+// reads them: no marker is added to the stream, and the time between the two events holds no event latency).
+struct LaunchEvents {
+    hipEvent_t start = nullptr, stop = nullptr;
+    int launches = 0;
+};
+extern thread_local LaunchEvents g_launch_events;
+#define COLLM_LAUNCH(kern, grid, block, smem, st, ...)                                                            \
+    do {                                                                                                          \
+        ::collm::LaunchEvents &le_ = ::collm::g_launch_events;                                                    \
+        if (le_.stop) {                                                                                           \
+            hipExtLaunchKernelGGL(kern, grid, block, smem, st, le_.launches == 0 ? le_.start : nullptr, le_.stop, \
+                                  0, __VA_ARGS__);                                                                \
+            ++le_.launches;                                                                                       \
+        } else {                                                                                                  \
+            hipLaunchKernelGGL(kern, grid, block, smem, st, __VA_ARGS__);                                         \
+        }                                                                                                         \
+    } while (0)
 
 enum { kTile256x256 = 0, kTile256x128 = 1, kTile128x128 = 2, kTile256x256w8 = 3, kNumTiles = 4 };
 

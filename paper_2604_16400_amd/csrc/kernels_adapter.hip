@@ -170,7 +170,7 @@ hipError_t launch_swiglu_bwd(const SwigluBwdArgs &a, hipStream_t st)
 {
     const int rows = a.row0[a.n_seg];
     if (rows <= 0 || a.d_ff <= 0) return hipSuccess;
-    hipLaunchKernelGGL(swiglu_bwd_kernel, dim3((a.d_ff / 8 + 255) / 256, rows), dim3(256), 0, st, a);
+    COLLM_LAUNCH(swiglu_bwd_kernel, dim3((a.d_ff / 8 + 255) / 256, rows), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
@@ -178,8 +178,8 @@ hipError_t launch_fedavg(const FedAvgArgs &a, bool bf16, hipStream_t st)
 {
     if (a.n <= 0) return hipSuccess;
     const int grid = grid_for(a.n / (bf16 ? 8 : 4));
-    if (bf16) hipLaunchKernelGGL(fedavg_kernel<true>, dim3(grid), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL(fedavg_kernel<false>, dim3(grid), dim3(256), 0, st, a);
+    if (bf16) COLLM_LAUNCH(fedavg_kernel<true>, dim3(grid), dim3(256), 0, st, a);
+    else COLLM_LAUNCH(fedavg_kernel<false>, dim3(grid), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
@@ -187,8 +187,8 @@ hipError_t launch_adamw(const AdamWArgs &a, bool bf16, hipStream_t st)
 {
     if (a.n <= 0) return hipSuccess;
     const int grid = grid_for((a.n + 3) / 4);
-    if (bf16) hipLaunchKernelGGL(adamw_kernel<true>, dim3(grid), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL(adamw_kernel<false>, dim3(grid), dim3(256), 0, st, a);
+    if (bf16) COLLM_LAUNCH(adamw_kernel<true>, dim3(grid), dim3(256), 0, st, a);
+    else COLLM_LAUNCH(adamw_kernel<false>, dim3(grid), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 

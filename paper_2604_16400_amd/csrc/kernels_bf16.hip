@@ -1888,7 +1888,7 @@ static hipError_t launch_gemm_t(const GemmArgs &a, hipStream_t st)
     }
     const int grid = a.tiles_m * a.tiles_n;
     if (grid <= 0) return hipSuccess;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), smem, st, a);
+    COLLM_LAUNCH(kern, dim3(grid), dim3(NT), smem, st, a);
     return hipGetLastError();
 }
 
@@ -1940,7 +1940,7 @@ hipError_t launch_wide(const GemmArgs &a, int n_items, int rpad, int n_split, bo
             if (e != hipSuccess) return e;
             attr_done = true;
         }
-        hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, a);
+        COLLM_LAUNCH(kern, grid, dim3(256), smem, st, a);
         return hipGetLastError();
     };
     // four waves side by side in the rows (32 rows x 128 rank columns each): the work of a wave shrinks with the rank
@@ -1951,7 +1951,7 @@ hipError_t launch_wide(const GemmArgs &a, int n_items, int rpad, int n_split, bo
 hipError_t launch_skinny_finish(const SkinnyArgs &a, int n_items, int item_rows, int n_split, hipStream_t st)
 {
     if (n_items <= 0) return hipSuccess;
-    hipLaunchKernelGGL(skinny_finish_kernel, dim3(n_items, (item_rows + 15) / 16), dim3(256), 0, st, a, n_split);
+    COLLM_LAUNCH(skinny_finish_kernel, dim3(n_items, (item_rows + 15) / 16), dim3(256), 0, st, a, n_split);
     return hipGetLastError();
 }
 
@@ -1984,7 +1984,7 @@ hipError_t launch_gemm_splitk(const GemmArgs &a, int n_split, bool b_kmajor, hip
             if (e != hipSuccess) return e;
             attr_done = true;
         }
-        hipLaunchKernelGGL(kern, dim3(tiles, n_split), dim3(256), smem, st, a);
+        COLLM_LAUNCH(kern, dim3(tiles, n_split), dim3(256), smem, st, a);
         return hipGetLastError();
     };
     if (a.n_sib > 1) return b_kmajor ? hipErrorInvalidValue : launch(gemm_lora_kernel<128, 128, 2, 2, false, false, false, false, true, true>);
@@ -1995,7 +1995,7 @@ hipError_t launch_gemm_splitk(const GemmArgs &a, int n_split, bool b_kmajor, hip
 hipError_t launch_gemm_finish(const GemmArgs &a, int n_split, hipStream_t st)
 {
     if (a.n_rows <= 0) return hipSuccess;
-    hipLaunchKernelGGL(gemm_finish_kernel, dim3((a.N / 4 + 255) / 256, a.n_rows), dim3(256), 0, st, a, n_split);
+    COLLM_LAUNCH(gemm_finish_kernel, dim3((a.N / 4 + 255) / 256, a.n_rows), dim3(256), 0, st, a, n_split);
     return hipGetLastError();
 }
 
@@ -2027,8 +2027,8 @@ static hipError_t launch_skinny_t(const SkinnyArgs &a, int n_items, int n_split,
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(n_items, n_split), dim3(C::KW * 64), smem, st, a);
-    if (n_split > 1) hipLaunchKernelGGL(skinny_finish_kernel, dim3(n_items, RT), dim3(256), 0, st, a, n_split);
+    COLLM_LAUNCH(kern, dim3(n_items, n_split), dim3(C::KW * 64), smem, st, a);
+    if (n_split > 1) COLLM_LAUNCH(skinny_finish_kernel, dim3(n_items, RT), dim3(256), 0, st, a, n_split);
     return hipGetLastError();
 }
 
@@ -2082,7 +2082,7 @@ static hipError_t launch_grad_t(const GradArgs &a, int n_grad, int rpad, hipStre
         attr_done = true;
     }
     const dim3 grid((a.N + 63) / 64, n_grad, (rpad + RP - 1) / RP);
-    hipLaunchKernelGGL(kern, grid, dim3(C::KW * 64), C::SMEM, st, a);
+    COLLM_LAUNCH(kern, grid, dim3(C::KW * 64), C::SMEM, st, a);
     return hipGetLastError();
 }
 
@@ -2125,7 +2125,7 @@ hipError_t launch_pack_rows(const float *src, int64_t ld_src, int src_cols, cons
     if (n_rows <= 0) return hipSuccess;
     const int64_t n = (int64_t)n_rows * (ld_dst / 8);
     const int grid = (int)std::min<int64_t>((n + 255) / 256, 4096);
-    hipLaunchKernelGGL(pack_rows_kernel, dim3(grid), dim3(256), 0, st, src, ld_src, src_cols, row_tok, n_rows, mult,
+    COLLM_LAUNCH(pack_rows_kernel, dim3(grid), dim3(256), 0, st, src, ld_src, src_cols, row_tok, n_rows, mult,
                        reinterpret_cast<uint16_t *>(dst), ld_dst);
     return hipGetLastError();
 }

@@ -221,7 +221,7 @@ hipError_t launch_plan_copy(const int32_t *src_pinned, int32_t *dst, size_t firs
     const size_t lo = first_int & ~(size_t)3, hi = (first_int + n_ints + 3) & ~(size_t)3;
     const int n16 = (int)((hi - lo) / 4);
     const int blocks = std::max(1, std::min(256, (n16 + 255) / 256));
-    hipLaunchKernelGGL(plan_copy_kernel, dim3(blocks), dim3(256), 0, st,
+    COLLM_LAUNCH(plan_copy_kernel, dim3(blocks), dim3(256), 0, st,
                        reinterpret_cast<const int4 *>(src_pinned + lo), reinterpret_cast<int4 *>(dst + lo), n16, counter,
                        done_host_dev, seq);
     return hipGetLastError();
@@ -231,23 +231,23 @@ hipError_t launch_gemm_f32(const GemmArgs &a, bool b_kmajor, hipStream_t st)
 {
     const dim3 grid((a.N + kF32Tile - 1) / kF32Tile, a.tiles_m);
     if (grid.x == 0 || grid.y == 0) return hipSuccess;
-    if (b_kmajor) hipLaunchKernelGGL(gemm_f32_kernel<true>, grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL(gemm_f32_kernel<false>, grid, dim3(256), 0, st, a);
+    if (b_kmajor) COLLM_LAUNCH(gemm_f32_kernel<true>, grid, dim3(256), 0, st, a);
+    else COLLM_LAUNCH(gemm_f32_kernel<false>, grid, dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
 hipError_t launch_skinny_f32(const SkinnyArgs &a, int n_items, bool t_kmajor, hipStream_t st)
 {
     if (n_items <= 0) return hipSuccess;
-    if (t_kmajor) hipLaunchKernelGGL(skinny_f32_kernel<true>, dim3(n_items), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL(skinny_f32_kernel<false>, dim3(n_items), dim3(256), 0, st, a);
+    if (t_kmajor) COLLM_LAUNCH(skinny_f32_kernel<true>, dim3(n_items), dim3(256), 0, st, a);
+    else COLLM_LAUNCH(skinny_f32_kernel<false>, dim3(n_items), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
 hipError_t launch_grad_f32(const GradArgs &a, int n_grad, hipStream_t st)
 {
     if (n_grad <= 0 || a.N <= 0) return hipSuccess;
-    hipLaunchKernelGGL(grad_f32_kernel, dim3((a.N + 255) / 256, n_grad), dim3(256), 0, st, a);
+    COLLM_LAUNCH(grad_f32_kernel, dim3((a.N + 255) / 256, n_grad), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
