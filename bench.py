@@ -10,8 +10,8 @@ bf16 configurations are reported per projection in `all_configs`.
 Prints ONE JSON line.  `value` is effective TFLOP/s: algorithmic flops of forward + backward
 (base GEMMs plus the low-rank terms) divided by wall time, inputs resident in HBM.
 `roofline` is for the dominant kernel (the forward GEMM with the fused expand): flops of one
-launch over its average duration, measured with HIP events recorded on the launch stream in a
-second, profiled pass over the same steps.  `cpu_baseline` times the fp64 CPU oracle on the
+launch over its average duration, measured with HIP events attached to the launch on its stream
+(the kernel's own start and end time stamps) in a second, profiled pass over the same steps.  `cpu_baseline` times the fp64 CPU oracle on the
 same workload in the same run; it is a reported baseline, not a target.
 """
 from __future__ import annotations
@@ -131,8 +131,8 @@ class Runner:
         return (time.perf_counter() - t0) / steps
 
     def kernel_times(self, steps, cold=False, stat="mean"):
-        """Duration (ms) of every kernel of a step (mean, or median / min over the steps): HIP events recorded
-        on the launch stream around each launch, read after each half step.  cold: a 512 MiB buffer is
+        """Duration (ms) of every kernel of a step (mean, or median / min over the steps): HIP events attached
+        to the launches on the launch stream (each kernel's own start and end), read after each half step.  cold: a 512 MiB buffer is
         overwritten before every call, so that nothing the call reads is left in the caches."""
         w, c, torch = self.w, self.ctx, self.torch
         c.profile_enable(True)
