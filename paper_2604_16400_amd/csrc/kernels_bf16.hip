@@ -1047,7 +1047,6 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
             {
                 // step 0, with the loads of the next batch (addresses and all) riding behind its MFMAs
                 const bool more = eb + kExtBatch < e1;
-                constexpr int NM = MI * NI;
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi) {
                     if (block_on(cur_b.rows[0], mi)) {
