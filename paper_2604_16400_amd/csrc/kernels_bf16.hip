@@ -441,6 +441,17 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     const __amdgpu_buffer_rsrc_t ra = make_rsrc(a_base, a_bytes);
     const __amdgpu_buffer_rsrc_t rb = make_rsrc(b_base, b_bytes);
 
+    // The block's first loads form chains (row order -> rows of the first operand; step offsets -> step records),
+    // and nothing else runs on the CU meanwhile (256x256) or little (128x128): the chains are started side by
+    // side, the tokens of this thread's rows first.
+    const int c8 = tid & 7, r8 = tid >> 3;
+    int tok_of[BM * 8 / NT];
+#pragma unroll
+    for (int i = 0; i < BM * 8 / NT; ++i) {
+        const int r = r8 + i * (NT / 8);
+        tok_of[i] = (!PARTIAL || r < rows_in) ? row_tok[m0 + r] : -1;
+    }
+
     // extension steps of this row tile; the first batch is fetched now, long before it is needed
     const int e0 = PARTIAL ? 0 : __builtin_amdgcn_readfirstlane(p.ext_off[tile_m]);
     const int e1 = PARTIAL ? 0 : ((SPLITK && blockIdx.y != 0) ? e0 : __builtin_amdgcn_readfirstlane(p.ext_off[tile_m + 1]));
@@ -466,13 +477,12 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         }
         return bt;
     };
-    // The first 64 step records of the tile are fetched once, one per lane, before any direct load is in
-    // flight; a batch then comes out of the lanes with readlane.  (Tiles with more steps fetch the later
+    // The first 64 step records of the tile are fetched once, one per lane (the load completes before any direct
+    // load is in flight, see below); a batch then comes out of the lanes with readlane.  (Tiles with more steps fetch the later
     // batches through the scalar cache.)
     uint4 rec = make_uint4(0u, 0u, 0u, 0u);
     if constexpr (!PARTIAL) {
         if (e0 + lane < e1) rec = *reinterpret_cast<const uint4 *>(p.ext + e0 + lane);
-        asm volatile("" : "+v"(rec.x), "+v"(rec.y), "+v"(rec.z), "+v"(rec.w));  // the load completes here
     }
     auto get_batch = [&](int eb) {
         const int rel = eb - e0;
@@ -497,7 +507,6 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     // in the N-major tile row bk0 + i NT/NG, chunk position bng.  The 64 lanes of a wave own
     // one contiguous KiB per i, which is what a direct-to-LDS load fills.  The swizzle decides
     // which chunk of the source belongs at that position.
-    const int c8 = tid & 7, r8 = tid >> 3;
     // rows r8 + i NT/8 differ in swizzle only through bit 2 of (row >> 3): NT/8 = 32 flips it
     // for odd i, NT/8 = 64 never does
     constexpr int SWZ_FLIP = (NT / 8 == 32) ? 4 : 0;
@@ -505,8 +514,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     uint32_t aoff[ACH];
 #pragma unroll
     for (int i = 0; i < ACH; ++i) {
-        const int r = r8 + i * (NT / 8);
-        const int tok = (!PARTIAL || r < rows_in) ? row_tok[m0 + r] : -1;
+        const int tok = tok_of[i];
         const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
         aoff[i] = tok >= 0 ? (uint32_t)tok * (uint32_t)p.lda * 2u + cl * 16u : kOob;
     }
@@ -716,6 +724,12 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     // the extension lies behind them and is loaded before the main loop starts.
     constexpr bool ROWS_EARLY = !PINGPONG && !PARTIAL && !SIBS && !CAN_PRE;
     constexpr uint32_t XA_EARLY = 2 * STAGE;
+    // Where the load of the step records is waited for.  The hand-scheduled pipeline does it behind the direct
+    // loads of its first tile (the records' chain of two loads is longer than the one that leads to those loads,
+    // and nothing needs the records before the main loop's last tiles); the other pipelines here.
+    constexpr bool REC_LATE = !PINGPONG && !PARTIAL;
+    auto records_are_in = [&] { asm volatile("" : "+v"(rec.x), "+v"(rec.y), "+v"(rec.z), "+v"(rec.w)); };
+    if constexpr (!PARTIAL && !REC_LATE) records_are_in();
     if constexpr (ROWS_EARLY) {
         if (e1 > e0) {
 #pragma unroll
@@ -723,12 +737,15 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         }
     }
     bool pre = false;
-    if constexpr (CAN_PRE) {
-        uint32_t kr_or = 0;  // lanes beyond the tile's steps hold zeros
+    auto decide_pre = [&] {
+        if constexpr (CAN_PRE) {
+            uint32_t kr_or = 0;  // lanes beyond the tile's steps hold zeros
 #pragma unroll
-        for (int j = 0; j < kExtBatch; ++j) kr_or |= (uint32_t)__builtin_amdgcn_readlane((int)rec.x, j);
-        pre = e1 > e0 && nk >= 2 && (!B_KMAJOR || ((kr_or >> 16) & 7u) == 0);
-    }
+            for (int j = 0; j < kExtBatch; ++j) kr_or |= (uint32_t)__builtin_amdgcn_readlane((int)rec.x, j);
+            pre = e1 > e0 && nk >= 2 && (!B_KMAJOR || ((kr_or >> 16) & 7u) == 0);
+        }
+    };
+    if constexpr (!REC_LATE) decide_pre();
     // acc[ni][mi] holds the transposed 32x32 block: lane = row m, registers = columns n
     floatx16 acc[NI][MI];
 #pragma unroll
@@ -890,6 +907,8 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
             rb_t = tile_rsrc(rb_w, 1);
 #pragma unroll
             for (int d = 0; d < D3; ++d) dma_chunk(even_c, d, 1, 1, ra_t, rb_t);
+            records_are_in();  // (the compiler waits for all loads it knows of, which lets the direct loads land too)
+            decide_pre();
             wait_dma_but<D3>();  // loads complete in order: tile 0 is in
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
