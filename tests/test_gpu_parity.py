@@ -280,6 +280,42 @@ def test_rank_wide_passes_as_row_tiles(transposed):
     _run_full(w, transposed=transposed, wide_min_rows=0)
 
 
+def test_two_contexts_on_two_streams_interleaved():
+    # Two contexts with different batches, each on a stream of its own, called alternately without waiting in
+    # between (forward A, forward B, backward A, backward B, twice): a context's plan, workspace and gradient
+    # stream are its own, and nothing in the library is shared between them but read-only code.
+    import torch
+
+    wa = _adhoc("bf16", 512, 384, [16, 64, 8], [300, 1, 1, 90, 150, 31], [0, 1, 2, 1, -1, 0], [1, 0, 0, 1, 0, 0], scale=0.3)
+    wb = _adhoc("bf16", 256, 640, [32, 128], [40, 200, 7, 260], [1, 0, -1, 1], [0, 1, 0, 1], scale=0.3, seed=11)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    ca, cb = make_ctx(wa), make_ctx(wb)
+    la, lb = DeviceLayer(wa, wl.make_tensors(wa), ca), DeviceLayer(wb, wl.make_tensors(wb), cb, transposed=True)
+    torch.cuda.synchronize()
+
+    def call(layer, stream, fwd):
+        w = layer.w
+        if fwd:
+            layer.ctx.collm_lora_linear_fwd(layer.x, layer.W, layer.A, layer.B, w.ranks, w.seg_start, w.seg_adapter,
+                                            w.seg_is_train, w.scale, layer.y, layer.h_save, stream=stream,
+                                            layout=layer.layout)
+        else:
+            layer.ctx.collm_lora_linear_bwd(layer.x, layer.W, layer.A, layer.B, w.ranks, w.seg_start, w.seg_adapter,
+                                            w.seg_is_train, w.scale, layer.dy, layer.h_save, layer.dx, layer.dA, layer.dB,
+                                            False, stream=stream, layout=layer.layout)
+
+    for _ in range(2):
+        call(la, sa, True)
+        call(lb, sb, True)
+        call(la, sa, False)
+        call(lb, sb, False)
+    torch.cuda.synchronize()
+    check_full(la, TOL["bf16"])
+    check_full(lb, TOL["bf16"])
+    ca.close()
+    cb.close()
+
+
 @pytest.mark.parametrize("transposed", [False, True])
 def test_many_extension_steps_in_one_row_tile(transposed):
     # Twelve adapters of ranks 128 and 256 with 20 rows each share one 256-row tile: 144 extension steps in four
