@@ -571,7 +571,8 @@ int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, cons
         g.tab_off = a.tab_off;
         const long blocks = (long)R.n_wide * ((rpad + 127) / 128);
         const long per_split = (long)c->rows_cap * c->rpad_cap * 4;
-        long ns = std::min<long>({256 / blocks, std::max(1, K / 512), (long)c->part_bytes / per_split,
+        // (one block per CU with K-major tables, two with tables as they lie in memory: see launch_wide)
+        long ns = std::min<long>({(t_kmajor ? 256 : 512) / blocks, std::max(1, K / 512), (long)c->part_bytes / per_split,
                                   (long)kSkinnyMaxSplit});
         ns = std::max<long>(ns, 1);
         g.k_per_split = round_up((int)((K + ns - 1) / ns), 64);

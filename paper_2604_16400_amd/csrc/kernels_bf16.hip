@@ -344,7 +344,13 @@ struct DmaSlots {
 // SPLITK: the GEMM itself with K cut into gridDim.y slices (few rows against a long contraction: too few tiles to
 // fill the GPU).  A block takes one tile and one slice; slice 0 also runs the tile's extension steps; the fp32
 // sums go to the workspace and gemm_finish_kernel adds the slices, rounds once and scatters the rows.
-constexpr int kWideStages = 4;  // LDS stages of the PARTIAL loop (128x128 tiles: 32 KiB each)
+// LDS stages of the PARTIAL loop (128x128 tiles: 32 KiB each).  The loop is bound by what a wave has to issue per
+// tile (its direct loads, then its fragment reads and MFMAs, one wave per SIMD), not by the latency of the loads
+// (about 800 cycles from L2 or beyond): with tables as they lie in memory ([K][rank], transposing reads) two
+// blocks per CU whose phases interleave, two stages each, beat one block with four; with K-major tables
+// (fewer, cheaper fragment reads) the four stages do.
+constexpr int kWideStages = 4;
+constexpr int wide_stages(bool t_kmajor) { return t_kmajor ? kWideStages : 2; }
 template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR, bool PINGPONG, bool PARTIAL = false, bool SWIGLU = false,
           bool SPLITK = false, bool SIBS = false>
 __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
@@ -826,7 +832,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         // stages of [rows tile | table tile]; the loads of kWideStages - 1 tiles are in flight while one is multiplied.
         // One barrier per tile: before it every wave has received its own loads of tile kc, after it all of the tile
         // is in LDS and every wave is done with tile kc - 1, whose stage the loads of tile kc + kWideStages - 1 may fill.
-        constexpr int NS = kWideStages;
+        constexpr int NS = wide_stages(B_KMAJOR);
         static_assert((NS - 2) * ND <= 63, "outstanding loads must fit the counter");
         auto issue_tile = [&](int kc) {
             const uint32_t base = lds_wave + (uint32_t)(kc % NS) * STAGE;
@@ -1948,7 +1954,7 @@ hipError_t launch_wide(const GemmArgs &a, int n_items, int rpad, int n_split, bo
     static_assert(kWideRows == 128, "the rank-wide pass runs 128x128 tiles");
     if (n_items <= 0) return hipSuccess;
     if (n_split < 1 || !a.part || !a.items || !a.tab || a.k_per_split % 64 != 0) return hipErrorInvalidValue;
-    constexpr int smem = kWideStages * (128 + 128) * 128;
+    const int smem = wide_stages(t_kmajor) * (128 + 128) * 128;
     const dim3 grid(n_items, (rpad + 127) / 128, n_split);
     auto launch = [&](auto kern) -> hipError_t {
         static bool attr_done = false;
