@@ -1964,12 +1964,12 @@ hipError_t launch_wide(const GemmArgs &a, int n_items, int rpad, int n_split, bo
             if (e != hipSuccess) return e;
             attr_done = true;
         }
-        COLLM_LAUNCH(kern, grid, dim3(256), smem, st, a);
+        COLLM_LAUNCH(kern, grid, dim3(512), smem, st, a);
         return hipGetLastError();
     };
-    // four waves side by side in the rows (32 rows x 128 rank columns each): the work of a wave shrinks with the rank
-    return t_kmajor ? launch(gemm_lora_kernel<128, 128, 4, 1, true, false, true>)
-                    : launch(gemm_lora_kernel<128, 128, 4, 1, false, false, true>);
+    // eight waves, 32 rows x 64 rank columns each (two per SIMD): the loop is bound by what a wave has to issue
+    return t_kmajor ? launch(gemm_lora_kernel<128, 128, 4, 2, true, false, true>)
+                    : launch(gemm_lora_kernel<128, 128, 4, 2, false, false, true>);
 }
 
 hipError_t launch_skinny_finish(const SkinnyArgs &a, int n_items, int item_rows, int n_split, hipStream_t st)
