@@ -177,10 +177,12 @@ class Runner:
             out["gemm_fwd_frac_mfma_peak"] = out["gemm_fwd_tflops"] / PEAK_BF16_TFLOPS
             # yardstick, not part of the library: the vendor GEMM on the base term alone (no adapters, no row
             # gather/scatter), same device, same shape
-            out["vendor_gemm_fwd_tflops"] = gemm_fwd_flops / self.vendor_gemm_seconds() / 1e12
+            out["vendor_gemm_fwd_tflops"] = gemm_fwd_flops / self.vendor_gemm_seconds(False) / 1e12
         if "gemm_dx" in kt:
             out["gemm_dx_tflops"] = gemm_dx_flops / (kt["gemm_dx"] * 1e-3) / 1e12
             out["gemm_dx_frac_mfma_peak"] = out["gemm_dx_tflops"] / PEAK_BF16_TFLOPS
+            if w.n_train_tokens > 0:  # the same yardstick for dy W^T over as many rows as there are training tokens
+                out["vendor_gemm_dx_tflops"] = gemm_dx_flops / self.vendor_gemm_seconds(True) / 1e12
         for k in ("shrink", "dh", "grad_dB", "grad_dA"):
             if k in kt:
                 gbs = by[k] / (kt[k] * 1e-3) / 1e9
@@ -188,15 +190,16 @@ class Runner:
                 out[f"{k}_frac_hbm_peak"] = gbs / PEAK_HBM_GBS
         return out, sec, kt
 
-    def vendor_gemm_seconds(self, iters=20):
+    def vendor_gemm_seconds(self, backward, iters=20):
         torch = self.torch
-        W = self.W if self.layout == 0 else self.W.t()
+        W = self.W if self.layout == 0 else self.W.t()  # [d_in, d_out], as a view
+        a, b = (self.dy[: self.w.n_train_tokens], W.t()) if backward else (self.x, W)
         for _ in range(3):
-            torch.matmul(self.x, W)
+            torch.matmul(a, b)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(iters):
-            torch.matmul(self.x, W)
+            torch.matmul(a, b)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / iters
 
