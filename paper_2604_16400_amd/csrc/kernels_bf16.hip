@@ -282,6 +282,15 @@ __device__ __forceinline__ void dma16g(uint64_t addr, uint32_t lds_base)
 {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(addr));
 }
+// One v_mfma_f32_16x16x32_bf16, accumulator in place.  Written out because the compiler's register allocation of
+// the builtin breaks down with 64 four-register accumulators per lane (it copies them between the two register
+// files around the MFMAs).  The waits for operands that LDS reads deliver are still placed by the compiler; the
+// wait states between the last MFMA and the first ordinary read of an accumulator are the caller's (mfma16_settle).
+__device__ __forceinline__ void mfma16(floatx4 &c, const bf16x8 &a, const bf16x8 &b)
+{
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma16_settle() { asm volatile("s_nop 7\n\ts_nop 7" ::: "memory"); }
 __device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 template <int N> __device__ __forceinline__ void wait_dma_but() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 // every load and LDS read of this wave has completed, then meet the other waves
@@ -352,9 +361,10 @@ struct DmaSlots {
 constexpr int kWideStages = 4;
 constexpr int wide_stages(bool t_kmajor) { return t_kmajor ? kWideStages : 2; }
 template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR, bool PINGPONG, bool PARTIAL = false, bool SWIGLU = false,
-          bool SPLITK = false, bool SIBS = false>
+          bool SPLITK = false, bool SIBS = false, bool M16 = false>
 __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 {
+    static_assert(!M16 || (B_KMAJOR && !PINGPONG && !PARTIAL && !SWIGLU && !SPLITK && !SIBS), "16x16x32 form: plain tiles, K-major operands");
     static_assert(!SWIGLU || (!B_KMAJOR && !PINGPONG && !PARTIAL && WGN == 2), "SwiGLU epilogue: N-major, two wave columns");
     static_assert(!SPLITK || (!PARTIAL && !SWIGLU && !PINGPONG), "K slices: plain tiles only");
     constexpr int NT = WGM * WGN * 64;
@@ -763,6 +773,50 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 
     const int rl = lane & 31, kh = lane >> 5;
     bf16x8 af[2][MI], bf[2][NI];
+    // 16x16x32 form: lane l supplies row (or column) l % 16 and K values 8 (l / 16) .. of a 32-wide K step; acc4[ni][mi]
+    // holds the transposed 16x16 block: lane = row l % 16, registers = columns 4 (l / 16) .. + 3.  The row blocks of a
+    // wave go in two halves of MH (a4, double-buffered by half); the second operand's fragments (b8) are single:
+    // each is read again as soon as the last MFMA of the step that uses it has been issued.
+    constexpr int MI16 = WM / 16, NI16 = WN / 16, MH = MI16 / 2, NM16 = NI16 * MH;
+    floatx4 acc4[M16 ? NI16 : 1][M16 ? MI16 : 1];
+    bf16x8 a4[2][M16 ? MH : 1], b8[M16 ? NI16 : 1];
+    const int r16 = lane & 15, kq = lane >> 4;
+    if constexpr (M16) {
+#pragma unroll
+        for (int ni = 0; ni < NI16; ++ni)
+#pragma unroll
+            for (int mi = 0; mi < MI16; ++mi) acc4[ni][mi] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+    // phase ph of a K tile: K step ph / 2 (32 wide), row half ph % 2.  j-th fragment read for phase ph: the MH row
+    // blocks of its half, then (first half of a step only) the NI16 blocks of the second operand
+    auto read16 = [&](int stage, int ph, int j) {
+        const uint8_t *ta = smem + (stage ? A_ST1 : 0);
+        const uint8_t *tb = smem + (stage ? B_ST1 : B_ST0);
+        const int c = (ph >> 1) * 4 + kq;
+        if (j < MH) a4[ph & 1][j] = lds_frag(ta, wm * WM + ((ph & 1) * MH + j) * 16 + r16, c);
+        else b8[j - MH] = lds_frag(tb, wn * WN + (j - MH) * 16 + r16, c);
+    };
+    auto mma16 = [&](int ph, int m) {
+        const int ni = m / MH, mi = m % MH;
+        mfma16(acc4[ni][(ph & 1) * MH + mi], b8[ni], a4[ph & 1][mi]);
+    };
+    // The reads for phase nph that ride behind MFMA m of the phase before it (`first`: the first MFMA they may
+    // follow).  Only two or three other instructions fit behind a 16-cycle MFMA, so an MFMA carries at most one
+    // memory instruction: the direct loads sit behind MFMAs 0, 4, 8, .. (DmaSlots), the row fragments behind
+    // first + 2, + 6, .., the second operand's behind the last MFMA that uses the register (3, 7, ..: odd).
+    auto reads16 = [&](int stage, int nph, int m, int first) {
+#pragma unroll
+        for (int i = 0; i < MH; ++i)
+            if (m == first + 2 + 4 * i) read16(stage, nph, i);
+        if ((nph & 1) == 0) {
+#pragma unroll
+            for (int ni = 0; ni < NI16; ++ni) {
+                const int last_use = ni * MH + MH - 1, early = first + 1 + 2 * ni, slot = last_use > early ? last_use : early;
+                if (m == slot) read16(stage, nph, MH + ni);
+            }
+        }
+    };
+    static_assert(!M16 || (MH == 4 && NM16 / 4 + 2 + 4 * (MH - 1) < NM16), "the read slots above are laid out for four row blocks per half");
     // N-major operand: byte offset of this lane's transposing read inside the tile for K step 0
     uint32_t btr[NI];
     {
@@ -884,7 +938,103 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         }
         wait_dma();  // loads of tiles beyond the last one (they fetch nothing)
     } else if (nk > 0) {
-        if constexpr (!PINGPONG) {
+        if constexpr (M16) {
+            // The pipeline below with the 16x16x32 form: a K tile is four phases of NM16 MFMAs of 16 cycles each; the
+            // direct loads keep their places (phase 3 after the barrier, phases 0 and 1), the fragment reads of the
+            // next phase ride behind the MFMAs of this one (see reads16).
+            constexpr int PRE = NM16 / 4;
+            constexpr DmaSlots<NM16, PRE, ND> SL{};
+            constexpr int D3 = SL.n[0];
+            static_assert(SL.placed() == ND, "not every direct load has a slot");
+            auto pipeline = [&](auto even_c) {
+            i32x4 ra_t = tile_rsrc(ra_w, 0), rb_t = tile_rsrc(rb_w, 0);
+#pragma unroll
+            for (int d = 0; d < ND; ++d) dma_chunk(even_c, d, 0, 0, ra_t, rb_t);
+            ra_t = tile_rsrc(ra_w, 1);
+            rb_t = tile_rsrc(rb_w, 1);
+#pragma unroll
+            for (int d = 0; d < D3; ++d) dma_chunk(even_c, d, 1, 1, ra_t, rb_t);
+            records_are_in();
+            decide_pre();
+            wait_dma_but<D3>();
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < MH + NI16; ++j) read16(0, 0, j);
+            auto k_tile = [&](auto cur_c, auto tail_c, int kc, const ExtBatch &b0) {
+                constexpr int cur = decltype(cur_c)::value, nxt = cur ^ 1, tail = decltype(tail_c)::value;
+#pragma unroll
+                for (int ph = 0; ph < 3; ++ph) {
+#pragma unroll
+                    for (int m = 0; m < NM16; ++m) {
+                        mma16(ph, m);
+                        reads16(cur, ph + 1, m, 0);
+                        if (ph < 2 && SL.slot[ph + 1][m] >= 0) {
+                            if constexpr (tail == 1) issue_piece(nxt ? A_ST1 : 0, nxt ? B_ST1 : B_ST0, b0, SL.slot[ph + 1][m], true, 0);
+                            else dma_chunk(even_c, SL.slot[ph + 1][m], nxt, kc + 1, ra_t, rb_t);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+                // (the resources of the tile after the next are formed behind the MFMAs before the barrier: the
+                // loads of the next tile, which used the old ones, were all issued in phases 0 and 1)
+#pragma unroll
+                for (int m = 0; m < PRE; ++m) {
+                    mma16(3, m);
+                    if (m == 0) ra_t = tile_rsrc(ra_w, kc + 2);
+                    if (m == 1) rb_t = tile_rsrc(rb_w, kc + 2);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                drain_and_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int m = PRE; m < NM16; ++m) {
+                    mma16(3, m);
+                    reads16(nxt, 0, m, PRE);
+                    if (SL.slot[0][m] >= 0) {
+                        if constexpr (tail == 2) issue_piece(cur ? A_ST1 : 0, cur ? B_ST1 : B_ST0, b0, SL.slot[0][m], true, 0);
+                        else if constexpr (tail == 0) dma_chunk(even_c, SL.slot[0][m], cur, kc + 2, ra_t, rb_t);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            using I0 = std::integral_constant<int, 0>;
+            using I1 = std::integral_constant<int, 1>;
+            using I2 = std::integral_constant<int, 2>;
+            const int n_loop = pre ? nk - 2 : nk;
+            const ExtBatch no_batch{};
+            // Where paths meet the compiler may copy accumulators from one register to another, and it does not
+            // know that the statements before are MFMAs whose results take time to land: every path that ends in
+            // MFMAs and leads to such a place ends in mfma16_settle (the loop's own back edge needs no copies).
+            int kc = 0;
+            for (; kc + 1 < n_loop; kc += 2) {
+                k_tile(I0{}, I0{}, kc, no_batch);
+                k_tile(I1{}, I0{}, kc + 1, no_batch);
+            }
+            mfma16_settle();
+            if (kc < n_loop) {
+                k_tile(I0{}, I0{}, kc++, no_batch);
+                mfma16_settle();
+            }
+            if constexpr (CAN_PRE) {
+                if (pre) {
+                    const ExtBatch b0 = get_batch(e0);
+                    if (kc & 1) {
+                        k_tile(I1{}, I2{}, kc, b0);
+                        k_tile(I0{}, I1{}, kc + 1, b0);
+                        mfma16_settle();
+                    } else {
+                        k_tile(I0{}, I2{}, kc, b0);
+                        k_tile(I1{}, I1{}, kc + 1, b0);
+                        mfma16_settle();
+                    }
+                }
+            }
+            wait_dma();
+            };
+            if (k_even) pipeline(std::true_type{});
+            else pipeline(std::false_type{});
+        } else if constexpr (!PINGPONG) {
             // One wave per SIMD; tiles travel global -> LDS without touching registers.  A K tile is
             // four MFMA steps.  Everything else a wave has to issue rides behind single MFMAs, one
             // instruction at a time, so that the matrix pipe never waits for the issue of a load:
@@ -1196,6 +1346,49 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                     g_cur = g;
                 }
             }
+            if constexpr (M16) {
+                // 16x16x32 form: two steps per MFMA.  K values 0-15 of lane groups 0 and 1 belong to step 2 q, 16-31 of
+                // groups 2 and 3 to step 2 q + 1: each lane takes the rank offset and the row range of its own step (a
+                // step that does not exist has an empty row range, and its part of the table area holds zeros).
+#pragma unroll
+                for (int q = 0; q < kExtBatch / 2; ++q) {
+                    if (2 * q < nsteps) {
+                        const uint32_t rows0 = cur_b.rows[2 * q], rows1 = cur_b.rows[2 * q + 1];
+                        const uint32_t kr_l = kq < 2 ? cur_b.kr[2 * q] : cur_b.kr[2 * q + 1];
+                        const uint32_t rows_l = kq < 2 ? rows0 : rows1;
+                        const int c0 = (int)((kr_l & 63u) >> 3) + (kq & 1);
+                        const int lo = (int)(rows_l & 0xffffu), hi = (int)(rows_l >> 16);
+                        auto on16 = [&](int mi) {
+                            const int r0 = wrow0 + mi * 16;
+                            return ((int)(rows0 & 0xffffu) < r0 + 16 && (int)(rows0 >> 16) > r0) ||
+                                   ((int)(rows1 & 0xffffu) < r0 + 16 && (int)(rows1 >> 16) > r0);
+                        };
+#pragma unroll
+                        for (int ni = 0; ni < NI16; ++ni) b8[ni] = lds_frag(smem + t_cur, wn * WN + ni * 16 + r16, q * 4 + kq);
+#pragma unroll
+                        for (int mi = 0; mi < MI16; ++mi) {
+                            if (on16(mi)) {
+                                const int row = wm * WM + mi * 16 + r16;
+                                uint4 v = __builtin_bit_cast(uint4, lds_frag(smem + xa, row, c0));
+                                const bool in = row >= lo && row < hi;
+                                v.x = in ? v.x : 0u;
+                                v.y = in ? v.y : 0u;
+                                v.z = in ? v.z : 0u;
+                                v.w = in ? v.w : 0u;
+                                a4[mi / MH][mi % MH] = __builtin_bit_cast(bf16x8, v);
+                            }
+                        }
+#pragma unroll
+                        for (int mi = 0; mi < MI16; ++mi) {
+                            if (on16(mi)) {
+#pragma unroll
+                                for (int ni = 0; ni < NI16; ++ni) mfma16(acc4[ni][mi], b8[ni], a4[mi / MH][mi % MH]);
+                                mfma16_settle();  // (a conditional block: paths meet behind it)
+                            }
+                        }
+                    }
+                }
+            } else {
             read_step(t_cur, 0, cur_b.kr[0], cur_b.rows[0], 0);
 #pragma unroll
             for (int j = 0; j < kExtBatch; ++j) {
@@ -1203,6 +1396,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                     if (j + 1 < nsteps) read_step(t_cur, j + 1, cur_b.kr[(j + 1) & 3], cur_b.rows[(j + 1) & 3], (j + 1) & 1);
                     mma_rows(j & 1, cur_b.rows[j]);
                 }
+            }
             }
             const uint32_t t = t_cur;
             t_cur = t_nxt;
@@ -1341,8 +1535,23 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
             else finish(std::integral_constant<int, MH>{}, std::false_type{}, xg);
             return;
         }
+        if constexpr (M16) {
+            mfma16_settle();
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
+            for (int mi = 0; mi < MI16; ++mi) {
+                uint8_t *erow = ep + (mi * 16 + r16) * EP;
+                if (kq == 0) *reinterpret_cast<int32_t *>(erow + WN * 2) = row_tok[m0 + wm * WM + mi * 16 + r16];
+#pragma unroll
+                for (int ni = 0; ni < NI16; ++ni) {
+                    uint2 v;
+                    v.x = pack_bf16(acc4[ni][mi][0], acc4[ni][mi][1]);
+                    v.y = pack_bf16(acc4[ni][mi][2], acc4[ni][mi][3]);
+                    *reinterpret_cast<uint2 *>(erow + (ni * 16 + kq * 4) * 2) = v;
+                }
+            }
+        }
+#pragma unroll
+        for (int mi = 0; mi < (M16 ? 0 : MI); ++mi) {
             uint8_t *erow = ep + (mi * 32 + rl) * EP;
             if (kh == 0) *reinterpret_cast<int32_t *>(erow + WN * 2) = row_tok[m0 + wm * WM + mi * 32 + rl];
 #pragma unroll
@@ -1893,7 +2102,7 @@ __global__ void __launch_bounds__(GradCfg<RP>::KW * 64) grad_kernel(GradArgs p)
 // =========================================================================================
 // launchers
 // =========================================================================================
-template <int BM, int BN, int WGM, int WGN, bool KM, bool PP, bool SWIGLU = false, bool SIBS = false>
+template <int BM, int BN, int WGM, int WGN, bool KM, bool PP, bool SWIGLU = false, bool SIBS = false, bool M16 = false>
 static hipError_t launch_gemm_t(const GemmArgs &a, hipStream_t st)
 {
     constexpr int NT = WGM * WGN * 64;
@@ -1902,7 +2111,7 @@ static hipError_t launch_gemm_t(const GemmArgs &a, hipStream_t st)
     constexpr int epi_bytes = BM * BN * 2 + BM * WGN * 16;  // per wave (BM/WGM) rows of (BN/WGN) * 2 + 16 bytes
     constexpr int smem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
     static_assert(!SWIGLU || smem >= BM * (BN / 2) * 4, "the up halves of all rows pass through LDS as fp32");
-    auto kern = gemm_lora_kernel<BM, BN, WGM, WGN, KM, PP, false, SWIGLU, false, SIBS>;
+    auto kern = gemm_lora_kernel<BM, BN, WGM, WGN, KM, PP, false, SWIGLU, false, SIBS, M16>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -1937,7 +2146,7 @@ hipError_t launch_gemm(const GemmArgs &a, int tile_cfg, bool b_kmajor, hipStream
     }
     switch (tile_cfg) {
     case kTile256x256:
-        return b_kmajor ? launch_gemm_t<256, 256, 2, 2, true, false>(a, st) : launch_gemm_t<256, 256, 2, 2, false, false>(a, st);
+        return b_kmajor ? launch_gemm_t<256, 256, 2, 2, true, false, false, false, true>(a, st) : launch_gemm_t<256, 256, 2, 2, false, false>(a, st);
     case kTile256x128:
         return b_kmajor ? launch_gemm_t<256, 128, 2, 2, true, false>(a, st) : launch_gemm_t<256, 128, 2, 2, false, false>(a, st);
     case kTile128x128:
