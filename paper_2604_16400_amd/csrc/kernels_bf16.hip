@@ -364,7 +364,7 @@ template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR, bool PINGPONG, bool P
           bool SPLITK = false, bool SIBS = false, bool M16 = false>
 __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
 {
-    static_assert(!M16 || (B_KMAJOR && !PINGPONG && !PARTIAL && !SWIGLU && !SPLITK && !SIBS), "16x16x32 form: plain tiles, K-major operands");
+    static_assert(!M16 || (!PINGPONG && !PARTIAL && !SWIGLU && !SPLITK && !SIBS), "16x16x32 form: plain tiles");
     static_assert(!SWIGLU || (!B_KMAJOR && !PINGPONG && !PARTIAL && WGN == 2), "SwiGLU epilogue: N-major, two wave columns");
     static_assert(!SPLITK || (!PARTIAL && !SWIGLU && !PINGPONG), "K slices: plain tiles only");
     constexpr int NT = WGM * WGN * 64;
@@ -372,7 +372,8 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     constexpr int MI = WM / 32, NI = WN / 32;
     // second operand in LDS: K-major -> BN rows of 64 K values (swizzled chunks); N-major ->
     // 64 rows (K) of BN values as they lie in memory, chunk c of row k stored at chunk position
-    // c ^ ((k & 3) << 2) so that the four rows a transposing read touches use different banks
+    // c ^ ((k & 3) << 2) so that the four rows a transposing read touches use different banks (16x16x32 form:
+    // also ^ 2 for rows 8-15 of every 16, see bcl_of)
     constexpr int BPITCH = BN * 2;
     constexpr int BTILE = B_KMAJOR ? BN * 128 : 64 * BPITCH;
     constexpr int ATILE = BM * 128;
@@ -540,6 +541,9 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     const uint32_t bstep_u = 64u * ldb * 2u;  // the same as a wave-uniform value
     const int bng = tid % NG, bk0 = tid / NG;
     const int bcl = bng ^ ((bk0 & 3) << 2);  // N-major: source chunk of this thread (same for all i)
+    // 16x16x32 form: a transposing read takes K rows r .. r + 3 in one lane group and r + 8 .. r + 11 in the next,
+    // so rows 8-15 of every 16 are stored with their chunk pairs swapped: the source chunk then depends on i
+    auto bcl_of = [&](int i) { return M16 ? bcl ^ ((((bk0 + i * (NT / NG)) >> 3) & 1) << 1) : bcl; };
     if constexpr (B_KMAJOR) {
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
@@ -552,7 +556,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
         bstep = on ? 64u * ldb * 2u : 0u;
 #pragma unroll
         for (int i = 0; i < NB; ++i)
-            boff[i] = on ? ((uint32_t)(bk0 + i * (NT / NG)) * ldb + src_col(bcl * 8)) * 2u : kOob;
+            boff[i] = col_on(bcl_of(i) * 8) ? ((uint32_t)(bk0 + i * (NT / NG)) * ldb + src_col(bcl_of(i) * 8)) * 2u : kOob;
     }
     // byte offset of the tile that starts at K index k0 = 64 kc, for chunk i; tiles that reach
     // beyond K mask their tail (K-major) or run off the end of the buffer (N-major rows)
@@ -565,6 +569,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
             const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
             return (full || k0 + cl * 8 < K) ? boff[i] + (uint32_t)k0 * 2u : kOob;
         } else {
+            if constexpr (M16) return boff[i] == kOob ? kOob : boff[i] + (uint32_t)kc * bstep_u;
             return boff[i] + (uint32_t)kc * bstep;
         }
     };
@@ -690,8 +695,9 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                 koff -= up ? rk : 0u;
                 mine = (bcl * 8 >= BN / 2) == up;
             }
+            const int bcl_i = bcl_of(i);
             const i32x4 rt = make_rsrc_words(reinterpret_cast<const void *>(bt.tab[j]), rk * (uint32_t)p.ext_ld * 2u);
-            const uint32_t off = (mine && col_on(bcl * 8)) ? ((koff + (uint32_t)(k & 15)) * (uint32_t)p.ext_ld + (uint32_t)src_col(bcl * 8)) * 2u : kOob;
+            const uint32_t off = (mine && col_on(bcl_i * 8)) ? ((koff + (uint32_t)(k & 15)) * (uint32_t)p.ext_ld + (uint32_t)src_col(bcl_i * 8)) * 2u : kOob;
             dma16(rt, off, lds_wave + b_base + i * (NT / 64) * 1024);
         } else {
             // table rows are output columns: A_a[n][q], row length rank.  The four steps of a
@@ -789,12 +795,33 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     }
     // phase ph of a K tile: K step ph / 2 (32 wide), row half ph % 2.  j-th fragment read for phase ph: the MH row
     // blocks of its half, then (first half of a step only) the NI16 blocks of the second operand
+    // N-major second operand: byte offset of this lane's transposing reads for K step 0 (16 lanes fetch a 4 (K) x 16 (N)
+    // block; lane group g takes K rows 8 g ..)
+    uint32_t btr16[(M16 && !B_KMAJOR) ? NI16 : 1];
+    if constexpr (M16 && !B_KMAJOR) {
+        const int krow = kq * 8 + (r16 >> 2);
+#pragma unroll
+        for (int ni = 0; ni < NI16; ++ni) {
+            const int col = wn * WN + ni * 16 + (r16 & 3) * 4;
+            btr16[ni] = krow * BPITCH + ((((col >> 3) ^ ((krow & 3) << 2) ^ (((krow >> 3) & 1) << 1))) << 4) + (col & 7) * 2;
+        }
+    }
+    // second-operand fragment ni of the 32-wide K step ks of the tile at tb
+    auto read_b16 = [&](const uint8_t *tb, int ks, int ni) {
+        if constexpr (B_KMAJOR) {
+            b8[ni] = lds_frag(tb, wn * WN + ni * 16 + r16, ks * 4 + kq);
+        } else {
+            const uint8_t *src = tb + btr16[ni] + ks * 32 * BPITCH;
+            const bf16x4 lo = lds_tr(src);
+            const bf16x4 hi = lds_tr(src + 4 * BPITCH);
+            b8[ni] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+    };
     auto read16 = [&](int stage, int ph, int j) {
         const uint8_t *ta = smem + (stage ? A_ST1 : 0);
         const uint8_t *tb = smem + (stage ? B_ST1 : B_ST0);
-        const int c = (ph >> 1) * 4 + kq;
-        if (j < MH) a4[ph & 1][j] = lds_frag(ta, wm * WM + ((ph & 1) * MH + j) * 16 + r16, c);
-        else b8[j - MH] = lds_frag(tb, wn * WN + (j - MH) * 16 + r16, c);
+        if (j < MH) a4[ph & 1][j] = lds_frag(ta, wm * WM + ((ph & 1) * MH + j) * 16 + r16, (ph >> 1) * 4 + kq);
+        else read_b16(tb, ph >> 1, j - MH);
     };
     auto mma16 = [&](int ph, int m) {
         const int ni = m / MH, mi = m % MH;
@@ -1364,7 +1391,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
                                    ((int)(rows1 & 0xffffu) < r0 + 16 && (int)(rows1 >> 16) > r0);
                         };
 #pragma unroll
-                        for (int ni = 0; ni < NI16; ++ni) b8[ni] = lds_frag(smem + t_cur, wn * WN + ni * 16 + r16, q * 4 + kq);
+                        for (int ni = 0; ni < NI16; ++ni) read_b16(smem + t_cur, q, ni);
 #pragma unroll
                         for (int mi = 0; mi < MI16; ++mi) {
                             if (on16(mi)) {
@@ -2146,7 +2173,8 @@ hipError_t launch_gemm(const GemmArgs &a, int tile_cfg, bool b_kmajor, hipStream
     }
     switch (tile_cfg) {
     case kTile256x256:
-        return b_kmajor ? launch_gemm_t<256, 256, 2, 2, true, false, false, false, true>(a, st) : launch_gemm_t<256, 256, 2, 2, false, false>(a, st);
+        return b_kmajor ? launch_gemm_t<256, 256, 2, 2, true, false, false, false, true>(a, st)
+                        : launch_gemm_t<256, 256, 2, 2, false, false, false, false, true>(a, st);
     case kTile256x128:
         return b_kmajor ? launch_gemm_t<256, 128, 2, 2, true, false>(a, st) : launch_gemm_t<256, 128, 2, 2, false, false>(a, st);
     case kTile128x128:
