@@ -362,7 +362,7 @@ constexpr int kWideStages = 4;
 constexpr int wide_stages(bool t_kmajor) { return t_kmajor ? kWideStages : 2; }
 template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR, bool PINGPONG, bool PARTIAL = false, bool SWIGLU = false,
           bool SPLITK = false, bool SIBS = false, bool M16 = false>
-__global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
+__global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ? 2 : 1) gemm_lora_kernel(GemmArgs p)
 {
     static_assert(!M16 || (!PINGPONG && !PARTIAL && !SWIGLU && !SPLITK && !SIBS), "16x16x32 form: plain tiles");
     static_assert(!SWIGLU || (!B_KMAJOR && !PINGPONG && !PARTIAL && WGN == 2), "SwiGLU epilogue: N-major, two wave columns");
@@ -741,7 +741,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     // Whether the first batch is loaded from inside the main loop (see k_tile): the hand-scheduled loop with at
     // least two tiles, and every piece of the batch one direct load (tables with K contiguous: ranks in eights).
     // Not for 256x256 tiles: their main loop leaves no registers for the address arithmetic of these loads.
-    constexpr bool CAN_PRE = !PINGPONG && !PARTIAL && !SIBS && BM * BN < 256 * 256;
+    constexpr bool CAN_PRE = !PINGPONG && !PARTIAL && !SIBS && !M16 && BM * BN < 256 * 256;
     // The 256x256 tiles instead use what the main loop's two stages leave of the LDS (32 KiB of 160): the rows' area of
     // the extension lies behind them and is loaded before the main loop starts.
     constexpr bool ROWS_EARLY = !PINGPONG && !PARTIAL && !SIBS && !CAN_PRE;
@@ -834,16 +834,17 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_lora_kernel(GemmArgs p)
     auto reads16 = [&](int stage, int nph, int m, int first) {
 #pragma unroll
         for (int i = 0; i < MH; ++i)
-            if (m == first + 2 + 4 * i) read16(stage, nph, i);
+            if (m == (MH == 4 ? first + 2 + 4 * i : first + 2 * i)) read16(stage, nph, i);
         if ((nph & 1) == 0) {
 #pragma unroll
             for (int ni = 0; ni < NI16; ++ni) {
-                const int last_use = ni * MH + MH - 1, early = first + 1 + 2 * ni, slot = last_use > early ? last_use : early;
+                const int last_use = ni * MH + MH - 1, early = MH == 4 ? first + 1 + 2 * ni : first + ni;
+                const int slot = last_use > early ? last_use : early;
                 if (m == slot) read16(stage, nph, MH + ni);
             }
         }
     };
-    static_assert(!M16 || (MH == 4 && NM16 / 4 + 2 + 4 * (MH - 1) < NM16), "the read slots above are laid out for four row blocks per half");
+    static_assert(!M16 || (MH == 4 && NM16 / 4 + 2 + 4 * (MH - 1) < NM16) || (MH == 2 && NM16 == 8), "the read slots above are laid out for four (or two) row blocks per half");
     // N-major operand: byte offset of this lane's transposing read inside the tile for K step 0
     uint32_t btr[NI];
     {
@@ -2134,7 +2135,7 @@ static hipError_t launch_gemm_t(const GemmArgs &a, hipStream_t st)
 {
     constexpr int NT = WGM * WGN * 64;
     // two stages; the 256x256 tiles of the direct-load pipeline keep the rows' area of the extension behind them
-    constexpr int stage_bytes = 2 * (BM + BN) * 128 + ((!PP && !SIBS && BM * BN == 256 * 256) ? BM * 128 : 0);
+    constexpr int stage_bytes = 2 * (BM + BN) * 128 + ((!PP && !SIBS && (BM * BN == 256 * 256 || M16)) ? BM * 128 : 0);
     constexpr int epi_bytes = BM * BN * 2 + BM * WGN * 16;  // per wave (BM/WGM) rows of (BN/WGN) * 2 + 16 bytes
     constexpr int smem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
     static_assert(!SWIGLU || smem >= BM * (BN / 2) * 4, "the up halves of all rows pass through LDS as fp32");
@@ -2178,7 +2179,8 @@ hipError_t launch_gemm(const GemmArgs &a, int tile_cfg, bool b_kmajor, hipStream
     case kTile256x128:
         return b_kmajor ? launch_gemm_t<256, 128, 2, 2, true, false>(a, st) : launch_gemm_t<256, 128, 2, 2, false, false>(a, st);
     case kTile128x128:
-        return b_kmajor ? launch_gemm_t<128, 128, 2, 2, true, false>(a, st) : launch_gemm_t<128, 128, 2, 2, false, false>(a, st);
+        return b_kmajor ? launch_gemm_t<128, 128, 2, 2, true, false, false, false, true>(a, st)
+                        : launch_gemm_t<128, 128, 2, 2, false, false, false, false, true>(a, st);
     case kTile256x256w8:
         return b_kmajor ? launch_gemm_t<256, 256, 2, 4, true, true>(a, st) : launch_gemm_t<256, 256, 2, 4, false, true>(a, st);
     default:
