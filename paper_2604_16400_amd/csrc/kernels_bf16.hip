@@ -364,7 +364,7 @@ template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR, bool PINGPONG, bool P
           bool SPLITK = false, bool SIBS = false, bool M16 = false>
 __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ? 2 : 1) gemm_lora_kernel(GemmArgs p)
 {
-    static_assert(!M16 || (!PINGPONG && !PARTIAL && !SWIGLU && !SPLITK && !SIBS), "16x16x32 form: plain tiles");
+    static_assert(!M16 || (!PINGPONG && !PARTIAL && !SWIGLU), "16x16x32 form: not the rank-wide pass, not the SwiGLU epilogue");
     static_assert(!SWIGLU || (!B_KMAJOR && !PINGPONG && !PARTIAL && WGN == 2), "SwiGLU epilogue: N-major, two wave columns");
     static_assert(!SPLITK || (!PARTIAL && !SWIGLU && !PINGPONG), "K slices: plain tiles only");
     constexpr int NT = WGM * WGN * 64;
@@ -744,7 +744,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
     constexpr bool CAN_PRE = !PINGPONG && !PARTIAL && !SIBS && !M16 && BM * BN < 256 * 256;
     // The 256x256 tiles instead use what the main loop's two stages leave of the LDS (32 KiB of 160): the rows' area of
     // the extension lies behind them and is loaded before the main loop starts.
-    constexpr bool ROWS_EARLY = !PINGPONG && !PARTIAL && !SIBS && !CAN_PRE;
+    constexpr bool ROWS_EARLY = !PINGPONG && !PARTIAL && !SIBS && !CAN_PRE && BM * BN == 256 * 256;
     constexpr uint32_t XA_EARLY = 2 * STAGE;
     // Where the load of the step records is waited for.  The hand-scheduled pipeline does it behind the direct
     // loads of its first tile (the records' chain of two loads is longer than the one that leads to those loads,
@@ -1245,6 +1245,46 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
         for (int eb = e0; eb < e1; eb += kExtBatch, stage ^= 1) {
             drain_and_barrier();  // this batch has landed; the stage of the batch before it is free
             const int nsteps = (e1 - eb) < kExtBatch ? (e1 - eb) : kExtBatch;
+            if constexpr (M16) {
+                // 16x16x32 form: two steps per MFMA (K values 0-15 one step, 16-31 the next).  The rows' operand of the
+                // batch holds zeros outside each step's row range already, so the fragments are used as they are; a
+                // wave multiplies the 16-row blocks that either step reaches.
+                const uint8_t *ta = smem + (stage ? A_ST1 : 0);
+                const uint8_t *tb = smem + (stage ? B_ST1 : B_ST0);
+                const bool more = eb + kExtBatch < e1;
+#pragma unroll
+                for (int q = 0; q < kExtBatch / 2; ++q) {
+                    if (2 * q < nsteps) {
+                        const uint32_t rows0 = cur_b.rows[2 * q], rows1 = cur_b.rows[2 * q + 1];
+                        auto on16 = [&](int mi) {
+                            const int r0 = wrow0 + mi * 16;
+                            return ((int)(rows0 & 0xffffu) < r0 + 16 && (int)(rows0 >> 16) > r0) ||
+                                   ((int)(rows1 & 0xffffu) < r0 + 16 && (int)(rows1 >> 16) > r0);
+                        };
+#pragma unroll
+                        for (int ni = 0; ni < NI16; ++ni) read_b16(tb, q, ni);
+#pragma unroll
+                        for (int mi = 0; mi < MI16; ++mi)
+                            if (on16(mi)) a4[mi / MH][mi % MH] = lds_frag(ta, wm * WM + mi * 16 + r16, q * 4 + kq);
+#pragma unroll
+                        for (int mi = 0; mi < MI16; ++mi) {
+                            if (on16(mi)) {
+#pragma unroll
+                                for (int ni = 0; ni < NI16; ++ni) mfma16(acc4[ni][mi], b8[ni], a4[mi / MH][mi % MH]);
+                                mfma16_settle();  // (a conditional block: paths meet behind it)
+                            }
+                        }
+                    }
+                    if (q == 0 && more) {
+                        // the loads of the next batch, into the other stage
+#pragma unroll
+                        for (int d = 0; d < ND; ++d) issue_piece(stage ? 0 : A_ST1, stage ? B_ST0 : B_ST1, nxt_b, d, false, 0);
+                    }
+                }
+                cur_b = nxt_b;
+                nxt_b = get_batch(eb + 2 * kExtBatch);
+                continue;
+            }
             read_frags(stage, 0, 0);
             if (nsteps > 1) read_frags(stage, 1, 1);
             {
@@ -1449,8 +1489,20 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
         if constexpr (SPLITK) rows_in = p.row_base + p.n_rows - m0;  // rows of the order beyond the last are padding
         float *__restrict__ part =
             p.part + ((int64_t)(SPLITK ? blockIdx.y : blockIdx.z) * p.part_rows + m0 - (SPLITK ? p.row_base : 0)) * p.part_ld;
+        if constexpr (M16) {
+            mfma16_settle();
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
+            for (int mi = 0; mi < MI16; ++mi) {
+                const int r = wm * WM + mi * 16 + r16;
+#pragma unroll
+                for (int ni = 0; ni < NI16; ++ni) {
+                    const int q = n0 + wn * WN + ni * 16 + kq * 4;
+                    if (r < rows_in && q < q_hi) *reinterpret_cast<floatx4 *>(part + (int64_t)r * p.part_ld + q) = acc4[ni][mi];
+                }
+            }
+        }
+#pragma unroll
+        for (int mi = 0; mi < (M16 ? 0 : MI); ++mi) {
             const int r = wm * WM + mi * 32 + rl;
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
@@ -2135,7 +2187,7 @@ static hipError_t launch_gemm_t(const GemmArgs &a, hipStream_t st)
 {
     constexpr int NT = WGM * WGN * 64;
     // two stages; the 256x256 tiles of the direct-load pipeline keep the rows' area of the extension behind them
-    constexpr int stage_bytes = 2 * (BM + BN) * 128 + ((!PP && !SIBS && (BM * BN == 256 * 256 || M16)) ? BM * 128 : 0);
+    constexpr int stage_bytes = 2 * (BM + BN) * 128 + ((!PP && !SIBS && BM * BN == 256 * 256) ? BM * 128 : 0);
     constexpr int epi_bytes = BM * BN * 2 + BM * WGN * 16;  // per wave (BM/WGM) rows of (BN/WGN) * 2 + 16 bytes
     constexpr int smem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
     static_assert(!SWIGLU || smem >= BM * (BN / 2) * 4, "the up halves of all rows pass through LDS as fp32");
@@ -2161,11 +2213,11 @@ hipError_t launch_gemm(const GemmArgs &a, int tile_cfg, bool b_kmajor, hipStream
         if (b_kmajor) return hipErrorInvalidValue;
         switch (tile_cfg) {
         case kTile256x256:
-            return launch_gemm_t<256, 256, 2, 2, false, false, false, true>(a, st);
+            return launch_gemm_t<256, 256, 2, 2, false, false, false, true, true>(a, st);
         case kTile256x128:
             return launch_gemm_t<256, 128, 2, 2, false, false, false, true>(a, st);
         case kTile128x128:
-            return launch_gemm_t<128, 128, 2, 2, false, false, false, true>(a, st);
+            return launch_gemm_t<128, 128, 2, 2, false, false, false, true, true>(a, st);
         case kTile256x256w8:
             return launch_gemm_t<256, 256, 2, 4, false, true, false, true>(a, st);
         default:
@@ -2250,9 +2302,9 @@ hipError_t launch_gemm_splitk(const GemmArgs &a, int n_split, bool b_kmajor, hip
         COLLM_LAUNCH(kern, dim3(tiles, n_split), dim3(256), smem, st, a);
         return hipGetLastError();
     };
-    if (a.n_sib > 1) return b_kmajor ? hipErrorInvalidValue : launch(gemm_lora_kernel<128, 128, 2, 2, false, false, false, false, true, true>);
-    return b_kmajor ? launch(gemm_lora_kernel<128, 128, 2, 2, true, false, false, false, true>)
-                    : launch(gemm_lora_kernel<128, 128, 2, 2, false, false, false, false, true>);
+    if (a.n_sib > 1) return b_kmajor ? hipErrorInvalidValue : launch(gemm_lora_kernel<128, 128, 2, 2, false, false, false, false, true, true, true>);
+    return b_kmajor ? launch(gemm_lora_kernel<128, 128, 2, 2, true, false, false, false, true, false, true>)
+                    : launch(gemm_lora_kernel<128, 128, 2, 2, false, false, false, false, true, false, true>);
 }
 
 hipError_t launch_gemm_finish(const GemmArgs &a, int n_split, hipStream_t st)
