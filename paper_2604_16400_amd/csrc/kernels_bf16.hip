@@ -364,7 +364,7 @@ template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR, bool PINGPONG, bool P
           bool SPLITK = false, bool SIBS = false, bool M16 = false>
 __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ? 2 : 1) gemm_lora_kernel(GemmArgs p)
 {
-    static_assert(!M16 || (!PINGPONG && !PARTIAL && !SWIGLU), "16x16x32 form: not the rank-wide pass, not the SwiGLU epilogue");
+    static_assert(!M16 || (!PINGPONG && !PARTIAL), "16x16x32 form: not the rank-wide pass");
     static_assert(!SWIGLU || (!B_KMAJOR && !PINGPONG && !PARTIAL && WGN == 2), "SwiGLU epilogue: N-major, two wave columns");
     static_assert(!SPLITK || (!PARTIAL && !SWIGLU && !PINGPONG), "K slices: plain tiles only");
     constexpr int NT = WGM * WGN * 64;
@@ -1519,6 +1519,86 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
         constexpr int EP = WN * 2 + 16;          // bytes per staged row
         constexpr int LPR = WN / 8, RPI = 64 / LPR;  // lanes per row, rows per store instruction
         uint8_t *ep = smem + wave * (WM * EP);
+        if constexpr (SWIGLU && M16) {
+            // The same exchange in the 16x16x32 accumulator layout (lane = row l % 16 of a 16x16 block, registers =
+            // columns 4 (l / 16) ..): the two waves of a pair hold gate and up of the same outputs lane for lane.
+            mfma16_settle();
+            if (p.pre_act) {
+                uint16_t *__restrict__ Pre = reinterpret_cast<uint16_t *>(p.pre_act);
+#pragma unroll
+                for (int mi = 0; mi < MI16; ++mi) {
+                    const int tok = row_tok[m0 + wm * WM + mi * 16 + r16];
+                    if (tok < 0 || !p.tok_train[tok]) continue;
+#pragma unroll
+                    for (int ni = 0; ni < NI16; ++ni) {
+                        const int c = ni * 16 + kq * 4;
+                        if (n0 + c >= N) continue;
+                        uint2 v;
+                        v.x = pack_bf16(acc4[ni][mi][0], acc4[ni][mi][1]);
+                        v.y = pack_bf16(acc4[ni][mi][2], acc4[ni][mi][3]);
+                        *reinterpret_cast<uint2 *>(Pre + (int64_t)tok * p.pre_ld + (wn ? p.act_col : 0) + n0 + c) = v;
+                    }
+                }
+            }
+            static_assert(MI16 % 2 == 0, "the rows of a wave pair are split in two");
+            constexpr int MH2 = MI16 / 2;
+            floatx4 *xg = reinterpret_cast<floatx4 *>(smem + wm * (WM * WN * 4));
+            floatx4 *xu = xg + MH2 * NI16 * 64;
+            auto send = [&](auto lo_c, floatx4 *dst) {
+                constexpr int LO = decltype(lo_c)::value;
+#pragma unroll
+                for (int mh = 0; mh < MH2; ++mh)
+#pragma unroll
+                    for (int ni = 0; ni < NI16; ++ni) dst[(mh * NI16 + ni) * 64 + lane] = acc4[ni][LO + mh];
+            };
+            if (wn == 0) send(std::integral_constant<int, MH2>{}, xg);
+            else send(std::integral_constant<int, 0>{}, xu);
+            __syncthreads();
+            auto finish = [&](auto lo_c, auto gate_c, const floatx4 *src) {
+                constexpr int LO = decltype(lo_c)::value;
+                constexpr bool OWN_GATE = decltype(gate_c)::value;
+                uint8_t *area = reinterpret_cast<uint8_t *>(const_cast<floatx4 *>(src));
+                uint2 out[MH2][NI16];
+#pragma unroll
+                for (int mh = 0; mh < MH2; ++mh) {
+#pragma unroll
+                    for (int ni = 0; ni < NI16; ++ni) {
+                        const floatx4 o = src[(mh * NI16 + ni) * 64 + lane];
+                        float r[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float own = acc4[ni][LO + mh][e];
+                            const float gt = OWN_GATE ? own : o[e], up = OWN_GATE ? o[e] : own;
+                            r[e] = gt * up * __builtin_amdgcn_rcpf(1.f + __expf(-gt));
+                        }
+                        out[mh][ni].x = pack_bf16(r[0], r[1]);
+                        out[mh][ni].y = pack_bf16(r[2], r[3]);
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();  // every lane has read what it needs of the area
+#pragma unroll
+                for (int mh = 0; mh < MH2; ++mh) {
+                    uint8_t *erow = area + (mh * 16 + r16) * EP;
+                    if (kq == 0) *reinterpret_cast<int32_t *>(erow + WN * 2) = row_tok[m0 + wm * WM + (LO + mh) * 16 + r16];
+#pragma unroll
+                    for (int ni = 0; ni < NI16; ++ni) *reinterpret_cast<uint2 *>(erow + (ni * 16 + kq * 4) * 2) = out[mh][ni];
+                }
+                __builtin_amdgcn_wave_barrier();
+                uint16_t *__restrict__ Out = reinterpret_cast<uint16_t *>(p.out);
+                const int rr = lane / LPR, cc = lane % LPR;
+                const int n = n0 + cc * 8;
+#pragma unroll 4
+                for (int it = 0; it < (WM / 2) / RPI; ++it) {
+                    const uint8_t *erow = area + (it * RPI + rr) * EP;
+                    const uint4 v = *reinterpret_cast<const uint4 *>(erow + cc * 16);
+                    const int tok = *reinterpret_cast<const int32_t *>(erow + WN * 2);
+                    if (tok >= 0 && n < N) *reinterpret_cast<uint4 *>(Out + (int64_t)tok * p.ldo + n) = v;
+                }
+            };
+            if (wn == 0) finish(std::integral_constant<int, 0>{}, std::true_type{}, xu);
+            else finish(std::integral_constant<int, MH2>{}, std::false_type{}, xg);
+            return;
+        }
         if constexpr (SWIGLU) {
             // pre-activations of training rows, as they are (8 bytes per lane: few rows need them)
             if (p.pre_act) {
@@ -2318,9 +2398,9 @@ hipError_t launch_gemm_swiglu(const GemmArgs &a, int tile_cfg, hipStream_t st)
 {
     switch (tile_cfg) {
     case kTile256x256:
-        return launch_gemm_t<256, 256, 2, 2, false, false, true>(a, st);
+        return launch_gemm_t<256, 256, 2, 2, false, false, true, false, true>(a, st);
     case kTile128x128:
-        return launch_gemm_t<128, 128, 2, 2, false, false, true>(a, st);
+        return launch_gemm_t<128, 128, 2, 2, false, false, true, false, true>(a, st);
     default:
         return hipErrorInvalidValue;
     }
