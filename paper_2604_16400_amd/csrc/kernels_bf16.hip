@@ -1208,6 +1208,20 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
         __syncthreads();
     }
 
+    // The epilogue needs the token of every row this lane stores: a load whose latency would stand at its start.
+    // The 128x128 tiles issue it here, so that it lands while the extension runs (headline step -0.7 %); the 256x256
+    // tiles have no registers to hold the tokens meanwhile (with them: spills, forward GEMM +2 %).
+    constexpr bool TOK_EARLY = M16 && !SPLITK && BM * BN < 256 * 256;
+    int etok[TOK_EARLY ? MI16 : 1];
+    if constexpr (TOK_EARLY) {
+#pragma unroll
+        for (int mi = 0; mi < MI16; ++mi) etok[mi] = row_tok[m0 + wm * WM + mi * 16 + r16];
+    }
+    auto row_token16 = [&](int mi) -> int {
+        if constexpr (TOK_EARLY) return etok[mi];
+        else return row_tok[m0 + wm * WM + mi * 16 + r16];
+    };
+
     // ---- low-rank extension: K-steps [s h | dh] x [B_a | A_a^T] of the tile's adapters ----
     // The steps are taken four at a time (one 64-wide K tile); the step records of a batch are fetched ahead of
     // its loads, those of the first batch before the main loop.  Rank indices beyond an adapter's rank and
@@ -1527,7 +1541,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
                 uint16_t *__restrict__ Pre = reinterpret_cast<uint16_t *>(p.pre_act);
 #pragma unroll
                 for (int mi = 0; mi < MI16; ++mi) {
-                    const int tok = row_tok[m0 + wm * WM + mi * 16 + r16];
+                    const int tok = row_token16(mi);
                     if (tok < 0 || !p.tok_train[tok]) continue;
 #pragma unroll
                     for (int ni = 0; ni < NI16; ++ni) {
@@ -1579,7 +1593,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
 #pragma unroll
                 for (int mh = 0; mh < MH2; ++mh) {
                     uint8_t *erow = area + (mh * 16 + r16) * EP;
-                    if (kq == 0) *reinterpret_cast<int32_t *>(erow + WN * 2) = row_tok[m0 + wm * WM + (LO + mh) * 16 + r16];
+                    if (kq == 0) *reinterpret_cast<int32_t *>(erow + WN * 2) = row_token16(LO + mh);
 #pragma unroll
                     for (int ni = 0; ni < NI16; ++ni) *reinterpret_cast<uint2 *>(erow + (ni * 16 + kq * 4) * 2) = out[mh][ni];
                 }
@@ -1700,7 +1714,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
 #pragma unroll
             for (int mi = 0; mi < MI16; ++mi) {
                 uint8_t *erow = ep + (mi * 16 + r16) * EP;
-                if (kq == 0) *reinterpret_cast<int32_t *>(erow + WN * 2) = row_tok[m0 + wm * WM + mi * 16 + r16];
+                if (kq == 0) *reinterpret_cast<int32_t *>(erow + WN * 2) = row_token16(mi);
 #pragma unroll
                 for (int ni = 0; ni < NI16; ++ni) {
                     uint2 v;
