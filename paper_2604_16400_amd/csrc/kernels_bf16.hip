@@ -309,11 +309,11 @@ struct ExtBatch {
 // on the CU's load path, issuing them late leaves the last ones too little time to land; 3/8 of the
 // loads in phase 0, 1/2 in phase 1 and the rest at the start of phase 2, evenly spaced inside a phase,
 // was the best split.  slot[phase][m] is the load issued behind MFMA m, or -1.
-template <int NM, int PRE, int ND>
+template <int NM, int PRE, int ND, int N0 = ND * 3 / 8, int N1 = ND / 2>
 struct DmaSlots {
     int slot[3][NM];
     int n[3];
-    constexpr DmaSlots() : slot{}, n{ND * 3 / 8, ND / 2, ND - ND * 3 / 8 - ND / 2}
+    constexpr DmaSlots() : slot{}, n{N0, N1, ND - N0 - N1}
     {
         int d = 0;
         for (int ph = 0; ph < 3; ++ph) {
@@ -971,7 +971,9 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
             // direct loads keep their places (phase 3 after the barrier, phases 0 and 1), the fragment reads of the
             // next phase ride behind the MFMAs of this one (see reads16).
             constexpr int PRE = NM16 / 4;
-            constexpr DmaSlots<NM16, PRE, ND> SL{};
+            // (split of the direct loads over the three phases: 3/8, 1/2, 1/8 on the 256x256 tile as in the other form -
+            // 1/4, 1/2, 1/4 and 1/2, 1/2, 0 were 1-3 % slower there; 1/4, 1/2, 1/4 on the smaller tiles, 1 % faster)
+            constexpr DmaSlots<NM16, PRE, ND, (BM * BN == 256 * 256 ? ND * 3 / 8 : ND / 4), ND / 2> SL{};
             constexpr int D3 = SL.n[0];
             static_assert(SL.placed() == ND, "not every direct load has a slot");
             auto pipeline = [&](auto even_c) {
