@@ -18,7 +18,10 @@
 // MFMA operand layout (v_mfma_f32_32x32x16_bf16): lane l supplies 8 consecutive K values
 // (one chunk) of row/column l % 32, K offset 8 * (l / 32); the result register j of lane l
 // is element [8 * (j / 4) + 4 * (l / 32) + j % 4][l % 32].  (16x16x32: row/column l % 16,
-// K offset 8 * (l / 16); result [4 * (l / 16) + j][l % 16].)
+// K offset 8 * (l / 16); result [4 * (l / 16) + j][l % 16].)  The GEMM tiles that the library
+// launches use the 16x16x32 form (template argument M16): with real operand values it costs
+// less power per flop, and the GEMMs are limited by power; the 32x32x16 form remains for the
+// rank-wide tile pass and the tile shapes kept for comparison.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -970,7 +973,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
             // The pipeline below with the 16x16x32 form: a K tile is four phases of NM16 MFMAs of 16 cycles each; the
             // direct loads keep their places (phase 3 after the barrier, phases 0 and 1), the fragment reads of the
             // next phase ride behind the MFMAs of this one (see reads16).
-            constexpr int PRE = NM16 / 4;
+            constexpr int PRE = NM16 / 4;  // (half of the phase before the barrier was 1 % slower on the 128x128 tile, an eighth level on the 256x256 one)
             // (split of the direct loads over the three phases: 3/8, 1/2, 1/8 on the 256x256 tile as in the other form -
             // 1/4, 1/2, 1/4 and 1/2, 1/2, 0 were 1-3 % slower there; 1/4, 1/2, 1/4 on the smaller tiles, 1 % faster)
             constexpr DmaSlots<NM16, PRE, ND, (BM * BN == 256 * 256 ? ND * 3 / 8 : ND / 4), ND / 2> SL{};
