@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 # HBM-side bytes of one forward-GEMM launch of configuration 2 (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by
 # what the same counters read for a plain 1 GiB copy; profiles/gemm_skinny_grad_config2_q_proj.txt).  Set to
 # None whenever gemm_lora_kernel changes until the counters have been taken again.
-ROOFLINE_TRAFFIC_BYTES = 153.8e6
+ROOFLINE_TRAFFIC_BYTES = 153.6e6
 
 
 def _dev_tensors(w, proj_index, torch, exact=False):
