@@ -392,6 +392,29 @@ def test_transposed_weight_and_table_layout(dtype):
         assert errs["y"] < 6e-3 and errs["dx"] < 6e-3
 
 
+@pytest.mark.parametrize("tile", [binding.TILE_256x256, binding.TILE_128x128])
+@pytest.mark.parametrize("dims", [(64, 192), (320, 64), (192, 448), (136, 328)])
+def test_odd_tile_counts_and_unpaired_extension_steps(tile, dims):
+    # The GEMM tiles multiply two 16-wide extension steps per MFMA and walk K in tiles of 64: contractions of 1, 2, 3, 5
+    # and 7 tiles (forward: d_in, backward: d_out), ranks of one, two and three steps (the last pair of a batch
+    # half empty), ranks that are no multiple of 8, adapters that change inside a 16-row block, columns that end
+    # inside a 16-column block; both layouts.  Every element is compared.
+    d_in, d_out = dims
+    lens = [5, 3, 9, 1, 1, 70, 130, 2, 40, 200, 7]
+    ads = [0, 1, 2, 3, 0, 1, 2, -1, 3, 0, 2]
+    trn = [0, 1, 0, 0, 0, 1, 1, 0, 1, 1, 0]
+    w = _adhoc("bf16", d_in, d_out, [16, 40, 8, 20], lens, ads, trn, scale=0.4, seed=11)
+    for transposed in (False, True):
+        t = wl.make_tensors(w)
+        ctx = make_ctx(w)
+        ctx.set_tiles(tile, tile)
+        layer = DeviceLayer(w, t, ctx, transposed=transposed)
+        layer.fwd()
+        layer.bwd()
+        check_full(layer, TOL["bf16"])
+        ctx.close()
+
+
 @pytest.mark.parametrize("tile", [binding.TILE_256x256, binding.TILE_256x128, binding.TILE_128x128,
                                   binding.TILE_256x256_W8])
 def test_every_gemm_tile_shape(tile):
