@@ -286,6 +286,22 @@ int collm_debug_set_gemm_split(collm_ctx *ctx, int n_slices);
 int collm_debug_set_wide_pass(collm_ctx *ctx, int min_rows);
 
 /*
+ * What the HIP runtime reports for GPU `device`: compute units, the highest engine clock and memory clock in
+ * kHz, the width of the memory bus in bits and the size of the L2 cache in bytes.  For reports; touches no context.
+ */
+int collm_device_info(int device, int32_t *compute_units, int32_t *clock_khz, int32_t *memory_clock_khz,
+                      int32_t *memory_bus_bits, int64_t *l2_bytes);
+
+/*
+ * Debug/profiling, HOST only: what the plan of the context's last compute call cost on the host.
+ * *mode = 0: the plan on the device was reused as it is; 1: built anew from the segment table; 2: same
+ * batch, other adapter tables (their addresses replaced in place); 3: only the dA/dB pointer tables were new.
+ * *build_us: host time spent building or patching; *upload_us: host time spent copying it into pinned
+ * staging and enqueueing the copy kernel; *bytes: bytes sent to the device.
+ */
+int collm_debug_plan_stats(const collm_ctx *ctx, float *build_us, float *upload_us, int32_t *bytes, int32_t *mode);
+
+/*
  * Debug/profiling: duration in milliseconds of each pass (one kernel, or the few kernels of
  * a pass) launched by the context's last compute call, from the start of its first kernel to
  * the end of its last by the kernels' own time stamps (HIP events attached to the launches on

@@ -112,6 +112,10 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.collm_debug_set_gemm_split.restype = ctypes.c_int
     lib.collm_debug_set_wide_pass.argtypes = [vp, ctypes.c_int]
     lib.collm_debug_set_wide_pass.restype = ctypes.c_int
+    lib.collm_device_info.argtypes = [ctypes.c_int, _i32p, _i32p, _i32p, _i32p, ctypes.POINTER(ctypes.c_int64)]
+    lib.collm_device_info.restype = ctypes.c_int
+    lib.collm_debug_plan_stats.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float), _i32p, _i32p]
+    lib.collm_debug_plan_stats.restype = ctypes.c_int
     lib.collm_profile_enable.argtypes = [vp, ctypes.c_int]
     lib.collm_profile_enable.restype = ctypes.c_int
     lib.collm_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float),
@@ -187,6 +191,16 @@ def host_row_order(rank, seg_start, seg_adapter, seg_is_train, tile_rows: int = 
     return row_tok[:n], steps[: (n + tile_rows - 1) // tile_rows]
 
 
+def device_info(device: int = 0):
+    """dict(compute_units, clock_mhz, memory_clock_mhz, memory_bus_bits, l2_bytes) of a GPU, as the runtime reports it."""
+    lib = load_library()
+    v = [ctypes.c_int32() for _ in range(4)]
+    l2 = ctypes.c_int64()
+    _check(lib.collm_device_info(device, *[ctypes.byref(x) for x in v], ctypes.byref(l2)), "collm_device_info")
+    return {"compute_units": v[0].value, "clock_mhz": v[1].value / 1e3, "memory_clock_mhz": v[2].value / 1e3,
+            "memory_bus_bits": v[3].value, "l2_bytes": l2.value}
+
+
 class PointerTable:
     """A HOST array of device pointers built once from a list of tensors (entries may be
     None).  Passing the same PointerTable to many calls skips rebuilding the array; the
@@ -242,6 +256,14 @@ class Context:
 
     def set_wide_pass(self, min_rows: int = -1):
         _check(self._lib.collm_debug_set_wide_pass(self._h, min_rows), "collm_debug_set_wide_pass")
+
+    def plan_stats(self):
+        """Host cost of the plan of the last compute call: dict(build_us, upload_us, bytes, mode)."""
+        b, u = ctypes.c_float(), ctypes.c_float()
+        n, m = ctypes.c_int32(), ctypes.c_int32()
+        _check(self._lib.collm_debug_plan_stats(self._h, ctypes.byref(b), ctypes.byref(u), ctypes.byref(n),
+                                                ctypes.byref(m)), "collm_debug_plan_stats")
+        return {"build_us": b.value, "upload_us": u.value, "bytes": n.value, "mode": m.value}
 
     def profile_enable(self, on: bool):
         _check(self._lib.collm_profile_enable(self._h, 1 if on else 0), "collm_profile_enable")

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -91,6 +92,11 @@ struct collm_ctx {
     // the adapter gradients run beside dh and the dX GEMM on a second stream
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_dh = nullptr, ev_join = nullptr;
+
+    // host cost of the plan of the last compute call (collm_debug_plan_stats)
+    float plan_build_us = 0.f, plan_upload_us = 0.f;
+    int plan_mode = 0;       // 0: reused as it is, 1: built anew, 2: table addresses replaced, 3: gradient pointers only
+    int plan_bytes_up = 0;   // bytes the call sent to the device
 
     bool profile = false;
     int n_prof = 0;
@@ -356,6 +362,7 @@ void patch_tables(collm_ctx *c, int N, const void *const *A, const void *const *
 int upload(collm_ctx *c, size_t lo, size_t hi, hipStream_t st)
 {
     if (hi <= lo) return COLLM_OK;
+    const auto t0 = std::chrono::steady_clock::now();
     const int sl = c->slot;
     c->slot = (c->slot + 1) % kSlots;
     if (c->stage_seq[sl] != 0) {
@@ -377,6 +384,8 @@ int upload(collm_ctx *c, size_t lo, size_t hi, hipStream_t st)
     HIP_TRY(launch_plan_copy(c->h_stage_dev[sl], c->d_plan, lo4, hi4 - lo4, c->d_copy_counter, c->h_done_dev, seq, st));
     c->stage_seq[sl] = seq;
     c->last_stream = st;
+    c->plan_upload_us += std::chrono::duration<float, std::micro>(std::chrono::steady_clock::now() - t0).count();
+    c->plan_bytes_up += (int)((hi4 - lo4) * sizeof(int32_t));
     return COLLM_OK;
 }
 
@@ -412,9 +421,17 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
     const bool reuse = allow_reuse && st == c->last_stream && n_sib == c->key_nsib &&
                        same_key(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, bm_all, bm_train, wide);
     bool upload_all = false;
+    c->plan_build_us = c->plan_upload_us = 0.f;
+    c->plan_mode = c->plan_bytes_up = 0;
+    const auto t_plan = std::chrono::steady_clock::now();
+    auto built = [&](int mode) {
+        c->plan_mode = mode;
+        c->plan_build_us = std::chrono::duration<float, std::micro>(std::chrono::steady_clock::now() - t_plan).count();
+    };
     if (reuse && !same_tables(c, s->n_adapters, A, B)) {
         patch_tables(c, s->n_adapters, A, B);
         upload_all = true;
+        built(2);
     }
     if (!reuse) {
         PlanRequest rq;
@@ -437,6 +454,7 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
         int rc = build_plan(rq, c->plan, c->L);
         if (rc != COLLM_OK) return rc;
         if ((size_t)c->L.total_ints > c->plan_cap) return COLLM_E_SHAPE;
+        built(1);
         rc = upload(c, 0, c->L.total_ints, st);
         if (rc != COLLM_OK) return rc;
         // remember what this plan was built from
@@ -472,6 +490,7 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
             int rc = upload(c, 0, c->L.total_ints, st);
             if (rc != COLLM_OK) return rc;
         } else if (changed) {
+            c->plan_mode = 3;
             int rc = upload(c, c->L.off_dA_ptr, (size_t)c->L.off_dB_ptr + 2 * (size_t)std::max(N, 1), st);
             if (rc != COLLM_OK) return rc;
         }
@@ -808,6 +827,30 @@ int collm_debug_set_wide_pass(collm_ctx *c, int min_rows)
     return COLLM_OK;
 }
 
+int collm_device_info(int device, int32_t *compute_units, int32_t *clock_khz, int32_t *memory_clock_khz,
+                      int32_t *memory_bus_bits, int64_t *l2_bytes)
+{
+    if (!compute_units || !clock_khz || !memory_clock_khz || !memory_bus_bits || !l2_bytes) return COLLM_E_NULL;
+    hipDeviceProp_t pr;
+    HIP_TRY(hipGetDeviceProperties(&pr, device));
+    *compute_units = pr.multiProcessorCount;
+    *clock_khz = pr.clockRate;
+    *memory_clock_khz = pr.memoryClockRate;
+    *memory_bus_bits = pr.memoryBusWidth;
+    *l2_bytes = pr.l2CacheSize;
+    return COLLM_OK;
+}
+
+int collm_debug_plan_stats(const collm_ctx *c, float *build_us, float *upload_us, int32_t *bytes, int32_t *mode)
+{
+    if (!c || !build_us || !upload_us || !bytes || !mode) return COLLM_E_NULL;
+    *build_us = c->plan_build_us;
+    *upload_us = c->plan_upload_us;
+    *bytes = c->plan_bytes_up;
+    *mode = c->plan_mode;
+    return COLLM_OK;
+}
+
 int collm_profile_enable(collm_ctx *c, int enable)
 {
     if (!c) return COLLM_E_NULL;
@@ -857,8 +900,11 @@ static int fwd_impl(collm_ctx *c, const collm_shape *s, const collm_siblings *si
     HIP_TRY(hipSetDevice(c->device));
     c->n_prof = 0;
     // (with the SwiGLU epilogue the extension steps run over both siblings' ranks, as in the backward GEMM)
-    rc = prepare_plan(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, nullptr, nullptr, true, st,
-                      P > 1 && !swiglu ? rank1 : nullptr, swiglu ? 16 + P : P);
+    {
+        Prof prof(c, st, "plan_copy");
+        rc = prepare_plan(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, nullptr, nullptr, true, st,
+                          P > 1 && !swiglu ? rank1 : nullptr, swiglu ? 16 + P : P);
+    }
     if (rc != COLLM_OK) return rc;
     const PlanLayout &L = c->L;
     const bool f32 = s->dtype == COLLM_F32;
@@ -958,8 +1004,11 @@ static int bwd_impl(collm_ctx *c, const collm_shape *s, const collm_siblings *si
     hipStream_t st = (hipStream_t)stream;
     HIP_TRY(hipSetDevice(c->device));
     c->n_prof = 0;
-    rc = prepare_plan(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, dA, dB, true, st,
-                      P > 1 ? rank1 : nullptr, P);
+    {
+        Prof prof(c, st, "plan_copy");
+        rc = prepare_plan(c, s, A, B, rank, seg_start, seg_adapter, seg_is_train, dA, dB, true, st,
+                          P > 1 ? rank1 : nullptr, P);
+    }
     if (rc != COLLM_OK) return rc;
     // siblings: widest single rank, padded, for the passes that take one sibling at a time
     int rpad1 = c->L.rpad;

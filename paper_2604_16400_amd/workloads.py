@@ -2,7 +2,7 @@
 
 This module only *draws inputs*: segment tables, adapter ranks and random tensors.  It holds
 none of the layer's arithmetic and is the one module that both the GPU tests/benchmark and
-the CPU oracle's tests may share.  numpy only.
+the CPU oracle's tests may share.  numpy only (to_device, the upload helper, also uses torch).
 
 The paper evaluates on ShareGPT / Alpaca request lengths replayed on Azure-Code and
 Azure-Conv arrival traces (section 8.1) with LLaMA-3.1-8B and LLaMA-2-13B replicas.  None
@@ -40,6 +40,17 @@ def bf16_widen(bits: np.ndarray) -> np.ndarray:
 def bf16_round(a: np.ndarray) -> np.ndarray:
     """fp32 array -> fp32 array holding bf16-representable values."""
     return bf16_widen(bf16_bits(a))
+
+
+def to_device(a: np.ndarray, dtype: str):
+    """Host array -> tensor on the current GPU in the element type of a workload ("bf16": the
+    array's values rounded to nearest even, which is exact for the tensors make_tensors draws)."""
+    import torch
+
+    if dtype == "bf16":
+        bits = bf16_bits(a).view(np.int16)
+        return torch.from_numpy(bits).view(torch.bfloat16).reshape(a.shape).cuda()
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
 
 
 # --------------------------------------------------------------------------------------

@@ -10,13 +10,7 @@ from paper_2604_16400_amd import workloads as wl
 TOL = {"bf16": 1e-2, "f32": 1e-5}  # max|got - ref| / max|ref| per output tensor
 
 
-def to_dev(a: np.ndarray, dtype: str):
-    import torch
-
-    if dtype == "bf16":
-        bits = wl.bf16_bits(a).view(np.int16)
-        return torch.from_numpy(bits).view(torch.bfloat16).reshape(a.shape).cuda()
-    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+to_dev = wl.to_device
 
 
 def to_host(t) -> np.ndarray:

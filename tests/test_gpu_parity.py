@@ -47,10 +47,11 @@ def test_config2_bf16_every_element():
     assert errs["y"] < 6e-3 and errs["dx"] < 6e-3
 
 
-def _sampled_projection(cfg, proj_index, n_rows=192, n_cols=768):
+def _sampled_projection(cfg, proj_index, max_rows=None):
     """Full-size run in the launch configuration the benchmark times.  The two W-sized
-    contractions are checked on sampled rows x sampled columns (the oracle computes each of
-    those outputs from its definition); h, dA and dB are checked on every element."""
+    contractions are checked on the row sample (first, last and two interior tokens of every
+    segment plus every token of the shortest training segment), all columns: the oracle computes
+    exactly those rows from its definition.  h, dA and dB are checked on every element."""
     import torch
 
     w = wl.make_config(cfg)
@@ -63,33 +64,27 @@ def _sampled_projection(cfg, proj_index, n_rows=192, n_cols=768):
     torch.cuda.synchronize()
     tol = TOL[w.dtype]
     ta, tt = layer.tok_adapter, layer.tok_train
-    rng = np.random.default_rng(cfg * 100 + proj_index)
-    rows_all = wl.sample_rows(w, seed=proj_index)
-    tr_rows = rows_all[tt[rows_all] != 0]
-    inf_rows = rows_all[tt[rows_all] == 0]
-    pick = lambda r, n: r if len(r) <= n else np.sort(rng.choice(r, size=n, replace=False))
-    rows = np.concatenate([pick(inf_rows, n_rows // 2), pick(tr_rows, n_rows // 2)])
+    rows = wl.sample_rows(w, seed=proj_index)
+    if max_rows is not None and len(rows) > max_rows:
+        # cap the rows, never the columns: keep every segment's first token, thin out the rest evenly
+        firsts = np.intersect1d(rows, w.seg_start[:-1])
+        rest = np.setdiff1d(rows, firsts)
+        keep = max(0, max_rows - len(firsts))
+        rest = rest[np.linspace(0, len(rest) - 1, keep).astype(np.int64)] if keep else rest[:0]
+        rows = np.union1d(firsts, rest)
 
-    def cols_of(d):
-        blocks = [np.arange(0, 64), np.arange(d - 64, d)]
-        starts = rng.integers(0, d // 8 - 8, size=(n_cols - 128) // 64) * 8
-        blocks += [np.arange(s, s + 64) for s in starts]
-        return np.unique(np.concatenate(blocks))
-
-    # forward: y[rows, cols]
-    cj = cols_of(p.d_out)
-    y_ref, _ = oracle.lora_linear_fwd(t.x[rows], t.W[:, cj], t.A, [b[:, cj] for b in t.B], ta[rows], w.scale)
+    # forward: y[rows, :]
+    y_ref, h_rows = oracle.lora_linear_fwd(t.x[rows], t.W, t.A, t.B, ta[rows], w.scale)
     y = to_host(layer.y)
     assert np.all(np.isfinite(y))
-    e_y = maxrel(y[np.ix_(rows, cj)], y_ref)
-    # backward: dx[train rows, cols] needs all of dy's columns but only rows ci of W and A
+    e_y = maxrel(y[rows], y_ref)
+    # backward: dx[training rows of the sample, :]
     trs = rows[tt[rows] != 0]
-    ci = cols_of(p.d_in)
-    dx_ref, _, _ = oracle.lora_linear_bwd(t.x[np.ix_(trs, ci)], t.W[ci], [a[ci] for a in t.A], t.B, ta[trs],
-                                          np.ones(len(trs), np.uint8), w.scale, t.dy[trs], want_dab=False)
+    dx_ref, _, _ = oracle.lora_linear_bwd(t.x[trs], t.W, t.A, t.B, ta[trs], np.ones(len(trs), np.uint8), w.scale,
+                                          t.dy[trs], want_dab=False)
     dx = to_host(layer.dx)
     assert np.all(np.isnan(dx[tt == 0])) and np.all(np.isfinite(dx[tt != 0]))
-    e_dx = maxrel(dx[np.ix_(trs, ci)], dx_ref)
+    e_dx = maxrel(dx[trs], dx_ref)
     # low-rank terms in full
     _, dA_ref, dB_ref = oracle.lora_linear_bwd(t.x, None, t.A, t.B, ta, tt, w.scale, t.dy, want_dx=False)
     errs = {"y": e_y, "dx": e_dx}
@@ -103,16 +98,23 @@ def _sampled_projection(cfg, proj_index, n_rows=192, n_cols=768):
     hs = to_host(layer.h_save)
     tr = tt != 0
     assert np.all(np.isnan(hs[~tr]))
-    h_ref = np.zeros((int(tr.sum()), hs.shape[1]))
-    for k, tok in enumerate(np.flatnonzero(tr)):
-        a = ta[tok]
-        h_ref[k, : w.ranks[a]] = np.asarray(t.x[tok], dtype=np.float64) @ np.asarray(t.A[a], dtype=np.float64)
+    # h of every training token, from the oracle's forward pass on those rows against a weight of one column
+    # (h does not depend on W)
+    tr_tok = np.flatnonzero(tr)
+    _, h_tr = oracle.lora_linear_fwd(t.x[tr_tok], t.W[:, :1], t.A, [b[:, :1] for b in t.B], ta[tr_tok], w.scale)
+    h_ref = np.zeros((len(tr_tok), hs.shape[1]))
+    for k, tok in enumerate(tr_tok):
+        h_ref[k, : w.ranks[ta[tok]]] = h_tr[k, : w.ranks[ta[tok]]]
     errs["h"] = maxrel(hs[tr], h_ref)
+    for tok in tr_tok[:: max(1, len(tr_tok) // 256)]:
+        assert np.all(hs[tok, w.ranks[ta[tok]]:] == 0.0)
     ts, ta_d, tt_d = ctx.device_token_map(w.n_tokens)
     rs, ra, rt = oracle.token_map(w.seg_start, w.seg_adapter, w.seg_is_train)
     assert np.array_equal(ts, rs) and np.array_equal(ta_d, ra) and np.array_equal(tt_d, rt)
     ctx.close()
-    print(f"config {cfg} {p.name}: rows {len(rows)} cols {len(cj)}/{len(ci)} errors", errs)
+    print(f"config {cfg} {p.name}: {len(rows)} rows ({len(trs)} training) x all {p.d_out}/{p.d_in} columns, errors",
+          {k: float("%.3g" % v) for k, v in errs.items() if k in ("y", "dx", "h")},
+          "max dA/dB", max([v for k, v in errs.items() if k[0] == "d" and k != "dx"], default=0.0))
     bad = {k: v for k, v in errs.items() if not v <= tol}
     assert not bad, bad
     return errs

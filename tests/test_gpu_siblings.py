@@ -252,10 +252,11 @@ def test_swiglu_backward_kernel_and_chain():
     assert np.all(np.isnan(dyh[~tr])) and np.all(np.isfinite(dyh[tr]))
     ref = oracle.swiglu_bwd(preh[tr], dout_h[tr])
     assert maxrel(dyh[tr], ref) <= TOL["bf16"]
-    # chain: the sibling backward on that dy against the oracle's backward on the oracle's own dy
-    y_pre_ref, _ = oracle.lora_siblings_fwd(c.x, c.W, c.A, c.B, c.d_outs, c.tok_adapter, c.scale)
+    # chain: the sibling backward on that dy.  Every link is compared at the stated tolerance with the oracle fed
+    # the values the link before it really produced (the rounded pre-activations above, the rounded dy here), so
+    # that no link's rounding is charged to the next one.
     dy_ref = np.zeros((T, 2 * d_ff))
-    dy_ref[tr] = oracle.swiglu_bwd(y_pre_ref[tr], dout_h[tr])
+    dy_ref[tr] = dyh[tr]
     dx_ref, dA_ref, dB_ref = oracle.lora_siblings_bwd(c.x, c.W, c.A, c.B, c.d_outs, c.tok_adapter, c.tok_train, c.scale, dy_ref)
     ctx = binding.Context(T, len(c.seg_adapter), len(c.ranks), 128, 1024)
     x, W = to_dev(c.x, "bf16"), to_dev(c.W, "bf16")
@@ -272,8 +273,7 @@ def test_swiglu_backward_kernel_and_chain():
             errs[f"dA{a}"] = maxrel(to_host(dA[a]), dA_ref[a])
             errs[f"dB{a}"] = maxrel(to_host(dB[a]), dB_ref[a])
     ctx.close()
-    # two bf16 roundings (pre-activations, dy) lie between the oracle's chain and this one
-    bad = {k: v for k, v in errs.items() if not v <= 2e-2}
+    bad = {k: v for k, v in errs.items() if not v <= TOL["bf16"]}
     assert not bad, f"beyond tolerance: {bad} (all: {errs})"
 
 
