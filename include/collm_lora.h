@@ -262,9 +262,9 @@ int collm_debug_host_row_order(const collm_shape *shape, const int32_t *rank, co
 
 /*
  * Debug/tuning: force the tile shape of the forward GEMM and of the dX GEMM
- * (0: 256x256, 1: 256x128, 2: 128x128 rows x columns of the output, 3: 256x256 run by eight
- * waves instead of four; -1: let the library
- * choose from the problem size).  Affects only speed, never results beyond rounding order.
+ * (0: 256x256, 2: 128x128 rows x columns of the output; -1: let the library choose from the
+ * problem size; anything else: COLLM_E_SHAPE).  Affects only speed, never results beyond
+ * rounding order.
  */
 int collm_debug_set_tiles(collm_ctx *ctx, int fwd_tile, int bwd_tile);
 

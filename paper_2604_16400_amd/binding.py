@@ -21,7 +21,7 @@ COLLM_BF16 = 1
 ACT_NONE, ACT_SWIGLU = 0, 1
 LAYOUT_IN_OUT, LAYOUT_OUT_IN = 0, 1  # W [d_in, d_out] (paper, row vectors) / W [d_out, d_in] (module weights)
 
-TILE_AUTO, TILE_256x256, TILE_256x128, TILE_128x128, TILE_256x256_W8 = -1, 0, 1, 2, 3
+TILE_AUTO, TILE_256x256, TILE_128x128 = -1, 0, 2
 
 
 class CollmError(RuntimeError):

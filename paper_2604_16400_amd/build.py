@@ -16,7 +16,7 @@ HEADERS = ["plan.h", "planner.h", "kernels.h"]
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-mcode-object-version=5",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-function",
+    "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 

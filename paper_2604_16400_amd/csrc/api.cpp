@@ -805,7 +805,8 @@ int collm_debug_host_row_order(const collm_shape *s, const int32_t *rank, const 
 int collm_debug_set_tiles(collm_ctx *c, int fwd_tile, int bwd_tile)
 {
     if (!c) return COLLM_E_NULL;
-    if (fwd_tile < -1 || fwd_tile >= kNumTiles || bwd_tile < -1 || bwd_tile >= kNumTiles) return COLLM_E_SHAPE;
+    auto ok = [](int t) { return t == -1 || t == kTile256x256 || t == kTile128x128; };
+    if (!ok(fwd_tile) || !ok(bwd_tile)) return COLLM_E_SHAPE;
     c->tile_fwd = fwd_tile;
     c->tile_bwd = bwd_tile;
     return COLLM_OK;
@@ -951,8 +952,7 @@ static int fwd_impl(collm_ctx *c, const collm_shape *s, const collm_siblings *si
         if (f32) {
             HIP_TRY(launch_gemm_f32(g, tr, st));
         } else {
-            const int forced = swiglu && c->tile_fwd != kTile256x256 && c->tile_fwd != kTile128x128 ? -1 : c->tile_fwd;
-            HIP_TRY(run_gemm(c, g, L.all, s->n_tokens, s->d_out, forced, tr, st, swiglu));
+            HIP_TRY(run_gemm(c, g, L.all, s->n_tokens, s->d_out, c->tile_fwd, tr, st, swiglu));
         }
     }
     return COLLM_OK;

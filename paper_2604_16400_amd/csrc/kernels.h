@@ -28,7 +28,7 @@ extern thread_local LaunchEvents g_launch_events;
         }                                                                                                         \
     } while (0)
 
-enum { kTile256x256 = 0, kTile256x128 = 1, kTile128x128 = 2, kTile256x256w8 = 3, kNumTiles = 4 };
+enum { kTile256x256 = 0, kTile128x128 = 2 };  // GEMM tile shapes (rows x columns of the output)
 
 // out[tok(m)][n] = sum_k a[tok(m)][k] * b(k, n)  +  sum over the row tile's extension steps
 struct GemmArgs {

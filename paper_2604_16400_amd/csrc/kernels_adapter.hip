@@ -133,10 +133,11 @@ int grid_for(int64_t work_items)
 // one block row = one training row, 8 columns per lane
 __global__ void __launch_bounds__(256) swiglu_bwd_kernel(SwigluBwdArgs p)
 {
+    // rows on grid.x (no 65535 limit there), 2048-column slabs on grid.y
     int k = 0;
-    while (k + 1 < p.n_seg && (int)blockIdx.y >= p.row0[k + 1]) ++k;
-    const int64_t tok = p.tok0[k] + ((int)blockIdx.y - p.row0[k]);
-    const int j = (blockIdx.x * 256 + threadIdx.x) * 8;
+    while (k + 1 < p.n_seg && (int)blockIdx.x >= p.row0[k + 1]) ++k;
+    const int64_t tok = p.tok0[k] + ((int)blockIdx.x - p.row0[k]);
+    const int j = (blockIdx.y * 256 + threadIdx.x) * 8;
     if (j >= p.d_ff) return;
     const uint16_t *pre = reinterpret_cast<const uint16_t *>(p.pre) + tok * p.ld_pre;
     const uint4 gv = *reinterpret_cast<const uint4 *>(pre + j);
@@ -170,7 +171,7 @@ hipError_t launch_swiglu_bwd(const SwigluBwdArgs &a, hipStream_t st)
 {
     const int rows = a.row0[a.n_seg];
     if (rows <= 0 || a.d_ff <= 0) return hipSuccess;
-    COLLM_LAUNCH(swiglu_bwd_kernel, dim3((a.d_ff / 8 + 255) / 256, rows), dim3(256), 0, st, a);
+    COLLM_LAUNCH(swiglu_bwd_kernel, dim3(rows, (a.d_ff / 8 + 255) / 256), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 

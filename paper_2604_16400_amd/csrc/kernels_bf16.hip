@@ -18,10 +18,9 @@
 // MFMA operand layout (v_mfma_f32_32x32x16_bf16): lane l supplies 8 consecutive K values
 // (one chunk) of row/column l % 32, K offset 8 * (l / 32); the result register j of lane l
 // is element [8 * (j / 4) + 4 * (l / 32) + j % 4][l % 32].  (16x16x32: row/column l % 16,
-// K offset 8 * (l / 16); result [4 * (l / 16) + j][l % 16].)  The GEMM tiles that the library
-// launches use the 16x16x32 form (template argument M16): with real operand values it costs
-// less power per flop, and the GEMMs are limited by power; the 32x32x16 form remains for the
-// rank-wide tile pass and the tile shapes kept for comparison.
+// K offset 8 * (l / 16); result [4 * (l / 16) + j][l % 16].)  The GEMM tiles use the 16x16x32
+// form: with real operand values it costs less power per flop, and the GEMMs are limited by
+// power; the 32x32x16 form remains for the rank-wide tile pass (PARTIAL), which is bound by memory.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -68,107 +67,6 @@ __device__ __forceinline__ bf16x4 lds_tr(const uint8_t *p)
 
 __device__ __forceinline__ uint4 ldg16(const void *p) { return *reinterpret_cast<const uint4 *>(p); }
 
-// 8x8 transpose of 16-bit values held as 8 rows of 4 dwords: out[n] holds the 8 values of
-// column n (row index ascending).
-__device__ __forceinline__ void transpose8x8(const uint4 (&in)[8], uint4 (&out)[8])
-{
-    const uint32_t *v = reinterpret_cast<const uint32_t *>(in);
-    uint32_t *o = reinterpret_cast<uint32_t *>(out);
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {      // dword p holds columns 2p, 2p+1
-#pragma unroll
-        for (int kp = 0; kp < 4; ++kp) {  // row pair 2kp, 2kp+1
-            const uint32_t a = v[(2 * kp) * 4 + p], b = v[(2 * kp + 1) * 4 + p];
-            o[(2 * p) * 4 + kp] = (a & 0xffffu) | (b << 16);
-            o[(2 * p + 1) * 4 + kp] = (a >> 16) | (b & 0xffff0000u);
-        }
-    }
-}
-
-// -----------------------------------------------------------------------------------------
-// Tile movers.  "K-major" sources have the contraction index contiguous (rows of x, dy and,
-// for the backward GEMM, rows of W): 16-byte chunks are copied as they are.  "N-major"
-// sources ([K][N] matrices: W, B_a in the forward; dy, x in the gradient kernel) are read
-// as 8x8 blocks, transposed in registers and written as chunks.
-// -----------------------------------------------------------------------------------------
-template <int ROWS, int NT>
-struct KMajorMover {
-    static constexpr int CH = (ROWS * 8 + NT - 1) / NT;
-    uint4 reg[CH];
-
-    // row_ptr(r) returns the address of element [r][0] of the source or nullptr
-    template <class RowPtr>
-    __device__ __forceinline__ void load(int tid, int k0, int K, RowPtr row_ptr)
-    {
-#pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const int idx = tid + i * NT;
-            const int r = idx >> 3, c = idx & 7;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (ROWS * 8 % NT == 0 || idx < ROWS * 8) {
-                const uint16_t *p = row_ptr(r);
-                const int k = k0 + c * 8;
-                if (p != nullptr && k < K) v = ldg16(p + k);
-            }
-            reg[i] = v;
-        }
-    }
-    __device__ __forceinline__ void store(int tid, uint8_t *tile) const
-    {
-#pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const int idx = tid + i * NT;
-            const int r = idx >> 3, c = idx & 7;
-            if (ROWS * 8 % NT == 0 || idx < ROWS * 8)
-                *reinterpret_cast<uint4 *>(tile + tile_off(r, c)) = reg[i];
-        }
-    }
-};
-
-template <int COLS, int NT>
-struct NMajorMover {
-    static constexpr int NG = COLS / 8;                 // 8-column groups
-    static constexpr int UN = (COLS + NT - 1) / NT;     // 8x8 units per thread (8 k-groups)
-    uint4 reg[UN][8];
-
-    // k_row_ptr(k) returns the address of source row k (tile-relative k in 0..63) at the
-    // tile's first column, or nullptr; cols_left = number of valid columns from there.
-    template <class KRowPtr>
-    __device__ __forceinline__ void load(int tid, int cols_left, KRowPtr k_row_ptr)
-    {
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int idx = tid + u * NT;
-            const int ng = idx % NG, kg = idx / NG;
-            const bool on = (COLS % NT == 0 || idx < COLS) && (ng * 8 < cols_left);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (on) {
-                    const uint16_t *p = k_row_ptr(kg * 8 + j);
-                    if (p != nullptr) v = ldg16(p + ng * 8);
-                }
-                reg[u][j] = v;
-            }
-        }
-    }
-    __device__ __forceinline__ void store(int tid, uint8_t *tile) const
-    {
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int idx = tid + u * NT;
-            const int ng = idx % NG, kg = idx / NG;
-            if (COLS % NT == 0 || idx < COLS) {
-                uint4 t[8];
-                transpose8x8(reg[u], t);
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    *reinterpret_cast<uint4 *>(tile + tile_off(ng * 8 + j, kg)) = t[j];
-            }
-        }
-    }
-};
-
 // XCD-aware tile order: consecutive workgroup ids go round-robin to the 8 XCDs, each with
 // its own L2.  Give every XCD one contiguous run of the logical tile order, and make that
 // order walk groups of GM row tiles column by column so that concurrently running tiles of
@@ -192,11 +90,8 @@ __device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, i
 // gemm_lora
 //
 // Block tile BM x BN, K step 64, WGM x WGN waves of (BM/WGM) x (BN/WGN) each.  Software
-// pipeline, two LDS stages:
-//   * the registers `areg`/`breg` always hold a tile in flight: the part of tile kc+1 that is
-//     written to LDS during MFMA step s of tile kc is re-loaded at once with tile kc+2, so a
-//     global load has a whole K step (64 MFMAs per wave) to arrive;
-//   * operand fragments of MFMA step s+1 are read from LDS while step s multiplies.
+// pipeline, two LDS stages filled by direct global -> LDS loads; operand fragments of the next
+// MFMA phase are read from LDS while this one multiplies.
 // Global loads are buffer loads: rows that do not exist (padding rows, columns beyond N,
 // K tail) get an offset beyond the buffer and read as zero, so the loop has no branches.
 // =========================================================================================
@@ -212,47 +107,6 @@ __device__ __forceinline__ uint4 buf16(__amdgpu_buffer_rsrc_t r, uint32_t off)
     const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
     return make_uint4(v.x, v.y, v.z, v.w);
 }
-
-// 4 rows x 8 columns of 16-bit values (4 x uint4) -> for each column the 4 row values (uint2)
-__device__ __forceinline__ void transpose4x8(const uint4 (&in)[4], uint2 (&out)[8])
-{
-    const uint32_t *v = reinterpret_cast<const uint32_t *>(in);
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const uint32_t r0 = v[0 * 4 + p], r1 = v[1 * 4 + p], r2 = v[2 * 4 + p], r3 = v[3 * 4 + p];
-        out[2 * p].x = (r0 & 0xffffu) | (r1 << 16);
-        out[2 * p].y = (r2 & 0xffffu) | (r3 << 16);
-        out[2 * p + 1].x = (r0 >> 16) | (r1 & 0xffff0000u);
-        out[2 * p + 1].y = (r2 >> 16) | (r3 & 0xffff0000u);
-    }
-}
-
-// Explicit instruction interleave for one MFMA step: each MFMA is followed by its share of the
-// step's other work (LDS reads, then LDS writes, then global loads), so that a wave that owns
-// its SIMD alone keeps the matrix pipe fed while it moves data.
-template <int MASK> __device__ __forceinline__ void sched_group1() { __builtin_amdgcn_sched_group_barrier(MASK, 1, 0); }
-template <int J, int HI, int NR, int NW> struct SchedOthers {
-    static __device__ __forceinline__ void run()
-    {
-        if constexpr (J < HI) {
-            if constexpr (J < NR) sched_group1<0x100>();            // LDS read
-            else if constexpr (J < NR + NW) sched_group1<0x200>();  // LDS write
-            else sched_group1<0x020>();                             // global load
-            SchedOthers<J + 1, HI, NR, NW>::run();
-        }
-    }
-};
-template <int I, int NM, int NR, int NW, int NL> struct SchedStep {
-    static __device__ __forceinline__ void run()
-    {
-        if constexpr (I < NM) {
-            sched_group1<0x008>();  // MFMA
-            constexpr int others = NR + NW + NL;
-            SchedOthers<others * I / NM, others * (I + 1) / NM, NR, NW>::run();
-            SchedStep<I + 1, NM, NR, NW, NL>::run();
-        }
-    }
-};
 
 // Direct global -> LDS load of 16 bytes per lane (buffer_load_dwordx4 ... lds): the 64 lanes
 // of a wave fill 1 KiB of LDS starting at the wave-uniform address `lds_base`, lane l at
@@ -273,17 +127,17 @@ __device__ __forceinline__ i32x4 make_rsrc_words(const void *base, uint32_t byte
 }
 __device__ __forceinline__ void dma16(i32x4 rsrc, uint32_t voff, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_base), "v"(voff), "s"(rsrc));
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_base), "v"(voff), "s"(rsrc) : "m0", "memory");
 }
 // the same with a wave-uniform byte offset added to every lane's address (not part of the range check)
 __device__ __forceinline__ void dma16s(i32x4 rsrc, uint32_t voff, uint32_t soff, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff));
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff) : "m0", "memory");
 }
 // the same from a 64-bit address per lane (no range check)
 __device__ __forceinline__ void dma16g(uint64_t addr, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(addr));
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(addr) : "m0", "memory");
 }
 // One v_mfma_f32_16x16x32_bf16, accumulator in place.  Written out because the compiler's register allocation of
 // the builtin breaks down with 64 four-register accumulators per lane (it copies them between the two register
@@ -363,13 +217,14 @@ struct DmaSlots {
 // (fewer, cheaper fragment reads) the four stages do.
 constexpr int kWideStages = 4;
 constexpr int wide_stages(bool t_kmajor) { return t_kmajor ? kWideStages : 2; }
-template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR, bool PINGPONG, bool PARTIAL = false, bool SWIGLU = false,
-          bool SPLITK = false, bool SIBS = false, bool M16 = false>
-__global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ? 2 : 1) gemm_lora_kernel(GemmArgs p)
+template <int BM, int BN, int WGM, int WGN, bool B_KMAJOR, bool PARTIAL = false, bool SWIGLU = false, bool SPLITK = false,
+          bool SIBS = false>
+__global__ void __launch_bounds__(WGM *WGN * 64, (!PARTIAL && BM * BN == 128 * 128) ? 2 : 1) gemm_lora_kernel(GemmArgs p)
 {
-    static_assert(!M16 || (!PINGPONG && !PARTIAL), "16x16x32 form: not the rank-wide pass");
-    static_assert(!SWIGLU || (!B_KMAJOR && !PINGPONG && !PARTIAL && WGN == 2), "SwiGLU epilogue: N-major, two wave columns");
-    static_assert(!SPLITK || (!PARTIAL && !SWIGLU && !PINGPONG), "K slices: plain tiles only");
+    // the GEMM tiles run the 16x16x32 MFMA form, the rank-wide pass the 32x32x16 one
+    constexpr bool M16 = !PARTIAL;
+    static_assert(!SWIGLU || (!B_KMAJOR && !PARTIAL && WGN == 2), "SwiGLU epilogue: N-major, two wave columns");
+    static_assert(!SPLITK || (!PARTIAL && !SWIGLU), "K slices: plain tiles only");
     constexpr int NT = WGM * WGN * 64;
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int MI = WM / 32, NI = WN / 32;
@@ -381,11 +236,11 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
     constexpr int BTILE = B_KMAJOR ? BN * 128 : 64 * BPITCH;
     constexpr int ATILE = BM * 128;
     constexpr int STAGE = ATILE + BTILE;
-    // LDS map.  Ping-pong pipeline: [A0 B0 A1 B1].  Direct-load pipeline: [A0 A1 B0 B1], so that the
-    // fragment reads of both stages lie within the immediate-offset range of one per-lane base.
-    constexpr int A_ST1 = PINGPONG ? STAGE : ATILE;
-    constexpr int B_ST0 = PINGPONG ? ATILE : 2 * ATILE;
-    constexpr int B_ST1 = PINGPONG ? STAGE + ATILE : 2 * ATILE + BTILE;
+    // LDS map [A0 A1 B0 B1], so that the fragment reads of both stages lie within the immediate-offset range of
+    // one per-lane base.
+    constexpr int A_ST1 = ATILE;
+    constexpr int B_ST0 = 2 * ATILE;
+    constexpr int B_ST1 = 2 * ATILE + BTILE;
     constexpr int ACH = BM * 8 / NT;   // 16-byte chunks of the row tile per thread
     constexpr int BCH = BN * 8 / NT;   // chunks of the second operand's tile per thread
     constexpr int NG = BN / 8;         // chunks per N-major row
@@ -458,8 +313,6 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
             if (j + 1 < p.n_sib && n0 >= p.sib_col[j]) sib = j + 1;
     }
 
-    const __amdgpu_buffer_rsrc_t ra = make_rsrc(a_base, a_bytes);
-    const __amdgpu_buffer_rsrc_t rb = make_rsrc(b_base, b_bytes);
 
     // The block's first loads form chains (row order -> rows of the first operand; step offsets -> step records),
     // and nothing else runs on the CU meanwhile (256x256) or little (128x128): the chains are started side by
@@ -577,47 +430,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
         }
     };
 
-    uint4 areg[PINGPONG ? ACH : 1];
-    uint4 breg[PINGPONG ? BCH : 1];
-
-    // register path (ping-pong pipeline): loads part `part` of `parts` of tile kc
-    auto load_a = [&](int k0, int part, int parts) {
-        if constexpr (PINGPONG) {
-#pragma unroll
-            for (int i = 0; i < ACH; ++i)
-                if (i * parts / ACH == part) areg[i] = buf16(ra, a_src(i, k0, false));
-        }
-    };
-    auto store_a = [&](int stage, int part, int parts) {
-        if constexpr (PINGPONG) {
-            uint8_t *ta = smem + (stage ? A_ST1 : 0);
-#pragma unroll
-            for (int i = 0; i < ACH; ++i)
-                if (i * parts / ACH == part)
-                    *reinterpret_cast<uint4 *>(ta + (r8 + i * (NT / 8)) * 128 + c8 * 16) = areg[i];
-        }
-    };
-    auto load_b = [&](int k0, int kc, int part, int parts) {
-        if constexpr (PINGPONG) {
-#pragma unroll
-            for (int i = 0; i < NB; ++i)
-                if (i * parts / NB == part) breg[i] = buf16(rb, b_src(i, k0, kc, false));
-        }
-    };
-    auto store_b = [&](int stage, int part, int parts) {
-        if constexpr (PINGPONG) {
-            uint8_t *tb = smem + (stage ? B_ST1 : B_ST0);
-#pragma unroll
-            for (int i = 0; i < NB; ++i)
-                if (i * parts / NB == part) {
-                    if constexpr (B_KMAJOR)
-                        *reinterpret_cast<uint4 *>(tb + (r8 + i * (NT / 8)) * 128 + c8 * 16) = breg[i];
-                    else
-                        *reinterpret_cast<uint4 *>(tb + (bk0 + i * (NT / NG)) * BPITCH + bng * 16) = breg[i];
-                }
-        }
-    };
-    // direct-to-LDS path: chunk idx (row chunks first, then the second operand's) of the tile that starts
+    // chunk idx (row chunks first, then the second operand's) of the tile that starts
     // at K index 64 kc goes to `stage`; the wave's 64 lanes fill the KiB (i NT/64 + wave) of the tile
     const i32x4 ra_w = make_rsrc_words(a_base, a_bytes), rb_w = make_rsrc_words(b_base, b_bytes);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)smem;
@@ -741,47 +554,32 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
         }
     };
 
-    // Whether the first batch is loaded from inside the main loop (see k_tile): the hand-scheduled loop with at
-    // least two tiles, and every piece of the batch one direct load (tables with K contiguous: ranks in eights).
-    // Not for 256x256 tiles: their main loop leaves no registers for the address arithmetic of these loads.
-    constexpr bool CAN_PRE = !PINGPONG && !PARTIAL && !SIBS && !M16 && BM * BN < 256 * 256;
-    // The 256x256 tiles instead use what the main loop's two stages leave of the LDS (32 KiB of 160): the rows' area of
-    // the extension lies behind them and is loaded before the main loop starts.
-    constexpr bool ROWS_EARLY = !PINGPONG && !PARTIAL && !SIBS && !CAN_PRE && BM * BN == 256 * 256;
+    // The 256x256 tiles use what the main loop's two stages leave of the LDS (32 KiB of 160): the rows' area of the
+    // extension lies behind them and is loaded before the main loop starts.
+    constexpr bool ROWS_EARLY = !PARTIAL && !SIBS && BM * BN == 256 * 256;
     constexpr uint32_t XA_EARLY = 2 * STAGE;
-    // Where the load of the step records is waited for.  The hand-scheduled pipeline does it behind the direct
-    // loads of its first tile (the records' chain of two loads is longer than the one that leads to those loads,
-    // and nothing needs the records before the main loop's last tiles); the other pipelines here.
-    constexpr bool REC_LATE = !PINGPONG && !PARTIAL;
+    // The load of the step records is waited for behind the direct loads of the first tile (the records' chain of
+    // two loads is longer than the one that leads to those loads, and nothing needs the records before the main
+    // loop's last tiles).
     auto records_are_in = [&] { asm volatile("" : "+v"(rec.x), "+v"(rec.y), "+v"(rec.z), "+v"(rec.w)); };
-    if constexpr (!PARTIAL && !REC_LATE) records_are_in();
     if constexpr (ROWS_EARLY) {
         if (e1 > e0) {
 #pragma unroll
             for (int d = 0; d < ACH; ++d) issue_piece(XA_EARLY, 0u, ExtBatch{}, d, true, 0);
         }
     }
-    bool pre = false;
-    auto decide_pre = [&] {
-        if constexpr (CAN_PRE) {
-            uint32_t kr_or = 0;  // lanes beyond the tile's steps hold zeros
+    // rank-wide pass: acc[ni][mi] holds the transposed 32x32 block: lane = row m, registers = columns n
+    floatx16 acc[PARTIAL ? NI : 1][PARTIAL ? MI : 1];
+    if constexpr (PARTIAL) {
 #pragma unroll
-            for (int j = 0; j < kExtBatch; ++j) kr_or |= (uint32_t)__builtin_amdgcn_readlane((int)rec.x, j);
-            pre = e1 > e0 && nk >= 2 && (!B_KMAJOR || ((kr_or >> 16) & 7u) == 0);
-        }
-    };
-    if constexpr (!REC_LATE) decide_pre();
-    // acc[ni][mi] holds the transposed 32x32 block: lane = row m, registers = columns n
-    floatx16 acc[NI][MI];
+        for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
+            for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) acc[ni][mi][j] = 0.f;
-
+                for (int j = 0; j < 16; ++j) acc[ni][mi][j] = 0.f;
+    }
     const int rl = lane & 31, kh = lane >> 5;
-    bf16x8 af[2][MI], bf[2][NI];
+    bf16x8 af[2][PARTIAL ? MI : 1], bf[2][PARTIAL ? NI : 1];
     // 16x16x32 form: lane l supplies row (or column) l % 16 and K values 8 (l / 16) .. of a 32-wide K step; acc4[ni][mi]
     // holds the transposed 16x16 block: lane = row l % 16, registers = columns 4 (l / 16) .. + 3.  The row blocks of a
     // wave go in two halves of MH (a4, double-buffered by half); the second operand's fragments (b8) are single:
@@ -859,58 +657,6 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
             btr[ni] = krow * BPITCH + ((((col >> 3) ^ ((i16 >> 2) << 2))) << 4) + (col & 7) * 2;
         }
     }
-    auto read_frags = [&](int stage, int ks, int buf) {
-        const uint8_t *ta = smem + (stage ? A_ST1 : 0);
-        const uint8_t *tb = smem + (stage ? B_ST1 : B_ST0);
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) af[buf][mi] = lds_frag(ta, wm * WM + mi * 32 + rl, ks * 2 + kh);
-        if constexpr (B_KMAJOR) {
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni) bf[buf][ni] = lds_frag(tb, wn * WN + ni * 32 + rl, ks * 2 + kh);
-        } else {
-            // transposing reads: 16 lanes fetch a 4 (K) x 16 (N) block, lane i of them reads 4
-            // values of row i / 4 and receives the 4 K values of column i
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
-                const uint8_t *src = tb + btr[ni] + ks * 16 * BPITCH;
-                const bf16x4 lo = lds_tr(src);
-                const bf16x4 hi = lds_tr(src + 4 * BPITCH);
-                bf[buf][ni] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            }
-        }
-    };
-    auto mma = [&](int buf) {
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-                acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[buf][ni], af[buf][mi], acc[ni][mi], 0, 0, 0);
-    };
-
-    // j-th fragment read of a K step (the order in which the MFMAs of the step need them):
-    // second operand block 0, the row blocks, then the remaining blocks of the second operand
-    auto read_one = [&](int stage, int ks, int buf, int j) {
-        const uint8_t *ta = smem + (stage ? A_ST1 : 0);
-        const uint8_t *tb = smem + (stage ? B_ST1 : B_ST0);
-        if (j >= 1 && j <= MI) {
-            af[buf][j - 1] = lds_frag(ta, wm * WM + (j - 1) * 32 + rl, ks * 2 + kh);
-        } else {
-            const int ni = j == 0 ? 0 : j - MI;
-            if constexpr (B_KMAJOR) {
-                bf[buf][ni] = lds_frag(tb, wn * WN + ni * 32 + rl, ks * 2 + kh);
-            } else {
-                const uint8_t *src = tb + btr[ni] + ks * 16 * BPITCH;
-                const bf16x4 lo = lds_tr(src);
-                const bf16x4 hi = lds_tr(src + 4 * BPITCH);
-                bf[buf][ni] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            }
-        }
-    };
-    auto mma_one = [&](int buf, int m) {
-        const int ni = m / MI, mi = m % MI;
-        acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[buf][ni], af[buf][mi], acc[ni][mi], 0, 0, 0);
-    };
-
     // ---- main K loop ----------------------------------------------------------------------
     if constexpr (PARTIAL) {
         // Rank-wide pass: bound by memory, not by the matrix pipe, so what counts is bytes in flight.  kWideStages LDS
@@ -969,10 +715,17 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
         }
         wait_dma();  // loads of tiles beyond the last one (they fetch nothing)
     } else if (nk > 0) {
-        if constexpr (M16) {
-            // The pipeline below with the 16x16x32 form: a K tile is four phases of NM16 MFMAs of 16 cycles each; the
-            // direct loads keep their places (phase 3 after the barrier, phases 0 and 1), the fragment reads of the
-            // next phase ride behind the MFMAs of this one (see reads16).
+        {
+            // One wave per SIMD (256x256) or two (128x128); tiles travel global -> LDS without touching registers.
+            // A K tile is four phases of NM16 MFMAs of 16 cycles each.  Everything else a wave has to issue rides
+            // behind single MFMAs, one instruction at a time, so that the matrix pipe never waits for the issue of a
+            // load: the fragment reads of the next phase (see reads16) and the ND direct loads of the next tile,
+            // spread over three phases (the MFMAs of phase 3 that follow the barrier, then phases 0 and 1, see
+            // DmaSlots): issuing one takes a wave about as long as half an MFMA, and the CU accepts 1 KiB only
+            // every 16-20 cycles; phases 2 and 3 give the last of them time to land.
+            // One barrier per tile sits inside phase 3, after its first MFMAs: before it every wave has received
+            // its own loads of tile kc+1 and all its fragments of tile kc, so after it the stage of tile kc may be
+            // overwritten (tile kc+2) and tile kc+1 may be read.
             constexpr int PRE = NM16 / 4;  // (half of the phase before the barrier was 1 % slower on the 128x128 tile, an eighth level on the 256x256 one)
             // (split of the direct loads over the three phases: 3/8, 1/2, 1/8 on the 256x256 tile as in the other form -
             // 1/4, 1/2, 1/4 and 1/2, 1/2, 0 were 1-3 % slower there; 1/4, 1/2, 1/4 on the smaller tiles, 1 % faster)
@@ -987,25 +740,21 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
             rb_t = tile_rsrc(rb_w, 1);
 #pragma unroll
             for (int d = 0; d < D3; ++d) dma_chunk(even_c, d, 1, 1, ra_t, rb_t);
-            records_are_in();
-            decide_pre();
-            wait_dma_but<D3>();
+            records_are_in();  // (the compiler waits for all loads it knows of, which lets the direct loads land too)
+            wait_dma_but<D3>();  // loads complete in order: tile 0 is in
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int j = 0; j < MH + NI16; ++j) read16(0, 0, j);
-            auto k_tile = [&](auto cur_c, auto tail_c, int kc, const ExtBatch &b0) {
-                constexpr int cur = decltype(cur_c)::value, nxt = cur ^ 1, tail = decltype(tail_c)::value;
+            auto k_tile = [&](auto cur_c, int kc) {
+                constexpr int cur = decltype(cur_c)::value, nxt = cur ^ 1;
 #pragma unroll
                 for (int ph = 0; ph < 3; ++ph) {
 #pragma unroll
                     for (int m = 0; m < NM16; ++m) {
                         mma16(ph, m);
                         reads16(cur, ph + 1, m, 0);
-                        if (ph < 2 && SL.slot[ph + 1][m] >= 0) {
-                            if constexpr (tail == 1) issue_piece(nxt ? A_ST1 : 0, nxt ? B_ST1 : B_ST0, b0, SL.slot[ph + 1][m], true, 0);
-                            else dma_chunk(even_c, SL.slot[ph + 1][m], nxt, kc + 1, ra_t, rb_t);
-                        }
+                        if (ph < 2 && SL.slot[ph + 1][m] >= 0) dma_chunk(even_c, SL.slot[ph + 1][m], nxt, kc + 1, ra_t, rb_t);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
@@ -1024,199 +773,38 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
                 for (int m = PRE; m < NM16; ++m) {
                     mma16(3, m);
                     reads16(nxt, 0, m, PRE);
-                    if (SL.slot[0][m] >= 0) {
-                        if constexpr (tail == 2) issue_piece(cur ? A_ST1 : 0, cur ? B_ST1 : B_ST0, b0, SL.slot[0][m], true, 0);
-                        else if constexpr (tail == 0) dma_chunk(even_c, SL.slot[0][m], cur, kc + 2, ra_t, rb_t);
-                    }
+                    if (SL.slot[0][m] >= 0) dma_chunk(even_c, SL.slot[0][m], cur, kc + 2, ra_t, rb_t);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             };
             using I0 = std::integral_constant<int, 0>;
             using I1 = std::integral_constant<int, 1>;
-            using I2 = std::integral_constant<int, 2>;
-            const int n_loop = pre ? nk - 2 : nk;
-            const ExtBatch no_batch{};
             // Where paths meet the compiler may copy accumulators from one register to another, and it does not
             // know that the statements before are MFMAs whose results take time to land: every path that ends in
             // MFMAs and leads to such a place ends in mfma16_settle (the loop's own back edge needs no copies).
             int kc = 0;
-            for (; kc + 1 < n_loop; kc += 2) {
-                k_tile(I0{}, I0{}, kc, no_batch);
-                k_tile(I1{}, I0{}, kc + 1, no_batch);
+            for (; kc + 1 < nk; kc += 2) {
+                k_tile(I0{}, kc);
+                k_tile(I1{}, kc + 1);
             }
             mfma16_settle();
-            if (kc < n_loop) {
-                k_tile(I0{}, I0{}, kc++, no_batch);
+            if (kc < nk) {
+                k_tile(I0{}, kc++);
                 mfma16_settle();
-            }
-            if constexpr (CAN_PRE) {
-                if (pre) {
-                    const ExtBatch b0 = get_batch(e0);
-                    if (kc & 1) {
-                        k_tile(I1{}, I2{}, kc, b0);
-                        k_tile(I0{}, I1{}, kc + 1, b0);
-                        mfma16_settle();
-                    } else {
-                        k_tile(I0{}, I2{}, kc, b0);
-                        k_tile(I1{}, I1{}, kc + 1, b0);
-                        mfma16_settle();
-                    }
-                }
-            }
-            wait_dma();
-            };
-            if (k_even) pipeline(std::true_type{});
-            else pipeline(std::false_type{});
-        } else if constexpr (!PINGPONG) {
-            // One wave per SIMD; tiles travel global -> LDS without touching registers.  A K tile is
-            // four MFMA steps.  Everything else a wave has to issue rides behind single MFMAs, one
-            // instruction at a time, so that the matrix pipe never waits for the issue of a load:
-            //   * the fragment reads of step s+1 follow the first MFMAs of step s;
-            //   * the ND direct loads of the next tile are spread over three steps (the last MFMAs of
-            //     step 3 of the tile before, then steps 0 and 1, see DmaSlots): issuing one takes a wave
-            //     about as long as half an MFMA, and the CU accepts 1 KiB only every 16-20 cycles;
-            //     steps 2 and 3 give the last of them time to land.
-            // One barrier per tile sits inside step 3, after its first MFMAs: before it every wave has
-            // received its own loads of tile kc+1 and all its fragments of tile kc, so after it the
-            // stage of tile kc may be overwritten (tile kc+2) and tile kc+1 may be read.
-            constexpr int NM = MI * NI;        // MFMAs per step
-            constexpr int NRD = MI + NI;       // fragment reads per step
-            constexpr int PRE = NM / 4;        // MFMAs of step 3 issued before the barrier
-            constexpr DmaSlots<NM, PRE, ND> SL{};
-            constexpr int D3 = SL.n[0];  // loads of a tile issued before its steps 0 and 1
-            static_assert(SL.placed() == ND, "not every direct load has a slot");
-            constexpr int RPS = (NRD + NM - 1) / NM;                  // reads per MFMA, steps 0..2
-            constexpr int RPS3 = (NRD + (NM - PRE) - 1) / (NM - PRE);  // reads per MFMA, tail of step 3
-
-            auto pipeline = [&](auto even_c) {
-            i32x4 ra_t = tile_rsrc(ra_w, 0), rb_t = tile_rsrc(rb_w, 0);
-#pragma unroll
-            for (int d = 0; d < ND; ++d) dma_chunk(even_c, d, 0, 0, ra_t, rb_t);
-            ra_t = tile_rsrc(ra_w, 1);
-            rb_t = tile_rsrc(rb_w, 1);
-#pragma unroll
-            for (int d = 0; d < D3; ++d) dma_chunk(even_c, d, 1, 1, ra_t, rb_t);
-            records_are_in();  // (the compiler waits for all loads it knows of, which lets the direct loads land too)
-            decide_pre();
-            wait_dma_but<D3>();  // loads complete in order: tile 0 is in
-            __builtin_amdgcn_s_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int j = 0; j < NRD; ++j) read_one(0, 0, 0, j);
-
-            // tail_c: 0 = a tile of the loop proper.  With `pre`, the first batch of the extension takes the place of the
-            // tile after the last one: the second-last tile (2) issues its first loads where it would issue those of
-            // that tile, the last tile (1) the others, and its latency hides behind the last tile's MFMAs.
-            auto k_tile = [&](auto cur_c, auto tail_c, int kc, const ExtBatch &b0) {
-                constexpr int cur = decltype(cur_c)::value, nxt = cur ^ 1, tail = decltype(tail_c)::value;
-                // steps 0..2: MFMAs of step s, fragment reads of step s+1, direct loads of tile kc+1
-#pragma unroll
-                for (int st = 0; st < 3; ++st) {
-#pragma unroll
-                    for (int m = 0; m < NM; ++m) {
-                        mma_one(st & 1, m);
-#pragma unroll
-                        for (int j = m * RPS; j < (m + 1) * RPS; ++j)
-                            if (j < NRD) read_one(cur, st + 1, (st + 1) & 1, j);
-                        if (st < 2 && SL.slot[st + 1][m] >= 0) {
-                            if constexpr (tail == 1) issue_piece(nxt ? A_ST1 : 0, nxt ? B_ST1 : B_ST0, b0, SL.slot[st + 1][m], true, 0);
-                            else dma_chunk(even_c, SL.slot[st + 1][m], nxt, kc + 1, ra_t, rb_t);
-                        }
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                }
-                // step 3
-#pragma unroll
-                for (int m = 0; m < PRE; ++m) mma_one(1, m);
-                __builtin_amdgcn_sched_barrier(0);
-                drain_and_barrier();
-                __builtin_amdgcn_sched_barrier(0);
-                ra_t = tile_rsrc(ra_w, kc + 2);
-                rb_t = tile_rsrc(rb_w, kc + 2);
-#pragma unroll
-                for (int m = PRE; m < NM; ++m) {
-                    mma_one(1, m);
-#pragma unroll
-                    for (int j = (m - PRE) * RPS3; j < (m - PRE + 1) * RPS3; ++j)
-                        if (j < NRD) read_one(nxt, 0, 0, j);
-                    if (SL.slot[0][m] >= 0) {
-                        if constexpr (tail == 2) issue_piece(cur ? A_ST1 : 0, cur ? B_ST1 : B_ST0, b0, SL.slot[0][m], true, 0);
-                        else if constexpr (tail == 0) dma_chunk(even_c, SL.slot[0][m], cur, kc + 2, ra_t, rb_t);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            };
-            using I0 = std::integral_constant<int, 0>;
-            using I1 = std::integral_constant<int, 1>;
-            using I2 = std::integral_constant<int, 2>;
-            const int n_loop = pre ? nk - 2 : nk;  // tiles of the loop proper
-            const ExtBatch no_batch{};
-            int kc = 0;
-            for (; kc + 1 < n_loop; kc += 2) {
-                k_tile(I0{}, I0{}, kc, no_batch);
-                k_tile(I1{}, I0{}, kc + 1, no_batch);
-            }
-            if (kc < n_loop) k_tile(I0{}, I0{}, kc++, no_batch);
-            if constexpr (CAN_PRE) {
-                if (pre) {
-                    const ExtBatch b0 = get_batch(e0);
-                    if (kc & 1) {
-                        k_tile(I1{}, I2{}, kc, b0);
-                        k_tile(I0{}, I1{}, kc + 1, b0);
-                    } else {
-                        k_tile(I0{}, I2{}, kc, b0);
-                        k_tile(I1{}, I1{}, kc + 1, b0);
-                    }
-                }
             }
             wait_dma();  // loads of tiles beyond the last one fetch nothing but still signal completion
             };
             if (k_even) pipeline(std::true_type{});
             else pipeline(std::false_type{});
-        } else {
-            // Two waves per SIMD in opposite phases: while one half of the waves multiplies out
-            // of registers, the other half reads its fragments of the next half K step and moves
-            // its share of the next tile; block barriers separate the phases, and the second
-            // half of the waves runs one phase behind the first.
-            load_a(0, 0, 1);
-            load_b(0, 0, 0, 1);
-            store_a(0, 0, 1);
-            store_b(0, 0, 1);
-            load_a(64, 0, 1);  // tile 1 stays in flight in the registers
-            load_b(64, 1, 0, 1);
-            __syncthreads();
-            const bool late = wave >= (WGM * WGN / 2);
-            if (late) __syncthreads();
-            for (int kc = 0; kc < nk; ++kc) {
-                const int cur = kc & 1, nxt = cur ^ 1;
-                const int k2 = (kc + 2) << 6;
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    read_frags(cur, 2 * h, 0);
-                    read_frags(cur, 2 * h + 1, 1);
-                    store_a(nxt, h, 2);
-                    store_b(nxt, h, 2);
-                    load_a(k2, h, 2);
-                    load_b(k2, kc + 2, h, 2);
-                    __builtin_amdgcn_sched_barrier(0);
-                    __syncthreads();
-                    __builtin_amdgcn_sched_barrier(0);
-                    mma(0);
-                    mma(1);
-                    __builtin_amdgcn_sched_barrier(0);
-                    __syncthreads();
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-            if (!late) __syncthreads();
         }
         __syncthreads();
     }
 
+
     // The epilogue needs the token of every row this lane stores: a load whose latency would stand at its start.
     // The 128x128 tiles issue it here, so that it lands while the extension runs (headline step -0.7 %); the 256x256
     // tiles have no registers to hold the tokens meanwhile (with them: spills, forward GEMM +2 %).
-    constexpr bool TOK_EARLY = M16 && !SPLITK && BM * BN < 256 * 256;
+    constexpr bool TOK_EARLY = !PARTIAL && !SPLITK && BM * BN < 256 * 256;
     int etok[TOK_EARLY ? MI16 : 1];
     if constexpr (TOK_EARLY) {
 #pragma unroll
@@ -1240,31 +828,17 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
             for (int d = 0; d < ND; ++d) issue_piece(stage ? A_ST1 : 0, stage ? B_ST1 : B_ST0, bt, d, false, 0);
         };
 
-        // A step touches only the rows of its adapter: a wave multiplies only those of its 32-row blocks that
+        // A step touches only the rows of its adapter: a wave multiplies only those of its 16-row blocks that
         // the step's row range reaches (the others would add zeros).  `rows` = lo | hi << 16, uniform.
         const int wrow0 = __builtin_amdgcn_readfirstlane(wm * WM);
-        auto block_on = [&](uint32_t rows, int mi) {
-            const int lo = (int)(rows & 0xffffu), hi = (int)(rows >> 16);
-            return lo < wrow0 + mi * 32 + 32 && hi > wrow0 + mi * 32;
-        };
-        auto mma_rows = [&](int buf, uint32_t rows) {
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi) {
-                if (block_on(rows, mi)) {
-#pragma unroll
-                    for (int ni = 0; ni < NI; ++ni)
-                        acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[buf][ni], af[buf][mi], acc[ni][mi], 0, 0, 0);
-                }
-            }
-        };
         ExtBatch cur_b = get_batch(e0);
-        if (!pre) issue_batch(0, cur_b);
+        issue_batch(0, cur_b);
         ExtBatch nxt_b = get_batch(e0 + kExtBatch);
-        int stage = pre ? (nk & 1) : 0;  // with `pre` the batch lies where the tile after the last would
+        int stage = 0;
         for (int eb = e0; eb < e1; eb += kExtBatch, stage ^= 1) {
             drain_and_barrier();  // this batch has landed; the stage of the batch before it is free
             const int nsteps = (e1 - eb) < kExtBatch ? (e1 - eb) : kExtBatch;
-            if constexpr (M16) {
+            {
                 // 16x16x32 form: two steps per MFMA (K values 0-15 one step, 16-31 the next).  The rows' operand of the
                 // batch holds zeros outside each step's row range already, so the fragments are used as they are; a
                 // wave multiplies the 16-row blocks that either step reaches.
@@ -1302,36 +876,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
                 }
                 cur_b = nxt_b;
                 nxt_b = get_batch(eb + 2 * kExtBatch);
-                continue;
             }
-            read_frags(stage, 0, 0);
-            if (nsteps > 1) read_frags(stage, 1, 1);
-            {
-                // step 0, with the loads of the next batch (addresses and all) riding behind its MFMAs
-                const bool more = eb + kExtBatch < e1;
-#pragma unroll
-                for (int mi = 0; mi < MI; ++mi) {
-                    if (block_on(cur_b.rows[0], mi)) {
-#pragma unroll
-                        for (int ni = 0; ni < NI; ++ni)
-                            acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[0][ni], af[0][mi], acc[ni][mi], 0, 0, 0);
-                    }
-                    if (more) {
-#pragma unroll
-                        for (int d = mi * ND / MI; d < (mi + 1) * ND / MI; ++d)
-                            issue_piece(stage ? 0 : A_ST1, stage ? B_ST0 : B_ST1, nxt_b, d, false, 0);
-                    }
-                }
-            }
-#pragma unroll
-            for (int ks = 1; ks < kExtBatch; ++ks) {
-                if (ks < nsteps) {
-                    if (ks + 1 < nsteps) read_frags(stage, ks + 1, (ks + 1) & 1);
-                    mma_rows(ks & 1, cur_b.rows[ks]);
-                }
-            }
-            cur_b = nxt_b;
-            nxt_b = get_batch(eb + 2 * kExtBatch);
         }
         drain_and_barrier();  // every wave has its last fragments: LDS is free for the epilogue
     } else if (!SIBS && !PARTIAL && e1 > e0) {
@@ -1342,14 +887,9 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
         // reads its fragments at its own rank offset and clears the rows outside its row range in registers.
         // Only the tables stream: three areas, the loads of two batches in flight while one multiplies.
         static_assert(ATILE >= BTILE, "a table area must fit the place of a row area");
-        const int par = pre ? (nk & 1) : 0;  // with `pre` the first batch lies where the tile after the last would
-        const uint32_t xa = ROWS_EARLY ? XA_EARLY : (par ? A_ST1 : 0);
-        uint32_t t_cur = par ? B_ST1 : B_ST0, t_nxt = par ? B_ST0 : B_ST1, t_far = par ? 0 : A_ST1;
+        const uint32_t xa = ROWS_EARLY ? XA_EARLY : 0;
+        uint32_t t_cur = B_ST0, t_nxt = B_ST1, t_far = A_ST1;
         const int wrow0 = __builtin_amdgcn_readfirstlane(wm * WM);
-        auto block_on = [&](uint32_t rows, int mi) {
-            const int lo = (int)(rows & 0xffffu), hi = (int)(rows >> 16);
-            return lo < wrow0 + mi * 32 + 32 && hi > wrow0 + mi * 32;
-        };
         auto issue_rows = [&](int g) {
 #pragma unroll
             for (int d = 0; d < ACH; ++d) issue_piece(xa, 0u, ExtBatch{}, d, true, g);
@@ -1360,56 +900,13 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
             for (int d = ACH; d < ND; ++d) issue_piece(0u, base, bt, d, false, 0);
             return !B_KMAJOR || (((bt.kr[0] | bt.kr[1] | bt.kr[2] | bt.kr[3]) >> 16) & 7u) == 0;
         };
-        // fragments of step j of the batch in the table area `base`: rank offset koff, rows [lo, hi)
-        auto read_step = [&](uint32_t base, int j, uint32_t kr, uint32_t rows, int buf) {
-            const int c0 = (int)((kr & 63u) >> 3) + kh;
-            const int lo = (int)(rows & 0xffffu), hi = (int)(rows >> 16);
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi) {
-                if (block_on(rows, mi)) {
-                    const int row = wm * WM + mi * 32 + rl;
-                    uint4 v = __builtin_bit_cast(uint4, lds_frag(smem + xa, row, c0));
-                    const bool in = row >= lo && row < hi;
-                    v.x = in ? v.x : 0u;
-                    v.y = in ? v.y : 0u;
-                    v.z = in ? v.z : 0u;
-                    v.w = in ? v.w : 0u;
-                    af[buf][mi] = __builtin_bit_cast(bf16x8, v);
-                }
-            }
-            const uint8_t *tb = smem + base;
-            if constexpr (B_KMAJOR) {
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni) bf[buf][ni] = lds_frag(tb, wn * WN + ni * 32 + rl, j * 2 + kh);
-            } else {
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni) {
-                    const uint8_t *src = tb + btr[ni] + j * 16 * BPITCH;
-                    const bf16x4 lo4 = lds_tr(src);
-                    const bf16x4 hi4 = lds_tr(src + 4 * BPITCH);
-                    bf[buf][ni] = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-                }
-            }
-        };
-        auto mma_rows = [&](int buf, uint32_t rows) {
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi) {
-                if (block_on(rows, mi)) {
-#pragma unroll
-                    for (int ni = 0; ni < NI; ++ni)
-                        acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[buf][ni], af[buf][mi], acc[ni][mi], 0, 0, 0);
-                }
-            }
-        };
         auto lds_done_and_barrier = [] { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
 
         ExtBatch cur_b = get_batch(e0);
         ExtBatch nxt_b = get_batch(e0 + kExtBatch);
-        int g_cur = (pre || ROWS_EARLY) ? 0 : (int)((cur_b.kr[0] & 0xffffu) >> 6);  // (what was loaded earlier: 0)
-        if (!pre) {
-            if (!ROWS_EARLY) issue_rows(g_cur);
-            issue_tab(t_cur, cur_b);
-        }
+        int g_cur = ROWS_EARLY ? 0 : (int)((cur_b.kr[0] & 0xffffu) >> 6);  // (what was loaded earlier: 0)
+        if (!ROWS_EARLY) issue_rows(g_cur);
+        issue_tab(t_cur, cur_b);
         bool nxt_direct = true;
         if (e0 + kExtBatch < e1) nxt_direct = issue_tab(t_nxt, nxt_b);
         for (int eb = e0; eb < e1; eb += kExtBatch) {
@@ -1433,8 +930,8 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
                     g_cur = g;
                 }
             }
-            if constexpr (M16) {
-                // 16x16x32 form: two steps per MFMA.  K values 0-15 of lane groups 0 and 1 belong to step 2 q, 16-31 of
+            {
+                // Two steps per MFMA.  K values 0-15 of lane groups 0 and 1 belong to step 2 q, 16-31 of
                 // groups 2 and 3 to step 2 q + 1: each lane takes the rank offset and the row range of its own step (a
                 // step that does not exist has an empty row range, and its part of the table area holds zeros).
 #pragma unroll
@@ -1475,15 +972,6 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
                         }
                     }
                 }
-            } else {
-            read_step(t_cur, 0, cur_b.kr[0], cur_b.rows[0], 0);
-#pragma unroll
-            for (int j = 0; j < kExtBatch; ++j) {
-                if (j < nsteps) {
-                    if (j + 1 < nsteps) read_step(t_cur, j + 1, cur_b.kr[(j + 1) & 3], cur_b.rows[(j + 1) & 3], (j + 1) & 1);
-                    mma_rows(j & 1, cur_b.rows[j]);
-                }
-            }
             }
             const uint32_t t = t_cur;
             t_cur = t_nxt;
@@ -1508,7 +996,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
         if constexpr (SPLITK) rows_in = p.row_base + p.n_rows - m0;  // rows of the order beyond the last are padding
         float *__restrict__ part =
             p.part + ((int64_t)(SPLITK ? blockIdx.y : blockIdx.z) * p.part_rows + m0 - (SPLITK ? p.row_base : 0)) * p.part_ld;
-        if constexpr (M16) {
+        if constexpr (SPLITK) {
             mfma16_settle();
 #pragma unroll
             for (int mi = 0; mi < MI16; ++mi) {
@@ -1521,7 +1009,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
             }
         }
 #pragma unroll
-        for (int mi = 0; mi < (M16 ? 0 : MI); ++mi) {
+        for (int mi = 0; mi < (PARTIAL ? MI : 0); ++mi) {
             const int r = wm * WM + mi * 32 + rl;
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
@@ -1538,9 +1026,13 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
         constexpr int EP = WN * 2 + 16;          // bytes per staged row
         constexpr int LPR = WN / 8, RPI = 64 / LPR;  // lanes per row, rows per store instruction
         uint8_t *ep = smem + wave * (WM * EP);
-        if constexpr (SWIGLU && M16) {
-            // The same exchange in the 16x16x32 accumulator layout (lane = row l % 16 of a 16x16 block, registers =
-            // columns 4 (l / 16) ..): the two waves of a pair hold gate and up of the same outputs lane for lane.
+        if constexpr (SWIGLU) {
+            // Each wave of a pair finishes half of the pair's rows: the gate wave the first half (it receives their
+            // up values), the up wave the second half (it receives their gate values).  Accumulator layout: lane =
+            // row l % 16 of a 16x16 block, registers = columns 4 (l / 16) ..: the two waves of a pair hold gate and
+            // up of the same outputs lane for lane.  Area of the pair: [gate values of the second half | up values
+            // of the first].  silu(g) u = g u / (1 + exp(-g)); the rounded rows are staged in the area just read and
+            // stored as whole lines.
             mfma16_settle();
             if (p.pre_act) {
                 uint16_t *__restrict__ Pre = reinterpret_cast<uint16_t *>(p.pre_act);
@@ -1618,103 +1110,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
             else finish(std::integral_constant<int, MH2>{}, std::false_type{}, xg);
             return;
         }
-        if constexpr (SWIGLU) {
-            // pre-activations of training rows, as they are (8 bytes per lane: few rows need them)
-            if (p.pre_act) {
-                uint16_t *__restrict__ Pre = reinterpret_cast<uint16_t *>(p.pre_act);
-#pragma unroll
-                for (int mi = 0; mi < MI; ++mi) {
-                    const int tok = row_tok[m0 + wm * WM + mi * 32 + rl];
-                    if (tok < 0 || !p.tok_train[tok]) continue;
-#pragma unroll
-                    for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            const int c = ni * 32 + g * 8 + kh * 4;
-                            if (n0 + c >= N) continue;
-                            uint2 v;
-                            v.x = pack_bf16(acc[ni][mi][g * 4 + 0], acc[ni][mi][g * 4 + 1]);
-                            v.y = pack_bf16(acc[ni][mi][g * 4 + 2], acc[ni][mi][g * 4 + 3]);
-                            *reinterpret_cast<uint2 *>(Pre + (int64_t)tok * p.pre_ld + (wn ? p.act_col : 0) + n0 + c) = v;
-                        }
-                }
-            }
-            // Each wave of a pair finishes half of the pair's rows: the gate wave the first half (it receives
-            // their up values), the up wave the second half (it receives their gate values), lane for lane as
-            // the sender holds them.  Area of the pair: [gate values of the second half | up values of the first].
-            static_assert(MI % 2 == 0, "the rows of a wave pair are split in two");
-            constexpr int MH = MI / 2;
-            floatx4 *xg = reinterpret_cast<floatx4 *>(smem + wm * (WM * WN * 4));
-            floatx4 *xu = xg + MH * NI * 4 * 64;
-            auto send = [&](auto lo_c, floatx4 *dst) {
-                constexpr int LO = decltype(lo_c)::value;
-#pragma unroll
-                for (int mh = 0; mh < MH; ++mh)
-#pragma unroll
-                    for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                        for (int g = 0; g < 4; ++g)
-                            dst[((mh * NI + ni) * 4 + g) * 64 + lane] =
-                                floatx4{acc[ni][LO + mh][g * 4 + 0], acc[ni][LO + mh][g * 4 + 1], acc[ni][LO + mh][g * 4 + 2],
-                                        acc[ni][LO + mh][g * 4 + 3]};
-            };
-            if (wn == 0) send(std::integral_constant<int, MH>{}, xg);
-            else send(std::integral_constant<int, 0>{}, xu);
-            __syncthreads();
-            // silu(g) u = g u / (1 + exp(-g)); stage the rounded rows in the area just read; store whole lines
-            auto finish = [&](auto lo_c, auto gate_c, const floatx4 *src) {
-                constexpr int LO = decltype(lo_c)::value;
-                constexpr bool OWN_GATE = decltype(gate_c)::value;
-#pragma unroll
-                for (int mh = 0; mh < MH; ++mh) {
-#pragma unroll
-                    for (int ni = 0; ni < NI; ++ni) {
-#pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            const floatx4 o = src[((mh * NI + ni) * 4 + g) * 64 + lane];
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const float own = acc[ni][LO + mh][g * 4 + e];
-                                const float gt = OWN_GATE ? own : o[e], up = OWN_GATE ? o[e] : own;
-                                acc[ni][LO + mh][g * 4 + e] = gt * up * __builtin_amdgcn_rcpf(1.f + __expf(-gt));
-                            }
-                        }
-                        __builtin_amdgcn_sched_barrier(0);  // one block of 16 at a time: few registers in flight
-                    }
-                }
-                __builtin_amdgcn_wave_barrier();
-                uint8_t *area = reinterpret_cast<uint8_t *>(const_cast<floatx4 *>(src));
-#pragma unroll
-                for (int mh = 0; mh < MH; ++mh) {
-                    uint8_t *erow = area + (mh * 32 + rl) * EP;
-                    if (kh == 0) *reinterpret_cast<int32_t *>(erow + WN * 2) = row_tok[m0 + wm * WM + (LO + mh) * 32 + rl];
-#pragma unroll
-                    for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            uint2 v;
-                            v.x = pack_bf16(acc[ni][LO + mh][g * 4 + 0], acc[ni][LO + mh][g * 4 + 1]);
-                            v.y = pack_bf16(acc[ni][LO + mh][g * 4 + 2], acc[ni][LO + mh][g * 4 + 3]);
-                            *reinterpret_cast<uint2 *>(erow + (ni * 32 + g * 8 + kh * 4) * 2) = v;
-                        }
-                }
-                __builtin_amdgcn_wave_barrier();
-                uint16_t *__restrict__ Out = reinterpret_cast<uint16_t *>(p.out);
-                const int rr = lane / LPR, cc = lane % LPR;
-                const int n = n0 + cc * 8;
-#pragma unroll 4
-                for (int it = 0; it < (WM / 2) / RPI; ++it) {
-                    const uint8_t *erow = area + (it * RPI + rr) * EP;
-                    const uint4 v = *reinterpret_cast<const uint4 *>(erow + cc * 16);
-                    const int tok = *reinterpret_cast<const int32_t *>(erow + WN * 2);
-                    if (tok >= 0 && n < N) *reinterpret_cast<uint4 *>(Out + (int64_t)tok * p.ldo + n) = v;
-                }
-            };
-            if (wn == 0) finish(std::integral_constant<int, 0>{}, std::true_type{}, xu);
-            else finish(std::integral_constant<int, MH>{}, std::false_type{}, xg);
-            return;
-        }
-        if constexpr (M16) {
+        {
             mfma16_settle();
 #pragma unroll
             for (int mi = 0; mi < MI16; ++mi) {
@@ -1726,21 +1122,6 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (M16 && BM * BN == 128 * 128) ?
                     v.x = pack_bf16(acc4[ni][mi][0], acc4[ni][mi][1]);
                     v.y = pack_bf16(acc4[ni][mi][2], acc4[ni][mi][3]);
                     *reinterpret_cast<uint2 *>(erow + (ni * 16 + kq * 4) * 2) = v;
-                }
-            }
-        }
-#pragma unroll
-        for (int mi = 0; mi < (M16 ? 0 : MI); ++mi) {
-            uint8_t *erow = ep + (mi * 32 + rl) * EP;
-            if (kh == 0) *reinterpret_cast<int32_t *>(erow + WN * 2) = row_tok[m0 + wm * WM + mi * 32 + rl];
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    uint2 v;
-                    v.x = pack_bf16(acc[ni][mi][g * 4 + 0], acc[ni][mi][g * 4 + 1]);
-                    v.y = pack_bf16(acc[ni][mi][g * 4 + 2], acc[ni][mi][g * 4 + 3]);
-                    *reinterpret_cast<uint2 *>(erow + (ni * 32 + g * 8 + kh * 4) * 2) = v;
                 }
             }
         }
@@ -2281,16 +1662,17 @@ __global__ void __launch_bounds__(GradCfg<RP>::KW * 64) grad_kernel(GradArgs p)
 // =========================================================================================
 // launchers
 // =========================================================================================
-template <int BM, int BN, int WGM, int WGN, bool KM, bool PP, bool SWIGLU = false, bool SIBS = false, bool M16 = false>
+template <int BM, int BN, bool KM, bool SWIGLU = false, bool SIBS = false>
 static hipError_t launch_gemm_t(const GemmArgs &a, hipStream_t st)
 {
-    constexpr int NT = WGM * WGN * 64;
-    // two stages; the 256x256 tiles of the direct-load pipeline keep the rows' area of the extension behind them
-    constexpr int stage_bytes = 2 * (BM + BN) * 128 + ((!PP && !SIBS && BM * BN == 256 * 256) ? BM * 128 : 0);
-    constexpr int epi_bytes = BM * BN * 2 + BM * WGN * 16;  // per wave (BM/WGM) rows of (BN/WGN) * 2 + 16 bytes
+    // four waves, 2 x 2
+    constexpr int NT = 256;
+    // two stages; the 256x256 tiles keep the rows' area of the extension behind them
+    constexpr int stage_bytes = 2 * (BM + BN) * 128 + ((!SIBS && BM * BN == 256 * 256) ? BM * 128 : 0);
+    constexpr int epi_bytes = BM * BN * 2 + BM * 2 * 16;  // per wave (BM/2) rows of (BN/2) * 2 + 16 bytes
     constexpr int smem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
     static_assert(!SWIGLU || smem >= BM * (BN / 2) * 4, "the up halves of all rows pass through LDS as fp32");
-    auto kern = gemm_lora_kernel<BM, BN, WGM, WGN, KM, PP, false, SWIGLU, false, SIBS, M16>;
+    auto kern = gemm_lora_kernel<BM, BN, 2, 2, KM, false, SWIGLU, false, SIBS>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -2312,28 +1694,18 @@ hipError_t launch_gemm(const GemmArgs &a, int tile_cfg, bool b_kmajor, hipStream
         if (b_kmajor) return hipErrorInvalidValue;
         switch (tile_cfg) {
         case kTile256x256:
-            return launch_gemm_t<256, 256, 2, 2, false, false, false, true, true>(a, st);
-        case kTile256x128:
-            return launch_gemm_t<256, 128, 2, 2, false, false, false, true>(a, st);
+            return launch_gemm_t<256, 256, false, false, true>(a, st);
         case kTile128x128:
-            return launch_gemm_t<128, 128, 2, 2, false, false, false, true, true>(a, st);
-        case kTile256x256w8:
-            return launch_gemm_t<256, 256, 2, 4, false, true, false, true>(a, st);
+            return launch_gemm_t<128, 128, false, false, true>(a, st);
         default:
             return hipErrorInvalidValue;
         }
     }
     switch (tile_cfg) {
     case kTile256x256:
-        return b_kmajor ? launch_gemm_t<256, 256, 2, 2, true, false, false, false, true>(a, st)
-                        : launch_gemm_t<256, 256, 2, 2, false, false, false, false, true>(a, st);
-    case kTile256x128:
-        return b_kmajor ? launch_gemm_t<256, 128, 2, 2, true, false>(a, st) : launch_gemm_t<256, 128, 2, 2, false, false>(a, st);
+        return b_kmajor ? launch_gemm_t<256, 256, true>(a, st) : launch_gemm_t<256, 256, false>(a, st);
     case kTile128x128:
-        return b_kmajor ? launch_gemm_t<128, 128, 2, 2, true, false, false, false, true>(a, st)
-                        : launch_gemm_t<128, 128, 2, 2, false, false, false, false, true>(a, st);
-    case kTile256x256w8:
-        return b_kmajor ? launch_gemm_t<256, 256, 2, 4, true, true>(a, st) : launch_gemm_t<256, 256, 2, 4, false, true>(a, st);
+        return b_kmajor ? launch_gemm_t<128, 128, true>(a, st) : launch_gemm_t<128, 128, false>(a, st);
     default:
         return hipErrorInvalidValue;
     }
@@ -2358,8 +1730,7 @@ hipError_t launch_wide(const GemmArgs &a, int n_items, int rpad, int n_split, bo
         return hipGetLastError();
     };
     // eight waves, 32 rows x 64 rank columns each (two per SIMD): the loop is bound by what a wave has to issue
-    return t_kmajor ? launch(gemm_lora_kernel<128, 128, 4, 2, true, false, true>)
-                    : launch(gemm_lora_kernel<128, 128, 4, 2, false, false, true>);
+    return t_kmajor ? launch(gemm_lora_kernel<128, 128, 4, 2, true, true>) : launch(gemm_lora_kernel<128, 128, 4, 2, false, true>);
 }
 
 hipError_t launch_skinny_finish(const SkinnyArgs &a, int n_items, int item_rows, int n_split, hipStream_t st)
@@ -2370,12 +1741,12 @@ hipError_t launch_skinny_finish(const SkinnyArgs &a, int n_items, int item_rows,
 }
 
 // adds the K slices of a split GEMM in slice order, rounds once and writes the rows to their tokens;
-// block row = row of the order, 4 columns per thread
+// block x = row of the order, 4 columns per thread
 __global__ void __launch_bounds__(256) gemm_finish_kernel(GemmArgs p, int n_split)
 {
-    const int r = blockIdx.y;  // row of the launch; row p.row_base + r of the order
+    const int r = blockIdx.x;  // row of the launch; row p.row_base + r of the order
     const int tok = p.row_tok[p.row_base + r];
-    const int n = (blockIdx.x * 256 + threadIdx.x) * 4;
+    const int n = (blockIdx.y * 256 + threadIdx.x) * 4;
     if (tok < 0 || n >= p.N) return;
     const floatx4 sum = sum_slices(p.part + (int64_t)r * p.part_ld + n, (int64_t)p.part_rows * p.part_ld, n_split);
     uint2 v;
@@ -2401,15 +1772,15 @@ hipError_t launch_gemm_splitk(const GemmArgs &a, int n_split, bool b_kmajor, hip
         COLLM_LAUNCH(kern, dim3(tiles, n_split), dim3(256), smem, st, a);
         return hipGetLastError();
     };
-    if (a.n_sib > 1) return b_kmajor ? hipErrorInvalidValue : launch(gemm_lora_kernel<128, 128, 2, 2, false, false, false, false, true, true, true>);
-    return b_kmajor ? launch(gemm_lora_kernel<128, 128, 2, 2, true, false, false, false, true, false, true>)
-                    : launch(gemm_lora_kernel<128, 128, 2, 2, false, false, false, false, true, false, true>);
+    if (a.n_sib > 1) return b_kmajor ? hipErrorInvalidValue : launch(gemm_lora_kernel<128, 128, 2, 2, false, false, false, true, true>);
+    return b_kmajor ? launch(gemm_lora_kernel<128, 128, 2, 2, true, false, false, true>)
+                    : launch(gemm_lora_kernel<128, 128, 2, 2, false, false, false, true>);
 }
 
 hipError_t launch_gemm_finish(const GemmArgs &a, int n_split, hipStream_t st)
 {
     if (a.n_rows <= 0) return hipSuccess;
-    COLLM_LAUNCH(gemm_finish_kernel, dim3((a.N / 4 + 255) / 256, a.n_rows), dim3(256), 0, st, a, n_split);
+    COLLM_LAUNCH(gemm_finish_kernel, dim3(a.n_rows, (a.N / 4 + 255) / 256), dim3(256), 0, st, a, n_split);
     return hipGetLastError();
 }
 
@@ -2417,16 +1788,16 @@ hipError_t launch_gemm_swiglu(const GemmArgs &a, int tile_cfg, hipStream_t st)
 {
     switch (tile_cfg) {
     case kTile256x256:
-        return launch_gemm_t<256, 256, 2, 2, false, false, true, false, true>(a, st);
+        return launch_gemm_t<256, 256, false, true>(a, st);
     case kTile128x128:
-        return launch_gemm_t<128, 128, 2, 2, false, false, true, false, true>(a, st);
+        return launch_gemm_t<128, 128, false, true>(a, st);
     default:
         return hipErrorInvalidValue;
     }
 }
 
 int gemm_tile_rows(int tile_cfg) { return tile_cfg == kTile128x128 ? 128 : 256; }
-int gemm_tile_cols(int tile_cfg) { return (tile_cfg == kTile256x256 || tile_cfg == kTile256x256w8) ? 256 : 128; }
+int gemm_tile_cols(int tile_cfg) { return tile_cfg == kTile256x256 ? 256 : 128; }
 
 template <int RP, bool KM, int RT>
 static hipError_t launch_skinny_t(const SkinnyArgs &a, int n_items, int n_split, hipStream_t st)

@@ -277,6 +277,26 @@ def test_swiglu_backward_kernel_and_chain():
     assert not bad, f"beyond tolerance: {bad} (all: {errs})"
 
 
+def test_swiglu_backward_more_rows_than_a_grid_dimension():
+    import torch
+
+    # 70000 training rows in one segment (beyond 65535) between two inference segments
+    d_ff, lens, trn = 64, [300, 70000, 17], [0, 1, 0]
+    T = sum(lens)
+    seg_start = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    rng = np.random.default_rng(11)
+    pre_h = wl.bf16_round(rng.standard_normal((T, 2 * d_ff)).astype(np.float32))
+    dout_h = wl.bf16_round(rng.standard_normal((T, d_ff)).astype(np.float32))
+    tr = np.repeat(np.array(trn), lens) != 0
+    pre, dout = to_dev(pre_h, "bf16"), to_dev(np.where(tr[:, None], dout_h, np.nan).astype(np.float32), "bf16")
+    dy = torch.full((T, 2 * d_ff), float("nan"), dtype=torch.bfloat16, device="cuda")
+    binding.collm_swiglu_bwd(seg_start, np.array(trn, np.uint8), pre, dout, dy)
+    torch.cuda.synchronize()
+    dyh = to_host(dy)
+    assert np.all(np.isnan(dyh[~tr])) and np.all(np.isfinite(dyh[tr]))
+    assert maxrel(dyh[tr], oracle.swiglu_bwd(pre_h[tr], dout_h[tr])) <= TOL["bf16"]
+
+
 def test_swiglu_error_statuses():
     import torch
 
