@@ -527,7 +527,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip adapter update, variants and sibling calls")
     ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy (known HBM bytes) for scaling rocprofv3 byte counters")
+                    help="also run one plain 1 GiB copy kernel (fedavg_kernel over one copy: known HBM bytes) for scaling "
+                         "rocprofv3 byte counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU; run it with --gpus 1 (no collectives or sharding exist)",
@@ -625,11 +626,13 @@ def main():
             all_cfg.append(o)
 
     if args.calibration_copy:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        # one launch of a plain copy kernel of known size (the library's aggregation kernel over a single copy
+        # reads 1 GiB and writes 1 GiB), against which a profiler's byte counters can be scaled
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda")
         dst = torch.empty_like(src)
         src.fill_(1)
         torch.cuda.synchronize()
-        dst.copy_(src)  # reads 1 GiB and writes 1 GiB
+        binding.collm_adapter_fedavg([src], dst)
         torch.cuda.synchronize()
         del src, dst
 
