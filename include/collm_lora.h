@@ -160,6 +160,27 @@ int collm_lora_linear_bwd(collm_ctx *ctx, const collm_shape *shape, const void *
                           void *stream);
 
 /*
+ * collm_lora_linear_fwd for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments and results as collm_lora_linear_fwd, but there is no
+ * context: the workspace (plan, scaled low-rank activations, partial sums) is a static array of 16 MiB in the
+ * library's device image, one copy per GPU, held until the process ends, and the plan reaches it inside kernel
+ * arguments instead of pinned staging memory.  The call allocates no device or pinned memory and calls no
+ * allocating HIP routine, at the first call or later; the first call on a device looks up the array's address on
+ * that device and clears the 256 bytes of it that must be zero.
+ *   device       GPU to run on (made current); 0 <= device < 64
+ *   h_save       dev fp32 [T, 64] (row stride 64) or NULL
+ *   everything else as for collm_lora_linear_fwd.
+ * Limits: n_tokens <= 2048, n_segments <= 2048, n_adapters <= 64, every rank <= 64, d_in and d_out <= 16384.
+ * Beyond them: COLLM_E_SHAPE (COLLM_E_RANK for a rank), collm_last_error() names the limits, nothing is launched.
+ * All calls on one GPU share that GPU's array: a call must not overlap in time with another call of this entry
+ * point on the same GPU (other stream or other thread); calls on one stream are ordered and safe.
+ */
+int collm_lora_linear_fwd_noalloc(int device, const collm_shape *shape, const void *x, const void *W,
+                                  const void *const *A, const void *const *B, const int32_t *rank,
+                                  const int32_t *seg_start, const int32_t *seg_adapter,
+                                  const uint8_t *seg_is_train, void *y, float *h_save, void *stream);
+
+/*
  * Sibling projections: several projections of the same x (gate and up of an MLP; q, k, v of an
  * attention block), each with its own base weight and its own adapter pair of the same rank
  * (paper section 4.2 parameterisation, applied per projection; the batch, the segments and the

@@ -89,6 +89,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.collm_lora_linear_bwd.argtypes = [vp, sp, vp, vp, _vpp, _vpp, _i32p, _i32p, _i32p, _u8p, vp, vp, vp,
                                           _vpp, _vpp, ctypes.c_int, vp]
     lib.collm_lora_linear_bwd.restype = ctypes.c_int
+    lib.collm_lora_linear_fwd_noalloc.argtypes = [ctypes.c_int, sp, vp, vp, _vpp, _vpp, _i32p, _i32p, _i32p, _u8p, vp, vp, vp]
+    lib.collm_lora_linear_fwd_noalloc.restype = ctypes.c_int
     sbp = ctypes.POINTER(collm_siblings)
     lib.collm_lora_siblings_fwd.argtypes = [vp, sp, sbp, vp, vp, _vpp, _vpp, _i32p, _i32p, _i32p, _u8p, vp, vp, vp]
     lib.collm_lora_siblings_fwd.restype = ctypes.c_int
@@ -134,7 +136,7 @@ def _check(status: int, where: str):
     if status != 0:
         lib = load_library()
         detail = lib.collm_status_string(status).decode()
-        if status == -8:
+        if status == -8 or where.endswith("_noalloc"):
             detail += ": " + lib.collm_last_error().decode()
         raise CollmError(status, where, detail)
 
@@ -385,6 +387,29 @@ class Context:
             rk.ctypes.data_as(_i32p), ss.ctypes.data_as(_i32p), sa.ctypes.data_as(_i32p), st.ctypes.data_as(_u8p),
             dy.data_ptr(), None if h_save is None else h_save.data_ptr(), None if dx is None else dx.data_ptr(),
             dAt, dBt, 1 if accumulate else 0, self._stream(stream)), "collm_lora_siblings_bwd")
+
+
+NOALLOC_MAX_RANK = 64  # row stride of h_save in collm_lora_linear_fwd_noalloc
+
+
+def collm_lora_linear_fwd_noalloc(x, W, A: List, B: List, rank, seg_start, seg_adapter, seg_is_train, scale: float, y,
+                                  h_save=None, stream=None, layout: int = 0):
+    """collm_lora_linear_fwd without a context: the workspace is the library's static device array (h_save, if
+    given, has row stride 64)."""
+    import torch
+
+    lib = load_library()
+    ss, sa, st = _seg_arrays(seg_start, seg_adapter, seg_is_train)
+    rk = np.ascontiguousarray(rank, dtype=np.int32)
+    dt = COLLM_BF16 if x.dtype == torch.bfloat16 else COLLM_F32
+    d_out = W.shape[0] if layout == LAYOUT_OUT_IN else W.shape[1]
+    sh = collm_shape(int(x.shape[1]), int(d_out), int(x.shape[0]), len(sa), len(rk), dt, float(scale), int(layout))
+    At, Bt = _ptr_table(A, len(rk)), _ptr_table(B, len(rk))
+    _check(lib.collm_lora_linear_fwd_noalloc(
+        x.device.index or 0, ctypes.byref(sh), x.data_ptr(), W.data_ptr(), At, Bt, rk.ctypes.data_as(_i32p),
+        ss.ctypes.data_as(_i32p), sa.ctypes.data_as(_i32p), st.ctypes.data_as(_u8p), y.data_ptr(),
+        None if h_save is None else h_save.data_ptr(), _stream_handle(stream)), "collm_lora_linear_fwd_noalloc")
+    return y
 
 
 def _dtype_of(t):

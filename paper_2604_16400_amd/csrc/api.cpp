@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <thread>
@@ -49,6 +50,7 @@ inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
 struct collm_ctx {
     int device = 0;
+    bool static_scratch = false;  // the workspace is the library's static device array; plans travel as kernel arguments
     int max_tokens = 0, max_segments = 0, max_adapters = 0, max_rank = 0, max_d = 0;
     int rows_cap = 0;   // padded row capacity
     int rpad_cap = 0;   // max_rank rounded up to 16
@@ -363,6 +365,15 @@ int upload(collm_ctx *c, size_t lo, size_t hi, hipStream_t st)
 {
     if (hi <= lo) return COLLM_OK;
     const auto t0 = std::chrono::steady_clock::now();
+    if (c->static_scratch) {
+        // no pinned staging exists: the words travel inside the arguments of a few small kernels
+        const size_t lo4 = lo & ~(size_t)3, hi4 = std::min((hi + 3) & ~(size_t)3, c->plan.size());
+        HIP_TRY(launch_plan_words(c->plan.data() + lo4, c->d_plan + lo4, hi4 - lo4, st));
+        c->last_stream = st;
+        c->plan_upload_us += std::chrono::duration<float, std::micro>(std::chrono::steady_clock::now() - t0).count();
+        c->plan_bytes_up += (int)((hi4 - lo4) * sizeof(int32_t));
+        return COLLM_OK;
+    }
     const int sl = c->slot;
     c->slot = (c->slot + 1) % kSlots;
     if (c->stage_seq[sl] != 0) {
@@ -453,7 +464,10 @@ int prepare_plan(collm_ctx *c, const collm_shape *s, const void *const *A, const
         c->plan_valid = false;
         int rc = build_plan(rq, c->plan, c->L);
         if (rc != COLLM_OK) return rc;
-        if ((size_t)c->L.total_ints > c->plan_cap) return COLLM_E_SHAPE;
+        if ((size_t)c->L.total_ints > c->plan_cap) {
+            g_last_error = "the plan of this batch is larger than the context's plan buffer";
+            return COLLM_E_SHAPE;
+        }
         built(1);
         rc = upload(c, 0, c->L.total_ints, st);
         if (rc != COLLM_OK) return rc;
@@ -639,6 +653,80 @@ int prepare_siblings(collm_ctx *c, const collm_shape *s, const collm_siblings *s
     return COLLM_OK;
 }
 
+}  // namespace
+
+// -----------------------------------------------------------------------------------------
+// Workspace of collm_lora_linear_fwd_noalloc: one array per GPU the library is loaded on, held until the
+// process ends.  The name is a host-side stand-in, not a device address: the address on a device comes from
+// hipGetSymbolAddress with that device current, once per device, and is what the kernels receive.
+namespace {
+constexpr size_t kScratchBytes = (size_t)16 << 20;
+constexpr int kScratchMaxTokens = 2048, kScratchMaxSegments = 2048, kScratchMaxAdapters = 64, kScratchMaxRank = 64,
+              kScratchMaxD = 16384;
+constexpr size_t kScratchZerosOff = 0, kScratchPlanOff = 4096, kScratchPlanBytes = (size_t)256 << 10,
+                 kScratchHsOff = kScratchPlanOff + kScratchPlanBytes,
+                 kScratchHsBytes = (size_t)kScratchMaxTokens * kScratchMaxRank * 4,
+                 kScratchPartOff = kScratchHsOff + kScratchHsBytes, kScratchPartBytes = kScratchBytes - kScratchPartOff;
+static_assert(kScratchMaxTokens % kRowPad == 0 && kScratchMaxRank % kKStep == 0, "limits are padded sizes already");
+static_assert(kScratchPartOff % 256 == 0 && kScratchHsOff % 256 == 0, "every region is 256-byte aligned");
+constexpr int kMaxDevices = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+namespace {
+std::mutex g_scratch_mutex;
+collm_ctx *g_scratch_ctx[kMaxDevices] = {};
+
+// The per-device context of the entry point that allocates nothing: host bookkeeping only, every device pointer
+// lies inside that device's copy of `scratch`.  Set up at the first call on the device.
+int scratch_context(int device, hipStream_t st, collm_ctx **out)
+{
+    if (device < 0 || device >= kMaxDevices) return COLLM_E_SHAPE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ctx[device]) {
+        HIP_TRY(hipSetDevice(device));
+        unsigned char *ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || ((uintptr_t)ptr & 255u)) {
+            g_last_error = "address of the static scratch array is null or misaligned";
+            return COLLM_E_HIP;
+        }
+        collm_ctx *c = new (std::nothrow) collm_ctx();
+        if (!c) return COLLM_E_NOMEM;
+        c->device = device;
+        c->static_scratch = true;
+        c->max_tokens = kScratchMaxTokens;
+        c->max_segments = kScratchMaxSegments;
+        c->max_adapters = kScratchMaxAdapters;
+        c->max_rank = kScratchMaxRank;
+        c->max_d = kScratchMaxD;
+        c->rows_cap = kScratchMaxTokens;
+        c->rpad_cap = kScratchMaxRank;
+        c->plan_cap = kScratchPlanBytes / sizeof(int32_t);
+        c->d_zeros = ptr + kScratchZerosOff;
+        c->d_plan = reinterpret_cast<int32_t *>(ptr + kScratchPlanOff);
+        c->d_hs = ptr + kScratchHsOff;
+        c->d_part = reinterpret_cast<float *>(ptr + kScratchPartOff);
+        c->part_bytes = kScratchPartBytes;
+        c->workspace_bytes = (int64_t)kScratchBytes;
+        // host vectors at their largest size, so that later calls do not grow them
+        c->plan.reserve(c->plan_cap);
+        c->key_seg_start.reserve(kScratchMaxSegments + 1);
+        c->key_seg_adapter.reserve(kScratchMaxSegments);
+        c->key_seg_train.reserve(kScratchMaxSegments);
+        c->key_rank.reserve(kScratchMaxAdapters);
+        c->key_A.reserve(kScratchMaxAdapters);
+        c->key_B.reserve(kScratchMaxAdapters);
+        // the block of zeros that masked 16-byte loads read (a small fill kernel, in stream order before any use)
+        hipError_t e = launch_fill_zero(c->d_zeros, 256, st);
+        if (e != hipSuccess) {
+            delete c;
+            return hip_fail(e, "launch_fill_zero");
+        }
+        g_scratch_ctx[device] = c;
+    }
+    *out = g_scratch_ctx[device];
+    return COLLM_OK;
+}
 }  // namespace
 
 // -----------------------------------------------------------------------------------------
@@ -964,6 +1052,32 @@ int collm_lora_linear_fwd(collm_ctx *c, const collm_shape *s, const void *x, con
                           const uint8_t *seg_is_train, void *y, float *h_save, void *stream)
 {
     return fwd_impl(c, s, nullptr, x, W, A, B, rank, seg_start, seg_adapter, seg_is_train, y, h_save, stream);
+}
+
+int collm_lora_linear_fwd_noalloc(int device, const collm_shape *s, const void *x, const void *W,
+                                  const void *const *A, const void *const *B, const int32_t *rank,
+                                  const int32_t *seg_start, const int32_t *seg_adapter,
+                                  const uint8_t *seg_is_train, void *y, float *h_save, void *stream)
+{
+    if (!s) return COLLM_E_NULL;
+    if (s->n_tokens > kScratchMaxTokens || s->n_segments > kScratchMaxSegments || s->n_adapters > kScratchMaxAdapters ||
+        s->d_in > kScratchMaxD || s->d_out > kScratchMaxD) {
+        char buf[200];
+        std::snprintf(buf, sizeof buf,
+                      "collm_lora_linear_fwd_noalloc serves at most %d tokens, %d segments, %d adapters of rank <= %d and "
+                      "d_in, d_out <= %d (static workspace of %zu MiB)",
+                      kScratchMaxTokens, kScratchMaxSegments, kScratchMaxAdapters, kScratchMaxRank, kScratchMaxD,
+                      kScratchBytes >> 20);
+        g_last_error = buf;
+        return COLLM_E_SHAPE;
+    }
+    collm_ctx *c = nullptr;
+    int rc = scratch_context(device, (hipStream_t)stream, &c);
+    if (rc != COLLM_OK) return rc;
+    rc = fwd_impl(c, s, nullptr, x, W, A, B, rank, seg_start, seg_adapter, seg_is_train, y, h_save, stream);
+    if (rc == COLLM_E_RANK)
+        g_last_error = "collm_lora_linear_fwd_noalloc: a rank is outside 1..64 (the static workspace's limit)";
+    return rc;
 }
 
 int collm_lora_siblings_fwd(collm_ctx *c, const collm_shape *s, const collm_siblings *sib, const void *x,

@@ -162,6 +162,12 @@ hipError_t launch_pack_rows(const float *src, int64_t ld_src, int src_cols, cons
 hipError_t launch_plan_copy(const int32_t *src_pinned, int32_t *dst, size_t first_int, size_t n_ints, int *counter,
                             uint32_t *done_host_dev, uint32_t seq, hipStream_t st);
 
+// copies n_ints ints (a multiple of 4) from HOST memory `src` to device memory `dst` in stream order without any
+// staging buffer: the words travel inside the arguments of as many small kernels as it takes (3.5 KiB each)
+hipError_t launch_plan_words(const int32_t *src_host, int32_t *dst, size_t n_ints, hipStream_t st);
+// clears `bytes` (a multiple of 16) bytes at dst with a small kernel
+hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t st);
+
 // dst[i] = (1/n_copies) sum_k src[k][i]; element type bf16 or fp32, fp32 sums in copy order
 constexpr int kMaxFedAvgCopies = 16;
 struct FedAvgArgs {

@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include <algorithm>
+#include <cstring>
 
 #include "kernels.h"
 
@@ -224,6 +225,43 @@ hipError_t launch_plan_copy(const int32_t *src_pinned, int32_t *dst, size_t firs
     COLLM_LAUNCH(plan_copy_kernel, dim3(blocks), dim3(256), 0, st,
                        reinterpret_cast<const int4 *>(src_pinned + lo), reinterpret_cast<int4 *>(dst + lo), n16, counter,
                        done_host_dev, seq);
+    return hipGetLastError();
+}
+
+// Plan upload without a staging buffer: a chunk of the plan is an argument of the kernel (arguments are copied
+// when the launch is enqueued, so the host block may change afterwards), and the kernel stores it.
+constexpr int kPlanChunkInts = 896;  // 3.5 KiB of the 4 KiB a kernel's arguments may take
+struct PlanChunk {
+    int32_t v[kPlanChunkInts];
+};
+__global__ void __launch_bounds__(256) plan_words_kernel(PlanChunk c, int32_t *__restrict__ dst, int n)
+{
+    for (int i = threadIdx.x; i < n; i += 256) dst[i] = c.v[i];
+}
+
+hipError_t launch_plan_words(const int32_t *src_host, int32_t *dst, size_t n_ints, hipStream_t st)
+{
+    PlanChunk c;
+    for (size_t lo = 0; lo < n_ints; lo += kPlanChunkInts) {
+        const int n = (int)std::min<size_t>(kPlanChunkInts, n_ints - lo);
+        std::memcpy(c.v, src_host + lo, (size_t)n * sizeof(int32_t));
+        COLLM_LAUNCH(plan_words_kernel, dim3(1), dim3(256), 0, st, c, dst + lo, n);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+__global__ void __launch_bounds__(64) fill_zero_kernel(int4 *__restrict__ dst, int n16)
+{
+    for (int i = blockIdx.x * 64 + threadIdx.x; i < n16; i += gridDim.x * 64) dst[i] = make_int4(0, 0, 0, 0);
+}
+
+hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t st)
+{
+    const int n16 = (int)(bytes / 16);
+    if (n16 <= 0) return hipSuccess;
+    COLLM_LAUNCH(fill_zero_kernel, dim3(std::min(256, (n16 + 63) / 64)), dim3(64), 0, st, reinterpret_cast<int4 *>(dst), n16);
     return hipGetLastError();
 }
 
