@@ -1,6 +1,7 @@
 """Batch sizing of the paper's Coordinator (section 5): the package's host logic against the oracle's
 brute force, and the oracle against what the equations fix."""
 import numpy as np
+import pytest
 
 import oracle
 from paper_2604_16400_amd import coordinator as co
@@ -59,3 +60,35 @@ def test_package_fit_equals_oracle():
     m, r2 = co.fit_latency_model(B, b, T)
     assert np.allclose((m.coef_B, m.coef_b, m.const), oracle.fit_plane(B, b, T), rtol=1e-8, atol=1e-16)
     assert 0.9 < r2 <= 1.0
+
+
+@pytest.mark.gpu
+def test_measured_planes_feed_the_same_choice_as_the_oracle():
+    """The sweep that feeds the model, on the GPU: a 3 x 3 grid of (training tokens, decode tokens) on a small layer,
+    the planes fitted to what was measured, and the batch sizing on them equal to the oracle's brute force."""
+    Bg, bg = (512, 1024, 2048), (128, 512, 1024)
+    rows = co.measure(d_in=2048, d_out=2048, n_adapters=8, rank=16, B_grid=Bg, b_grid=bg, iters=5)
+    assert [(r["B"], r["b"]) for r in rows] == [(B, b) for B in Bg for b in bg]
+    Bv, bv = [r["B"] for r in rows], [r["b"] for r in rows]
+    for r in rows:
+        assert all(np.isfinite(r[k]) and 0 < r[k] < 0.1 for k in ("fused_s", "streams_train_s", "streams_infer_s"))
+    # more work never runs faster by much: the largest batch takes longer than the smallest one
+    assert rows[-1]["fused_s"] > rows[0]["fused_s"]
+    fits = {}
+    for key in ("fused_s", "streams_train_s", "streams_infer_s"):
+        T = [r[key] for r in rows]
+        m, r2 = co.fit_latency_model(Bv, bv, T)
+        ref = oracle.fit_plane(Bv, bv, T)
+        assert np.allclose((m.coef_B, m.coef_b, m.const), ref, rtol=1e-6, atol=1e-12)
+        fits[key] = m
+    assert fits["fused_s"].coef_B > 0 and fits["streams_train_s"].coef_B > 0
+    tau = 2.0 * min(r["fused_s"] for r in rows)
+    grid = list(range(256, 2049, 128))
+    for train, infer in ((fits["fused_s"], fits["fused_s"]), (fits["streams_train_s"], fits["streams_infer_s"])):
+        got = co.choose_batch_sizes(train, infer, tau, grid, 1024, 1.0, 2048.0, 1.0, 1024.0)
+        ref = oracle.coordinator_choice((train.coef_B, train.coef_b, train.const), (infer.coef_B, infer.coef_b, infer.const),
+                                        tau, grid, 1024, 1.0, 2048.0, 1.0, 1024.0)
+        if ref is None:
+            assert got is None
+        else:
+            assert got[:2] == ref[:2] and abs(got[2] - ref[2]) <= 1e-9 * abs(ref[2])

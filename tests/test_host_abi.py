@@ -167,3 +167,36 @@ def test_gemm_tiling_covers_the_rows_and_matches_the_measured_choices():
     assert binding.host_tiling(8192, 5120, 5120) == (binding.TILE_256x256, 32, 0, 4)    # c4 forward: 2 rounds + 512 tiles of 128x128
     assert binding.host_tiling(4096, 11008, 4096) == (binding.TILE_256x256, 16, 0, 0)   # c3 forward: 2.7 rounds, no split pays
     assert binding.host_tiling(64, 4096, 4096)[0] == binding.TILE_128x128               # decode-sized
+
+
+def _sanitizer_run(tmp_path, compiler, std, sources, args):
+    """Builds the sources with the address and undefined-behaviour sanitizers (static runtimes, so that nothing
+    preloaded into this process matters) and runs the result."""
+    import subprocess
+
+    exe = str(tmp_path / "sanitized")
+    cmd = [compiler, std, "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-static-libasan",
+           "-static-libubsan", "-I", os.path.join(ROOT, "include"), "-I", os.path.join(ROOT, "paper_2604_16400_amd", "csrc"),
+           *sources, "-lm", "-o", exe]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", LD_PRELOAD="")
+    r = subprocess.run([exe, *args], capture_output=True, text=True, env=env, timeout=240)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-4000:]
+    return r.stdout
+
+
+def test_planner_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    # 10^4 random segment tables through build_plan with every option (tile sizes, item sizes, the tiled pass,
+    # sibling ranks), each plan checked against what the table fixes: csrc/planner.cpp is offset arithmetic into
+    # one int32 block
+    out = _sanitizer_run(tmp_path, "g++", "-std=c++17",
+                         [os.path.join(ROOT, "tests", "sanitize_planner.cpp"),
+                          os.path.join(ROOT, "paper_2604_16400_amd", "csrc", "planner.cpp")], ["10000"])
+    assert "planner ok 10000" in out
+
+
+def test_oracle_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    out = _sanitizer_run(tmp_path, "gcc", "-std=c11",
+                         [os.path.join(ROOT, "tests", "sanitize_oracle.c"), os.path.join(ROOT, "oracle", "collm_oracle.c")],
+                         ["300"])
+    assert "oracle ok 300" in out
