@@ -311,17 +311,47 @@ def _report(torch, r, steps, warmup, prof_steps, vendor=True):
 
 
 def _rotating(torch, w, pi, steps, warmup, prof_steps, min_bytes=320 << 20):
-    """A projection whose tensors fit the 256 MB last-level cache, timed the way a model runs it: every step
-    uses the next of enough independent copies of W, A and B (the model's layers) that no copy is still cached
-    when its turn comes again.  x, y, dy and dx are the same buffers at every step (a layer's input was written
-    just before it runs)."""
+    """A projection whose tensors fit the 256 MB last-level cache, timed the way a model runs it: enough
+    independent copies of W, A and B (the model's layers) that no copy is still cached when its turn comes again,
+    forward through all of them, then backward through all of them in reverse order, each layer with the h it kept.
+    x, y, dy and dx are the same buffers for every layer (a layer's input was written just before it runs).  A step
+    is one layer's forward + backward: the pass over all layers divided by their number."""
     p = w.projections[pi]
     n_sets = max(2, -(-min_bytes // (p.d_in * p.d_out * 2)) + 1)
     r = Runner(w, pi, torch, weight_sets=n_sets)
-    sec, _ = _timed(torch, [r], steps, warmup)
-    kt = r.kernel_times(prof_steps, stat="median")
+    hs = [torch.empty_like(r.h_save) for _ in range(n_sets)]
+
+    def model_pass(acc=None):
+        for k in range(n_sets):
+            r.k, r.h_save = k, hs[k]
+            r.fwd()
+            if acc is not None:
+                for name, ms in r.ctx.profile_read():
+                    acc.setdefault(name, []).append(ms)
+        for k in reversed(range(n_sets)):
+            r.k, r.h_save = k, hs[k]
+            r.bwd()
+            if acc is not None:
+                for name, ms in r.ctx.profile_read():
+                    acc.setdefault(name, []).append(ms)
+
+    n = max(1, steps // n_sets)
+    for _ in range(max(1, warmup // n_sets)):
+        model_pass()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n):
+        model_pass()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / (n * n_sets)
+    acc = {}
+    r.ctx.profile_enable(True)
+    for _ in range(max(1, prof_steps // n_sets)):
+        model_pass(acc)
+    r.ctx.profile_enable(False)
+    kt = {k: sorted(v)[len(v) // 2] for k, v in acc.items() if any(v)}
     f_fwd, f_bwd = w.flops(p)
-    out = {"weight_sets": n_sets, "ms_per_step": sec * 1e3, "tflops": (f_fwd + f_bwd) / sec / 1e12,
+    out = {"layers": n_sets, "ms_per_step": sec * 1e3, "tflops": (f_fwd + f_bwd) / sec / 1e12,
            "kernel_ms_median": {k: round(v, 5) for k, v in kt.items()}}
     r.rates(kt, out)
     r.close()

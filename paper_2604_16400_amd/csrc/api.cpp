@@ -41,6 +41,7 @@ int hip_fail(hipError_t e, const char *what)
     } while (0)
 
 constexpr int kSlots = 16;             // pinned staging ring: the host may run this many uploads ahead
+constexpr uint64_t kWarmMaxBytes = (uint64_t)40 << 20;  // largest weight a rank-wide pass fetches ahead of its GEMM
 constexpr int kMaxProfile = 16;
 
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
@@ -88,6 +89,7 @@ struct collm_ctx {
     int tile_fwd = -1, tile_bwd = -1;  // forced GEMM tile shapes (-1 = choose)
     int wide_min_rows = -1;            // forced threshold of the tiled rank-wide pass (-1 = choose, 0 = never)
     int gemm_split = -1;               // forced number of K slices of a GEMM with few rows (-1 = choose, 1 = never)
+    int n_cus = 0;                     // compute units of the device
     int key_wide = 0, key_nsib = 0;
     std::vector<int32_t> sum_rank;     // sibling calls: ranks summed over the siblings
     hipStream_t last_stream = nullptr;
@@ -525,10 +527,21 @@ struct SiblingPass {
 int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, const void *in, int K,
                int32_t off_tab, bool t_kmajor, float *f32_out, int64_t f32_ld, int f32_cols,
                int f32_by_token, float f32_mult, void *bf_out, float bf_mult, const char *name,
-               hipStream_t st, const SiblingPass *sp = nullptr)
+               hipStream_t st, const SiblingPass *sp = nullptr, const void *warm = nullptr, uint64_t warm_bytes = 0)
 {
     if (R.n_items == 0 && R.n_wide == 0) return COLLM_OK;
     SkinnyArgs a{};
+    // The weight of the GEMM that follows, fetched into the last-level cache by extra blocks of this pass (one per
+    // compute unit) - if the weight is small (a GEMM of so few K tiles per block cannot hide the memory's latency:
+    // 4096x4096 runs a fifth longer on a weight that comes from memory, 69 instead of 59 us) and this pass streams
+    // less than the weight (it is then bound by latency and leaves the memory system idle; the fetch, about 12 us for
+    // 33 MB, makes it 4 us longer).  Larger passes lose more than the GEMM gains (5120x5120, 8192 rows: +13 us / -11 us).
+    const uint64_t pass_bytes = (uint64_t)R.n_rows * (uint64_t)K * (s->dtype == COLLM_BF16 ? 2 : 4);
+    if (warm && warm_bytes <= kWarmMaxBytes && pass_bytes <= warm_bytes && c->n_cus > 0) {
+        a.warm_base = warm;
+        a.warm_bytes = warm_bytes;
+        a.warm_blocks = c->n_cus;
+    }
     const int64_t esz = s->dtype == COLLM_BF16 ? 2 : 4;
     a.in = in;
     a.ld_in = K;
@@ -602,6 +615,11 @@ int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, cons
         g.part_n_sib = a.n_sib;
         g.tab_ld = a.tab_ld;
         g.tab_off = a.tab_off;
+        // (the warm-up rides with the tiled pass when there is one, else with the 16-row items)
+        g.warm_base = a.warm_base;
+        g.warm_bytes = a.warm_bytes;
+        g.warm_blocks = a.warm_blocks;
+        a.warm_blocks = 0;
         const long blocks = (long)R.n_wide * ((rpad + 127) / 128);
         const long per_split = (long)c->rows_cap * c->rpad_cap * 4;
         // (one block per CU with K-major tables, two with tables as they lie in memory: see launch_wide)
@@ -707,6 +725,7 @@ int scratch_context(int device, hipStream_t st, collm_ctx **out)
         c->d_hs = ptr + kScratchHsOff;
         c->d_part = reinterpret_cast<float *>(ptr + kScratchPartOff);
         c->part_bytes = kScratchPartBytes;
+        if (hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) c->n_cus = 0;
         c->workspace_bytes = (int64_t)kScratchBytes;
         // host vectors at their largest size, so that later calls do not grow them
         c->plan.reserve(c->plan_cap);
@@ -782,6 +801,7 @@ int collm_ctx_create(collm_ctx **out, int device, int32_t max_tokens, int32_t ma
     c->rows_cap = round_up(max_tokens, kRowPad);
     c->rpad_cap = round_up(max_rank, kKStep);
     c->plan_cap = plan_ints_upper_bound(max_tokens, max_segments, max_adapters, max_rank);
+    if (hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) c->n_cus = 0;
 
     auto fail = [&](int rc) {
         collm_ctx_destroy(c);
@@ -1003,7 +1023,7 @@ static int fwd_impl(collm_ctx *c, const collm_shape *s, const collm_siblings *si
     // counterpart in the other direction uses
     const bool tr = s->layout == COLLM_LAYOUT_OUT_IN;
     rc = run_skinny(c, s, L.all, x, s->d_in, L.off_A_ptr, tr, h_save, c->max_rank, c->max_rank, 1, 1.0f,
-                    c->d_hs, s->scale, "shrink", st);
+                    c->d_hs, s->scale, "shrink", st, nullptr, f32 ? nullptr : W, (uint64_t)s->d_in * s->d_out * 2);
     if (rc != COLLM_OK) return rc;
 
     GemmArgs g{};
@@ -1209,7 +1229,7 @@ static int bwd_impl(collm_ctx *c, const collm_shape *s, const collm_siblings *si
     // dh = s dy B_a^T: fp32 for dA, element type for the dX GEMM's extra K-steps
     if (P == 1) {
         rc = run_skinny(c, s, L.train, dy, s->d_out, L.off_B_ptr, !tr, c->d_dh32, L.rpad, L.rpad, 0, s->scale,
-                        c->d_dhs, s->scale, "dh", st);
+                        c->d_dhs, s->scale, "dh", st, nullptr, (f32 || !dx) ? nullptr : W, (uint64_t)s->d_in * s->d_out * 2);
         if (rc != COLLM_OK) return rc;
     } else {
         // one pass per sibling over its columns of dy and of the tables, each writing its columns of dh

@@ -74,6 +74,10 @@ struct GemmArgs {
                               // (row_base = 128 tile_m_base); part row = row - row_base
     int part_n_sib;           // as SkinnyArgs::n_sib (0 or 1: ranks as the items give them)
     int64_t tab_ld, tab_off;  // as SkinnyArgs
+    // launch_wide: warm-up of the GEMM that follows, as in SkinnyArgs (extra blocks behind the n_items items)
+    const void *warm_base;
+    uint64_t warm_bytes;
+    int warm_blocks, n_items;
 };
 
 // out[m][q] = sum_k in[tok(m)][k] * tab_a(k, q), one SkinnyItem per blockIdx.x
@@ -103,6 +107,12 @@ struct SkinnyArgs {
     // the row from n_sib * rank on.  n_sib 0 or 1: none of this (tab_ld = K, tab_off = 0).
     int n_sib, sib;
     int64_t tab_ld, tab_off;
+    // Warm-up of the GEMM that follows this pass (bf16 kernels): warm_blocks extra blocks behind the items (block
+    // index n_items ..) read warm_bytes at warm_base once and drop them, so that the weight is in the last-level cache
+    // when the GEMM asks for it.  The pass itself leaves most of the memory bandwidth idle.  0 blocks: none of this.
+    const void *warm_base;
+    uint64_t warm_bytes;
+    int warm_blocks, n_items;
 };
 
 // out_a(q, n) = sum_t small[t][q] * big[tok(t)][n] over one adapter's training rows
