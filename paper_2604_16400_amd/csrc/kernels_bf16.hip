@@ -43,7 +43,11 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
+// Chunk swizzle of a K-major tile (rows of 128 bytes = 8 chunks of 16).  Measured on the device with the two
+// fragment-read patterns (16 rows x 4 chunks per ds_read_b128 for the 16x16x32 MFMA, 32 rows x 2 chunks for the
+// 32x32x16 one), four waves reading at once: this choice reads 1 KiB per wave in 28-29 cycles in both patterns;
+// (row ^ (row >> 3)) & 7 takes 32 in the first and row & 7 takes 35 in the second (no swizzle: 64 and 128).
+__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
 // byte offset of chunk c of row r inside a tile
 __device__ __forceinline__ int tile_off(int row, int c) { return row * 128 + ((c ^ swz(row)) << 4); }
@@ -409,15 +413,14 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (!PARTIAL && BM * BN == 128 * 1
     // in the N-major tile row bk0 + i NT/NG, chunk position bng.  The 64 lanes of a wave own
     // one contiguous KiB per i, which is what a direct-to-LDS load fills.  The swizzle decides
     // which chunk of the source belongs at that position.
-    // rows r8 + i NT/8 differ in swizzle only through bit 2 of (row >> 3): NT/8 = 32 flips it
-    // for odd i, NT/8 = 64 never does
-    constexpr int SWZ_FLIP = (NT / 8 == 32) ? 4 : 0;
-    const int cl0 = c8 ^ swz(r8);  // source chunk of this thread for even i
+    // rows r8 + i NT/8 (NT/8 = 32 or 64) all have the swizzle of row r8
+    static_assert((NT / 8) % 16 == 0, "the swizzle repeats every 16 rows");
+    const int cl0 = c8 ^ swz(r8);  // source chunk of this thread, for every i
     uint32_t aoff[ACH];
 #pragma unroll
     for (int i = 0; i < ACH; ++i) {
         const int tok = tok_of[i];
-        const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
+        const int cl = cl0;
         aoff[i] = tok >= 0 ? (uint32_t)tok * (uint32_t)p.lda * 2u + cl * 16u : kOob;
     }
     constexpr int NB = BCH;
@@ -433,7 +436,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (!PARTIAL && BM * BN == 128 * 1
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             const int n = n0 + r8 + i * (NT / 8);
-            const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
+            const int cl = cl0;
             boff[i] = n < N ? (uint32_t)n * ldb * 2u + cl * 16u : kOob;
         }
     } else {
@@ -446,12 +449,12 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (!PARTIAL && BM * BN == 128 * 1
     // byte offset of the tile that starts at K index k0 = 64 kc, for chunk i; tiles that reach
     // beyond K mask their tail (K-major) or run off the end of the buffer (N-major rows)
     auto a_src = [&](int i, int k0, bool full) -> uint32_t {
-        const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
+        const int cl = cl0;
         return (full || k0 + cl * 8 < K) ? aoff[i] + (uint32_t)k0 * 2u : kOob;
     };
     auto b_src = [&](int i, int k0, int kc, bool full) -> uint32_t {
         if constexpr (B_KMAJOR) {
-            const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
+            const int cl = cl0;
             return (full || k0 + cl * 8 < K) ? boff[i] + (uint32_t)k0 * 2u : kOob;
         } else {
             if constexpr (M16) return boff[i] == kOob ? kOob : boff[i] + (uint32_t)kc * bstep_u;
@@ -505,7 +508,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (!PARTIAL && BM * BN == 128 * 1
         if (D < ACH && once) {
             const int i = D;
             const int r = r8 + i * (NT / 8);
-            const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
+            const int cl = cl0;
             const int k = 64 * g + cl * 8;
             const uint32_t off = k < p.hs_ld ? ((uint32_t)(m0 + r) * (uint32_t)p.hs_ld + (uint32_t)k) * 2u : kOob;
             dma16(rh_w, off, lds_wave + a_base + i * (NT / 64) * 1024);
@@ -514,7 +517,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (!PARTIAL && BM * BN == 128 * 1
             // indices koff + 8 (cl % 2) ..
             const int i = D;
             const int r = r8 + i * (NT / 8);
-            const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
+            const int cl = cl0;
             const int j = cl >> 1;
             const uint32_t kr = pick(j, bt.kr[0], bt.kr[1], bt.kr[2], bt.kr[3]);
             const uint32_t rows = pick(j, bt.rows[0], bt.rows[1], bt.rows[2], bt.rows[3]);
@@ -550,7 +553,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (!PARTIAL && BM * BN == 128 * 1
             const int i = D - ACH;
             const bool all8 = (((bt.kr[0] | bt.kr[1] | bt.kr[2] | bt.kr[3]) >> 16) & 7u) == 0;
             const int r = r8 + i * (NT / 8);
-            const int cl = cl0 ^ ((i & 1) ? SWZ_FLIP : 0);
+            const int cl = cl0;
             const int j = cl >> 1;
             const uint32_t kr = pick(j, bt.kr[0], bt.kr[1], bt.kr[2], bt.kr[3]);
             const uint32_t tlo = pick(j, (uint32_t)bt.tab[0], (uint32_t)bt.tab[1], (uint32_t)bt.tab[2], (uint32_t)bt.tab[3]);
@@ -1341,16 +1344,22 @@ __global__ void __launch_bounds__(SkinnyCfg<RP>::KW * 64) skinny_kernel(SkinnyAr
     }
     auto load_t_nmajor = [&](int k0, int buf) {
         if constexpr (!T_KMAJOR) {
-            if (fast_copy) {
+            // (issued for every rank, out of range where the slow copy below does the work: the number of loads
+            // per chunk must not depend on a branch, or the compiler cannot count how many may still be in flight
+            // and waits for more of them than the chunk it needs)
 #pragma unroll
-                for (int i = 0; i < NCP; ++i) {
-                    const int c = lane + i * 64;
-                    // rows beyond K lie beyond the table and read as zero
-                    creg[buf][i] = buf16(rt, c < CHK * cpr ? ((uint32_t)k0 * (uint32_t)rank) * 2u + (uint32_t)c * 16u : kOob);
-                }
+            for (int i = 0; i < NCP; ++i) {
+                const int c = lane + i * 64;
+                // rows beyond K lie beyond the table and read as zero
+                creg[buf][i] = buf16(rt, (fast_copy && c < CHK * cpr) ? ((uint32_t)k0 * (uint32_t)rank) * 2u + (uint32_t)c * 16u : kOob);
             }
         }
     };
+    // The loads of a chunk stay together and the chunks stay in order (the compiler may not move memory operations
+    // across this): the wait before a chunk's first use then counts exactly the loads of the D - 1 chunks behind it.
+    // Left to itself the compiler issues the first chunk's loads last in the prologue, and the loop then waits
+    // for all loads at the top of every round.
+    auto fence_chunk = [] { asm volatile("" ::: "memory"); };
     auto store_t_nmajor = [&](int k0, int buf) {
         if constexpr (!T_KMAJOR) {
             if (fast_copy) {
@@ -1382,6 +1391,7 @@ __global__ void __launch_bounds__(SkinnyCfg<RP>::KW * 64) skinny_kernel(SkinnyAr
             load_x(k_lo + d * CHK, d);
             load_t_kmajor(k_lo + d * CHK, d);
             load_t_nmajor(k_lo + d * CHK, d);
+            fence_chunk();
         }
         for (int kb = k_lo; kb < k_hi; kb += D * CHK) {
 #pragma unroll
@@ -1411,9 +1421,11 @@ __global__ void __launch_bounds__(SkinnyCfg<RP>::KW * 64) skinny_kernel(SkinnyAr
                     }
                 }
                 // refill this register set with the chunk D further on
+                fence_chunk();
                 load_x(k0 + D * CHK, d);
                 load_t_kmajor(k0 + D * CHK, d);
                 load_t_nmajor(k0 + D * CHK, d);
+                fence_chunk();
             }
         }
     }
