@@ -33,10 +33,11 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
-# HBM-side bytes of one forward-GEMM launch of configuration 5's 8192->28672 projection (rocprofv3 FETCH_SIZE and
-# WRITE_SIZE, scaled by what the same counters read for a plain 1 GiB copy; profiles/gemm_fwd_config5_gate_up.txt),
+# Bytes between the L2s and the memory side (Infinity Cache + HBM) of one forward-GEMM launch of configuration 5's
+# 8192->28672 projection: rocprofv3 FETCH_SIZE and WRITE_SIZE in KiB, scaled by what the same counters read for a
+# plain 1 GiB copy (x 2.0 and x 1.0; profiles/gemm_lora_config5.txt),
 # with the digest of the kernel source the counters were taken on: a build from other source reports null.
-ROOFLINE_TRAFFIC = {"bytes": None, "kernels_sha256_16": None}
+ROOFLINE_TRAFFIC = {"bytes": (5596429 * 2.0 + 946176 * 1.0) * 1024, "kernels_sha256_16": "d2ca8c553fb393b4"}
 KERNEL_SOURCE = os.path.join(ROOT, "paper_2604_16400_amd", "csrc", "kernels_bf16.hip")
 
 
@@ -548,12 +549,41 @@ def _cpu_baseline(w, sample):
                       f"fp64 (includes widening the weights to fp64); the full step is extrapolated by flops"}
 
 
+def _per_config(torch, wl, cfgs, args):
+    """Every requested configuration, one projection at a time."""
+    all_cfg = []
+    for c in cfgs:
+        if c == 1:
+            continue
+        w = wl.make_config(c)
+        for pi in range(len(w.projections)):
+            rr = Runner(w, pi, torch, exact=(c == 2))
+            steps = max(5, min(args.steps, 100 if c == 2 else 30))
+            o, _, _ = _report(torch, rr, steps, 3, min(steps, 10 if c > 2 else 50))
+            if c == 2:
+                kt_cold = rr.kernel_times(20, cold=True, stat="median")
+                o["kernel_ms_min"] = {k: round(v, 5) for k, v in rr.kernel_times(20, stat="min").items()}
+                o["kernel_ms_cold_median"] = {k: round(v, 5) for k, v in kt_cold.items()}
+            rr.close()
+            del rr
+            torch.cuda.empty_cache()
+            p = w.projections[pi]
+            if 2 * (p.d_in * p.d_out + w.n_tokens * (p.d_in + p.d_out)) < (256 << 20):
+                # fits the last-level cache when a step repeats on the same buffers: also as a model's layers run it
+                o["rotating_weights"] = _rotating(torch, w, pi, steps, 3, min(steps, 20))
+            all_cfg.append(o)
+    return all_cfg
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--configs", type=str, default="2,3,4,5", help="configurations reported per projection (5 is always run)")
+    ap.add_argument("--only-configs", action="store_true",
+                    help="profiling aid: run only the per-projection section of --configs (no headline step, no "
+                         "roofline or cpu_baseline); prints {\"all_configs\": ...}")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip adapter update, variants and sibling calls")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -576,6 +606,9 @@ def main():
     binding.load_library()
     props = torch.cuda.get_device_properties(0)
     cfgs = [int(s) for s in args.configs.split(",") if s.strip()]
+    if args.only_configs:
+        print(json.dumps({"profile_only": True, "all_configs": _per_config(torch, wl, cfgs, args)}))
+        return
 
     # ---- headline: configuration 5, its three projections one after the other on the same batch ----
     w5 = wl.make_config(5)
@@ -633,27 +666,7 @@ def main():
     torch.cuda.empty_cache()
 
     # ---- every configuration, one projection at a time ----
-    all_cfg = []
-    for c in cfgs:
-        if c == 1:
-            continue
-        w = wl.make_config(c)
-        for pi in range(len(w.projections)):
-            rr = Runner(w, pi, torch, exact=(c == 2))
-            steps = max(5, min(args.steps, 100 if c == 2 else 30))
-            o, _, _ = _report(torch, rr, steps, 3, min(steps, 10 if c > 2 else 50))
-            if c == 2:
-                kt_cold = rr.kernel_times(20, cold=True, stat="median")
-                o["kernel_ms_min"] = {k: round(v, 5) for k, v in rr.kernel_times(20, stat="min").items()}
-                o["kernel_ms_cold_median"] = {k: round(v, 5) for k, v in kt_cold.items()}
-            rr.close()
-            del rr
-            torch.cuda.empty_cache()
-            p = w.projections[pi]
-            if 2 * (p.d_in * p.d_out + w.n_tokens * (p.d_in + p.d_out)) < (256 << 20):
-                # fits the last-level cache when a step repeats on the same buffers: also as a model's layers run it
-                o["rotating_weights"] = _rotating(torch, w, pi, steps, 3, min(steps, 20))
-            all_cfg.append(o)
+    all_cfg = _per_config(torch, wl, cfgs, args)
 
     if args.calibration_copy:
         # one launch of a plain copy kernel of known size (the library's aggregation kernel over a single copy

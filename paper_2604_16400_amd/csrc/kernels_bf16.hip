@@ -1188,7 +1188,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (!PARTIAL && BM * BN == 128 * 1
 // =========================================================================================
 // Results of four rank indices q .. q + 3 of row m of an item: the fp32 copy (token-indexed h_save
 // or row-indexed workspace) and the scaled copy in the element type.
-__device__ __forceinline__ void skinny_store(const SkinnyArgs &p, const SkinnyItem &it, int m, int q, floatx4 sum)
+__device__ __forceinline__ void skinny_store(const SkinnyArgs &p, const SkinnyItem it, int m, int q, floatx4 sum)
 {
     const int row = it.row_lo + m;
     const int tok = p.row_tok[row];
@@ -1271,7 +1271,10 @@ __global__ void __launch_bounds__(SkinnyCfg<RP>::KW * 64) skinny_kernel(SkinnyAr
         if (blockIdx.y == 0) warm_cache(p.warm_base, p.warm_bytes, blockIdx.x - p.n_items, p.warm_blocks, tid, KW * 64);
         return;
     }
-    const SkinnyItem it = p.items[blockIdx.x];
+    // (the item is the same for the whole block: kept in scalar registers)
+    const SkinnyItem *ip = p.items + blockIdx.x;
+    const SkinnyItem it = {__builtin_amdgcn_readfirstlane(ip->adapter), __builtin_amdgcn_readfirstlane(ip->row_lo),
+                           __builtin_amdgcn_readfirstlane(ip->n_rows), __builtin_amdgcn_readfirstlane(ip->rank)};
     const int K = p.K, rank = p.n_sib > 1 ? it.rank / p.n_sib : it.rank;
     const int rp = (rank + 15) & ~15;
     const int l16 = lane & 15, kg = lane >> 4;
