@@ -456,6 +456,41 @@ def test_same_batch_other_adapter_tables_reuses_the_plan():
         ctx.close()
 
 
+def test_weight_fetch_beside_the_rank_wide_passes():
+    # A small weight is read once by extra blocks of the rank-wide pass that runs before each GEMM (the pass must
+    # stream fewer bytes than the weight).  Those blocks compute nothing: results are as the oracle's, on the
+    # 16-row items (rank 16), on the tiled pass (rank 64, long runs) and with both in one launch sequence; ragged
+    # K so that the last share of the weight is a partial one.
+    for ranks, lens, ads, trn in (([16, 16], [300, 40, 1, 171], [0, 1, 1, 0], [1, 0, 0, 0]),
+                                  ([64, 64], [300, 40, 1, 171], [0, 1, 1, 0], [1, 0, 0, 1]),
+                                  ([64, 16, 8], [260, 30, 1, 190, 31], [0, 1, 2, 0, 1], [1, 1, 0, 0, 0])):
+        w = _adhoc("bf16", 1096, 2056, ranks, lens, ads, trn, scale=0.7)
+        assert w.n_tokens * 1096 * 2 < 1096 * 2056 * 2  # the condition under which the weight is fetched
+        _run_full(w)
+        _run_full(w, transposed=True)
+        _run_full(w, h_save=False)
+
+
+def test_plan_statistics_and_device_info():
+    info = binding.device_info(0)
+    assert info["compute_units"] > 0 and info["clock_mhz"] > 0 and info["memory_bus_bits"] > 0
+    w1 = _adhoc("bf16", 256, 128, [16, 8], [40, 1, 30, 9], [0, 1, 1, 0], [1, 0, 0, 0])
+    w2 = _adhoc("bf16", 256, 128, [16, 8], [40, 1, 30, 9], [1, 0, 0, 1], [1, 0, 0, 0])
+    ctx = make_ctx(w1)
+    l1 = DeviceLayer(w1, wl.make_tensors(w1), ctx)
+    l2 = DeviceLayer(w2, wl.make_tensors(w2), ctx)
+    l1.fwd()
+    st = ctx.plan_stats()
+    assert st["mode"] == 1 and st["build_us"] > 0 and st["upload_us"] > 0 and st["bytes"] > 0   # built and uploaded
+    l1.fwd()
+    assert ctx.plan_stats()["mode"] == 0                                                          # reused as it is
+    l2.fwd()
+    assert ctx.plan_stats()["mode"] == 1                                                          # another batch
+    l2.bwd()
+    check_full(l2, TOL["bf16"])
+    ctx.close()
+
+
 # ------------------------------------------------------------------ contracts
 def test_recompute_h_and_accumulate_and_run_to_run():
     import torch
