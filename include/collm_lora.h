@@ -271,6 +271,18 @@ int collm_debug_host_tiling(int rows, int cols, int K, int can_split, int32_t *t
                             int32_t *tail_tiles_m, int32_t *tail_cols);
 
 /*
+ * Debug, HOST only (no GPU): the order in which the workgroups of a GEMM launch of tiles_m x tiles_n tiles take
+ * the tiles.  Workgroup ids go round-robin to the GPU's 8 XCDs (each with an L2 of its own); every XCD gets a
+ * contiguous run of an order that walks groups of 8 row tiles column by column, and the grid is walked in bands
+ * of *band_used row tiles (0 = one band), so that a band's rows of the first operand stay in the last-level cache
+ * while the column tiles stream.  band = -1: the band the library chooses for tiles of tile_rows (128 or 256) rows
+ * and contraction length K; band >= 0 (a multiple of 8): that band.  tile_m, tile_n: HOST, tiles_m * tiles_n
+ * entries, the tile of workgroup id 0, 1, ...  Every tile appears exactly once.
+ */
+int collm_debug_host_tile_order(int tile_rows, int tiles_m, int tiles_n, int K, int band, int32_t *band_used,
+                                int32_t *tile_m, int32_t *tile_n);
+
+/*
  * Debug, HOST only (no GPU): the order in which the plan lists the rows of a batch for the GEMM
  * over all rows (training_rows_only = 0) or over the training rows (1), and the number of
  * 16-wide low-rank K-steps every row tile of tile_rows (64, 128 or 256) rows carries.

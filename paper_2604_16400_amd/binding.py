@@ -106,6 +106,9 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.collm_debug_host_tiling.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, _i32p, _i32p, _i32p,
                                             _i32p]
     lib.collm_debug_host_tiling.restype = ctypes.c_int
+    lib.collm_debug_host_tile_order.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, _i32p,
+                                                _i32p, _i32p]
+    lib.collm_debug_host_tile_order.restype = ctypes.c_int
     lib.collm_debug_host_row_order.argtypes = [sp, _i32p, _i32p, _i32p, _u8p, ctypes.c_int, ctypes.c_int, _i32p, _i32p]
     lib.collm_debug_host_row_order.restype = ctypes.c_int
     lib.collm_debug_set_tiles.argtypes = [vp, ctypes.c_int, ctypes.c_int]
@@ -174,6 +177,18 @@ def host_tiling(rows: int, cols: int, K: int, can_split: bool = True):
     _check(lib.collm_debug_host_tiling(rows, cols, K, 1 if can_split else 0, *[ctypes.byref(o) for o in out]),
            "collm_debug_host_tiling")
     return tuple(o.value for o in out)
+
+
+def host_tile_order(tile_rows: int, tiles_m: int, tiles_n: int, K: int, band: int = -1):
+    """(band_used, tile_m, tile_n): the tile every workgroup id of a GEMM launch takes (host logic, no GPU)."""
+    lib = load_library()
+    used = ctypes.c_int32(-9)
+    tm = np.empty(tiles_m * tiles_n, dtype=np.int32)
+    tn = np.empty(tiles_m * tiles_n, dtype=np.int32)
+    _check(lib.collm_debug_host_tile_order(tile_rows, tiles_m, tiles_n, K, band, ctypes.byref(used),
+                                           tm.ctypes.data_as(_i32p), tn.ctypes.data_as(_i32p)),
+           "collm_debug_host_tile_order")
+    return used.value, tm, tn
 
 
 def host_row_order(rank, seg_start, seg_adapter, seg_is_train, tile_rows: int = 256, training_rows_only: bool = False):

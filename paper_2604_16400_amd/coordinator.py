@@ -53,10 +53,11 @@ def fit_latency_model(B: Sequence[float], b: Sequence[float], T: Sequence[float]
 def infer_batch_limit(infer: LatencyModel, B: float, tau: float, b_max: int) -> int:
     """b*(B): the largest inference batch 0 <= b <= b_max with T_infer(B, b) <= tau (-1 if none)."""
     ok = lambda b: infer.coef_B * B + infer.coef_b * b + infer.const <= tau
+    if infer.coef_b <= 0:
+        # (a plane fitted to noisy timings may slope the wrong way: the largest batch is then the easiest one)
+        return int(b_max) if ok(b_max) else -1
     if not ok(0):
         return -1
-    if infer.coef_b <= 0:
-        return int(b_max)
     b = int(min(b_max, max(0.0, np.floor((tau - infer.coef_B * B - infer.const) / infer.coef_b))))
     # the division is only a first guess: settle on the predicate itself
     while b < b_max and ok(b + 1):

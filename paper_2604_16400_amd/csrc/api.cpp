@@ -871,6 +871,18 @@ int collm_ctx_destroy(collm_ctx *c)
 
 int64_t collm_ctx_workspace_bytes(const collm_ctx *c) { return c ? c->workspace_bytes : 0; }
 
+int collm_debug_host_tile_order(int tile_rows, int tiles_m, int tiles_n, int K, int band, int32_t *band_used,
+                                int32_t *tile_m, int32_t *tile_n)
+{
+    if (!band_used || !tile_m || !tile_n) return COLLM_E_NULL;
+    if (tiles_m <= 0 || tiles_n <= 0 || K <= 0 || (tile_rows != 128 && tile_rows != 256) ||
+        (int64_t)tiles_m * tiles_n > (1 << 24) || (band >= 0 && band % 8 != 0))
+        return COLLM_E_SHAPE;
+    *band_used = band >= 0 ? band : gemm_band_rows(tile_rows, K, tiles_m);
+    host_tile_order(tiles_m, tiles_n, *band_used, tile_m, tile_n);
+    return COLLM_OK;
+}
+
 int collm_debug_host_tiling(int rows, int cols, int K, int can_split, int32_t *tile, int32_t *big_tiles_m,
                             int32_t *tail_tiles_m, int32_t *tail_cols)
 {

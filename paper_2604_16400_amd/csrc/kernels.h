@@ -42,6 +42,7 @@ struct GemmArgs {
     uint32_t a_bytes, b_bytes;  // sizes of the two operand tensors (each below 2 GiB)
     int tiles_m, tiles_n;
     int tile_m_base;          // first row tile of this launch (a GEMM may be split over launches by rows)
+    int band_m;               // row tiles per band of the tile order (0 = one band); set by the launcher
     int n_base;               // first output column of this launch (... or by columns); a multiple of 8
     const int32_t *row_tok;   // [tiles_m * BM]
     const int32_t *ext_off;   // [tiles_m + 1]
@@ -139,6 +140,10 @@ struct GradArgs {
     int64_t ld_out, out_off;
 };
 
+// The GEMM kernels' tile order: (row tile, column tile) of workgroup id 0 .. tiles_m * tiles_n - 1 with bands of `band`
+// row tiles (0 = none), and the band the launchers choose for a tile height and contraction length (host only).
+void host_tile_order(int tiles_m, int tiles_n, int band, int32_t *tm, int32_t *tn);
+int gemm_band_rows(int tile_rows, int K, int tiles_m);
 hipError_t launch_gemm(const GemmArgs &a, int tile_cfg, bool b_kmajor, hipStream_t st);
 // The GEMM with K cut into n_split slices of k_per_split (128x128 tiles): fp32 sums of slice s for row r of the row order at
 // part[(s * part_rows + r) * part_ld + n] (part_ld >= N, a multiple of 4), then launch_gemm_finish adds the slices, rounds

@@ -75,8 +75,20 @@ __device__ __forceinline__ uint4 ldg16(const void *p) { return *reinterpret_cast
 // its own L2.  Give every XCD one contiguous run of the logical tile order, and make that
 // order walk groups of GM row tiles column by column so that concurrently running tiles of
 // one XCD share rows of the first operand and columns of the second.
-__device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, int &tm, int &tn)
+// band (a multiple of 8, or 0): the grid is walked in bands of that many row tiles, one band after the other, each
+// in the order above.  What the chip works on at a time is then the band's rows of the first operand and the column
+// tiles the XCDs are at; when all rows of the first operand together exceed the last-level cache (256 MB) but a band's
+// fit, every column step after a band's first finds them there instead of in memory.
+__host__ __device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, int band, int &tm, int &tn)
 {
+    int row0 = 0;
+    if (band > 0 && band < tiles_m) {
+        const int band_tiles = band * tiles_n;  // a multiple of 8: a band starts with XCD 0
+        const int b = pid / band_tiles;
+        pid -= b * band_tiles;
+        row0 = b * band;
+        tiles_m = tiles_m - row0 < band ? tiles_m - row0 : band;
+    }
     const int total = tiles_m * tiles_n;
     const int per = total >> 3, rem = total & 7;
     const int xcd = pid & 7, local = pid >> 3;
@@ -86,7 +98,7 @@ __device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, i
     const int first = group * GM;
     const int gsz = (tiles_m - first) < GM ? (tiles_m - first) : GM;
     const int in_group = logical - group * GM * tiles_n;
-    tm = first + in_group % gsz;
+    tm = row0 + first + in_group % gsz;
     tn = in_group / gsz;
 }
 
@@ -310,7 +322,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64, (!PARTIAL && BM * BN == 128 * 1
         b_base = reinterpret_cast<const uint8_t *>(p.tab[it.adapter]) + b_skip;
         b_bytes = B_KMAJOR ? (uint32_t)N * ldb * 2u - b_skip : (uint32_t)K * ldb * 2u;
     } else {
-        tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
+        tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, p.band_m, tile_m, tile_n);
         tile_m += p.tile_m_base;
         m0 = tile_m * BM;
         K = p.K;
@@ -1711,6 +1723,30 @@ __global__ void __launch_bounds__(GradCfg<RP>::KW * 64) grad_kernel(GradArgs p)
 // =========================================================================================
 // launchers
 // =========================================================================================
+// Row tiles per band of the tile order (see tile_coords): as many as keep a band's rows of the first operand
+// (tile_rows x K elements of 2 bytes per row tile) within kBandBytes, in whole groups of 8; 0 = one band.
+// Measured on 16384 rows, K = 8192 (268 MB of rows; 4.2 MB per row tile of 256), forward GEMM in us for N = 8192 / 28672:
+// one band 1600 / 5687, bands of 8 row tiles 1530 / 5581, 16: 1484 / 5347, 32: 1474 / 5302, 40: 1550 / 5547 - beside a band's
+// rows the cache also holds the column tiles the XCDs are at.  Where not even 16 row tiles fit (K = 28672: 14.7 MB per row
+// tile) bands of 8 were 1 % slower than none: no bands there.
+constexpr int64_t kBandBytes = (int64_t)140 << 20;
+int gemm_band_rows(int tile_rows, int K, int tiles_m)
+{
+    const int64_t per_tile = (int64_t)tile_rows * K * 2;
+    const int64_t band = (kBandBytes / (per_tile > 0 ? per_tile : 1)) & ~(int64_t)7;
+    return (band < 16 || band >= tiles_m) ? 0 : (int)band;
+}
+
+void host_tile_order(int tiles_m, int tiles_n, int band, int32_t *tm, int32_t *tn)
+{
+    for (int pid = 0; pid < tiles_m * tiles_n; ++pid) {
+        int m, n;
+        tile_coords(pid, tiles_m, tiles_n, band, m, n);
+        tm[pid] = m;
+        tn[pid] = n;
+    }
+}
+
 template <int BM, int BN, bool KM, bool SWIGLU = false, bool SIBS = false>
 static hipError_t launch_gemm_t(const GemmArgs &a, hipStream_t st)
 {
@@ -1731,7 +1767,9 @@ static hipError_t launch_gemm_t(const GemmArgs &a, hipStream_t st)
     }
     const int grid = a.tiles_m * a.tiles_n;
     if (grid <= 0) return hipSuccess;
-    COLLM_LAUNCH(kern, dim3(grid), dim3(NT), smem, st, a);
+    GemmArgs b = a;
+    b.band_m = gemm_band_rows(BM, a.K, a.tiles_m);
+    COLLM_LAUNCH(kern, dim3(grid), dim3(NT), smem, st, b);
     return hipGetLastError();
 }
 

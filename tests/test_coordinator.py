@@ -52,6 +52,24 @@ def test_package_logic_equals_oracle_on_random_models():
             assert got[:2] == ref[:2] and abs(got[2] - ref[2]) <= 1e-12 * abs(ref[2])
 
 
+def test_package_logic_equals_oracle_on_planes_of_any_slope():
+    # planes fitted to noisy timings may have coefficients of either sign (or zero): the sizing still has to be
+    # the brute force's
+    rng = np.random.default_rng(99)
+    for _ in range(400):
+        tr = (rng.uniform(-2e-7, 1e-6), rng.uniform(-2e-7, 5e-7), rng.uniform(-1e-5, 1e-4))
+        inf = (rng.uniform(-2e-7, 5e-7), float(rng.choice([0.0, rng.uniform(-5e-7, 1e-6)])), rng.uniform(-1e-5, 1e-4))
+        tau = rng.uniform(-1e-5, 1e-3)
+        grid = list(range(64, 2049, 192))
+        b_max = int(rng.integers(0, 1500))
+        ref = oracle.coordinator_choice(tr, inf, tau, grid, b_max, 1.0, 100.0, 1.0, 128.0)
+        got = co.choose_batch_sizes(co.LatencyModel(*tr), co.LatencyModel(*inf), tau, grid, b_max, 1.0, 100.0, 1.0, 128.0)
+        if ref is None:
+            assert got is None
+        else:
+            assert got[:2] == ref[:2] and abs(got[2] - ref[2]) <= 1e-12 * abs(ref[2])
+
+
 def test_package_fit_equals_oracle():
     rng = np.random.default_rng(8)
     B = rng.integers(64, 4096, size=25).astype(float)
@@ -72,8 +90,7 @@ def test_measured_planes_feed_the_same_choice_as_the_oracle():
     Bv, bv = [r["B"] for r in rows], [r["b"] for r in rows]
     for r in rows:
         assert all(np.isfinite(r[k]) and 0 < r[k] < 0.1 for k in ("fused_s", "streams_train_s", "streams_infer_s"))
-    # more work never runs faster by much: the largest batch takes longer than the smallest one
-    assert rows[-1]["fused_s"] > rows[0]["fused_s"]
+    # (no claim about the timings themselves beyond being sane: what is tested is the arithmetic on whatever was measured)
     fits = {}
     for key in ("fused_s", "streams_train_s", "streams_infer_s"):
         T = [r[key] for r in rows]
@@ -81,7 +98,6 @@ def test_measured_planes_feed_the_same_choice_as_the_oracle():
         ref = oracle.fit_plane(Bv, bv, T)
         assert np.allclose((m.coef_B, m.coef_b, m.const), ref, rtol=1e-6, atol=1e-12)
         fits[key] = m
-    assert fits["fused_s"].coef_B > 0 and fits["streams_train_s"].coef_B > 0
     tau = 2.0 * min(r["fused_s"] for r in rows)
     grid = list(range(256, 2049, 128))
     for train, infer in ((fits["fused_s"], fits["fused_s"]), (fits["streams_train_s"], fits["streams_infer_s"])):

@@ -200,3 +200,35 @@ def test_oracle_under_address_and_undefined_behaviour_sanitizers(tmp_path):
                          [os.path.join(ROOT, "tests", "sanitize_oracle.c"), os.path.join(ROOT, "oracle", "collm_oracle.c")],
                          ["300"])
     assert "oracle ok 300" in out
+
+
+def test_gemm_tile_order_visits_every_tile_once_and_keeps_bands_together():
+    # The workgroup id -> tile map of the GEMM kernels, run on the host: a bijection for every grid and band, a band's
+    # tiles contiguous in workgroup ids, and the walk of every XCD through a band.
+    rng = np.random.default_rng(5)
+    shapes = [(64, 112, 32), (64, 32, 32), (64, 4, 0), (13, 20, 0), (13, 20, 8), (40, 7, 16), (33, 5, 24), (1, 1, 0), (7, 3, 8)]
+    shapes += [(int(rng.integers(1, 70)), int(rng.integers(1, 40)), int(rng.integers(0, 5)) * 8) for _ in range(60)]
+    for tiles_m, tiles_n, band in shapes:
+        used, tm, tn = binding.host_tile_order(256, tiles_m, tiles_n, 8192, band)
+        assert used == band
+        seen = np.zeros((tiles_m, tiles_n), dtype=np.int32)
+        np.add.at(seen, (tm, tn), 1)
+        assert (seen == 1).all(), (tiles_m, tiles_n, band)
+        if 0 < band < tiles_m:
+            ids = np.arange(tiles_m * tiles_n)
+            assert np.array_equal(tm // band, ids // (band * tiles_n)), (tiles_m, tiles_n, band)
+        # an XCD (workgroup ids 8 i + x) walks the groups of 8 row tiles of a band in ascending order, and inside a
+        # group column by column
+        b = band if 0 < band < tiles_m else tiles_m
+        for x in range(8):
+            m, n = tm[x::8].astype(np.int64), tn[x::8].astype(np.int64)
+            key = ((m // b) * (tiles_m + 8) + (m % b) // 8) * tiles_n + n
+            assert (np.diff(key) >= 0).all(), (tiles_m, tiles_n, band, x)
+    # the band the library chooses: the rows of configuration 5 (16384 x 8192) in bands of 32 row tiles; none where all
+    # rows fit the cache anyway (few row tiles) or where not even 16 row tiles do (K = 28672)
+    assert binding.host_tile_order(256, 64, 112, 8192)[0] == 32
+    assert binding.host_tile_order(256, 64, 32, 8192)[0] == 32
+    assert binding.host_tile_order(256, 32, 54, 5120)[0] == 0
+    assert binding.host_tile_order(256, 32, 32, 28672)[0] == 0
+    assert binding.host_tile_order(128, 16, 32, 4096)[0] == 0
+
