@@ -591,7 +591,7 @@ def main():
                          "rocprofv3 byte counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU; run it with --gpus 1 (no collectives or sharding exist)",
+        print("bench.py: this library measures one GPU; run it with --gpus 1 (no collectives or sharding exist)",
               file=sys.stderr)
         sys.exit(2)
 

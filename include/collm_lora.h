@@ -359,7 +359,7 @@ int collm_profile_read(collm_ctx *ctx, const char **names, float *ms, int cap);
  * Sums are fp32 in copy order, one rounding to `dtype`.  COLLM_E_SHAPE for n_copies out of range.
  *
  * collm_adapter_adamw: one AdamW update (decoupled weight decay, bias-corrected moments; only the
- * adapters train, paper section 4.2; the optimizer itself is this build's reading) from the fp32
+ * adapters train, paper section 4.2; the optimizer itself is this library's reading) from the fp32
  * gradient that collm_lora_linear_bwd produced:
  *   m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2
  *   w = w (1 - lr wd) - lr / (1 - beta1^step) * m / (sqrt(v) / sqrt(1 - beta2^step) + eps)

@@ -281,7 +281,7 @@ def adamw_step(p, g, m, v, lr, beta1, beta2, eps, weight_decay, step):
     """One AdamW update (Loshchilov & Hutter 2019, decoupled weight decay, bias-corrected moments) of
     one adapter table in fp64.  The paper trains only the adapters (section 4.2) and keeps "gradients
     and optimizer state" with the fine-tuning task (section 2.1) without naming the optimizer; AdamW
-    is this build's reading.  `step` counts from 1.  Returns (p, m, v)."""
+    is this library's reading.  `step` counts from 1.  Returns (p, m, v)."""
     p, g, m, v = _f64(p).copy(), _f64(g), _f64(m).copy(), _f64(v).copy()
     assert step >= 1
     it = np.nditer([p, g, m, v], op_flags=[["readwrite"], ["readonly"], ["readwrite"], ["readwrite"]])
