@@ -117,6 +117,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.collm_debug_set_gemm_split.restype = ctypes.c_int
     lib.collm_debug_set_wide_pass.argtypes = [vp, ctypes.c_int]
     lib.collm_debug_set_wide_pass.restype = ctypes.c_int
+    lib.collm_debug_set_dual_pass.argtypes = [vp, ctypes.c_int]
+    lib.collm_debug_set_dual_pass.restype = ctypes.c_int
     lib.collm_device_info.argtypes = [ctypes.c_int, _i32p, _i32p, _i32p, _i32p, ctypes.POINTER(ctypes.c_int64)]
     lib.collm_device_info.restype = ctypes.c_int
     lib.collm_debug_plan_stats.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float), _i32p, _i32p]
@@ -273,6 +275,10 @@ class Context:
 
     def set_wide_pass(self, min_rows: int = -1):
         _check(self._lib.collm_debug_set_wide_pass(self._h, min_rows), "collm_debug_set_wide_pass")
+
+    def set_dual_pass(self, mode: int = -1):
+        """-1: dh and dB from one pass over dy where that pays; 1: wherever it applies; 0: never."""
+        _check(self._lib.collm_debug_set_dual_pass(self._h, mode), "collm_debug_set_dual_pass")
 
     def plan_stats(self):
         """Host cost of the plan of the last compute call: dict(build_us, upload_us, bytes, mode)."""

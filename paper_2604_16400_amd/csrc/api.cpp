@@ -88,6 +88,7 @@ struct collm_ctx {
 
     int tile_fwd = -1, tile_bwd = -1;  // forced GEMM tile shapes (-1 = choose)
     int wide_min_rows = -1;            // forced threshold of the tiled rank-wide pass (-1 = choose, 0 = never)
+    int dual_pass = -1;                // dh and dB from one pass over dy: -1 = where it pays, 0 = never, 1 = wherever it applies
     int gemm_split = -1;               // forced number of K slices of a GEMM with few rows (-1 = choose, 1 = never)
     int n_cus = 0;                     // compute units of the device
     int key_wide = 0, key_nsib = 0;
@@ -260,7 +261,7 @@ struct Prof {
     int idx = -1;
     Prof(collm_ctx *c_, hipStream_t, const char *name) : c(c_)
     {
-        if (c->profile && c->n_prof < kMaxProfile) {
+        if (name && c->profile && c->n_prof < kMaxProfile) {
             idx = c->n_prof++;
             c->prof_name[idx] = name;
             c->prof_launches[idx] = 0;
@@ -523,11 +524,19 @@ struct SiblingPass {
     int rpad = 0;  // padded width of the widest single rank
 };
 
+// Partial sums of a rank-wide pass that another kernel has left in the layout of the pass's own K slices
+// (part[(slice * part_rows + row) * part_ld + q]): run_skinny then only adds them up and stores.
+struct SliceSums {
+    float *part;
+    int part_rows, part_ld, n_slices;
+};
+
 // One skinny pass over a row order.
 int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, const void *in, int K,
                int32_t off_tab, bool t_kmajor, float *f32_out, int64_t f32_ld, int f32_cols,
                int f32_by_token, float f32_mult, void *bf_out, float bf_mult, const char *name,
-               hipStream_t st, const SiblingPass *sp = nullptr, const void *warm = nullptr, uint64_t warm_bytes = 0)
+               hipStream_t st, const SiblingPass *sp = nullptr, const void *warm = nullptr, uint64_t warm_bytes = 0,
+               const SliceSums *sums = nullptr)
 {
     if (R.n_items == 0 && R.n_wide == 0) return COLLM_OK;
     SkinnyArgs a{};
@@ -592,6 +601,15 @@ int run_skinny(collm_ctx *c, const collm_shape *s, const RowOrderLayout &R, cons
     a.part = c->d_part;
     a.part_rows = c->rows_cap;
     a.part_ld = c->rpad_cap;
+    if (sums) {
+        // the slices are there already: only the kernel that adds them and does this pass's stores
+        if (R.n_wide > 0 || s->dtype != COLLM_BF16) return COLLM_E_SHAPE;
+        a.part = sums->part;
+        a.part_rows = sums->part_rows;
+        a.part_ld = sums->part_ld;
+        HIP_TRY(launch_skinny_finish(a, R.n_items, R.item_rows, sums->n_slices, st));
+        return COLLM_OK;
+    }
     Prof prof(c, st, name);
     if (s->dtype == COLLM_F32) {
         HIP_TRY(launch_skinny_f32(a, R.n_items, t_kmajor, st));
@@ -940,6 +958,14 @@ int collm_debug_set_gemm_split(collm_ctx *c, int n_slices)
     return COLLM_OK;
 }
 
+int collm_debug_set_dual_pass(collm_ctx *c, int mode)
+{
+    if (!c) return COLLM_E_NULL;
+    if (mode < -1 || mode > 1) return COLLM_E_SHAPE;
+    c->dual_pass = mode;
+    return COLLM_OK;
+}
+
 int collm_debug_set_wide_pass(collm_ctx *c, int min_rows)
 {
     if (!c) return COLLM_E_NULL;
@@ -1180,14 +1206,79 @@ static int bwd_impl(collm_ctx *c, const collm_shape *s, const collm_siblings *si
     hipStream_t gs = overlap ? c->side : st;
     GradArgs ga{};
     const int64_t esz = f32 ? 4 : 2;
-    if (dA) {
+    ga.row_tok = c->d_plan + L.train.off_row_tok;
+    ga.items = reinterpret_cast<const GradItem *>(c->d_plan + L.off_grad);
+    ga.accumulate = accumulate ? 1 : 0;
+
+    // Narrow ranks (all at most 16), tables as [rank][d_out]: dh and dB_a both come from ONE pass over the training
+    // rows of dy (kernels.h, DualArgs), which is the largest operand of the backward pass beside W.  The rows of
+    // every trained adapter are cut into pieces so that two blocks per CU exist (pieces of 512 rows down to 64), as
+    // long as the per-group slices of dh and the per-piece sums of dB fit the workspace of partial sums.  It pays where
+    // dy is large: 8192 rows of 28672 columns 151 us against 94 + 122 for the two passes, of 8192 columns 60 against
+    // 31 + 41; on 8192 x 1024 (34 against 10 + 15) and 1792 x 4096 (28 against 14 + 10) the partial sums and the two
+    // kernels that add them cost more than the second read of dy, which comes from the last-level cache there anyway.
+    constexpr int64_t kDualMinBytes = (int64_t)64 << 20;
+    DualArgs du{};
+    bool dual = false;
+    if (!f32 && !tr && P == 1 && dA && c->dual_pass != 0 && L.rpad == kKStep && L.train.n_wide == 0 && L.n_grad > 0 &&
+        (c->dual_pass == 1 || (int64_t)L.train.n_rows * s->d_out * 2 >= kDualMinBytes)) {
+        const int groups = (s->d_out + kDualCols - 1) / kDualCols;
+        auto pieces_of = [&](int rows) { return (L.max_grad_rows + rows - 1) / rows; };
+        auto fits = [&](int rows) {
+            const size_t dh_floats = (size_t)round_up(groups * L.train.n_rows_pad * kKStep, 64);
+            return (dh_floats + (size_t)L.n_grad * pieces_of(rows) * kKStep * s->d_out) * 4 <= c->part_bytes;
+        };
+        int rows = kDualMaxPieceRows;
+        while (rows > 64 && (long)groups * L.n_grad * pieces_of(rows) < 2L * std::max(c->n_cus, 1)) rows >>= 1;
+        while (rows < kDualMaxPieceRows && !fits(rows)) rows <<= 1;
+        if (fits(rows)) {
+            dual = true;
+            du.dy = dy;
+            du.ld_dy = s->d_out;
+            du.dy_bytes = (uint32_t)((int64_t)s->n_tokens * s->d_out * 2);
+            du.N = s->d_out;
+            du.hs = c->d_hs;
+            du.ld_hs = L.rpad;
+            du.hs_bytes = (uint32_t)((size_t)L.train.n_rows_pad * L.rpad * 2);
+            du.row_tok = ga.row_tok;
+            du.items = ga.items;
+            du.n_grad = L.n_grad;
+            du.tab_b = reinterpret_cast<const uint64_t *>(c->d_plan + L.off_B_ptr);
+            du.out_tab = reinterpret_cast<const uint64_t *>(c->d_plan + L.off_dB_ptr);
+            du.accumulate = ga.accumulate;
+            du.piece_rows = rows;
+            du.max_pieces = pieces_of(rows);
+            du.part_dh = c->d_part;
+            du.part_rows = L.train.n_rows_pad;
+            du.part_ld = kKStep;
+            du.part_dB = c->d_part + round_up(groups * L.train.n_rows_pad * kKStep, 64);
+            // (the weight of the dX GEMM, as the dh pass would fetch it: see run_skinny)
+            const uint64_t w_bytes = (uint64_t)s->d_in * s->d_out * 2;
+            if (dx && w_bytes <= kWarmMaxBytes && (uint64_t)L.train.n_rows * s->d_out * 2 <= w_bytes && c->n_cus > 0) {
+                du.warm_base = W;
+                du.warm_bytes = w_bytes;
+                du.warm_rows = (c->n_cus + groups - 1) / groups;
+            }
+        }
+    }
+    if (dual) {
+        Prof prof(c, st, "dh_dB");
+        // s h as bf16 in training row order: left by the recomputing pass, or packed from h_save here
+        if (h_save)
+            HIP_TRY(launch_pack_rows(h_save, c->max_rank, c->max_rank, c->d_plan + L.train.off_row_tok, L.train.n_rows,
+                                     s->scale, c->d_hs, L.rpad, st));
+        HIP_TRY(launch_dual(du, st));
+        const SliceSums sums{du.part_dh, du.part_rows, du.part_ld, (s->d_out + kDualCols - 1) / kDualCols};
+        rc = run_skinny(c, s, L.train, dy, s->d_out, L.off_B_ptr, true, c->d_dh32, L.rpad, L.rpad, 0, s->scale, c->d_dhs,
+                        s->scale, nullptr, st, nullptr, nullptr, 0, &sums);
+        if (rc != COLLM_OK) return rc;
+        HIP_TRY(launch_dual_sum(du, st));
+    }
+    if (dA && !dual) {
         if (overlap) {
             HIP_TRY(hipEventRecord(c->ev_fork, st));
             HIP_TRY(hipStreamWaitEvent(c->side, c->ev_fork, 0));
         }
-        ga.row_tok = c->d_plan + L.train.off_row_tok;
-        ga.items = reinterpret_cast<const GradItem *>(c->d_plan + L.off_grad);
-        ga.accumulate = accumulate ? 1 : 0;
         // dB_a = s h^T dy
         ga.big = dy;
         ga.ld_big = s->d_out;
@@ -1239,7 +1330,9 @@ static int bwd_impl(collm_ctx *c, const collm_shape *s, const collm_siblings *si
     }
 
     // dh = s dy B_a^T: fp32 for dA, element type for the dX GEMM's extra K-steps
-    if (P == 1) {
+    if (dual) {
+        // (done above)
+    } else if (P == 1) {
         rc = run_skinny(c, s, L.train, dy, s->d_out, L.off_B_ptr, !tr, c->d_dh32, L.rpad, L.rpad, 0, s->scale,
                         c->d_dhs, s->scale, "dh", st, nullptr, (f32 || !dx) ? nullptr : W, (uint64_t)s->d_in * s->d_out * 2);
         if (rc != COLLM_OK) return rc;

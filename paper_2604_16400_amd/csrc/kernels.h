@@ -140,6 +140,39 @@ struct GradArgs {
     int64_t ld_out, out_off;
 };
 
+// One read of the training rows of dy for both dh and dB_a (narrow ranks: every rank at most 16).
+//   dh[t][q]   = sum_n dy[tok(t)][n] * B_a[q][n]      -> unscaled fp32 partial sums, one slice per group of kDualCols columns:
+//                part_dh[(group * part_rows + t) * part_ld + q]; launch_skinny_finish adds the groups, scales and stores
+//   dB_a[q][n] = sum_t hs[t][q] * dy[tok(t)][n]       (hs = s h as bf16, row order, zero from the rank up to 16)
+// The rows of a trained adapter are cut into pieces of piece_rows rows (a multiple of 32, at most kDualMaxPieceRows); an adapter
+// of one piece gets dB_a written (or added to, `accumulate`) directly, one of more pieces gets per-piece sums
+// part_dB[((item * max_pieces + piece) * 16 + q) * N + n], which launch_dual_sum adds in piece order.
+constexpr int kDualCols = 512, kDualMaxPieceRows = 512;
+struct DualArgs {
+    const void *dy;           // [T][N] bf16, rows gathered through row_tok
+    int64_t ld_dy;
+    uint32_t dy_bytes;
+    int N;
+    const void *hs;           // bf16 [row order][ld_hs]
+    int ld_hs;
+    uint32_t hs_bytes;        // size of hs (the kernel reads it through a buffer resource)
+    const int32_t *row_tok;   // training row order
+    const GradItem *items;    // one per trained adapter
+    int n_grad;
+    const uint64_t *tab_b;    // adapter -> B_a [rank][N] bf16
+    const uint64_t *out_tab;  // adapter -> dB_a fp32 [rank][N]
+    int accumulate;
+    int piece_rows, max_pieces;
+    float *part_dh;
+    int part_rows, part_ld;
+    float *part_dB;
+    // extra rows of blocks that read `warm_bytes` bytes at warm_base once and drop them (the weight of the GEMM that follows)
+    const void *warm_base;
+    uint64_t warm_bytes;
+    int warm_rows;
+};
+hipError_t launch_dual(const DualArgs &a, hipStream_t st);
+hipError_t launch_dual_sum(const DualArgs &a, hipStream_t st);
 // The GEMM kernels' tile order: (row tile, column tile) of workgroup id 0 .. tiles_m * tiles_n - 1 with bands of `band`
 // row tiles (0 = none), and the band the launchers choose for a tile height and contraction length (host only).
 void host_tile_order(int tiles_m, int tiles_n, int band, int32_t *tm, int32_t *tn);

@@ -1721,6 +1721,211 @@ __global__ void __launch_bounds__(GradCfg<RP>::KW * 64) grad_kernel(GradArgs p)
 }
 
 // =========================================================================================
+// dy pass for narrow ranks (see DualArgs): one read of the training rows of dy gives dh and dB_a.
+//
+// One block = one piece of a trained adapter's rows (blockIdx.y) x one group of 512 columns (blockIdx.x).  Wave w owns
+// the group's 64-column slab w for all rows of the piece, so dB_a needs no sum across waves; the rows go by in chunks
+// of 32 (one MFMA K step of dB).  Per chunk a wave copies its 32 x 64 values of dy and the chunk's 32 x 16 of s h, as
+// they lie in memory, into a private LDS area (from a ring of four chunks of loads in flight), builds both dB operands
+// with transposing reads (the contraction index, the row, is the slow index of both), reads the same dy values again
+// row by row as the dh operand (contraction over the slab's columns against B_a's, which the wave holds in registers)
+// and leaves its 32 x 16 partial dh in LDS, where the eight waves' partials are added in wave order and written as the
+// group's slice.  One barrier per chunk (the area of the partials is double-buffered).  The tokens of the piece's rows
+// are read into LDS once, so that no load of the ring waits for another load; the sums of dh stay in LDS until the
+// piece is done, so that the loop holds loads only (loads and stores complete out of order with respect to each other,
+// and with both in flight the compiler has to wait for everything before it touches a loaded register).
+// =========================================================================================
+constexpr int kDualRing = 4;
+struct DualCfg {
+    static constexpr int BPITCH = 64 * 2 + 32, SPITCH = 16 * 2 + 16;  // bytes
+    static constexpr int STAGE = 32 * (BPITCH + SPITCH);              // per wave
+    static constexpr int RED_LD = 20;                                 // floats per row of a wave's partial dh
+    static constexpr int RED = 8 * 32 * RED_LD * 4;                   // one buffer, all waves
+    static constexpr int TOK = (kDualMaxPieceRows + kDualRing * 32) * 4;  // tokens of the piece's rows, then -1 for the ring's overrun
+    static constexpr int DH = kDualMaxPieceRows * 16 * 4;             // the piece's dh sums of this column group
+    static constexpr int SMEM = TOK + 8 * STAGE + 2 * RED + DH;
+};
+static_assert(kDualCols == 8 * 64 && kDualMaxPieceRows == 512, "eight waves of a 64-column slab; one token per thread");
+
+__global__ void __launch_bounds__(512) dydual_kernel(DualArgs p)
+{
+    using C = DualCfg;
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n_item_rows = p.n_grad * p.max_pieces;
+    if ((int)blockIdx.y >= n_item_rows) {
+        // a row of blocks that fetch the next GEMM's weight: each reads its share once and drops it
+        warm_cache(p.warm_base, p.warm_bytes, ((int)blockIdx.y - n_item_rows) * (int)gridDim.x + (int)blockIdx.x,
+                   p.warm_rows * (int)gridDim.x, tid, 512);
+        return;
+    }
+    const int g = blockIdx.y / p.max_pieces, piece = blockIdx.y - g * p.max_pieces;
+    const GradItem it = p.items[g];
+    const int n_pieces = (it.row_hi - it.row_lo + p.piece_rows - 1) / p.piece_rows;
+    if (piece >= n_pieces) return;
+    const int r_lo = it.row_lo + piece * p.piece_rows;
+    const int r_hi = r_lo + p.piece_rows < it.row_hi ? r_lo + p.piece_rows : it.row_hi;
+    const int n_rows = r_hi - r_lo, n_chunks = (n_rows + 31) >> 5;
+    const int rank = it.rank, N = p.N;
+    const int n0 = blockIdx.x * kDualCols + wave * 64;  // first column of this wave's slab
+    const int l16 = lane & 15, kg = lane >> 4;
+
+    int32_t *s_tok = reinterpret_cast<int32_t *>(smem);
+    uint8_t *stage_b = smem + C::TOK + wave * C::STAGE;
+    uint8_t *stage_s = stage_b + 32 * C::BPITCH;
+    float *red = reinterpret_cast<float *>(smem + C::TOK + 8 * C::STAGE);
+    float *s_dh = reinterpret_cast<float *>(smem + C::TOK + 8 * C::STAGE + 2 * C::RED);
+
+    s_tok[tid] = tid < n_rows ? p.row_tok[r_lo + tid] : -1;
+    if (tid < kDualRing * 32) s_tok[kDualMaxPieceRows + tid] = -1;
+    // B_a's columns of the slab as the dh operand: lane = rank index l16, columns 8 kg .. of each 32-wide step
+    // (through a buffer resource, like every other load here: the table's address is itself loaded from memory, and a
+    // load through such a pointer is a flat one, which may complete out of order with the buffer loads - with one of
+    // those pending the compiler waits for all loads wherever it has to wait for any)
+    uint4 bfrag[2];
+    {
+        const __amdgpu_buffer_rsrc_t rtb = make_rsrc(reinterpret_cast<const void *>(p.tab_b[it.adapter]), (uint32_t)rank * (uint32_t)N * 2u);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const int col = n0 + ks * 32 + kg * 8;
+            bfrag[ks] = buf16(rtb, (l16 < rank && col < N) ? ((uint32_t)l16 * (uint32_t)N + (uint32_t)col) * 2u : kOob);
+        }
+    }
+    __syncthreads();
+
+    // Every load of the loop goes through a buffer resource and happens whatever the data (rows beyond the piece get
+    // an offset beyond the buffer and deliver zeros): the compiler counts the loads between a load and its use, and can
+    // only do so when none of them sits behind a branch.
+    const __amdgpu_buffer_rsrc_t rdy = make_rsrc(p.dy, p.dy_bytes);
+    const __amdgpu_buffer_rsrc_t rhs = make_rsrc(p.hs, p.hs_bytes);
+    const int bc = lane & 7, br = lane >> 3;  // dy: lane copies the 16-byte piece bc of rows br + 8 i
+    const uint32_t bcol = (n0 + bc * 8 < N) ? (uint32_t)(n0 + bc * 8) * 2u : kOob;
+    uint4 breg[kDualRing][4], sreg[kDualRing];
+    auto load_chunk = [&](int ch, int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int tok = s_tok[ch * 32 + br + 8 * i];  // (-1 beyond the piece: no branch, so the four reads go out together)
+            breg[buf][i] = buf16(rdy, (tok >= 0 && bcol != kOob) ? (uint32_t)tok * (uint32_t)p.ld_dy * 2u + bcol : kOob);
+        }
+        // s h of the chunk: 32 rows x 16 values = 64 pieces of 16 bytes, one per lane
+        const int m = ch * 32 + (lane >> 1);
+        sreg[buf] = buf16(rhs, m < n_rows ? ((uint32_t)(r_lo + m) * (uint32_t)p.ld_hs + (lane & 1) * 8u) * 2u : kOob);
+    };
+    auto store_chunk = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4 *>(stage_b + (br + 8 * i) * C::BPITCH + bc * 16) = breg[buf][i];
+        *reinterpret_cast<uint4 *>(stage_s + (lane >> 1) * C::SPITCH + (lane & 1) * 16) = sreg[buf];
+    };
+    // (the loads of a chunk stay together and the chunks in order, as in skinny_kernel)
+    auto fence_chunk = [] { asm volatile("" ::: "memory"); };
+
+    floatx4 acc_db[4];
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) acc_db[nb] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int d = 0; d < kDualRing; ++d) {
+        load_chunk(d, d);
+        fence_chunk();
+    }
+    for (int c0 = 0; c0 < n_chunks; c0 += kDualRing) {
+#pragma unroll
+        for (int d = 0; d < kDualRing; ++d) {
+            // (slots beyond the piece's last chunk hold zeros and are worked through like the others: a loop body
+            // without branches is what lets the compiler count the loads in flight)
+            const int ch = c0 + d;
+            store_chunk(d);
+            fence_chunk();
+            load_chunk(ch + kDualRing, d);
+            fence_chunk();
+            {
+                // dB: (s h)^T (rank index x rows) times dy (rows x columns), both by transposing reads
+                const int rrow = kg * 8 + (l16 >> 2), rcol = (l16 & 3) * 4;
+                bf16x8 sf;
+                {
+                    const uint8_t *src = stage_s + rrow * C::SPITCH + rcol * 2;
+                    const bf16x4 lo = lds_tr(src), hi = lds_tr(src + 4 * C::SPITCH);
+                    sf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                }
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) {
+                    const uint8_t *src = stage_b + rrow * C::BPITCH + (nb * 16 + rcol) * 2;
+                    const bf16x4 lo = lds_tr(src), hi = lds_tr(src + 4 * C::BPITCH);
+                    const bf16x8 bf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    acc_db[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf, bf, acc_db[nb], 0, 0, 0);
+                }
+                // dh: B_a (rank index x columns) times dy rows (columns x rows); lane = row l16 of a 16-row tile
+                floatx4 acc_dh[2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    acc_dh[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        const bf16x8 dyf = *reinterpret_cast<const bf16x8 *>(stage_b + (t * 16 + l16) * C::BPITCH + (ks * 32 + kg * 8) * 2);
+                        acc_dh[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bfrag[ks]), dyf, acc_dh[t], 0, 0, 0);
+                    }
+                }
+                // lane holds row 16 t + l16 of the chunk, rank indices 4 kg + 0..3
+                float *mine = red + (((ch & 1) * 8 + wave) * 32) * C::RED_LD;
+#pragma unroll
+                for (int t = 0; t < 2; ++t) *reinterpret_cast<floatx4 *>(mine + (t * 16 + l16) * C::RED_LD + kg * 4) = acc_dh[t];
+                __syncthreads();
+                const int m = tid >> 4, q = tid & 15;
+                float sum = 0.f;
+#pragma unroll
+                for (int w = 0; w < 8; ++w) sum += red[((((ch & 1) * 8 + w) * 32) + m) * C::RED_LD + q];
+                if (ch * 32 + m < kDualMaxPieceRows) s_dh[(ch * 32 + m) * 16 + q] = sum;
+            }
+        }
+    }
+
+    // this group's slice of dh for the piece's rows
+    __syncthreads();
+    for (int idx = tid; idx < n_rows * 16; idx += 512)
+        p.part_dh[((int64_t)blockIdx.x * p.part_rows + r_lo + (idx >> 4)) * p.part_ld + (idx & 15)] = s_dh[idx];
+
+    // dB: lane holds column nb*16 + l16 of the slab, rank indices 4 kg + j
+    const bool direct = n_pieces == 1;
+    float *base = direct ? reinterpret_cast<float *>(p.out_tab[it.adapter]) : p.part_dB + (int64_t)blockIdx.y * 16 * N;
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+        const int n = n0 + nb * 16 + l16;
+        if (n >= N) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int q = kg * 4 + j;
+            if (q >= rank) continue;
+            float *d = base + (int64_t)q * N + n;
+            *d = (direct && p.accumulate) ? *d + acc_db[nb][j] : acc_db[nb][j];
+        }
+    }
+}
+
+// dB_a of the adapters whose rows were cut into several pieces: the pieces' sums added in piece order, four loads in
+// flight at a time.  Block (x, q, item): 256 columns of rank index q.
+__global__ void __launch_bounds__(256) dual_sum_kernel(DualArgs p)
+{
+    const GradItem it = p.items[blockIdx.z];
+    const int n_pieces = (it.row_hi - it.row_lo + p.piece_rows - 1) / p.piece_rows;
+    const int n = blockIdx.x * 256 + threadIdx.x, q = blockIdx.y;
+    if (n_pieces <= 1 || n >= p.N || q >= it.rank) return;
+    const float *part = p.part_dB + ((int64_t)blockIdx.z * p.max_pieces * 16 + q) * p.N + n;
+    const int64_t stride = (int64_t)16 * p.N;
+    float sum = 0.f;
+    int pc = 0;
+    for (; pc + 4 <= n_pieces; pc += 4) {
+        const float v0 = part[(pc + 0) * stride], v1 = part[(pc + 1) * stride], v2 = part[(pc + 2) * stride],
+                    v3 = part[(pc + 3) * stride];
+        sum += v0;
+        sum += v1;
+        sum += v2;
+        sum += v3;
+    }
+    for (; pc < n_pieces; ++pc) sum += part[pc * stride];
+    float *d = reinterpret_cast<float *>(p.out_tab[it.adapter]) + (int64_t)q * p.N + n;
+    *d = p.accumulate ? *d + sum : sum;
+}
+
+// =========================================================================================
 // launchers
 // =========================================================================================
 // Row tiles per band of the tile order (see tile_coords): as many as keep a band's rows of the first operand
@@ -1961,6 +2166,33 @@ static hipError_t launch_grad_t(const GradArgs &a, int n_grad, int rpad, hipStre
     }
     const dim3 grid((a.N + 63) / 64, n_grad, (rpad + RP - 1) / RP);
     COLLM_LAUNCH(kern, grid, dim3(C::KW * 64), C::SMEM, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_dual(const DualArgs &a, hipStream_t st)
+{
+    if (a.n_grad <= 0) return hipSuccess;
+    if (a.piece_rows < 32 || a.piece_rows % 32 || a.piece_rows > kDualMaxPieceRows || a.max_pieces < 1 || !a.part_dh ||
+        !a.part_dB || a.part_ld < 16)
+        return hipErrorInvalidValue;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(dydual_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, DualCfg::SMEM);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    DualArgs b = a;
+    if (!b.warm_base || b.warm_bytes < 16) b.warm_rows = 0;
+    const dim3 grid((a.N + kDualCols - 1) / kDualCols, a.n_grad * a.max_pieces + b.warm_rows);
+    COLLM_LAUNCH(dydual_kernel, grid, dim3(512), DualCfg::SMEM, st, b);
+    return hipGetLastError();
+}
+
+hipError_t launch_dual_sum(const DualArgs &a, hipStream_t st)
+{
+    if (a.n_grad <= 0 || a.max_pieces <= 1) return hipSuccess;
+    COLLM_LAUNCH(dual_sum_kernel, dim3((a.N + 255) / 256, 16, a.n_grad), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 

@@ -83,6 +83,7 @@ struct PlanLayout {
     RowOrderLayout all;           // every token (forward)
     RowOrderLayout train;         // training tokens (backward)
     int32_t n_grad = 0, off_grad = 0;        // GradItem[n_grad]
+    int32_t max_grad_rows = 0;               // most training rows of one trained adapter
     int32_t total_ints = 0;
 };
 

@@ -309,6 +309,7 @@ int build_plan(const PlanRequest &rq, std::vector<int32_t> &blk, PlanLayout &L)
             g.row_hi = e;
             g.rank = rq.rank[a];
             grad.push_back(g);
+            L.max_grad_rows = std::max(L.max_grad_rows, e - r);
             r = e;
         }
     }

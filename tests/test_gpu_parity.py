@@ -15,9 +15,11 @@ from gpu_util import TOL, DeviceLayer, check_full, make_ctx, maxrel, to_dev, to_
 pytestmark = pytest.mark.gpu
 
 
-def _run_full(w, tol=None, h_save=True, transposed=False, wide_min_rows=None, gemm_split=None, **kw):
+def _run_full(w, tol=None, h_save=True, transposed=False, wide_min_rows=None, gemm_split=None, dual_pass=None, **kw):
     t = wl.make_tensors(w)
     ctx = make_ctx(w, **kw)
+    if dual_pass is not None:
+        ctx.set_dual_pass(dual_pass)
     if wide_min_rows is not None:
         ctx.set_wide_pass(wide_min_rows)
     if gemm_split is not None:
@@ -469,6 +471,36 @@ def test_weight_fetch_beside_the_rank_wide_passes():
         _run_full(w)
         _run_full(w, transposed=True)
         _run_full(w, h_save=False)
+
+
+def test_dh_and_dB_from_one_pass_over_dy():
+    # Ranks up to 16: the backward call may take dh and dB from one pass over the training rows of dy (forced here,
+    # since the library only chooses it for large dy).  Ragged everything: d_out no multiple of the 512-column groups
+    # or of 64, ranks 16, 8, 12 and 5, adapters of 1, 33, 70, 600 and 1100 training rows (one piece, several pieces,
+    # pieces that end inside a 32-row chunk), an adapter shared by inference and training segments, accumulate on and
+    # off, h recomputed; each against the oracle, and the forced pass against the two separate passes.
+    cases = [(264, 1096, [16, 8, 12, 5], [600, 1, 33, 9, 70, 1, 1100, 17], [0, 1, 1, 2, 3, 0, 2, 3], [1, 0, 1, 0, 1, 1, 1, 0]),
+             (128, 2048, [16, 16], [512, 64, 5], [0, 1, 1], [1, 1, 0]),
+             (64, 40, [16], [3, 200], [0, 0], [0, 1])]
+    for d_in, d_out, ranks, lens, ads, trn in cases:
+        w = _adhoc("bf16", d_in, d_out, ranks, lens, ads, trn, scale=0.6)
+        for h_save in (True, False):
+            e1 = _run_full(w, h_save=h_save, dual_pass=1)
+            e0 = _run_full(w, h_save=h_save, dual_pass=0)
+            assert set(e1) == set(e0)
+    # gradient accumulation through the one-pass path (pieces summed by the second kernel, and the direct write)
+    w = _adhoc("bf16", 128, 1032, [16, 8], [700, 40, 3], [0, 1, 1], [1, 1, 0])
+    t = wl.make_tensors(w)
+    ctx = make_ctx(w)
+    ctx.set_dual_pass(1)
+    layer = DeviceLayer(w, t, ctx)
+    layer.fwd()
+    layer.bwd()
+    first = [to_host(g).copy() for g in layer.dB]
+    layer.bwd(accumulate=True)
+    for g, f in zip(layer.dB, first):
+        assert maxrel(to_host(g), 2.0 * f) < 1e-6
+    ctx.close()
 
 
 def test_plan_statistics_and_device_info():
