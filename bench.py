@@ -37,7 +37,7 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 # 8192->28672 projection: rocprofv3 FETCH_SIZE and WRITE_SIZE in KiB, scaled by what the same counters read for a
 # plain 1 GiB copy (x 2.0 and x 1.0; profiles/gemm_lora_config5.txt),
 # with the digest of the kernel source the counters were taken on: a build from other source reports null.
-ROOFLINE_TRAFFIC = {"bytes": (6559734 * 2.0 + 946176 * 1.0) * 1024, "kernels_sha256_16": "8dd425baebd1080a"}
+ROOFLINE_TRAFFIC = {"bytes": (7145453 * 2.0 + 946176 * 1.0) * 1024, "kernels_sha256_16": "8669576208ae579e"}
 KERNEL_SOURCE = os.path.join(ROOT, "paper_2604_16400_amd", "csrc", "kernels_bf16.hip")
 
 
