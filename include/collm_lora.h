@@ -322,7 +322,8 @@ int collm_debug_set_wide_pass(collm_ctx *ctx, int min_rows);
  * Debug/tuning: whether the backward call takes dh and dB from ONE pass over the training rows of dy.
  * That pass applies to bf16, COLLM_LAYOUT_IN_OUT, no siblings, every rank of the batch at most 16, adapter gradients
  * requested, partial sums within the context's workspace.  -1 (default): where it applies and the training rows of dy
- * are at least 64 MiB (below that the second read of dy is cheaper than the partial sums); 1: wherever it applies;
+ * are at least 192 MiB (below that the second read of dy comes from the last-level cache and is cheaper than the
+ * partial sums); 1: wherever it applies;
  * 0: never, dh and dB each read dy (what every other case does).  Affects only speed and rounding order.
  */
 int collm_debug_set_dual_pass(collm_ctx *ctx, int mode);

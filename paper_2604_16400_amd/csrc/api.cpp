@@ -1214,10 +1214,12 @@ static int bwd_impl(collm_ctx *c, const collm_shape *s, const collm_siblings *si
     // rows of dy (kernels.h, DualArgs), which is the largest operand of the backward pass beside W.  The rows of
     // every trained adapter are cut into pieces so that two blocks per CU exist (pieces of 512 rows down to 64), as
     // long as the per-group slices of dh and the per-piece sums of dB fit the workspace of partial sums.  It pays where
-    // dy is large: 8192 rows of 28672 columns 151 us against 94 + 122 for the two passes, of 8192 columns 60 against
-    // 31 + 41; on 8192 x 1024 (34 against 10 + 15) and 1792 x 4096 (28 against 14 + 10) the partial sums and the two
-    // kernels that add them cost more than the second read of dy, which comes from the last-level cache there anyway.
-    constexpr int64_t kDualMinBytes = (int64_t)64 << 20;
+    // the training rows of dy do not fit the last-level cache (256 MB): 8192 rows of 28672 columns (470 MB) take 153 us
+    // against 94 + 122 for the two passes and the step is 1 % shorter; 8192 x 8192 (134 MB) 65 against 31 + 43 with
+    // no gain for the step (the two passes run side by side on two streams and the second reader finds dy in the
+    // cache); on 8192 x 1024 (34 against 10 + 15) and 1792 x 4096 (28 against 14 + 10) the partial sums and the two
+    // kernels that add them cost more than the second read.
+    constexpr int64_t kDualMinBytes = (int64_t)192 << 20;
     DualArgs du{};
     bool dual = false;
     if (!f32 && !tr && P == 1 && dA && c->dual_pass != 0 && L.rpad == kKStep && L.train.n_wide == 0 && L.n_grad > 0 &&
