@@ -1333,7 +1333,7 @@ static int bwd_impl(collm_ctx *c, const collm_shape *s, const collm_siblings *si
 
     // dh = s dy B_a^T: fp32 for dA, element type for the dX GEMM's extra K-steps
     if (dual) {
-        // (done above)
+        // dh came out of the pass over dy above, together with dB
     } else if (P == 1) {
         rc = run_skinny(c, s, L.train, dy, s->d_out, L.off_B_ptr, !tr, c->d_dh32, L.rpad, L.rpad, 0, s->scale,
                         c->d_dhs, s->scale, "dh", st, nullptr, (f32 || !dx) ? nullptr : W, (uint64_t)s->d_in * s->d_out * 2);
