@@ -1228,7 +1228,9 @@ static int bwd_impl(collm_ctx *c, const collm_shape *s, const collm_siblings *si
         auto pieces_of = [&](int rows) { return (L.max_grad_rows + rows - 1) / rows; };
         auto fits = [&](int rows) {
             const size_t dh_floats = (size_t)round_up(groups * L.train.n_rows_pad * kKStep, 64);
-            return (dh_floats + (size_t)L.n_grad * pieces_of(rows) * kKStep * s->d_out) * 4 <= c->part_bytes;
+            // (pieces are the grid's second dimension, with the rows of blocks that fetch the weight behind them)
+            return (long)L.n_grad * pieces_of(rows) + c->n_cus < 65536 &&
+                   (dh_floats + (size_t)L.n_grad * pieces_of(rows) * kKStep * s->d_out) * 4 <= c->part_bytes;
         };
         int rows = kDualMaxPieceRows;
         while (rows > 64 && (long)groups * L.n_grad * pieces_of(rows) < 2L * std::max(c->n_cus, 1)) rows >>= 1;
